@@ -1,0 +1,464 @@
+"""Pins for the CPU oracle: facts the paper and the mathematics fix, none of which
+is a retyping of the oracle's own formulae.  CPU only."""
+import itertools
+
+import numpy as np
+import pytest
+import scipy.ndimage as ndi
+import torch
+import torch.nn.functional as F
+
+import workloads as wl
+from oracle import deltacnn_oracle as orc
+from oracle.deltacnn_oracle import Delta
+
+INF = float("inf")
+
+
+def _video(net, seed, n_streams=1):
+    v = wl.make_batch(net["video"], seed, n_streams)          # [T,N,H,W,C]
+    return v
+
+
+def _run(net, S, seed=3, n_streams=1, use_xT=True):
+    wts = wl.make_weights(net, seed)
+    on = orc.OracleNet(net, wts, S, use_xT)
+    vid = _video(net, seed, n_streams)
+    return on, wts, vid
+
+
+NETS_DENSE_MODE = {
+    "conv3x3": lambda e: wl.single_conv_relu(eps=e, h=16, w=12, c=4, frames=4),
+    "bottleneck": lambda e: wl.bottleneck_block(eps=e, h=12, w=12, cin=8, mid=8, cout=16, frames=4, n_objects=1),
+    "mixed": lambda e: wl.tiny_mixed_net(eps=e, frames=4),
+}
+
+
+# ---- P1: nothing truncated  =>  the method reproduces ordinary per-frame inference -----------
+@pytest.mark.parametrize("name", list(NETS_DENSE_MODE))
+def test_negative_thresholds_reproduce_dense_inference(name):
+    """Section 3.1 Eq. 1 + Eq. 3; Section 5: negative thresholds = dense mode."""
+    net = NETS_DENSE_MODE[name](-1.0)
+    on, wts, vid = _run(net, "f64", n_streams=2)
+    for t in range(vid.shape[0]):
+        out = on.frame(vid[t])
+        ref = orc.dense_reference(net, wts, vid[t])
+        assert np.abs(out - ref).max() <= 1e-10 * max(1.0, np.abs(ref).max()), (name, t)
+
+
+def test_bias_only_in_first_frame():
+    """Zero weights, non-zero bias: every later delta must be exactly zero."""
+    net = wl.single_conv_relu(eps=-1.0, h=8, w=8, c=4, frames=3)
+    wts = wl.make_weights(net, 5)
+    wts = {i: (np.zeros_like(w), np.full_like(b, 0.7)) for i, (w, b) in wts.items()}
+    on = orc.OracleNet(net, wts, "f64")
+    vid = _video(net, 5)
+    o1 = on.frame(vid[0])
+    assert np.allclose(o1, 0.7)
+    o2 = on.frame(vid[1])
+    assert np.array_equal(o1, o2)
+    assert np.all(on.outs[1].zero_filled() == 0)
+
+
+# ---- P2/P3: bookkeeping invariants of Eqs. 5 and 6 ------------------------------------------
+@pytest.mark.parametrize("f", ["relu", "relu6"])
+@pytest.mark.parametrize("eps", [0.3, 1.5])
+def test_state_invariants(f, eps):
+    rng = np.random.default_rng(11)
+    shape = (2, 6, 5, 4)
+    layer = orc.ActTrunc(f, eps, "f64")
+    x0 = rng.normal(0, 2, shape)
+    y0 = layer.init(x0)
+    total_in = x0.copy()
+    total_out = y0.copy()
+    xa_init = x0.copy()
+    fn = {"relu": lambda v: np.maximum(v, 0), "relu6": lambda v: np.clip(v, 0, 6)}[f]
+    saw_trunc = saw_upd = False
+    for _ in range(12):
+        mask = (rng.random(shape[:3]) < 0.6).astype(np.uint8)
+        dx = rng.normal(0, 0.4, shape)
+        d = Delta(dx, mask).poisoned()
+        o = layer.step(d)
+        total_in += np.where(mask[..., None] != 0, dx, 0)
+        total_out += o.zero_filled()
+        saw_upd |= bool(o.mask.any())
+        saw_trunc |= bool(((mask == 1) & (o.mask == 0)).any())
+        assert np.all(o.mask <= mask)
+        # x^A + x^T is the sum of everything received
+        assert np.abs(layer.xA + layer.xT - total_in).max() < 1e-12
+        # the emitted deltas telescope to f(x^A_now) - f(x^A_init)
+        assert np.abs(total_out - y0 - (fn(layer.xA) - fn(xa_init))).max() < 1e-12
+        # x^T is zero wherever the pixel was just updated
+        assert np.all(layer.xT[o.mask == 1] == 0)
+        # un-propagated residue stays below the threshold
+        assert np.abs(fn(layer.xA + layer.xT) - fn(layer.xA)).max(axis=-1).max() < eps
+        assert not np.isnan(layer.xA).any() and not np.isnan(layer.xT).any()
+        assert not np.isnan(o.data[o.mask == 1]).any()
+    assert saw_trunc and saw_upd
+
+
+# ---- P4: slow drift -- the reason x^T exists -------------------------------------------------
+def test_slow_drift_fires_with_xT_and_is_lost_without():
+    """Section 3.1 ("sun slowly rising"): per-frame change eps/10; with x^T an update fires
+    within about ten frames and the output error never reaches eps; without x^T it never fires."""
+    eps = 0.5
+    shape = (1, 2, 2, 3)
+    step = np.full(shape, eps / 10)
+    mask = np.ones(shape[:3], np.uint8)
+    for use_xT in (True, False):
+        layer = orc.ActTrunc("relu", eps, "f64", use_xT=use_xT)
+        x0 = np.full(shape, 1.0)
+        y = layer.init(x0).copy()
+        fired_at = None
+        worst = 0.0
+        for t in range(1, 31):
+            o = layer.step(Delta(step.copy(), mask))
+            y = y + o.zero_filled()
+            truth = np.maximum(x0 + t * step, 0)
+            worst = max(worst, np.abs(y - truth).max())
+            if fired_at is None and o.mask.any():
+                fired_at = t
+        if use_xT:
+            assert fired_at is not None and 9 <= fired_at <= 11
+            assert worst < eps
+        else:
+            assert fired_at is None
+            assert worst > 2 * eps          # the error keeps growing: the negative control
+
+
+def test_input_layer_keeps_last_propagated_value():
+    """Same drift at the input layer: the frame is compared with the last propagated
+    input, so a drift of eps0/4 per frame is flagged every fourth frame."""
+    eps0 = 0.4
+    g = orc.DeltaGen(eps0, 0, "f64")
+    base = np.zeros((1, 3, 3, 2))
+    g.init(base)
+    flagged = []
+    for t in range(1, 13):
+        d = g.step(base + t * eps0 / 4 + 1e-12)
+        flagged.append(int(d.mask.all()))
+        if d.mask.all():
+            assert np.allclose(d.data, eps0, atol=1e-9)
+    assert flagged == [0, 0, 0, 1] * 3
+
+
+# ---- P5: nothing changes => nothing happens ---------------------------------------------------
+@pytest.mark.parametrize("S", ["f32", "f16"])
+def test_identical_frames_give_empty_masks(S):
+    net = wl.tiny_mixed_net(eps=0.05)
+    on, wts, vid = _run(net, S)
+    o1 = on.frame(vid[0]).copy()
+    state = [(getattr(l, "xA", None), getattr(l, "xT", None)) for l in on.layers]
+    state = [(None if a is None else a.copy(), None if b is None else b.copy()) for a, b in state]
+    o2 = on.frame(vid[0])
+    assert np.array_equal(o1, o2)
+    for i, o in enumerate(on.outs[:-1]):
+        assert o.count == 0 and o.idx.size == 0, i
+    for l, (a, b) in zip(on.layers, state):
+        if a is not None:
+            assert np.array_equal(l.xA, a)
+        if b is not None:
+            assert np.array_equal(l.xT, b)
+
+
+def test_infinite_threshold_freezes_output():
+    """Table 1's eps = infinity row: no update propagates after frame 1."""
+    net = wl.single_conv_relu(eps=INF, eps0=INF, h=16, w=16, c=4)
+    on, wts, vid = _run(net, "f32")
+    o1 = on.frame(vid[0]).copy()
+    for t in range(1, 4):
+        assert np.array_equal(on.frame(vid[t]), o1)
+        assert on.outs[0].count == 0
+
+
+def test_threshold_equality_updates():
+    """max |dy| == eps counts as an update (only strictly smaller values truncate);
+    eps = 0 therefore propagates every visited pixel, even with dy = 0."""
+    layer = orc.ActTrunc("relu", 0.5, "f64")
+    layer.init(np.array([[[[1.0, 2.0]]]]))
+    o = layer.step(Delta(np.array([[[[0.5, 0.25]]]]), np.ones((1, 1, 1), np.uint8)))
+    assert o.mask[0, 0, 0] == 1
+    o = layer.step(Delta(np.array([[[[0.4999, 0.25]]]]), np.ones((1, 1, 1), np.uint8)))
+    assert o.mask[0, 0, 0] == 0
+    z = orc.ActTrunc("relu", 0.0, "f64")
+    z.init(np.array([[[[-3.0]]]]))
+    o = z.step(Delta(np.array([[[[1.0]]]]), np.ones((1, 1, 1), np.uint8)))
+    assert o.mask[0, 0, 0] == 1 and o.data[0, 0, 0, 0] == 0.0
+
+
+# ---- P6: mask dilation -----------------------------------------------------------------------
+def test_one_pixel_becomes_49_after_three_3x3(golden):
+    c = 2
+    net_nodes = wl.nets._B()
+    x = net_nodes.deltagen(0.5)
+    for _ in range(3):
+        x = net_nodes.conv(x, 3, 1, c, c)
+    net_nodes.accum(x)
+    net = {"name": "t", "dtype": "f32", "h": 15, "w": 15, "c": c, "video": None, "nodes": net_nodes.nodes}
+    wts = wl.make_weights(net, 1)
+    on = orc.OracleNet(net, wts, "f64")
+    f0 = np.zeros((1, 15, 15, c))
+    on.frame(f0)
+    f1 = f0.copy()
+    f1[0, 7, 7, :] = 1.0
+    on.frame(f1)
+    counts = [on.outs[i].count for i in range(4)]
+    assert counts == [1, 9, 25, golden["dilation_after_three_3x3"]]
+    m = np.zeros((15, 15), bool)
+    m[7, 7] = True
+    for i in range(1, 4):
+        m = ndi.binary_dilation(m, structure=np.ones((3, 3), bool))
+        assert np.array_equal(on.outs[i].mask[0].astype(bool), m)
+        assert np.array_equal(on.outs[i].idx, np.flatnonzero(m))
+
+
+@pytest.mark.parametrize("k,stride,pad", [(3, 1, 1), (3, 2, 1), (1, 1, 0), (1, 2, 0), (7, 2, 3), (5, 1, 2), (3, 2, 0)])
+def test_window_mask_brute_force(k, stride, pad):
+    rng = np.random.default_rng(k * 100 + stride * 10 + pad)
+    m = (rng.random((2, 11, 9)) < 0.08).astype(np.uint8)
+    got = orc.window_mask(m, k, stride, pad)
+    ho = (11 + 2 * pad - k) // stride + 1
+    wo = (9 + 2 * pad - k) // stride + 1
+    ref = np.zeros((2, ho, wo), np.uint8)
+    for n, oy, ox, ky, kx in itertools.product(range(2), range(ho), range(wo), range(k), range(k)):
+        iy, ix = oy * stride - pad + ky, ox * stride - pad + kx
+        if 0 <= iy < 11 and 0 <= ix < 9 and m[n, iy, ix]:
+            ref[n, oy, ox] = 1
+    assert np.array_equal(got, ref)
+    if stride == 1 and 2 * pad == k - 1:
+        for n in range(2):
+            assert np.array_equal(got[n].astype(bool),
+                                  ndi.binary_dilation(m[n].astype(bool), structure=np.ones((k, k), bool)))
+
+
+def test_input_mask_dilation_is_a_square():
+    m = np.zeros((1, 21, 21), np.uint8)
+    m[0, 10, 10] = 1
+    out = orc.dilate_square(m, 7)
+    assert out.sum() == 15 * 15 and out[0, 3, 3] == 1 and out[0, 2, 3] == 0
+
+
+# ---- P7: the paper's scalar example -----------------------------------------------------------
+def test_relu_scalar_example(golden):
+    prev, dlt = float(golden["relu_prev"]), float(golden["relu_delta"])
+    layer = orc.ActTrunc("relu", -1.0, "f64")
+    layer.init(np.array([[[[prev]]]]))
+    o = layer.step(Delta(np.array([[[[dlt]]]]), np.ones((1, 1, 1), np.uint8)))
+    assert o.data[0, 0, 0, 0] == golden["relu_correct_delta"] != golden["relu_wrong_sum"]
+    layer = orc.ActTrunc("relu", -1.0, "f64")
+    layer.init(np.array([[[[1.0]]]]))
+    o = layer.step(Delta(np.array([[[[-3.0]]]]), np.ones((1, 1, 1), np.uint8)))
+    assert o.data[0, 0, 0, 0] == -1.0
+
+
+# ---- P8: convolution / pooling / upsampling against brute force and a library -----------------
+CONV_CASES = [(3, 1, 1, False), (3, 2, 1, False), (1, 1, 0, False), (1, 2, 0, False), (7, 2, 3, False),
+              (3, 1, 1, True), (3, 2, 1, True), (3, 1, 0, False)]
+
+
+@pytest.mark.parametrize("k,stride,pad,dw", CONV_CASES)
+def test_conv_dense_brute_force_and_torch(k, stride, pad, dw):
+    rng = np.random.default_rng(k + 10 * stride + 100 * pad + 1000 * dw)
+    n, h, w, cin = 2, 9, 8, 3
+    cout = cin if dw else 4
+    x = rng.normal(size=(n, h, w, cin))
+    wgt = rng.normal(size=(k, k, cin) if dw else (k, k, cin, cout))
+    got = orc.conv_dense(x, wgt, stride, pad, dw)
+    ho = (h + 2 * pad - k) // stride + 1
+    wo = (w + 2 * pad - k) // stride + 1
+    ref = np.zeros((n, ho, wo, cout))
+    for b, oy, ox, co in itertools.product(range(n), range(ho), range(wo), range(cout)):
+        acc = 0.0
+        for ky, kx in itertools.product(range(k), range(k)):
+            iy, ix = oy * stride - pad + ky, ox * stride - pad + kx
+            if not (0 <= iy < h and 0 <= ix < w):
+                continue
+            if dw:
+                acc += x[b, iy, ix, co] * wgt[ky, kx, co]
+            else:
+                for ci in range(cin):
+                    acc += x[b, iy, ix, ci] * wgt[ky, kx, ci, co]
+        ref[b, oy, ox, co] = acc
+    assert got.shape == ref.shape
+    assert np.abs(got - ref).max() < 1e-12
+    xt = torch.from_numpy(x).permute(0, 3, 1, 2)
+    if dw:
+        wt = torch.from_numpy(wgt).permute(2, 0, 1).unsqueeze(1)            # [C,1,k,k]
+        yt = F.conv2d(xt, wt, stride=stride, padding=pad, groups=cin)
+    else:
+        wt = torch.from_numpy(wgt).permute(3, 2, 0, 1)                       # [Cout,Cin,k,k]
+        yt = F.conv2d(xt, wt, stride=stride, padding=pad)
+    assert np.abs(got - yt.permute(0, 2, 3, 1).numpy()).max() < 1e-12
+
+
+@pytest.mark.parametrize("k,stride,pad,dw", CONV_CASES)
+def test_sparse_conv_step_equals_conv_of_zero_filled_delta(k, stride, pad, dw):
+    """Linearity (Eq. 1): the step equals the dense conv of the delta with zeros at unflagged
+    pixels -- computed here through torch, with NaN poison proving unflagged values are not used."""
+    rng = np.random.default_rng(7 + k)
+    n, h, w, cin = 1, 10, 9, 4
+    cout = cin if dw else 6
+    wgt = rng.normal(size=(k, k, cin) if dw else (k, k, cin, cout))
+    layer = orc.Conv(wgt, rng.normal(size=cout), stride, pad, dw, "f64")
+    mask = (rng.random((n, h, w)) < 0.15).astype(np.uint8)
+    data = rng.normal(size=(n, h, w, cin))
+    out = layer.step(Delta(data, mask).poisoned())
+    zf = np.where(mask[..., None] != 0, data, 0.0)
+    xt = torch.from_numpy(zf).permute(0, 3, 1, 2)
+    if dw:
+        yt = F.conv2d(xt, torch.from_numpy(wgt).permute(2, 0, 1).unsqueeze(1), stride=stride, padding=pad, groups=cin)
+    else:
+        yt = F.conv2d(xt, torch.from_numpy(wgt).permute(3, 2, 0, 1), stride=stride, padding=pad)
+    ref = yt.permute(0, 2, 3, 1).numpy()
+    sel = out.mask != 0
+    assert sel.any()
+    assert not np.isnan(out.data[sel]).any()
+    assert np.abs(out.data[sel] - ref[sel]).max() < 1e-12
+    assert not (~sel).any() or np.abs(ref[~sel]).max() == 0.0   # nothing outside the mask is non-zero
+    assert np.isnan(out.data[~sel]).all()
+
+
+def test_maxpool_and_upsample_against_torch():
+    rng = np.random.default_rng(2)
+    x = rng.normal(size=(2, 9, 11, 3))
+    got = orc.maxpool_dense(x, 3, 2, 1)
+    ref = F.max_pool2d(torch.from_numpy(x).permute(0, 3, 1, 2), 3, 2, 1).permute(0, 2, 3, 1).numpy()
+    assert np.array_equal(got, ref)
+    up = orc.Upsample(2, "f64").init(x)
+    ref = F.interpolate(torch.from_numpy(x).permute(0, 3, 1, 2), scale_factor=2, mode="nearest")
+    assert np.array_equal(up, ref.permute(0, 2, 3, 1).numpy())
+
+
+def test_maxpool_step_tracks_dense_pooling():
+    """dy = pool(x + dx) - pool(x): summed deltas equal pooling of the summed input."""
+    rng = np.random.default_rng(4)
+    layer = orc.MaxPool(3, 2, 1, "f64")
+    x = rng.normal(size=(1, 8, 8, 2))
+    y = layer.init(x).copy()
+    for _ in range(5):
+        mask = (rng.random((1, 8, 8)) < 0.2).astype(np.uint8)
+        dx = rng.normal(size=x.shape)
+        o = layer.step(Delta(dx, mask).poisoned())
+        x = x + np.where(mask[..., None] != 0, dx, 0)
+        y = y + o.zero_filled()
+        assert np.abs(y - orc.maxpool_dense(x, 3, 2, 1)).max() < 1e-12
+        assert np.array_equal(o.mask, orc.window_mask(mask, 3, 2, 1))
+        assert not np.isnan(o.data[o.mask == 1]).any()
+
+
+def test_add_and_accumulate():
+    rng = np.random.default_rng(9)
+    a = Delta(rng.normal(size=(1, 4, 4, 2)), (rng.random((1, 4, 4)) < 0.5).astype(np.uint8)).poisoned()
+    b = Delta(rng.normal(size=(1, 4, 4, 2)), (rng.random((1, 4, 4)) < 0.5).astype(np.uint8)).poisoned()
+    s = orc.Add("f64").step(a, b)
+    assert np.array_equal(s.mask, a.mask | b.mask)
+    for y, x in itertools.product(range(4), range(4)):
+        exp = np.zeros(2)
+        if a.mask[0, y, x]:
+            exp = exp + a.data[0, y, x]
+        if b.mask[0, y, x]:
+            exp = exp + b.data[0, y, x]
+        if s.mask[0, y, x]:
+            assert np.allclose(s.data[0, y, x], exp, atol=1e-15)
+        else:
+            assert np.isnan(s.data[0, y, x]).all()
+    acc = orc.Accumulate("f64")
+    base = rng.normal(size=(1, 4, 4, 2))
+    acc.init(base)
+    out = acc.step(s)
+    assert np.allclose(out, base + s.zero_filled(), atol=1e-15)
+
+
+# ---- P9: compaction ---------------------------------------------------------------------------
+def test_compaction_is_flatnonzero():
+    rng = np.random.default_rng(1)
+    m = (rng.random((3, 7, 5)) < 0.3).astype(np.uint8)
+    idx, cnt = orc.compact(m)
+    assert idx.dtype == np.int32 and cnt == int(m.sum())
+    assert np.all(np.diff(idx) > 0)
+    n, y, x = np.unravel_index(idx, m.shape)
+    assert np.all(m[n, y, x] == 1)
+    e_idx, e_cnt = orc.compact(np.zeros((1, 4, 4), np.uint8))
+    assert e_cnt == 0 and e_idx.size == 0
+
+
+# ---- P10: the never-read rule, end to end -----------------------------------------------------
+@pytest.mark.parametrize("S", ["f64", "f32", "f16"])
+def test_no_nan_reaches_outputs_or_state(S):
+    net = wl.tiny_mixed_net(eps=0.05)
+    on, wts, vid = _run(net, S, n_streams=2)
+    for t in range(vid.shape[0]):
+        out = on.frame(vid[t])
+        assert not np.isnan(out).any()
+        for ly, o in zip(on.layers, on.outs):
+            for nm in ("xA", "xT", "P", "O"):
+                v = getattr(ly, nm, None)
+                if v is not None:
+                    assert not np.isnan(v).any()
+            if isinstance(o, Delta):
+                assert not np.isnan(o.data[o.mask == 1]).any()
+                assert np.isnan(o.data[o.mask == 0]).all()
+
+
+# ---- P11: the paper's tile arithmetic ---------------------------------------------------------
+def test_tile_cost_matches_paper(golden):
+    c = golden["tile_channels"]
+    cost = orc.conv_tile_cost(golden["tile_out"], golden["tile_out"], golden["tile_k"], 1, c, c)
+    assert cost["inputs"] == golden["tile_inputs"]
+    assert cost["weights"] == golden["tile_weights"]
+    assert cost["multiplications"] == golden["tile_multiplications"]
+
+
+def test_sparse_mac_count_brute_force():
+    rng = np.random.default_rng(3)
+    m = (rng.random((2, 7, 6)) < 0.3).astype(np.uint8)
+    for k, s, p in [(3, 1, 1), (3, 2, 1), (1, 1, 0), (7, 2, 3)]:
+        ho, wo = (7 + 2 * p - k) // s + 1, (6 + 2 * p - k) // s + 1
+        pairs = 0
+        for n, oy, ox, ky, kx in itertools.product(range(2), range(ho), range(wo), range(k), range(k)):
+            iy, ix = oy * s - p + ky, ox * s - p + kx
+            if 0 <= iy < 7 and 0 <= ix < 6 and m[n, iy, ix]:
+                pairs += 1
+        assert orc.conv_sparse_macs(m, k, s, p, 5, 3) == pairs * 15
+    full = np.ones((1, 8, 8), np.uint8)
+    assert orc.conv_sparse_macs(full, 1, 1, 0, 4, 4) == 64 * 16
+
+
+# ---- storage precisions -----------------------------------------------------------------------
+@pytest.mark.parametrize("S,tol", [("f32", 2e-5), ("f16", 3e-2)])
+def test_reduced_precision_tracks_f64(S, tol):
+    """The f32 / f16 runs stay close to the f64 run in dense mode (no threshold decisions)."""
+    net = wl.tiny_mixed_net(eps=-1.0)
+    wts = wl.make_weights(net, 3)
+    a = orc.OracleNet(net, wts, "f64")
+    b = orc.OracleNet(net, wts, S)
+    vid = _video(net, 3)
+    for t in range(vid.shape[0]):
+        ya, yb = a.frame(vid[t]), b.frame(vid[t])
+        assert yb.dtype == {"f32": np.float32, "f16": np.float16}[S]
+        assert np.abs(ya - yb.astype(np.float64)).max() <= tol * np.abs(ya).max()
+
+
+def test_reset_restarts_from_a_dense_frame():
+    net = wl.single_conv_relu(eps=0.05, h=16, w=16, c=4)
+    on, wts, vid = _run(net, "f32")
+    for t in range(3):
+        on.frame(vid[t])
+    on.reset()
+    out = on.frame(vid[3])
+    fresh = orc.OracleNet(net, wts, "f32").frame(vid[3])
+    assert np.array_equal(out, fresh)
+
+
+def test_truncation_error_is_bounded_not_accumulating():
+    """With eps > 0 the accumulated output differs from dense inference, but the difference
+    does not grow with the number of frames (Section 3.1, last sentence)."""
+    net = wl.single_conv_relu(eps=0.05, h=32, w=32, c=8, frames=40)
+    on, wts, vid = _run(net, "f64")
+    errs = []
+    for t in range(vid.shape[0]):
+        out = on.frame(vid[t])
+        errs.append(np.abs(out - orc.dense_reference(net, wts, vid[t])).max())
+    assert errs[0] < 1e-12
+    assert max(errs[20:]) < 2.0 * max(errs[1:20]) + 1e-9
+    assert max(errs) < 1.0
