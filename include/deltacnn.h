@@ -1,0 +1,194 @@
+/*
+ * deltacnn.h -- C ABI of the MI355X (gfx950) sparse frame-difference CNN inference library.
+ *
+ * The library implements the per-frame hot path of DeltaCNN (arXiv 2203.03996): after one
+ * dense first frame has initialised every layer's buffers, each later frame travels through
+ * the network as a sparse update (delta feature map + per-pixel update mask).
+ *
+ * Conventions that hold for every call
+ * ------------------------------------
+ *  - Pointers named *_dev are DEVICE pointers, *_host are HOST pointers.  The library never
+ *    allocates device memory: every buffer (tensors, layer state, workspace, the network arena)
+ *    is allocated by the caller with the sizes the *_query calls report, and must stay valid
+ *    until the object that uses it is destroyed.  All device buffers must be 256-byte aligned.
+ *  - Feature maps are NHWC, element type dcnn_dtype.  Masks are uint8 [n,h,w] holding 0 or 1.
+ *    Index lists are int32, the ascending linear pixel indices (n*H + y)*W + x of the flagged
+ *    pixels; `count` is one int32 in device memory.  Active counts never travel to the host.
+ *  - A delta feature map is defined only where its mask is 1.  Everywhere else its memory is
+ *    undefined, is never read by the library, and may hold anything (supplementary Section 1.3).
+ *  - Every call returns a dcnn_status; nothing throws.  Arguments are validated before anything
+ *    is launched.  dcnn_last_error() gives a text for the last failure of a context.
+ *  - All work is enqueued on the context's HIP stream; no call synchronises except
+ *    dcnn_layer_stats, dcnn_net_stats and dcnn_ctx_sync.  Calls on one context must not overlap.
+ *  - Results are deterministic run to run: no floating-point atomics, ordered compaction.
+ *  - fp16 tensors are stored as IEEE binary16 and all arithmetic is done in fp32 with one
+ *    round-to-nearest-even at each store; thresholds are fp32.
+ */
+#ifndef DELTACNN_H
+#define DELTACNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DCNN_OK = 0,
+    DCNN_EINVAL = 1,        /* null pointer, bad enum, bad size */
+    DCNN_ESHAPE = 2,        /* shapes of inputs / descriptor do not fit together */
+    DCNN_EDTYPE = 3,
+    DCNN_ESTATE = 4,        /* step before init, object not bound, ... */
+    DCNN_ENOMEM = 5,        /* a caller-provided buffer is too small */
+    DCNN_EHIP = 6,          /* a HIP call failed; text in dcnn_last_error */
+    DCNN_EUNSUPPORTED = 7
+} dcnn_status;
+
+typedef enum { DCNN_F32 = 0, DCNN_F16 = 1 } dcnn_dtype;
+
+typedef enum {
+    DCNN_DELTAGEN = 0,      /* input layer: dense frame -> (delta, mask)            Fig. 2; Section 4   */
+    DCNN_CONV = 1,          /* k x k dense-weight convolution on deltas              Section 3.1, Eq. 1  */
+    DCNN_DWCONV = 2,        /* k x k depthwise convolution on deltas                 suppl. Section 1.2  */
+    DCNN_ACT = 3,           /* activation + truncation, optionally of a sum of two   Section 3.1 Eqs 4-6 */
+    DCNN_MAXPOOL = 4,       /* max pooling with accumulated-input buffer             Section 3.1, Eq. 3  */
+    DCNN_UPSAMPLE = 5,      /* nearest-neighbour upsampling                          Section 3.4         */
+    DCNN_ACCUM = 6          /* output layer: deltas accumulated into a dense map     Fig. 2              */
+} dcnn_kind;
+
+typedef enum { DCNN_ACT_NONE = 0, DCNN_ACT_RELU = 1, DCNN_ACT_RELU6 = 2 } dcnn_act;
+
+/* A sparse update.  All pointers are device pointers owned by the caller (or, for a layer's
+ * output, carved by the library out of the layer's caller-provided state memory).
+ * idx has room for n*h*w entries.  For DCNN_DELTAGEN the single input is a dense frame:
+ * only `data` and the shape are used. */
+typedef struct {
+    void*    data;          /* [n,h,w,c] NHWC                                      */
+    uint8_t* mask;          /* [n,h,w], 0/1                                         */
+    int32_t* idx;           /* ascending flagged pixel indices, first *count valid  */
+    int32_t* count;         /* number of flagged pixels                             */
+    int32_t  n, h, w, c;
+    int32_t  dtype;         /* dcnn_dtype                                           */
+} dcnn_delta;
+
+/* One layer.  n,h,w,c is the shape of the (first) input.
+ *  CONV / DWCONV : kh=kw in {1,3,5,7}, stride in {1,2}, pad < k; cout (DWCONV: cout == c).
+ *                  act != NONE fuses activation + truncation (threshold eps) behind the
+ *                  convolution; n_in == 2 adds a second delta stream of the OUTPUT shape
+ *                  (residual) before the activation.
+ *  ACT           : n_in in {1,2}: activation + truncation of the input / of the sum of both.
+ *                  act == NONE with n_in == 2 is a plain, stateless add.
+ *  DELTAGEN      : eps is the input threshold, dilate_r the radius of the square mask dilation.
+ *  MAXPOOL       : kh, stride, pad.     UPSAMPLE : factor.     ACCUM : nothing else.
+ * The update rule is "update iff max_c |dy_c| >= eps": eps < 0 updates every visited pixel,
+ * eps = +infinity none. */
+typedef struct {
+    int32_t kind;           /* dcnn_kind  */
+    int32_t dtype;          /* dcnn_dtype */
+    int32_t n, h, w, c;
+    int32_t kh, kw, stride, pad, cout;
+    int32_t act;            /* dcnn_act   */
+    float   eps;
+    int32_t n_in;
+    int32_t dilate_r;
+    int32_t factor;
+    int32_t want_idx;       /* 0: the output's idx/count need not be produced (no consumer reads them) */
+} dcnn_layer_desc;
+
+typedef struct {
+    size_t  state_bytes;    /* persistent per-layer device memory (buffers + outputs + packed weights) */
+    int32_t on, oh, ow, oc; /* output shape */
+} dcnn_layer_sizes;
+
+/* Counters of the last step of a layer (Section 5 reports the same quantities per network). */
+typedef struct {
+    int64_t pixels_in;      /* flagged pixels of input 0                       */
+    int64_t pixels_work;    /* pixels the layer visited (its work list)        */
+    int64_t pixels_out;     /* flagged pixels of the output                    */
+    int64_t pixels_total;   /* n*h*w of the output                             */
+} dcnn_stats;
+
+typedef struct dcnn_ctx dcnn_ctx;
+typedef struct dcnn_layer dcnn_layer;
+typedef struct dcnn_net dcnn_net;
+
+/* ---- context ------------------------------------------------------------------------------- */
+/* hip_stream: a hipStream_t (may be NULL = default stream), borrowed.  workspace_dev: scratch
+ * shared by all layers of the context (partial counts, survivor bits); dcnn_workspace_bytes(p)
+ * is enough for any layer whose output has at most p = n*h*w pixels. */
+size_t      dcnn_workspace_bytes(int64_t max_pixels);
+dcnn_status dcnn_ctx_create(void* hip_stream, void* workspace_dev, size_t workspace_bytes, dcnn_ctx** out);
+void        dcnn_ctx_destroy(dcnn_ctx* ctx);
+dcnn_status dcnn_ctx_sync(dcnn_ctx* ctx);
+const char* dcnn_status_str(dcnn_status s);
+const char* dcnn_last_error(const dcnn_ctx* ctx);
+
+/* ---- mask propagation + ordered compaction (Section 3.2 "Update mask"; Section 3.3) ---------- */
+/* mask_out[o] = OR of mask_in over the in-bounds taps of the k x k window of output pixel o
+ * (k = 1, stride 1, pad 0: a copy), optionally OR-ed with mask_b (a second mask of the OUTPUT
+ * shape, may be NULL); then idx_out = ascending indices of the flagged output pixels and
+ * *count_out their number.  mask_out may be NULL (only the list is wanted).  Output shape:
+ * oh = (h + 2*pad - k)/stride + 1, same for ow. */
+dcnn_status dcnn_mask_compact(dcnn_ctx* ctx, const uint8_t* mask_in_dev, int32_t n, int32_t h, int32_t w,
+                              int32_t k, int32_t stride, int32_t pad, const uint8_t* mask_b_dev,
+                              uint8_t* mask_out_dev, int32_t* idx_out_dev, int32_t* count_out_dev);
+
+/* ---- layers -------------------------------------------------------------------------------- */
+dcnn_status dcnn_layer_query(const dcnn_layer_desc* desc, dcnn_layer_sizes* out);
+/* weights_dev: CONV [kh][kw][cin][cout], DWCONV [kh][kw][c]; bias_dev [cout] or NULL; both of the
+ * layer's dtype, read once here (packed into state memory) -- they may be freed after
+ * dcnn_ctx_sync.  state_dev: at least state_bytes from dcnn_layer_query, zero-filled or not. */
+dcnn_status dcnn_layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const void* weights_dev,
+                              const void* bias_dev, void* state_dev, size_t state_bytes, dcnn_layer** out);
+void        dcnn_layer_destroy(dcnn_layer* layer);
+/* Frame 1 (Fig. 2): dense inputs -> dense output (the layer's ordinary definition, with bias),
+ * and the layer's buffers are initialised (x^A <- dense input of the non-linearity, x^T <- 0,
+ * input layer: stored frame, output layer: dense output).  dense_out_dev has the output shape.
+ * Afterwards the layer's sparse output is empty (mask 0, count 0). */
+dcnn_status dcnn_layer_init(dcnn_layer* layer, const void* const* dense_in_dev, int32_t n_in, void* dense_out_dev);
+/* Frames >= 2: consume sparse inputs, update the buffers, produce the sparse output, which
+ * lives in the layer's state memory and is described by dcnn_layer_output.  For DCNN_ACCUM the
+ * output's data is the dense accumulated map (all pixels valid). */
+dcnn_status dcnn_layer_step(dcnn_layer* layer, const dcnn_delta* const* in, int32_t n_in);
+dcnn_status dcnn_layer_output(const dcnn_layer* layer, dcnn_delta* out_view);
+/* Forget the buffers: the next call must be dcnn_layer_init (supplementary Section 1.4). */
+dcnn_status dcnn_layer_reset(dcnn_layer* layer);
+/* which: 0 = x^A (ACT/CONV+act/MAXPOOL), stored frame (DELTAGEN), dense output (ACCUM); 1 = x^T.
+ * Returns the device pointer and byte size of that buffer inside the state memory. */
+dcnn_status dcnn_layer_state(const dcnn_layer* layer, int32_t which, void** ptr_dev, size_t* bytes);
+/* Counters of the last step; synchronises the stream. */
+dcnn_status dcnn_layer_stats(dcnn_layer* layer, dcnn_stats* stats_host);
+
+/* ---- networks ------------------------------------------------------------------------------ */
+/* A network is a DAG of plain nodes (kinds above with act/n_in unfused: CONV has no activation,
+ * ACT has one input, adds are ACT nodes with act NONE and two inputs).  dcnn_net_finalize fuses
+ * conv -> (add) -> act chains into single layers and plans the buffers. */
+dcnn_status dcnn_net_create(dcnn_ctx* ctx, int32_t dtype, int32_t n, int32_t h, int32_t w, int32_t c, dcnn_net** out);
+void        dcnn_net_destroy(dcnn_net* net);
+/* inputs: node ids returned by earlier calls (none for DELTAGEN).  weights/bias as in
+ * dcnn_layer_create, DEVICE pointers that must stay valid until dcnn_net_bind has returned and
+ * the context has been synchronised.  Returns the node id in *node_id. */
+dcnn_status dcnn_net_add(dcnn_net* net, const dcnn_layer_desc* desc, const int32_t* inputs, int32_t n_inputs,
+                         const void* weights_dev, const void* bias_dev, int32_t* node_id);
+/* flags: bit 0 fuses conv -> (add) -> activation chains into one layer (otherwise every node is a
+ * layer of its own); bit 1 makes every layer produce its output index list even when no consumer
+ * reads it.  Reports the arena size. */
+dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t flags, size_t* arena_bytes);
+dcnn_status dcnn_net_bind(dcnn_net* net, void* arena_dev, size_t arena_bytes);
+/* First frame / later frames.  frame_dev: dense [n,h,w,c].  out_dev: dense output of the last
+ * node, or NULL (the dense output also lives in the arena: dcnn_net_output). */
+dcnn_status dcnn_net_init(dcnn_net* net, const void* frame_dev, void* out_dev);
+dcnn_status dcnn_net_step(dcnn_net* net, const void* frame_dev, void* out_dev);
+dcnn_status dcnn_net_reset(dcnn_net* net);
+dcnn_status dcnn_net_output(const dcnn_net* net, dcnn_delta* out_view);
+int32_t     dcnn_net_num_layers(const dcnn_net* net);
+/* Layer i of the fused plan, and the node id whose output it produces. */
+dcnn_status dcnn_net_layer(const dcnn_net* net, int32_t i, dcnn_layer** layer, int32_t* node_id);
+/* Per-layer counters of the last step, stats_host[dcnn_net_num_layers]; synchronises. */
+dcnn_status dcnn_net_stats(dcnn_net* net, dcnn_stats* stats_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DELTACNN_H */

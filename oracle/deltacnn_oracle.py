@@ -219,7 +219,7 @@ class ActTrunc:
 
     def __init__(self, f: str, eps: float, S: str = "f32", use_xT: bool = True):
         self.f, self.eps, self.S, self.use_xT = f, eps, S, use_xT
-        self.xA = self.xT = None
+        self.xA = self.xT = self.last_u = None
 
     def init(self, x: np.ndarray) -> np.ndarray:
         st = _STORE[self.S]
@@ -231,6 +231,7 @@ class ActTrunc:
         st, mt = _STORE[self.S], _MATH[self.S]
         out = np.full(d.data.shape, np.nan, dtype=st)
         m_out = np.zeros_like(d.mask)
+        self.last_u = np.full(d.mask.shape, np.nan)   # max_k |dy_k| of the visited pixels (inspection only)
         sel = np.nonzero(d.mask)                      # only flagged pixels are touched
         if sel[0].size:
             xa = self.xA[sel].astype(mt)
@@ -239,6 +240,7 @@ class ActTrunc:
             s = (xa + xt) + dx
             dy = act_fn(self.f, s) - act_fn(self.f, xa)
             u = np.abs(dy).max(axis=-1)
+            self.last_u[sel] = u
             upd = u >= mt(self.eps)
             new_xa = np.where(upd[:, None], s.astype(st), self.xA[sel])
             if self.use_xT:

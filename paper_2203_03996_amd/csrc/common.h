@@ -1,0 +1,155 @@
+// Internal declarations shared by the translation units of libdeltacnn (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/deltacnn.h"
+
+namespace dcnn {
+
+constexpr int kWave = 64;            // gfx950 wavefront
+constexpr int kTile = 32;            // list entries one wave processes at a time (= MFMA N)
+constexpr int kChunk = 2048;         // pixels per workgroup in the pixel-space mask passes
+constexpr int kXcd = 8;              // accelerator complex dies, each with its own L2
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t dtype_size(int dt) { return dt == DCNN_F16 ? 2 : 4; }
+
+}  // namespace dcnn
+
+struct dcnn_ctx {
+    hipStream_t stream;
+    char* ws;
+    size_t ws_bytes;
+    int num_cu;
+    size_t max_lds;
+    char err[512];
+};
+
+namespace dcnn {
+
+dcnn_status fail(dcnn_ctx* ctx, dcnn_status s, const char* fmt, ...);
+dcnn_status check_hip(dcnn_ctx* ctx, hipError_t e, const char* what);
+
+// Workspace carve-up (all offsets 256-byte aligned).
+struct Workspace {
+    int32_t* chunk_counts;   // one per kChunk pixels
+    uint32_t* surv;          // one survivor word per kTile list entries
+    uint8_t* scratch_mask;   // mask of a pass whose caller only wants the list
+    int64_t max_pixels;
+};
+size_t workspace_bytes(int64_t max_pixels);
+dcnn_status workspace_view(dcnn_ctx* ctx, int64_t pixels, Workspace* out);
+
+// ---- kernel launchers (defined in the *.hip files) -------------------------------------------
+struct MaskPassArgs {
+    const uint8_t* mask_in;      // [n,h,w] or nullptr (treated as all zero)
+    const uint8_t* mask_b;       // [n,oh,ow] or nullptr
+    uint8_t* mask_out;           // [n,oh,ow] or nullptr
+    int32_t* idx_out;            // may be nullptr (then only mask_out is written)
+    int32_t* count_out;
+    int n, h, w, oh, ow, k, stride, pad;
+    int up;                      // > 1: nearest upsampling of the input mask by this factor (k = 1)
+    int emit_only;               // 1: mask_in is final and its chunk counts are in the workspace already
+};
+dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& a);
+
+// Ordered compaction of the entries of a work list that survived (bit set in surv).
+dcnn_status launch_emit_sublist(dcnn_ctx* ctx, const int32_t* list, const int32_t* count, int64_t max_count,
+                                const uint32_t* surv, int32_t* idx_out, int32_t* count_out);
+dcnn_status launch_fill_i32(dcnn_ctx* ctx, int32_t* p, int32_t v, int64_t n);
+dcnn_status launch_fill_u8(dcnn_ctx* ctx, uint8_t* p, uint8_t v, int64_t n);
+
+// Element-wise tail shared by CONV / ACT: (+bias) (+residual) activation, truncation, state.
+struct EpilogueArgs {
+    int c;                       // channels of the output pixel
+    int act;                     // dcnn_act
+    float eps;
+    const void* bias;            // [c] or nullptr (first frame only)
+    const void* res_data;        // second delta stream (output shape) or nullptr
+    const uint8_t* res_mask;     // nullptr in the first frame (dense residual)
+    void* xA;                    // nullptr when act == NONE
+    void* xT;
+    void* out_data;
+    uint8_t* out_mask;           // written at every visited pixel (0 or 1); nullptr: not written
+    uint32_t* surv;              // survivor word per tile; nullptr: not written
+};
+
+struct ListArgs {
+    const int32_t* list;         // nullptr: identity (entry j is pixel j)
+    const int32_t* count;        // nullptr: use count_host
+    int64_t count_host;
+    int64_t max_count;           // upper bound used to size the grid
+};
+
+struct ConvArgs {
+    const void* in_data;
+    const uint8_t* in_mask;      // nullptr: every in-bounds pixel is flagged (first frame)
+    const void* wpacked;
+    int n, h, w, cin, oh, ow, cout, cout_pad, k, stride, pad, kch;
+    int depthwise;
+};
+dcnn_status launch_conv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const ConvArgs& c,
+                        const EpilogueArgs& e);
+size_t conv_packed_weight_bytes(int dtype, int k, int cin, int cout, int depthwise);
+dcnn_status launch_pack_weights(dcnn_ctx* ctx, int dtype, const void* w, void* wpacked, int k, int cin, int cout,
+                                int depthwise);
+bool conv_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cout, int depthwise, bool fused,
+                    char* why, size_t why_len);
+
+struct ActArgs {
+    const void* in_data;         // first delta stream
+    const uint8_t* in_mask;      // nullptr: always valid (single input: the list is its mask)
+};
+dcnn_status launch_act(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const ActArgs& a,
+                       const EpilogueArgs& e);
+dcnn_status launch_dwconv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const ConvArgs& c,
+                          const EpilogueArgs& e);
+
+struct DeltaGenArgs {
+    const void* frame;
+    void* P;
+    void* out_data;
+    uint8_t* out_mask;
+    int32_t* out_idx;
+    int32_t* out_count;
+    int64_t pixels;
+    int n, h, w, c;
+    float eps;
+    int dilate_r;
+};
+dcnn_status launch_deltagen(dcnn_ctx* ctx, int dtype, const DeltaGenArgs& a);
+dcnn_status launch_copy(dcnn_ctx* ctx, void* dst, const void* src, size_t bytes);
+
+struct AccumArgs {
+    const void* in_data;
+    void* O;
+    int c;
+};
+dcnn_status launch_accum(dcnn_ctx* ctx, int dtype, const ListArgs& l, const AccumArgs& a);
+
+struct PoolArgs {
+    const void* in_data;         // delta at flagged input pixels
+    const uint8_t* in_mask;
+    void* xA;                    // accumulated dense input [n,h,w,c]
+    void* out_data;              // [n,oh,ow,c]
+    int n, h, w, c, oh, ow, k, stride, pad;
+};
+// work list = flagged OUTPUT pixels; a second pass over the flagged INPUT pixels folds the delta into xA
+dcnn_status launch_maxpool_out(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const PoolArgs& a);
+dcnn_status launch_maxpool_commit(dcnn_ctx* ctx, int dtype, const ListArgs& l_in, const PoolArgs& a);
+
+struct UpsampleArgs {
+    const void* in_data;
+    void* out_data;
+    int n, h, w, c, factor;
+};
+dcnn_status launch_upsample(dcnn_ctx* ctx, int dtype, const ListArgs& l_out, const UpsampleArgs& a);
+
+}  // namespace dcnn

@@ -1,0 +1,31 @@
+// Internal layout of a layer object (shared by layer.hip and net.hip).
+#pragma once
+
+#include "common.h"
+
+struct dcnn_layer {
+    dcnn_ctx* ctx;
+    dcnn_layer_desc d;
+    int oh, ow, oc;
+    int64_t in_pixels, out_pixels;
+    bool inited;
+    bool alias_mask;            // output mask / index list are those of input 0
+    bool has_bias;
+    size_t state_bytes;
+    // pieces of the caller-provided state memory
+    void* buf0; size_t buf0_bytes;      // x^A | stored input frame | dense output
+    void* buf1; size_t buf1_bytes;      // x^T
+    void* out_data;
+    uint8_t* out_mask;
+    int32_t* out_idx;
+    int32_t* out_count;
+    int32_t* list;                      // work list when the layer builds its own
+    int32_t* list_count;
+    void* wpacked;
+    void* bias;
+    int32_t* counters;
+    // bookkeeping of the last step
+    dcnn_delta view;
+    const int32_t* last_in_count;
+    const int32_t* last_work_count;
+};

@@ -1,0 +1,483 @@
+// Layer objects: validation, carve-up of the caller-provided state memory, and the launch
+// sequence of one layer for the first (dense) frame and for later (sparse) frames.
+#include <new>
+
+#include "layer.h"
+
+using namespace dcnn;
+
+namespace dcnn {
+
+static bool has_act(const dcnn_layer_desc& d) { return d.act != DCNN_ACT_NONE; }
+
+// Does the layer build a work list of its own (window dilation / union of two masks), or does
+// it walk the index list of its first input as it is?
+static bool own_list(const dcnn_layer_desc& d) {
+    switch (d.kind) {
+        case DCNN_CONV:
+        case DCNN_DWCONV: return !(d.kh == 1 && d.stride == 1 && d.n_in == 1);
+        case DCNN_ACT: return d.n_in == 2;
+        case DCNN_MAXPOOL:
+        case DCNN_UPSAMPLE: return true;
+        default: return false;
+    }
+}
+
+static dcnn_status out_shape(const dcnn_layer_desc& d, int* oh, int* ow, int* oc) {
+    *oh = d.h; *ow = d.w; *oc = d.c;
+    switch (d.kind) {
+        case DCNN_CONV:
+        case DCNN_DWCONV:
+        case DCNN_MAXPOOL:
+            if (d.kh < 1 || d.kh > 7 || d.kw != d.kh || d.stride < 1 || d.stride > 2 || d.pad < 0 || d.pad >= d.kh)
+                return DCNN_EINVAL;
+            if (d.h + 2 * d.pad < d.kh || d.w + 2 * d.pad < d.kh) return DCNN_ESHAPE;
+            *oh = (d.h + 2 * d.pad - d.kh) / d.stride + 1;
+            *ow = (d.w + 2 * d.pad - d.kh) / d.stride + 1;
+            if (d.kind != DCNN_MAXPOOL) {
+                if (d.cout < 1) return DCNN_EINVAL;
+                if (d.kind == DCNN_DWCONV && d.cout != d.c) return DCNN_ESHAPE;
+                *oc = d.cout;
+            }
+            return DCNN_OK;
+        case DCNN_UPSAMPLE:
+            if (d.factor < 1 || d.factor > 16) return DCNN_EINVAL;
+            *oh = d.h * d.factor; *ow = d.w * d.factor;
+            return DCNN_OK;
+        default: return DCNN_OK;
+    }
+}
+
+static dcnn_status validate_desc(const dcnn_layer_desc& d) {
+    if (d.kind < DCNN_DELTAGEN || d.kind > DCNN_ACCUM) return DCNN_EINVAL;
+    if (d.dtype != DCNN_F32 && d.dtype != DCNN_F16) return DCNN_EDTYPE;
+    if (d.n < 1 || d.h < 1 || d.w < 1 || d.c < 1) return DCNN_ESHAPE;
+    if ((int64_t)d.n * d.h * d.w > INT32_MAX / 4) return DCNN_ESHAPE;
+    if (d.act < DCNN_ACT_NONE || d.act > DCNN_ACT_RELU6) return DCNN_EINVAL;
+    if (d.eps != d.eps) return DCNN_EINVAL;                               // NaN threshold
+    switch (d.kind) {
+        case DCNN_DELTAGEN: if (d.n_in != 0 && d.n_in != 1) return DCNN_EINVAL; break;
+        case DCNN_CONV:
+        case DCNN_DWCONV: if (d.n_in != 1 && d.n_in != 2) return DCNN_EINVAL; break;
+        case DCNN_ACT:
+            if (d.n_in != 1 && d.n_in != 2) return DCNN_EINVAL;
+            if (d.n_in == 1 && d.act == DCNN_ACT_NONE) return DCNN_EINVAL;  // would be the identity
+            break;
+        default: if (d.n_in != 1) return DCNN_EINVAL;
+    }
+    int oh, ow, oc;
+    return out_shape(d, &oh, &ow, &oc);
+}
+
+// Walks the state memory and hands out aligned pieces; with base == nullptr it only measures.
+struct Carver {
+    char* base;
+    size_t off = 0;
+    explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+    void* take(size_t bytes) {
+        void* p = base ? base + off : nullptr;
+        off += align_up(bytes);
+        return p;
+    }
+};
+
+static void carve(dcnn_layer* L, void* state) {
+    const dcnn_layer_desc& d = L->d;
+    const size_t es = dtype_size(d.dtype);
+    Carver cv(state);
+    const size_t in_map = (size_t)L->in_pixels * d.c * es;
+    const size_t out_map = (size_t)L->out_pixels * L->oc * es;
+    const bool act = has_act(d), own = own_list(d);
+    L->buf0 = L->buf1 = nullptr; L->buf0_bytes = L->buf1_bytes = 0;
+    L->out_data = nullptr; L->out_mask = nullptr; L->out_idx = nullptr; L->out_count = nullptr;
+    L->list = nullptr; L->list_count = nullptr; L->wpacked = nullptr; L->bias = nullptr;
+    L->counters = static_cast<int32_t*>(cv.take(kAlign));
+    switch (d.kind) {
+        case DCNN_DELTAGEN:
+            L->buf0 = cv.take(in_map); L->buf0_bytes = in_map;
+            break;
+        case DCNN_CONV:
+        case DCNN_DWCONV:
+        case DCNN_ACT:
+            if (act) {
+                L->buf0 = cv.take(out_map); L->buf0_bytes = out_map;
+                L->buf1 = cv.take(out_map); L->buf1_bytes = out_map;
+            }
+            break;
+        case DCNN_MAXPOOL:
+            L->buf0 = cv.take(in_map); L->buf0_bytes = in_map;
+            break;
+        case DCNN_ACCUM:
+            L->buf0 = cv.take(out_map); L->buf0_bytes = out_map;
+            break;
+        default: break;
+    }
+    if (d.kind != DCNN_ACCUM) {
+        L->out_data = cv.take(out_map);
+        // a stateless, mask-preserving layer (1x1 s1 conv without activation) forwards its input's
+        // mask and index list; every other layer owns them
+        L->alias_mask = !act && !own && (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV);
+        if (!L->alias_mask) {
+            L->out_mask = static_cast<uint8_t*>(cv.take((size_t)L->out_pixels));
+            L->out_idx = static_cast<int32_t*>(cv.take((size_t)L->out_pixels * sizeof(int32_t)));
+            L->out_count = static_cast<int32_t*>(cv.take(kAlign));
+        }
+        if (own) {
+            if (act) {                                            // work list distinct from the output list
+                L->list = static_cast<int32_t*>(cv.take((size_t)L->out_pixels * sizeof(int32_t)));
+                L->list_count = static_cast<int32_t*>(cv.take(kAlign));
+            } else {
+                L->list = L->out_idx;
+                L->list_count = L->out_count;
+            }
+        }
+    } else {
+        L->alias_mask = true;
+    }
+    if (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV) {
+        L->wpacked = cv.take(conv_packed_weight_bytes(d.dtype, d.kh, d.c, L->oc, d.kind == DCNN_DWCONV));
+        L->bias = cv.take((size_t)L->oc * es);
+    }
+    L->state_bytes = cv.off;
+}
+
+static dcnn_status clear_sparse_output(dcnn_layer* L) {
+    if (L->alias_mask) return DCNN_OK;
+    dcnn_status st = launch_fill_u8(L->ctx, L->out_mask, 0, (int64_t)align_up((size_t)L->out_pixels, 4));
+    if (st != DCNN_OK) return st;
+    st = launch_fill_i32(L->ctx, L->out_count, 0, 1);
+    if (st != DCNN_OK) return st;
+    if (L->list_count && L->list_count != L->out_count) st = launch_fill_i32(L->ctx, L->list_count, 0, 1);
+    return st;
+}
+
+static ListArgs full_list(int64_t pixels) {
+    ListArgs l{};
+    l.list = nullptr; l.count = nullptr; l.count_host = pixels; l.max_count = pixels;
+    return l;
+}
+
+static dcnn_status check_input(dcnn_layer* L, const dcnn_delta* in, int which, int h, int w, int c, bool need_idx) {
+    dcnn_ctx* ctx = L->ctx;
+    if (!in) return fail(ctx, DCNN_EINVAL, "step: input %d is null", which);
+    if (in->dtype != L->d.dtype) return fail(ctx, DCNN_EDTYPE, "step: input %d has dtype %d, layer %d", which, in->dtype, L->d.dtype);
+    if (in->n != L->d.n || in->h != h || in->w != w || in->c != c)
+        return fail(ctx, DCNN_ESHAPE, "step: input %d is [%d,%d,%d,%d], expected [%d,%d,%d,%d]", which, in->n, in->h,
+                    in->w, in->c, L->d.n, h, w, c);
+    if (!in->data) return fail(ctx, DCNN_EINVAL, "step: input %d has no data", which);
+    if (L->d.kind != DCNN_DELTAGEN) {
+        if (!in->mask) return fail(ctx, DCNN_EINVAL, "step: input %d has no mask", which);
+        if (need_idx && (!in->idx || !in->count)) return fail(ctx, DCNN_EINVAL, "step: input %d has no index list", which);
+    }
+    return DCNN_OK;
+}
+
+}  // namespace dcnn
+
+extern "C" {
+
+dcnn_status dcnn_layer_query(const dcnn_layer_desc* desc, dcnn_layer_sizes* out) {
+    if (!desc || !out) return DCNN_EINVAL;
+    dcnn_status st = validate_desc(*desc);
+    if (st != DCNN_OK) return st;
+    dcnn_layer tmp{};
+    tmp.d = *desc;
+    out_shape(*desc, &tmp.oh, &tmp.ow, &tmp.oc);
+    tmp.in_pixels = (int64_t)desc->n * desc->h * desc->w;
+    tmp.out_pixels = (int64_t)desc->n * tmp.oh * tmp.ow;
+    carve(&tmp, nullptr);
+    out->state_bytes = tmp.state_bytes;
+    out->on = desc->n; out->oh = tmp.oh; out->ow = tmp.ow; out->oc = tmp.oc;
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const void* weights_dev, const void* bias_dev,
+                              void* state_dev, size_t state_bytes, dcnn_layer** out) {
+    if (!ctx) return DCNN_EINVAL;
+    if (!desc || !out) return fail(ctx, DCNN_EINVAL, "layer_create: null argument");
+    *out = nullptr;
+    dcnn_status st = validate_desc(*desc);
+    if (st != DCNN_OK) return fail(ctx, st, "layer_create: invalid descriptor (kind %d)", desc->kind);
+    if (!state_dev || (reinterpret_cast<uintptr_t>(state_dev) % kAlign) != 0)
+        return fail(ctx, DCNN_EINVAL, "layer_create: state memory missing or not 256-byte aligned");
+    dcnn_layer* L = new (std::nothrow) dcnn_layer();
+    if (!L) return fail(ctx, DCNN_ENOMEM, "layer_create: host allocation failed");
+    L->ctx = ctx;
+    L->d = *desc;
+    out_shape(*desc, &L->oh, &L->ow, &L->oc);
+    L->in_pixels = (int64_t)desc->n * desc->h * desc->w;
+    L->out_pixels = (int64_t)desc->n * L->oh * L->ow;
+    L->inited = false;
+    carve(L, state_dev);
+    if (L->state_bytes > state_bytes) {
+        st = fail(ctx, DCNN_ENOMEM, "layer_create: state memory of %zu bytes, need %zu", state_bytes, L->state_bytes);
+        delete L;
+        return st;
+    }
+    const bool conv = desc->kind == DCNN_CONV || desc->kind == DCNN_DWCONV;
+    if (conv) {
+        if (!weights_dev) { delete L; return fail(ctx, DCNN_EINVAL, "layer_create: convolution without weights"); }
+        char why[256];
+        if (!conv_supported(ctx, desc->dtype, desc->kh, desc->c, L->oc, desc->kind == DCNN_DWCONV, has_act(*desc), why,
+                            sizeof(why))) {
+            delete L;
+            return fail(ctx, DCNN_EUNSUPPORTED, "layer_create: %s", why);
+        }
+        st = launch_pack_weights(ctx, desc->dtype, weights_dev, L->wpacked, desc->kh, desc->c, L->oc,
+                                 desc->kind == DCNN_DWCONV);
+        if (st == DCNN_OK && bias_dev) st = launch_copy(ctx, L->bias, bias_dev, (size_t)L->oc * dtype_size(desc->dtype));
+        if (st != DCNN_OK) { delete L; return st; }
+        L->has_bias = bias_dev != nullptr;
+    }
+    if (desc->kind == DCNN_DELTAGEN && desc->dilate_r != 0) {
+        delete L;
+        return fail(ctx, DCNN_EUNSUPPORTED, "layer_create: input-mask dilation is not implemented");
+    }
+    st = clear_sparse_output(L);
+    if (st == DCNN_OK) st = launch_fill_i32(ctx, L->counters, 0, kAlign / sizeof(int32_t));
+    if (st != DCNN_OK) { delete L; return st; }
+    *out = L;
+    return DCNN_OK;
+}
+
+void dcnn_layer_destroy(dcnn_layer* layer) { delete layer; }
+
+dcnn_status dcnn_layer_reset(dcnn_layer* layer) {
+    if (!layer) return DCNN_EINVAL;
+    layer->inited = false;
+    return clear_sparse_output(layer);
+}
+
+dcnn_status dcnn_layer_init(dcnn_layer* L, const void* const* dense_in, int32_t n_in, void* dense_out) {
+    if (!L) return DCNN_EINVAL;
+    dcnn_ctx* ctx = L->ctx;
+    const dcnn_layer_desc& d = L->d;
+    const int want_in = d.kind == DCNN_DELTAGEN ? 1 : d.n_in;
+    if (!dense_in || n_in != want_in) return fail(ctx, DCNN_EINVAL, "init: expected %d dense inputs, got %d", want_in, n_in);
+    for (int i = 0; i < n_in; ++i)
+        if (!dense_in[i]) return fail(ctx, DCNN_EINVAL, "init: dense input %d is null", i);
+    if (!dense_out && d.kind != DCNN_ACCUM) return fail(ctx, DCNN_EINVAL, "init: dense output is null");
+    const size_t es = dtype_size(d.dtype);
+    dcnn_status st = DCNN_OK;
+    switch (d.kind) {
+        case DCNN_DELTAGEN:
+            st = launch_copy(ctx, L->buf0, dense_in[0], L->buf0_bytes);
+            if (st == DCNN_OK && dense_out != dense_in[0]) st = launch_copy(ctx, dense_out, dense_in[0], L->buf0_bytes);
+            break;
+        case DCNN_CONV:
+        case DCNN_DWCONV: {
+            ConvArgs c{};
+            c.in_data = dense_in[0]; c.in_mask = nullptr; c.wpacked = L->wpacked;
+            c.n = d.n; c.h = d.h; c.w = d.w; c.cin = d.c; c.oh = L->oh; c.ow = L->ow; c.cout = L->oc;
+            c.k = d.kh; c.stride = d.stride; c.pad = d.pad; c.depthwise = d.kind == DCNN_DWCONV;
+            EpilogueArgs e{};
+            e.c = L->oc; e.act = d.act; e.eps = d.eps; e.bias = L->has_bias ? L->bias : nullptr;
+            e.res_data = d.n_in == 2 ? dense_in[1] : nullptr; e.res_mask = nullptr;
+            e.xA = L->buf0; e.xT = L->buf1; e.out_data = dense_out; e.out_mask = nullptr; e.surv = nullptr;
+            st = launch_conv(ctx, d.dtype, true, full_list(L->out_pixels), c, e);
+            break;
+        }
+        case DCNN_ACT: {
+            ActArgs a{dense_in[0], nullptr};
+            EpilogueArgs e{};
+            e.c = L->oc; e.act = d.act; e.eps = d.eps; e.bias = nullptr;
+            e.res_data = d.n_in == 2 ? dense_in[1] : nullptr; e.res_mask = nullptr;
+            e.xA = L->buf0; e.xT = L->buf1; e.out_data = dense_out;
+            st = launch_act(ctx, d.dtype, true, full_list(L->out_pixels), a, e);
+            break;
+        }
+        case DCNN_MAXPOOL: {
+            st = launch_copy(ctx, L->buf0, dense_in[0], L->buf0_bytes);
+            if (st != DCNN_OK) break;
+            PoolArgs a{};
+            a.in_data = nullptr; a.in_mask = nullptr; a.xA = L->buf0; a.out_data = dense_out;
+            a.n = d.n; a.h = d.h; a.w = d.w; a.c = d.c; a.oh = L->oh; a.ow = L->ow; a.k = d.kh; a.stride = d.stride; a.pad = d.pad;
+            st = launch_maxpool_out(ctx, d.dtype, true, full_list(L->out_pixels), a);
+            break;
+        }
+        case DCNN_UPSAMPLE: {
+            UpsampleArgs a{dense_in[0], dense_out, d.n, d.h, d.w, d.c, d.factor};
+            st = launch_upsample(ctx, d.dtype, full_list(L->out_pixels), a);
+            break;
+        }
+        case DCNN_ACCUM:
+            st = launch_copy(ctx, L->buf0, dense_in[0], L->buf0_bytes);
+            if (st == DCNN_OK && dense_out) st = launch_copy(ctx, dense_out, dense_in[0], L->buf0_bytes);
+            break;
+    }
+    (void)es;
+    if (st != DCNN_OK) return st;
+    st = clear_sparse_output(L);
+    if (st != DCNN_OK) return st;
+    L->inited = true;
+    L->last_in_count = nullptr;
+    L->view = dcnn_delta{};
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t n_in) {
+    if (!L) return DCNN_EINVAL;
+    dcnn_ctx* ctx = L->ctx;
+    const dcnn_layer_desc& d = L->d;
+    if (!L->inited) return fail(ctx, DCNN_ESTATE, "step: the layer has not seen a first frame (call init)");
+    const int want_in = d.kind == DCNN_DELTAGEN ? 1 : d.n_in;
+    if (!in || n_in != want_in) return fail(ctx, DCNN_EINVAL, "step: expected %d inputs, got %d", want_in, n_in);
+    const bool act = has_act(d), own = own_list(d);
+    dcnn_status st = check_input(L, in[0], 0, d.h, d.w, d.c, !own || d.kind == DCNN_MAXPOOL);
+    if (st != DCNN_OK) return st;
+    if (n_in == 2) {
+        st = check_input(L, in[1], 1, L->oh, L->ow, L->oc, false);
+        if (st != DCNN_OK) return st;
+    }
+    Workspace ws;
+    st = workspace_view(ctx, L->out_pixels > L->in_pixels ? L->out_pixels : L->in_pixels, &ws);
+    if (st != DCNN_OK) return st;
+
+    // the output view (aliases are refreshed every step)
+    dcnn_delta& v = L->view;
+    v.n = d.n; v.h = L->oh; v.w = L->ow; v.c = L->oc; v.dtype = d.dtype;
+    v.data = L->out_data;
+    v.mask = L->alias_mask ? in[0]->mask : L->out_mask;
+    v.idx = L->alias_mask ? in[0]->idx : L->out_idx;
+    v.count = L->alias_mask ? in[0]->count : L->out_count;
+    L->last_in_count = in[0]->count;
+
+    if (d.kind == DCNN_DELTAGEN) {
+        DeltaGenArgs a{};
+        a.frame = in[0]->data; a.P = L->buf0; a.out_data = L->out_data; a.out_mask = L->out_mask;
+        a.out_idx = L->out_idx; a.out_count = L->out_count; a.pixels = L->in_pixels;
+        a.n = d.n; a.h = d.h; a.w = d.w; a.c = d.c; a.eps = d.eps; a.dilate_r = d.dilate_r;
+        L->last_in_count = nullptr;
+        L->last_work_count = L->out_count;
+        return launch_deltagen(ctx, d.dtype, a);
+    }
+
+    // ---- work list -----------------------------------------------------------------------------
+    ListArgs l{};
+    l.max_count = L->out_pixels;
+    if (own) {
+        MaskPassArgs m{};
+        m.mask_in = in[0]->mask; m.mask_b = n_in == 2 ? in[1]->mask : nullptr;
+        m.mask_out = L->out_mask; m.idx_out = L->list; m.count_out = L->list_count;
+        m.n = d.n; m.h = d.h; m.w = d.w; m.oh = L->oh; m.ow = L->ow;
+        m.k = 1; m.stride = 1; m.pad = 0; m.up = 1; m.emit_only = 0;
+        if (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV || d.kind == DCNN_MAXPOOL) { m.k = d.kh; m.stride = d.stride; m.pad = d.pad; }
+        if (d.kind == DCNN_UPSAMPLE) m.up = d.factor;
+        st = launch_mask_compact(ctx, m);
+        if (st != DCNN_OK) return st;
+        l.list = L->list; l.count = L->list_count;
+    } else {
+        l.list = in[0]->idx; l.count = in[0]->count;
+        if (act) {
+            // the truncation below rewrites the mask at the visited pixels only: start from a copy
+            MaskPassArgs m{};
+            m.mask_in = in[0]->mask; m.mask_out = L->out_mask; m.idx_out = nullptr;
+            m.n = d.n; m.h = d.h; m.w = d.w; m.oh = L->oh; m.ow = L->ow; m.k = 1; m.stride = 1; m.pad = 0; m.up = 1;
+            st = launch_mask_compact(ctx, m);
+            if (st != DCNN_OK) return st;
+        }
+    }
+    L->last_work_count = l.count;
+
+    // ---- compute -------------------------------------------------------------------------------
+    switch (d.kind) {
+        case DCNN_CONV:
+        case DCNN_DWCONV: {
+            ConvArgs c{};
+            c.in_data = in[0]->data; c.in_mask = in[0]->mask; c.wpacked = L->wpacked;
+            c.n = d.n; c.h = d.h; c.w = d.w; c.cin = d.c; c.oh = L->oh; c.ow = L->ow; c.cout = L->oc;
+            c.k = d.kh; c.stride = d.stride; c.pad = d.pad; c.depthwise = d.kind == DCNN_DWCONV;
+            EpilogueArgs e{};
+            e.c = L->oc; e.act = d.act; e.eps = d.eps; e.bias = nullptr;
+            e.res_data = n_in == 2 ? in[1]->data : nullptr; e.res_mask = n_in == 2 ? in[1]->mask : nullptr;
+            e.xA = L->buf0; e.xT = L->buf1; e.out_data = L->out_data;
+            e.out_mask = act ? L->out_mask : nullptr;
+            e.surv = (act && d.want_idx) ? ws.surv : nullptr;
+            st = launch_conv(ctx, d.dtype, false, l, c, e);
+            break;
+        }
+        case DCNN_ACT: {
+            ActArgs a{in[0]->data, n_in == 2 ? in[0]->mask : nullptr};
+            EpilogueArgs e{};
+            e.c = L->oc; e.act = d.act; e.eps = d.eps;
+            e.res_data = n_in == 2 ? in[1]->data : nullptr; e.res_mask = n_in == 2 ? in[1]->mask : nullptr;
+            e.xA = L->buf0; e.xT = L->buf1; e.out_data = L->out_data;
+            e.out_mask = act ? L->out_mask : nullptr;
+            e.surv = (act && d.want_idx) ? ws.surv : nullptr;
+            st = launch_act(ctx, d.dtype, false, l, a, e);
+            break;
+        }
+        case DCNN_MAXPOOL: {
+            PoolArgs a{};
+            a.in_data = in[0]->data; a.in_mask = in[0]->mask; a.xA = L->buf0; a.out_data = L->out_data;
+            a.n = d.n; a.h = d.h; a.w = d.w; a.c = d.c; a.oh = L->oh; a.ow = L->ow; a.k = d.kh; a.stride = d.stride; a.pad = d.pad;
+            st = launch_maxpool_out(ctx, d.dtype, false, l, a);
+            if (st != DCNN_OK) break;
+            ListArgs li{};
+            li.list = in[0]->idx; li.count = in[0]->count; li.max_count = L->in_pixels;
+            st = launch_maxpool_commit(ctx, d.dtype, li, a);
+            break;
+        }
+        case DCNN_UPSAMPLE: {
+            UpsampleArgs a{in[0]->data, L->out_data, d.n, d.h, d.w, d.c, d.factor};
+            st = launch_upsample(ctx, d.dtype, l, a);
+            break;
+        }
+        case DCNN_ACCUM: {
+            AccumArgs a{in[0]->data, L->buf0, d.c};
+            v.data = L->buf0;
+            st = launch_accum(ctx, d.dtype, l, a);
+            break;
+        }
+        default: return fail(ctx, DCNN_EINVAL, "step: bad layer kind");
+    }
+    if (st != DCNN_OK) return st;
+    // ---- ordered list of the pixels that stayed flagged ------------------------------------------
+    if (act && d.want_idx && (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV || d.kind == DCNN_ACT))
+        st = launch_emit_sublist(ctx, l.list, l.count, L->out_pixels, ws.surv, L->out_idx, L->out_count);
+    return st;
+}
+
+dcnn_status dcnn_layer_output(const dcnn_layer* L, dcnn_delta* out_view) {
+    if (!L || !out_view) return DCNN_EINVAL;
+    if (L->view.data == nullptr) {
+        // before the first step: an empty update
+        dcnn_delta v{};
+        v.n = L->d.n; v.h = L->oh; v.w = L->ow; v.c = L->oc; v.dtype = L->d.dtype;
+        v.data = L->d.kind == DCNN_ACCUM ? L->buf0 : L->out_data;
+        v.mask = L->out_mask; v.idx = L->out_idx; v.count = L->out_count;
+        *out_view = v;
+        return DCNN_OK;
+    }
+    *out_view = L->view;
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_layer_state(const dcnn_layer* L, int32_t which, void** ptr_dev, size_t* bytes) {
+    if (!L || !ptr_dev || !bytes) return DCNN_EINVAL;
+    if (which == 0 && L->buf0) { *ptr_dev = L->buf0; *bytes = L->buf0_bytes; return DCNN_OK; }
+    if (which == 1 && L->buf1) { *ptr_dev = L->buf1; *bytes = L->buf1_bytes; return DCNN_OK; }
+    return fail(L->ctx, DCNN_EINVAL, "layer_state: the layer has no buffer %d", which);
+}
+
+dcnn_status dcnn_layer_stats(dcnn_layer* L, dcnn_stats* s) {
+    if (!L || !s) return DCNN_EINVAL;
+    dcnn_ctx* ctx = L->ctx;
+    dcnn_status st = check_hip(ctx, hipStreamSynchronize(ctx->stream), "hipStreamSynchronize");
+    if (st != DCNN_OK) return st;
+    auto read = [&](const int32_t* p, int64_t* dst) -> dcnn_status {
+        *dst = 0;
+        if (!p) return DCNN_OK;
+        int32_t v = 0;
+        dcnn_status r = check_hip(ctx, hipMemcpy(&v, p, sizeof(v), hipMemcpyDeviceToHost), "hipMemcpy(count)");
+        *dst = v;
+        return r;
+    };
+    st = read(L->last_in_count, &s->pixels_in);
+    if (st == DCNN_OK) st = read(L->last_work_count, &s->pixels_work);
+    if (st == DCNN_OK) st = read(L->view.count, &s->pixels_out);
+    s->pixels_total = L->out_pixels;
+    return st;
+}
+
+}  // extern "C"

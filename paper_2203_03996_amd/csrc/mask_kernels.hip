@@ -1,0 +1,202 @@
+// Update-mask propagation and ordered compaction (Section 3.2 "Update mask", Section 3.3).
+//
+// mask pass  : pixel space; out[o] = OR of the input mask over the in-bounds window taps of o
+//              (or the nearest-upsampled input mask), OR a second mask; one count per chunk.
+// emit       : pixel space; exclusive prefix over the chunk counts + an in-chunk scan turn the
+//              mask into the ascending list of flagged pixels.  No atomics: the list order is
+//              fixed, so results are identical from run to run.
+// emit_sublist: list space; keeps the entries of a work list whose survivor bit is set.
+#include "device_utils.h"
+
+namespace dcnn {
+
+constexpr int kMaskThreads = 256;
+constexpr int kPxPerThread = kChunk / kMaskThreads;     // 8 consecutive pixels per thread
+static_assert(kPxPerThread == 8, "one 64-bit mask word per thread");
+
+__device__ __forceinline__ int block_sum(int v, int* s_red) {
+    for (int m = kWave >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    if (lane == 0) s_red[wave] = v;
+    __syncthreads();
+    int t = 0;
+    for (int i = 0; i < kMaskThreads / kWave; ++i) t += s_red[i];
+    __syncthreads();
+    return t;
+}
+
+// Exclusive prefix of v over the threads of the block (thread order), and the block total.
+__device__ __forceinline__ int block_exclusive_scan(int v, int* s_red, int* total) {
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    int inc = v;
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int o = __shfl_up(inc, d, kWave);
+        if (lane >= d) inc += o;
+    }
+    if (lane == kWave - 1) s_red[wave] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+    for (int i = 0; i < kMaskThreads / kWave; ++i) {
+        const int s = s_red[i];
+        if (i < wave) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+struct MaskKernelArgs {
+    const uint8_t* mask_in;
+    const uint8_t* mask_b;
+    uint8_t* mask_out;
+    int32_t* chunk_counts;
+    int64_t out_pixels;
+    int n, h, w, oh, ow, k, stride, pad, up;
+};
+
+__global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs a) {
+    __shared__ int s_red[kMaskThreads / kWave];
+    const int64_t p0 = (int64_t)blockIdx.x * kChunk + (int64_t)threadIdx.x * kPxPerThread;
+    uint64_t word = 0;
+    int cnt = 0;
+    if (p0 < a.out_pixels) {
+        if (a.k == 1 && a.stride == 1 && a.up == 1 && p0 + kPxPerThread <= a.out_pixels) {
+            word = *reinterpret_cast<const uint64_t*>(a.mask_in + p0);
+            if (a.mask_b) word |= *reinterpret_cast<const uint64_t*>(a.mask_b + p0);
+        } else {
+            int ox = (int)(p0 % a.ow);
+            int64_t t = p0 / a.ow;
+            int oy = (int)(t % a.oh);
+            int64_t n = t / a.oh;
+            for (int i = 0; i < kPxPerThread && p0 + i < a.out_pixels; ++i) {
+                uint8_t f = 0;
+                if (a.up > 1) {
+                    f = a.mask_in[(n * a.h + oy / a.up) * a.w + ox / a.up];
+                } else {
+                    for (int ky = 0; ky < a.k; ++ky) {
+                        const int iy = oy * a.stride - a.pad + ky;
+                        if (iy < 0 || iy >= a.h) continue;
+                        const uint8_t* row = a.mask_in + (n * a.h + iy) * a.w;
+                        for (int kx = 0; kx < a.k; ++kx) {
+                            const int ix = ox * a.stride - a.pad + kx;
+                            if (ix >= 0 && ix < a.w) f |= row[ix];
+                        }
+                    }
+                }
+                if (a.mask_b) f |= a.mask_b[p0 + i];
+                word |= (uint64_t)(f ? 1 : 0) << (8 * i);
+                if (++ox == a.ow) { ox = 0; if (++oy == a.oh) { oy = 0; ++n; } }
+            }
+        }
+        cnt = __popcll(word);
+        if (p0 + kPxPerThread <= a.out_pixels) {
+            *reinterpret_cast<uint64_t*>(a.mask_out + p0) = word;
+        } else {
+            for (int i = 0; p0 + i < a.out_pixels; ++i) a.mask_out[p0 + i] = (uint8_t)((word >> (8 * i)) & 1);
+        }
+    }
+    const int total = block_sum(cnt, s_red);
+    if (threadIdx.x == 0) a.chunk_counts[blockIdx.x] = total;
+}
+
+struct EmitArgs {
+    const uint8_t* mask;
+    const int32_t* chunk_counts;
+    int32_t* idx_out;
+    int32_t* count_out;
+    int64_t pixels;
+};
+
+__global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
+    __shared__ int s_red[kMaskThreads / kWave];
+    const int chunk = blockIdx.x;
+    const bool last = chunk == (int)gridDim.x - 1;
+    const int mine = a.chunk_counts[chunk];
+    if (mine == 0 && !last) return;                           // uniform for the block
+    int part = 0;
+    for (int i = threadIdx.x; i < chunk; i += kMaskThreads) part += a.chunk_counts[i];
+    const int prefix = block_sum(part, s_red);
+    if (last && threadIdx.x == 0) *a.count_out = prefix + mine;
+    if (mine == 0) return;
+    const int64_t p0 = (int64_t)chunk * kChunk + (int64_t)threadIdx.x * kPxPerThread;
+    uint64_t word = 0;
+    if (p0 + kPxPerThread <= a.pixels) {
+        word = *reinterpret_cast<const uint64_t*>(a.mask + p0);
+    } else {
+        for (int i = 0; p0 + i < a.pixels; ++i) word |= (uint64_t)(a.mask[p0 + i] ? 1 : 0) << (8 * i);
+    }
+    int total;
+    int pos = prefix + block_exclusive_scan(__popcll(word), s_red, &total);
+    for (int i = 0; i < kPxPerThread; ++i)
+        if ((word >> (8 * i)) & 1) a.idx_out[pos++] = (int32_t)(p0 + i);
+}
+
+dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
+    const int64_t out_pixels = (int64_t)m.n * m.oh * m.ow;
+    if (out_pixels <= 0 || out_pixels > INT32_MAX) return fail(ctx, DCNN_ESHAPE, "mask pass: bad pixel count");
+    Workspace ws;
+    dcnn_status st = workspace_view(ctx, out_pixels, &ws);
+    if (st != DCNN_OK) return st;
+    const int nchunks = (int)cdiv(out_pixels, kChunk);
+    const uint8_t* emit_mask = m.mask_in;
+    if (!m.emit_only) {
+        MaskKernelArgs a{};
+        a.mask_in = m.mask_in; a.mask_b = m.mask_b;
+        a.mask_out = m.mask_out ? m.mask_out : ws.scratch_mask;
+        a.chunk_counts = ws.chunk_counts;
+        a.out_pixels = out_pixels;
+        a.n = m.n; a.h = m.h; a.w = m.w; a.oh = m.oh; a.ow = m.ow;
+        a.k = m.k; a.stride = m.stride; a.pad = m.pad;
+        a.up = m.up > 1 ? m.up : 1;
+        hipLaunchKernelGGL(mask_pass_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, a);
+        st = check_hip(ctx, hipGetLastError(), "mask_pass_kernel launch");
+        if (st != DCNN_OK) return st;
+        emit_mask = a.mask_out;
+    }
+    if (m.idx_out == nullptr) return DCNN_OK;
+    EmitArgs e{emit_mask, ws.chunk_counts, m.idx_out, m.count_out, out_pixels};
+    hipLaunchKernelGGL(emit_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, e);
+    return check_hip(ctx, hipGetLastError(), "emit_kernel launch");
+}
+
+// ---- list-space compaction ---------------------------------------------------------------------
+constexpr int kSubTilesPerWg = kMaskThreads / 4;              // 64 tiles (2048 entries) per workgroup
+
+__global__ __launch_bounds__(kMaskThreads) void emit_sublist_kernel(const int32_t* list, const int32_t* count,
+                                                                    const uint32_t* surv, int32_t* idx_out,
+                                                                    int32_t* count_out) {
+    __shared__ int s_red[kMaskThreads / kWave];
+    const int64_t n = *count;
+    const int64_t ntiles = (n + kTile - 1) / kTile;
+    const int64_t nwg = (ntiles + kSubTilesPerWg - 1) / kSubTilesPerWg;
+    if (n == 0) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) *count_out = 0;
+        return;
+    }
+    if ((int64_t)blockIdx.x >= nwg) return;
+    const int64_t first_tile = (int64_t)blockIdx.x * kSubTilesPerWg;
+    int part = 0;
+    for (int64_t i = threadIdx.x; i < first_tile; i += kMaskThreads) part += __popc(surv[i]);
+    const int prefix = block_sum(part, s_red);
+    const int64_t tile = first_tile + threadIdx.x / 4;
+    const int quarter = threadIdx.x % 4;
+    uint32_t bits = 0;
+    if (tile < ntiles) bits = (surv[tile] >> (8 * quarter)) & 0xffu;
+    int total;
+    int pos = prefix + block_exclusive_scan(__popc(bits), s_red, &total);
+    if ((int64_t)blockIdx.x == nwg - 1 && threadIdx.x == 0) *count_out = prefix + total;
+    const int64_t j0 = tile * kTile + 8 * quarter;
+    for (int i = 0; i < 8; ++i)
+        if ((bits >> i) & 1) idx_out[pos++] = list ? list[j0 + i] : (int32_t)(j0 + i);
+}
+
+dcnn_status launch_emit_sublist(dcnn_ctx* ctx, const int32_t* list, const int32_t* count, int64_t max_count,
+                                const uint32_t* surv, int32_t* idx_out, int32_t* count_out) {
+    const int grid = (int)cdiv(cdiv(max_count > 0 ? max_count : 1, kTile), kSubTilesPerWg);
+    hipLaunchKernelGGL(emit_sublist_kernel, dim3(grid), dim3(kMaskThreads), 0, ctx->stream, list, count, surv,
+                       idx_out, count_out);
+    return check_hip(ctx, hipGetLastError(), "emit_sublist_kernel launch");
+}
+
+}  // namespace dcnn

@@ -1,0 +1,319 @@
+// Network executor: a DAG of plain nodes is fused into layers (conv -> add -> activation chains
+// become one launch sequence), the layers' state is planned into one caller-provided arena, and
+// a frame is run by stepping the layers in topological order on the context's stream.
+#include <new>
+#include <vector>
+
+#include "layer.h"
+
+using namespace dcnn;
+
+namespace {
+
+struct Node {
+    dcnn_layer_desc d;
+    std::vector<int> in;
+    const void* w;
+    const void* b;
+    int oh, ow, oc;
+    std::vector<int> consumers;
+};
+
+struct Planned {
+    dcnn_layer_desc d;
+    std::vector<int> in_nodes;      // producer node of each sparse input
+    int out_node;                   // node whose output this layer produces
+    const void* w;
+    const void* b;
+    size_t state_off, state_bytes;
+    dcnn_layer* layer;
+};
+
+bool is_add(const dcnn_layer_desc& d) { return d.kind == DCNN_ACT && d.act == DCNN_ACT_NONE && d.n_in == 2; }
+bool is_plain_act(const dcnn_layer_desc& d) { return d.kind == DCNN_ACT && d.act != DCNN_ACT_NONE && d.n_in == 1; }
+bool is_conv(const dcnn_layer_desc& d) { return d.kind == DCNN_CONV || d.kind == DCNN_DWCONV; }
+
+}  // namespace
+
+struct dcnn_net {
+    dcnn_ctx* ctx;
+    int dtype, n, h, w, c;
+    std::vector<Node> nodes;
+    std::vector<Planned> plan;
+    std::vector<int> layer_of_node;  // plan index producing a node's output, -1 if absorbed midway
+    bool finalized = false, bound = false, inited = false;
+    size_t arena_bytes = 0;
+};
+
+extern "C" {
+
+dcnn_status dcnn_net_create(dcnn_ctx* ctx, int32_t dtype, int32_t n, int32_t h, int32_t w, int32_t c, dcnn_net** out) {
+    if (!ctx) return DCNN_EINVAL;
+    if (!out) return fail(ctx, DCNN_EINVAL, "net_create: null output");
+    *out = nullptr;
+    if (dtype != DCNN_F32 && dtype != DCNN_F16) return fail(ctx, DCNN_EDTYPE, "net_create: bad dtype %d", dtype);
+    if (n < 1 || h < 1 || w < 1 || c < 1) return fail(ctx, DCNN_ESHAPE, "net_create: bad input shape");
+    dcnn_net* net = new (std::nothrow) dcnn_net();
+    if (!net) return fail(ctx, DCNN_ENOMEM, "net_create: host allocation failed");
+    net->ctx = ctx; net->dtype = dtype; net->n = n; net->h = h; net->w = w; net->c = c;
+    *out = net;
+    return DCNN_OK;
+}
+
+void dcnn_net_destroy(dcnn_net* net) {
+    if (!net) return;
+    for (auto& p : net->plan) dcnn_layer_destroy(p.layer);
+    delete net;
+}
+
+dcnn_status dcnn_net_add(dcnn_net* net, const dcnn_layer_desc* desc, const int32_t* inputs, int32_t n_inputs,
+                         const void* weights_dev, const void* bias_dev, int32_t* node_id) {
+    if (!net) return DCNN_EINVAL;
+    dcnn_ctx* ctx = net->ctx;
+    if (!desc || !node_id) return fail(ctx, DCNN_EINVAL, "net_add: null argument");
+    if (net->finalized) return fail(ctx, DCNN_ESTATE, "net_add: the network is finalized");
+    Node nd;
+    nd.d = *desc;
+    nd.w = weights_dev; nd.b = bias_dev;
+    const int id = (int)net->nodes.size();
+    if (desc->kind == DCNN_DELTAGEN) {
+        if (id != 0 || n_inputs != 0) return fail(ctx, DCNN_EINVAL, "net_add: the input layer must be node 0 without inputs");
+        nd.d.n = net->n; nd.d.h = net->h; nd.d.w = net->w; nd.d.c = net->c; nd.d.n_in = 1;
+    } else {
+        if (id == 0) return fail(ctx, DCNN_EINVAL, "net_add: node 0 must be the input layer (DCNN_DELTAGEN)");
+        const int want = (desc->kind == DCNN_ACT) ? desc->n_in : 1;
+        if (n_inputs != want || !inputs) return fail(ctx, DCNN_EINVAL, "net_add: node %d expects %d inputs, got %d", id, want, n_inputs);
+        if (is_conv(*desc) && (desc->act != DCNN_ACT_NONE || desc->n_in != 1))
+            return fail(ctx, DCNN_EINVAL, "net_add: add convolutions unfused (act NONE, one input); finalize fuses");
+        for (int i = 0; i < n_inputs; ++i) {
+            if (inputs[i] < 0 || inputs[i] >= id) return fail(ctx, DCNN_EINVAL, "net_add: node %d input %d out of range", id, inputs[i]);
+            if (net->nodes[inputs[i]].d.kind == DCNN_ACCUM) return fail(ctx, DCNN_EINVAL, "net_add: the output layer has no consumers");
+            nd.in.push_back(inputs[i]);
+        }
+        const Node& p0 = net->nodes[inputs[0]];
+        nd.d.n = net->n; nd.d.h = p0.oh; nd.d.w = p0.ow; nd.d.c = p0.oc;
+        if (n_inputs == 2) {
+            const Node& p1 = net->nodes[inputs[1]];
+            if (p1.oh != p0.oh || p1.ow != p0.ow || p1.oc != p0.oc)
+                return fail(ctx, DCNN_ESHAPE, "net_add: node %d adds [%d,%d,%d] and [%d,%d,%d]", id, p0.oh, p0.ow, p0.oc, p1.oh, p1.ow, p1.oc);
+        }
+        if (desc->kind == DCNN_DWCONV) nd.d.cout = nd.d.c;
+    }
+    nd.d.dtype = net->dtype;
+    nd.d.kw = nd.d.kh;
+    nd.d.want_idx = 1;
+    dcnn_layer_sizes sz;
+    dcnn_status st = dcnn_layer_query(&nd.d, &sz);
+    if (st != DCNN_OK) return fail(ctx, st, "net_add: node %d has an invalid descriptor", id);
+    nd.oh = sz.oh; nd.ow = sz.ow; nd.oc = sz.oc;
+    if (is_conv(nd.d) && !weights_dev) return fail(ctx, DCNN_EINVAL, "net_add: convolution node %d without weights", id);
+    for (int i : nd.in) net->nodes[i].consumers.push_back(id);
+    net->nodes.push_back(nd);
+    *node_id = id;
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t fuse, size_t* arena_bytes) {
+    if (!net) return DCNN_EINVAL;
+    dcnn_ctx* ctx = net->ctx;
+    if (!arena_bytes) return fail(ctx, DCNN_EINVAL, "net_finalize: null argument");
+    if (net->finalized) return fail(ctx, DCNN_ESTATE, "net_finalize: already finalized");
+    const int N = (int)net->nodes.size();
+    if (N < 2 || net->nodes[N - 1].d.kind != DCNN_ACCUM)
+        return fail(ctx, DCNN_EINVAL, "net_finalize: the last node must be the output layer (DCNN_ACCUM)");
+    for (int i = 0; i < N - 1; ++i)
+        if (net->nodes[i].d.kind == DCNN_ACCUM) return fail(ctx, DCNN_EINVAL, "net_finalize: only the last node may be DCNN_ACCUM");
+
+    std::vector<char> absorbed(N, 0);
+    net->layer_of_node.assign(N, -1);
+    auto sole_consumer = [&](int i) { return net->nodes[i].consumers.size() == 1 ? net->nodes[i].consumers[0] : -1; };
+    char why[256];
+    for (int i = 0; i < N; ++i) {
+        if (absorbed[i]) continue;
+        const Node& nd = net->nodes[i];
+        Planned p{};
+        p.d = nd.d; p.in_nodes = nd.in; p.out_node = i; p.w = nd.w; p.b = nd.b; p.layer = nullptr;
+        if ((fuse & 1) && is_conv(nd.d)) {
+            int cur = i;
+            dcnn_layer_desc d = nd.d;
+            std::vector<int> ins = nd.in, taken;
+            int j = sole_consumer(cur);
+            if (j >= 0 && !absorbed[j] && is_add(net->nodes[j].d)) {
+                const Node& add = net->nodes[j];
+                const int other = add.in[0] == cur ? add.in[1] : add.in[0];
+                if (other != cur) {
+                    d.n_in = 2;
+                    ins.push_back(other);
+                    taken.push_back(j);
+                    cur = j;
+                }
+            }
+            int k = sole_consumer(cur);
+            if (k >= 0 && !absorbed[k] && is_plain_act(net->nodes[k].d)) {
+                d.act = net->nodes[k].d.act;
+                d.eps = net->nodes[k].d.eps;
+                taken.push_back(k);
+                cur = k;
+            }
+            if (cur != i && conv_supported(ctx, d.dtype, d.kh, d.c, nd.oc, d.kind == DCNN_DWCONV, true, why, sizeof(why))) {
+                for (int a : taken) absorbed[a] = 1;
+                p.d = d; p.in_nodes = ins; p.out_node = cur;
+            }
+        } else if ((fuse & 1) && is_add(nd.d)) {
+            int k = sole_consumer(i);
+            if (k >= 0 && !absorbed[k] && is_plain_act(net->nodes[k].d)) {
+                p.d.act = net->nodes[k].d.act;
+                p.d.eps = net->nodes[k].d.eps;
+                p.out_node = k;
+                absorbed[k] = 1;
+            }
+        }
+        net->plan.push_back(p);
+    }
+    // run layers in the order of the node whose output they produce (inputs always come earlier)
+    for (size_t a = 1; a < net->plan.size(); ++a)
+        for (size_t b = a; b > 0 && net->plan[b].out_node < net->plan[b - 1].out_node; --b) std::swap(net->plan[b], net->plan[b - 1]);
+    for (size_t a = 0; a < net->plan.size(); ++a) net->layer_of_node[net->plan[a].out_node] = (int)a;
+    // every sparse input must be the output of a planned layer
+    for (auto& p : net->plan)
+        for (int in : p.in_nodes)
+            if (net->layer_of_node[in] < 0) return fail(ctx, DCNN_EINVAL, "net_finalize: internal: node %d was fused away but is still consumed", in);
+    // which outputs need an index list: consumers that walk their input's list as it is
+    for (auto& p : net->plan) p.d.want_idx = (fuse & 2) ? 1 : 0;
+    for (auto& p : net->plan) {
+        if (p.in_nodes.empty()) continue;
+        const dcnn_layer_desc& d = p.d;
+        const bool walks_input_list = d.kind == DCNN_ACCUM || d.kind == DCNN_MAXPOOL ||
+                                      (is_conv(d) && d.kh == 1 && d.stride == 1 && d.n_in == 1) ||
+                                      (d.kind == DCNN_ACT && d.n_in == 1);
+        if (walks_input_list) net->plan[net->layer_of_node[p.in_nodes[0]]].d.want_idx = 1;
+    }
+    size_t off = 0;
+    for (auto& p : net->plan) {
+        dcnn_layer_sizes sz;
+        dcnn_status st = dcnn_layer_query(&p.d, &sz);
+        if (st != DCNN_OK) return fail(ctx, st, "net_finalize: layer for node %d is invalid", p.out_node);
+        p.state_off = off;
+        p.state_bytes = sz.state_bytes;
+        off += align_up(sz.state_bytes);
+    }
+    net->arena_bytes = off;
+    net->finalized = true;
+    *arena_bytes = off;
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_net_bind(dcnn_net* net, void* arena_dev, size_t arena_bytes) {
+    if (!net) return DCNN_EINVAL;
+    dcnn_ctx* ctx = net->ctx;
+    if (!net->finalized) return fail(ctx, DCNN_ESTATE, "net_bind: finalize first");
+    if (net->bound) return fail(ctx, DCNN_ESTATE, "net_bind: already bound");
+    if (!arena_dev || (reinterpret_cast<uintptr_t>(arena_dev) % kAlign) != 0)
+        return fail(ctx, DCNN_EINVAL, "net_bind: arena missing or not 256-byte aligned");
+    if (arena_bytes < net->arena_bytes) return fail(ctx, DCNN_ENOMEM, "net_bind: arena of %zu bytes, need %zu", arena_bytes, net->arena_bytes);
+    for (auto& p : net->plan) {
+        dcnn_status st = dcnn_layer_create(ctx, &p.d, p.w, p.b, static_cast<char*>(arena_dev) + p.state_off, p.state_bytes, &p.layer);
+        if (st != DCNN_OK) {
+            for (auto& q : net->plan) { dcnn_layer_destroy(q.layer); q.layer = nullptr; }
+            return st;
+        }
+    }
+    net->bound = true;
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_net_init(dcnn_net* net, const void* frame_dev, void* out_dev) {
+    if (!net) return DCNN_EINVAL;
+    dcnn_ctx* ctx = net->ctx;
+    if (!net->bound) return fail(ctx, DCNN_ESTATE, "net_init: bind an arena first");
+    if (!frame_dev) return fail(ctx, DCNN_EINVAL, "net_init: null frame");
+    // during the dense first frame every layer writes its dense output into its own (dense-shaped)
+    // delta buffer, which the consumers read; afterwards those buffers hold sparse updates again
+    for (auto& p : net->plan) {
+        const void* ins[2] = {nullptr, nullptr};
+        int n_in = 0;
+        if (p.d.kind == DCNN_DELTAGEN) {
+            ins[0] = frame_dev; n_in = 1;
+        } else {
+            for (int in : p.in_nodes) ins[n_in++] = net->plan[net->layer_of_node[in]].layer->out_data;
+        }
+        void* dense_out = p.d.kind == DCNN_ACCUM ? out_dev : p.layer->out_data;
+        dcnn_status st = dcnn_layer_init(p.layer, ins, n_in, dense_out);
+        if (st != DCNN_OK) return st;
+    }
+    net->inited = true;
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_net_step(dcnn_net* net, const void* frame_dev, void* out_dev) {
+    if (!net) return DCNN_EINVAL;
+    dcnn_ctx* ctx = net->ctx;
+    if (!net->bound) return fail(ctx, DCNN_ESTATE, "net_step: bind an arena first");
+    if (!net->inited) return fail(ctx, DCNN_ESTATE, "net_step: no first frame yet (call net_init)");
+    if (!frame_dev) return fail(ctx, DCNN_EINVAL, "net_step: null frame");
+    for (auto& p : net->plan) {
+        dcnn_delta views[2];
+        const dcnn_delta* ins[2] = {nullptr, nullptr};
+        int n_in = 0;
+        if (p.d.kind == DCNN_DELTAGEN) {
+            views[0] = dcnn_delta{};
+            views[0].data = const_cast<void*>(frame_dev);
+            views[0].n = net->n; views[0].h = net->h; views[0].w = net->w; views[0].c = net->c; views[0].dtype = net->dtype;
+            ins[0] = &views[0]; n_in = 1;
+        } else {
+            for (int in : p.in_nodes) {
+                dcnn_status st = dcnn_layer_output(net->plan[net->layer_of_node[in]].layer, &views[n_in]);
+                if (st != DCNN_OK) return st;
+                ins[n_in] = &views[n_in];
+                ++n_in;
+            }
+        }
+        dcnn_status st = dcnn_layer_step(p.layer, ins, n_in);
+        if (st != DCNN_OK) return st;
+    }
+    if (out_dev) {
+        dcnn_layer* last = net->plan.back().layer;
+        return launch_copy(ctx, out_dev, last->buf0, last->buf0_bytes);
+    }
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_net_reset(dcnn_net* net) {
+    if (!net) return DCNN_EINVAL;
+    if (!net->bound) return fail(net->ctx, DCNN_ESTATE, "net_reset: bind an arena first");
+    for (auto& p : net->plan) {
+        dcnn_status st = dcnn_layer_reset(p.layer);
+        if (st != DCNN_OK) return st;
+    }
+    net->inited = false;
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_net_output(const dcnn_net* net, dcnn_delta* out_view) {
+    if (!net || !out_view) return DCNN_EINVAL;
+    if (!net->bound) return fail(net->ctx, DCNN_ESTATE, "net_output: bind an arena first");
+    return dcnn_layer_output(net->plan.back().layer, out_view);
+}
+
+int32_t dcnn_net_num_layers(const dcnn_net* net) { return net && net->finalized ? (int32_t)net->plan.size() : 0; }
+
+dcnn_status dcnn_net_layer(const dcnn_net* net, int32_t i, dcnn_layer** layer, int32_t* node_id) {
+    if (!net || !layer || !node_id) return DCNN_EINVAL;
+    if (!net->bound) return fail(net->ctx, DCNN_ESTATE, "net_layer: bind an arena first");
+    if (i < 0 || i >= (int32_t)net->plan.size()) return fail(net->ctx, DCNN_EINVAL, "net_layer: index %d out of range", i);
+    *layer = net->plan[i].layer;
+    *node_id = net->plan[i].out_node;
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_net_stats(dcnn_net* net, dcnn_stats* stats_host) {
+    if (!net || !stats_host) return DCNN_EINVAL;
+    if (!net->bound) return fail(net->ctx, DCNN_ESTATE, "net_stats: bind an arena first");
+    for (size_t i = 0; i < net->plan.size(); ++i) {
+        dcnn_status st = dcnn_layer_stats(net->plan[i].layer, &stats_host[i]);
+        if (st != DCNN_OK) return st;
+    }
+    return DCNN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,433 @@
+// Memory-bound kernels of the sparse path: input delta generation, activation + truncation
+// (optionally of a sum of two streams), depthwise convolution, max pooling, upsampling and the
+// final accumulation.  All of them walk a compacted work list of flagged pixels; LP lanes share
+// one pixel so every access is a coalesced 16-byte vector of channels (NHWC).
+#include "device_utils.h"
+
+namespace dcnn {
+
+constexpr int kTileWaves = 4;                       // waves (tiles) per workgroup
+constexpr int kTileThreads = kTileWaves * kWave;
+
+static int list_grid(const dcnn_ctx* ctx, int64_t max_count, int entries_per_wg, int wg_per_cu) {
+    int64_t want = cdiv(max_count > 0 ? max_count : 1, entries_per_wg);
+    int64_t cap = (int64_t)ctx->num_cu * wg_per_cu;
+    int64_t g = want < cap ? want : cap;
+    return (int)(cdiv(g, kXcd) * kXcd);
+}
+
+// ---- activation + truncation (+ add) ----------------------------------------------------------
+template <typename T, int V, int VPL>
+__global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a, EpilogueArgs e, int init) {
+    const int64_t count = list_count(l);
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int C = e.c;
+    const T* in = static_cast<const T*>(a.in_data);
+    const uint8_t* in_mask = a.in_mask;
+    auto dx = [&](int, int64_t p, int c0, float (&o)[V]) {
+        if (in_mask == nullptr || in_mask[p] != 0) load_vec<T, V>(in + p * C + c0, o);
+    };
+    const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
+    for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
+        const int64_t tile = wt * kTileWaves + wave;
+        const int64_t base = tile * kTile;
+        if (base >= count) continue;
+        const uint32_t bits = act_trunc_tile<T, V, VPL>(e, init != 0, l.list, base, count, lane, dx);
+        if (e.surv && lane == 0) e.surv[tile] = bits;
+    }
+}
+
+template <typename T>
+static dcnn_status launch_act_t(dcnn_ctx* ctx, bool init, const ListArgs& l, const ActArgs& a, const EpilogueArgs& e) {
+    constexpr int VEC = Elem<T>::VEC;
+    const bool vec = (e.c % VEC) == 0;
+    const int nvec = vec ? e.c / VEC : e.c;
+    const int vpl = (int)cdiv(nvec, kWave);
+    const int grid = list_grid(ctx, l.max_count, kTileWaves * kTile, 8);
+    dim3 g(grid), b(kTileThreads);
+    const int ini = init ? 1 : 0;
+#define DCNN_ACT_LAUNCH(V, VPL) hipLaunchKernelGGL((act_kernel<T, V, VPL>), g, b, 0, ctx->stream, l, a, e, ini)
+    if (vec) {
+        if (vpl <= 1) DCNN_ACT_LAUNCH(VEC, 1);
+        else if (vpl <= 2) DCNN_ACT_LAUNCH(VEC, 2);
+        else if (vpl <= 4) DCNN_ACT_LAUNCH(VEC, 4);
+        else if (vpl <= 8 && sizeof(T) == 4) DCNN_ACT_LAUNCH(VEC, 8);
+        else return fail(ctx, DCNN_EUNSUPPORTED, "activation: %d channels exceed the supported 8 KB per pixel", e.c);
+    } else {
+        if (vpl <= 1) DCNN_ACT_LAUNCH(1, 1);
+        else if (vpl <= 2) DCNN_ACT_LAUNCH(1, 2);
+        else if (vpl <= 4) DCNN_ACT_LAUNCH(1, 4);
+        else return fail(ctx, DCNN_EUNSUPPORTED, "activation: %d unaligned channels exceed 256 per pixel", e.c);
+    }
+#undef DCNN_ACT_LAUNCH
+    return check_hip(ctx, hipGetLastError(), "act_kernel launch");
+}
+
+dcnn_status launch_act(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const ActArgs& a, const EpilogueArgs& e) {
+    return dtype == DCNN_F16 ? launch_act_t<f16>(ctx, init, l, a, e) : launch_act_t<float>(ctx, init, l, a, e);
+}
+
+// ---- depthwise convolution: the first delta stream is formed on the fly ------------------------
+// Work list = flagged OUTPUT pixels.  Every tap's update flag is checked before its values are
+// read (unflagged memory is invalid), load and multiply are fused per pixel.
+template <typename T, int V, int VPL>
+__global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init) {
+    const int64_t count = list_count(l);
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int C = e.c;
+    const T* in = static_cast<const T*>(c.in_data);
+    const T* wgt = static_cast<const T*>(c.wpacked);           // [k][k][C], unpacked
+    auto dx = [&](int, int64_t p, int c0, float (&o)[V]) {
+        const int ox = (int)(p % c.ow);
+        const int64_t t = p / c.ow;
+        const int oy = (int)(t % c.oh);
+        const int64_t n = t / c.oh;
+        float acc[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+        for (int ky = 0; ky < c.k; ++ky) {
+            const int iy = oy * c.stride - c.pad + ky;
+            if (iy < 0 || iy >= c.h) continue;
+            for (int kx = 0; kx < c.k; ++kx) {
+                const int ix = ox * c.stride - c.pad + kx;
+                if (ix < 0 || ix >= c.w) continue;
+                const int64_t q = (n * c.h + iy) * c.w + ix;
+                if (c.in_mask && c.in_mask[q] == 0) continue;
+                float xv[V], wv[V];
+                load_vec<T, V>(in + q * C + c0, xv);
+                load_vec<T, V>(wgt + (int64_t)(ky * c.k + kx) * C + c0, wv);
+#pragma unroll
+                for (int i = 0; i < V; ++i) acc[i] = fmaf(xv[i], wv[i], acc[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < V; ++i) o[i] = round_store<T>(acc[i]);
+    };
+    const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
+    for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
+        const int64_t tile = wt * kTileWaves + wave;
+        const int64_t base = tile * kTile;
+        if (base >= count) continue;
+        const uint32_t bits = act_trunc_tile<T, V, VPL>(e, init != 0, l.list, base, count, lane, dx);
+        if (e.surv && lane == 0) e.surv[tile] = bits;
+    }
+}
+
+template <typename T>
+static dcnn_status launch_dwconv_t(dcnn_ctx* ctx, bool init, const ListArgs& l, const ConvArgs& c, const EpilogueArgs& e) {
+    constexpr int VEC = Elem<T>::VEC;
+    const bool vec = (e.c % VEC) == 0;
+    const int nvec = vec ? e.c / VEC : e.c;
+    const int vpl = (int)cdiv(nvec, kWave);
+    const int grid = list_grid(ctx, l.max_count, kTileWaves * kTile, 8);
+    dim3 g(grid), b(kTileThreads);
+    const int ini = init ? 1 : 0;
+#define DCNN_DW_LAUNCH(V, VPL) hipLaunchKernelGGL((dwconv_kernel<T, V, VPL>), g, b, 0, ctx->stream, l, c, e, ini)
+    if (vec) {
+        if (vpl <= 1) DCNN_DW_LAUNCH(VEC, 1);
+        else if (vpl <= 2) DCNN_DW_LAUNCH(VEC, 2);
+        else if (vpl <= 4) DCNN_DW_LAUNCH(VEC, 4);
+        else return fail(ctx, DCNN_EUNSUPPORTED, "depthwise conv: %d channels not supported", e.c);
+    } else {
+        if (vpl <= 1) DCNN_DW_LAUNCH(1, 1);
+        else if (vpl <= 2) DCNN_DW_LAUNCH(1, 2);
+        else if (vpl <= 4) DCNN_DW_LAUNCH(1, 4);
+        else return fail(ctx, DCNN_EUNSUPPORTED, "depthwise conv: %d channels not supported", e.c);
+    }
+#undef DCNN_DW_LAUNCH
+    return check_hip(ctx, hipGetLastError(), "dwconv_kernel launch");
+}
+
+dcnn_status launch_dwconv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const ConvArgs& c,
+                          const EpilogueArgs& e) {
+    return dtype == DCNN_F16 ? launch_dwconv_t<f16>(ctx, init, l, c, e) : launch_dwconv_t<float>(ctx, init, l, c, e);
+}
+
+// ---- input delta generation (dense pass over the frame) ---------------------------------------
+// Per pixel: d = frame - P (P = value last propagated); flagged iff max_c |d_c| >= eps;
+// flagged: delta <- d, P <- frame.  Writes the whole mask and one count per chunk of pixels.
+template <typename T, int V, int VPL>
+__global__ __launch_bounds__(256) void deltagen_kernel(DeltaGenArgs a, int32_t* chunk_counts) {
+    __shared__ int s_count;
+    if (threadIdx.x == 0) s_count = 0;
+    __syncthreads();
+    const int C = a.c;
+    const int nvec = (C + V - 1) / V;
+    int LP = pow2_ceil((nvec + VPL - 1) / VPL);
+    LP = LP > kWave ? kWave : LP;
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int sub = lane % LP, grp = lane / LP, PPI = kWave / LP;
+    const T* frame = static_cast<const T*>(a.frame);
+    T* P = static_cast<T*>(a.P);
+    T* out = static_cast<T*>(a.out_data);
+    const int64_t chunk_begin = (int64_t)blockIdx.x * kChunk;
+    const int64_t chunk_end = min(chunk_begin + kChunk, a.pixels);
+    int mine = 0;
+    for (int64_t p0 = chunk_begin + (int64_t)wave * PPI; p0 < chunk_end; p0 += 4 * PPI) {
+        const int64_t p = p0 + grp;
+        const bool valid = p < chunk_end;
+        float f[VPL][V], d[VPL][V];
+        float u = 0.0f;
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+            const int vi = sub + v * LP;
+            if (valid && vi < nvec) {
+                float q[V];
+                load_vec<T, V>(frame + p * C + vi * V, f[v]);
+                load_vec<T, V>(P + p * C + vi * V, q);
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    d[v][i] = f[v][i] - q[i];
+                    u = fmaxf(u, fabsf(d[v][i]));
+                }
+            }
+        }
+        for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
+        const bool flag = valid && (u >= a.eps);
+        if (flag) {
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) {
+                const int vi = sub + v * LP;
+                if (vi < nvec) {
+                    store_vec<T, V>(out + p * C + vi * V, d[v]);
+                    store_vec<T, V>(P + p * C + vi * V, f[v]);
+                }
+            }
+        }
+        if (valid && sub == 0) {
+            a.out_mask[p] = flag ? 1 : 0;
+            mine += flag ? 1 : 0;
+        }
+    }
+    if (mine) atomicAdd(&s_count, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) chunk_counts[blockIdx.x] = s_count;
+}
+
+// ---- final accumulation, max pooling, upsampling ----------------------------------------------
+template <typename T, int V>
+__global__ __launch_bounds__(256) void accum_kernel(ListArgs l, AccumArgs a) {
+    const int64_t count = list_count(l);
+    const int C = a.c;
+    const int nvec = (C + V - 1) / V;
+    const T* in = static_cast<const T*>(a.in_data);
+    T* O = static_cast<T*>(a.O);
+    const int64_t total = count * nvec;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t j = i / nvec;
+        const int vi = (int)(i - j * nvec);
+        const int64_t p = l.list ? (int64_t)l.list[j] : j;
+        float d[V], o[V];
+        load_vec<T, V>(in + p * C + vi * V, d);
+        load_vec<T, V>(O + p * C + vi * V, o);
+#pragma unroll
+        for (int k = 0; k < V; ++k) o[k] = o[k] + d[k];
+        store_vec<T, V>(O + p * C + vi * V, o);
+    }
+}
+
+// Pooling output pass over the flagged OUTPUT pixels: dy = max_w(x^A (+ delta at flagged inputs)) - max_w(x^A).
+// x^A itself is brought up to date by the commit pass afterwards.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void maxpool_out_kernel(ListArgs l, PoolArgs a, int init) {
+    const int64_t count = list_count(l);
+    const int C = a.c;
+    const int nvec = (C + V - 1) / V;
+    const T* in = static_cast<const T*>(a.in_data);
+    const T* xA = static_cast<const T*>(a.xA);
+    T* out = static_cast<T*>(a.out_data);
+    const int64_t total = count * nvec;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t j = i / nvec;
+        const int vi = (int)(i - j * nvec);
+        const int64_t p = l.list ? (int64_t)l.list[j] : j;
+        const int ox = (int)(p % a.ow);
+        const int64_t t = p / a.ow;
+        const int oy = (int)(t % a.oh);
+        const int64_t n = t / a.oh;
+        float mo[V], mn[V];
+#pragma unroll
+        for (int k = 0; k < V; ++k) { mo[k] = -INFINITY; mn[k] = -INFINITY; }
+        for (int ky = 0; ky < a.k; ++ky) {
+            const int iy = oy * a.stride - a.pad + ky;
+            if (iy < 0 || iy >= a.h) continue;
+            for (int kx = 0; kx < a.k; ++kx) {
+                const int ix = ox * a.stride - a.pad + kx;
+                if (ix < 0 || ix >= a.w) continue;
+                const int64_t q = (n * a.h + iy) * a.w + ix;
+                float x[V];
+                load_vec<T, V>(xA + q * C + vi * V, x);
+#pragma unroll
+                for (int k = 0; k < V; ++k) mo[k] = fmaxf(mo[k], x[k]);
+                if (!init && a.in_mask[q] != 0) {
+                    float d[V];
+                    load_vec<T, V>(in + q * C + vi * V, d);
+#pragma unroll
+                    for (int k = 0; k < V; ++k) x[k] = round_store<T>(x[k] + d[k]);
+                }
+#pragma unroll
+                for (int k = 0; k < V; ++k) mn[k] = fmaxf(mn[k], x[k]);
+            }
+        }
+        float r[V];
+#pragma unroll
+        for (int k = 0; k < V; ++k) r[k] = init ? mo[k] : mn[k] - mo[k];
+        store_vec<T, V>(out + p * C + vi * V, r);
+    }
+}
+
+template <typename T, int V>
+__global__ __launch_bounds__(256) void maxpool_commit_kernel(ListArgs l, PoolArgs a) {
+    const int64_t count = list_count(l);
+    const int C = a.c;
+    const int nvec = (C + V - 1) / V;
+    const T* in = static_cast<const T*>(a.in_data);
+    T* xA = static_cast<T*>(a.xA);
+    const int64_t total = count * nvec;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t j = i / nvec;
+        const int vi = (int)(i - j * nvec);
+        const int64_t p = l.list ? (int64_t)l.list[j] : j;
+        float d[V], x[V];
+        load_vec<T, V>(in + p * C + vi * V, d);
+        load_vec<T, V>(xA + p * C + vi * V, x);
+#pragma unroll
+        for (int k = 0; k < V; ++k) x[k] = x[k] + d[k];
+        store_vec<T, V>(xA + p * C + vi * V, x);
+    }
+}
+
+template <typename T, int V>
+__global__ __launch_bounds__(256) void upsample_kernel(ListArgs l, UpsampleArgs a) {
+    const int64_t count = list_count(l);
+    const int C = a.c;
+    const int nvec = (C + V - 1) / V;
+    const T* in = static_cast<const T*>(a.in_data);
+    T* out = static_cast<T*>(a.out_data);
+    const int ow = a.w * a.factor, oh = a.h * a.factor;
+    const int64_t total = count * nvec;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t j = i / nvec;
+        const int vi = (int)(i - j * nvec);
+        const int64_t p = l.list ? (int64_t)l.list[j] : j;
+        const int ox = (int)(p % ow);
+        const int64_t t = p / ow;
+        const int oy = (int)(t % oh);
+        const int64_t n = t / oh;
+        const int64_t q = (n * a.h + oy / a.factor) * a.w + ox / a.factor;
+        float x[V];
+        load_vec<T, V>(in + q * C + vi * V, x);
+        store_vec<T, V>(out + p * C + vi * V, x);
+    }
+}
+
+static int flat_grid(const dcnn_ctx* ctx, int64_t max_count, int c, int vec) {
+    int64_t total = (max_count > 0 ? max_count : 1) * cdiv(c, vec);
+    int64_t want = cdiv(total, 256);
+    int64_t cap = (int64_t)ctx->num_cu * 8;
+    return (int)(want < cap ? want : cap);
+}
+
+#define DCNN_FLAT_DISPATCH(KERNEL, CHANNELS, MAXCOUNT, ...)                                               \
+    do {                                                                                                  \
+        if (dtype == DCNN_F16) {                                                                          \
+            if ((CHANNELS) % 8 == 0)                                                                      \
+                hipLaunchKernelGGL((KERNEL<f16, 8>), dim3(flat_grid(ctx, MAXCOUNT, CHANNELS, 8)), dim3(256), 0, \
+                                   ctx->stream, __VA_ARGS__);                                             \
+            else                                                                                          \
+                hipLaunchKernelGGL((KERNEL<f16, 1>), dim3(flat_grid(ctx, MAXCOUNT, CHANNELS, 1)), dim3(256), 0, \
+                                   ctx->stream, __VA_ARGS__);                                             \
+        } else {                                                                                          \
+            if ((CHANNELS) % 4 == 0)                                                                      \
+                hipLaunchKernelGGL((KERNEL<float, 4>), dim3(flat_grid(ctx, MAXCOUNT, CHANNELS, 4)), dim3(256), 0, \
+                                   ctx->stream, __VA_ARGS__);                                             \
+            else                                                                                          \
+                hipLaunchKernelGGL((KERNEL<float, 1>), dim3(flat_grid(ctx, MAXCOUNT, CHANNELS, 1)), dim3(256), 0, \
+                                   ctx->stream, __VA_ARGS__);                                             \
+        }                                                                                                 \
+    } while (0)
+
+dcnn_status launch_accum(dcnn_ctx* ctx, int dtype, const ListArgs& l, const AccumArgs& a) {
+    DCNN_FLAT_DISPATCH(accum_kernel, a.c, l.max_count, l, a);
+    return check_hip(ctx, hipGetLastError(), "accum_kernel launch");
+}
+
+dcnn_status launch_maxpool_out(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const PoolArgs& a) {
+    const int ini = init ? 1 : 0;
+    DCNN_FLAT_DISPATCH(maxpool_out_kernel, a.c, l.max_count, l, a, ini);
+    return check_hip(ctx, hipGetLastError(), "maxpool_out_kernel launch");
+}
+
+dcnn_status launch_maxpool_commit(dcnn_ctx* ctx, int dtype, const ListArgs& l, const PoolArgs& a) {
+    DCNN_FLAT_DISPATCH(maxpool_commit_kernel, a.c, l.max_count, l, a);
+    return check_hip(ctx, hipGetLastError(), "maxpool_commit_kernel launch");
+}
+
+dcnn_status launch_upsample(dcnn_ctx* ctx, int dtype, const ListArgs& l, const UpsampleArgs& a) {
+    DCNN_FLAT_DISPATCH(upsample_kernel, a.c, l.max_count, l, a);
+    return check_hip(ctx, hipGetLastError(), "upsample_kernel launch");
+}
+
+dcnn_status launch_deltagen(dcnn_ctx* ctx, int dtype, const DeltaGenArgs& a) {
+    if (a.dilate_r != 0) return fail(ctx, DCNN_EUNSUPPORTED, "input-mask dilation is not implemented");
+    Workspace ws;
+    dcnn_status st = workspace_view(ctx, a.pixels, &ws);
+    if (st != DCNN_OK) return st;
+    const int nchunks = (int)cdiv(a.pixels, kChunk);
+    dim3 g(nchunks), b(256);
+#define DCNN_DG_LAUNCH(T, V, VPL) hipLaunchKernelGGL((deltagen_kernel<T, V, VPL>), g, b, 0, ctx->stream, a, ws.chunk_counts)
+#define DCNN_DG_PICK(T, V)                                                                       \
+    do {                                                                                         \
+        const int64_t vpl = cdiv(cdiv(a.c, V), kWave);                                           \
+        if (vpl <= 1) DCNN_DG_LAUNCH(T, V, 1);                                                   \
+        else if (vpl <= 2) DCNN_DG_LAUNCH(T, V, 2);                                              \
+        else if (vpl <= 4) DCNN_DG_LAUNCH(T, V, 4);                                              \
+        else return fail(ctx, DCNN_EUNSUPPORTED, "delta generation: %d channels not supported", a.c); \
+    } while (0)
+    if (dtype == DCNN_F16) {
+        if (a.c % 8 == 0) DCNN_DG_PICK(f16, 8); else DCNN_DG_PICK(f16, 1);
+    } else {
+        if (a.c % 4 == 0) DCNN_DG_PICK(float, 4); else DCNN_DG_PICK(float, 1);
+    }
+#undef DCNN_DG_PICK
+#undef DCNN_DG_LAUNCH
+    st = check_hip(ctx, hipGetLastError(), "deltagen_kernel launch");
+    if (st != DCNN_OK) return st;
+    // ordered emission of the flagged pixels from the mask just written and the chunk counts
+    MaskPassArgs m{};
+    m.mask_in = a.out_mask;
+    m.mask_out = nullptr;
+    m.idx_out = a.out_idx;
+    m.count_out = a.out_count;
+    m.n = a.n; m.h = a.h; m.w = a.w; m.oh = a.h; m.ow = a.w; m.k = 1;
+    m.stride = 1; m.pad = 0; m.up = 1; m.emit_only = 1;
+    return launch_mask_compact(ctx, m);
+}
+
+// ---- small utilities ------------------------------------------------------------------------
+template <typename T> __global__ void fill_kernel(T* p, T v, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+dcnn_status launch_fill_i32(dcnn_ctx* ctx, int32_t* p, int32_t v, int64_t n) {
+    int grid = (int)(cdiv(n, 256) < 2048 ? cdiv(n, 256) : 2048);
+    hipLaunchKernelGGL((fill_kernel<int32_t>), dim3(grid > 0 ? grid : 1), dim3(256), 0, ctx->stream, p, v, n);
+    return check_hip(ctx, hipGetLastError(), "fill_kernel launch");
+}
+
+dcnn_status launch_fill_u8(dcnn_ctx* ctx, uint8_t* p, uint8_t v, int64_t n) {
+    // fill 4 bytes at a time where the length allows (buffers are 256-byte aligned)
+    if (n % 4 == 0) {
+        const int32_t w = (int32_t)(0x01010101u * v);
+        return launch_fill_i32(ctx, reinterpret_cast<int32_t*>(p), w, n / 4);
+    }
+    int grid = (int)(cdiv(n, 256) < 2048 ? cdiv(n, 256) : 2048);
+    hipLaunchKernelGGL((fill_kernel<uint8_t>), dim3(grid > 0 ? grid : 1), dim3(256), 0, ctx->stream, p, v, n);
+    return check_hip(ctx, hipGetLastError(), "fill_kernel launch");
+}
+
+dcnn_status launch_copy(dcnn_ctx* ctx, void* dst, const void* src, size_t bytes) {
+    return check_hip(ctx, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, ctx->stream), "hipMemcpyAsync");
+}
+
+}  // namespace dcnn

@@ -1,0 +1,58 @@
+"""Shared helpers of the GPU parity tests."""
+import numpy as np
+import torch
+
+NP_DTYPE = {"f32": np.float32, "f16": np.float16}
+# acceptance tolerances on values (max relative error, see rel_err)
+TOL = {"f32": 1e-4, "f16": 2e-2}
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max |got - ref| / max(|ref|, 1e-3 * max|ref|) over the given elements."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    if ref.size == 0:
+        return 0.0
+    scale = np.abs(ref).max()
+    if scale == 0:
+        return float(np.abs(got).max())
+    den = np.maximum(np.abs(ref), 1e-3 * scale)
+    return float((np.abs(got - ref) / den).max())
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().numpy()
+
+
+def poison(shape, dtype, device="cuda"):
+    """A device buffer full of NaN: whatever the library reads from unflagged pixels shows up."""
+    return torch.full(shape, float("nan"), dtype=dtype, device=device)
+
+
+def check_delta(out, ref, S, what, exact_values=False, allow_mask_diff=None):
+    """Compare a library Delta (torch views) with an oracle Delta.
+    Returns the number of tolerated mask mismatches (threshold ties)."""
+    g_mask = to_np(out.mask)
+    r_mask = ref.mask
+    diff = g_mask != r_mask
+    n_diff = int(diff.sum())
+    if n_diff:
+        assert allow_mask_diff is not None, f"{what}: {n_diff} mask mismatches"
+        assert np.all(allow_mask_diff[diff]), f"{what}: mask mismatch away from a threshold tie"
+    if out.count is not None and out.idx is not None:
+        cnt = int(to_np(out.count)[0])
+        idx = to_np(out.idx)[:cnt]
+        assert cnt == int(g_mask.sum()), f"{what}: count {cnt} vs mask {int(g_mask.sum())}"
+        assert np.array_equal(idx, np.flatnonzero(g_mask.reshape(-1))), f"{what}: index list is not the ordered compaction"
+        if n_diff == 0:
+            assert np.array_equal(idx, ref.idx), f"{what}: index list differs from the oracle"
+    both = (g_mask == 1) & (r_mask == 1)
+    g = to_np(out.data)[both]
+    r = ref.data[both]
+    assert not np.isnan(g.astype(np.float64)).any(), f"{what}: NaN in a flagged output (an unflagged value was read)"
+    if exact_values:
+        assert np.array_equal(g, r), f"{what}: values differ (max abs {np.abs(g.astype(np.float64) - r).max()})"
+    else:
+        e = rel_err(g, r)
+        assert e <= TOL[S], f"{what}: max relative error {e:.3e} > {TOL[S]}"
+    return n_diff

@@ -1,0 +1,381 @@
+"""GPU parity, layer by layer (teacher-forced): every HIP layer is fed the oracle's inputs and
+state for a frame and must reproduce the oracle's outputs and state -- masks, index lists and
+all element-wise arithmetic bit-exactly, convolution sums within the stated tolerance.
+All calls go through the C ABI (ctypes binding)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2203_03996_amd as pkg
+from oracle import deltacnn_oracle as orc
+from oracle.deltacnn_oracle import Delta as ODelta
+from tests.helpers import NP_DTYPE, TOL, check_delta, rel_err, to_np
+
+pytestmark = pytest.mark.gpu
+DT = {"f32": pkg.F32, "f16": pkg.F16}
+TDT = {"f32": torch.float32, "f16": torch.float16}
+
+
+def _rand_delta(rng, shape, density, S, scale=1.0):
+    """Random delta whose unflagged pixels are NaN (reading them would poison the result)."""
+    n, h, w, c = shape
+    mask = (rng.random((n, h, w)) < density).astype(np.uint8)
+    data = (rng.normal(0, scale, shape)).astype(NP_DTYPE[S])
+    return ODelta(data, mask).poisoned()
+
+
+def _upload(d: ODelta):
+    return pkg.Delta.from_numpy(d.data, d.mask)
+
+
+# ---- mask propagation + compaction (bit-exact) --------------------------------------------------
+@pytest.mark.parametrize("n,h,w", [(1, 64, 64), (3, 37, 53), (2, 128, 128), (1, 7, 5)])
+@pytest.mark.parametrize("k,stride,pad", [(1, 1, 0), (3, 1, 1), (3, 2, 1), (7, 2, 3), (1, 2, 0)])
+@pytest.mark.parametrize("density", [0.0, 0.03, 0.5, 1.0])
+def test_mask_compact(n, h, w, k, stride, pad, density):
+    rng = np.random.default_rng(n * 1000 + h + k * 7 + int(density * 100))
+    m = (rng.random((n, h, w)) < density).astype(np.uint8)
+    ctx = pkg.Context(n * h * w)
+    mo, idx, cnt = ctx.mask_compact(torch.from_numpy(m).cuda(), k, stride, pad)
+    ctx.sync()
+    ref = orc.window_mask(m, k, stride, pad)
+    assert np.array_equal(to_np(mo), ref)
+    ridx, rcnt = orc.compact(ref)
+    assert int(to_np(cnt)[0]) == rcnt
+    assert np.array_equal(to_np(idx)[:rcnt], ridx)
+
+
+def test_mask_union():
+    rng = np.random.default_rng(5)
+    a = (rng.random((2, 33, 47)) < 0.1).astype(np.uint8)
+    b = (rng.random((2, 33, 47)) < 0.1).astype(np.uint8)
+    ctx = pkg.Context(a.size)
+    mo, idx, cnt = ctx.mask_compact(torch.from_numpy(a).cuda(), 1, 1, 0, mask_b=torch.from_numpy(b).cuda())
+    ctx.sync()
+    assert np.array_equal(to_np(mo), a | b)
+    assert np.array_equal(to_np(idx)[:int(to_np(cnt)[0])], np.flatnonzero((a | b).reshape(-1)))
+
+
+# ---- input delta generation (bit-exact) ---------------------------------------------------------
+@pytest.mark.parametrize("S", ["f32", "f16"])
+@pytest.mark.parametrize("shape", [(1, 64, 64, 32), (2, 45, 31, 64), (1, 40, 56, 3), (1, 9, 9, 17), (1, 16, 16, 1024)])
+def test_deltagen(S, shape):
+    rng = np.random.default_rng(sum(shape))
+    n, h, w, c = shape
+    ref = orc.DeltaGen(0.3, 0, S)
+    ctx = pkg.Context(n * h * w)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.DELTAGEN, DT[S], n, h, w, c, eps=0.3))
+    f0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
+    r0 = ref.init(f0)
+    g0 = layer.init([torch.from_numpy(f0).cuda()])
+    ctx.sync()
+    assert np.array_equal(to_np(g0), r0)
+    frame = f0.astype(np.float64)
+    for t in range(4):
+        frame = frame + (rng.random((n, h, w, 1)) < 0.2) * rng.normal(0, 0.4, shape)
+        fr = frame.astype(NP_DTYPE[S])
+        want = ref.step(fr).poisoned()
+        out = layer.step([pkg.Delta(torch.from_numpy(fr).cuda(), None, None, None)])
+        ctx.sync()
+        check_delta(out, want, S, f"deltagen frame {t}", exact_values=True)
+        assert np.array_equal(to_np(layer.state_tensor(0)), ref.P)
+    st = layer.stats()
+    assert st["pixels_out"] == want.count and st["pixels_total"] == n * h * w
+
+
+# ---- activation + truncation (bit-exact) ---------------------------------------------------------
+@pytest.mark.parametrize("S", ["f32", "f16"])
+@pytest.mark.parametrize("f", ["relu", "relu6"])
+@pytest.mark.parametrize("shape", [(1, 64, 64, 32), (2, 33, 29, 64), (1, 24, 24, 256), (1, 12, 12, 960),
+                                   (1, 10, 10, 2048), (1, 9, 11, 3), (1, 9, 11, 17), (1, 8, 8, 100)])
+def test_act_trunc(S, f, shape):
+    rng = np.random.default_rng(sum(shape) + len(f))
+    n, h, w, c = shape
+    eps = 0.35
+    ref = orc.ActTrunc(f, eps, S)
+    ctx = pkg.Context(n * h * w)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.ACT, DT[S], n, h, w, c, act=pkg.ACT_CODES[f], eps=eps))
+    x0 = rng.normal(0, 2, shape).astype(NP_DTYPE[S])
+    r0 = ref.init(x0)
+    g0 = layer.init([torch.from_numpy(x0).cuda()])
+    ctx.sync()
+    assert np.array_equal(to_np(g0), r0)
+    assert np.array_equal(to_np(layer.state_tensor(0)), ref.xA)
+    saw = set()
+    for t in range(4):
+        d = _rand_delta(rng, shape, [0.3, 0.05, 1.0, 0.0][t], S, scale=0.3)
+        want = ref.step(d).poisoned()
+        out = layer.step([_upload(d)])
+        ctx.sync()
+        check_delta(out, want, S, f"act frame {t}", exact_values=True)
+        assert np.array_equal(to_np(layer.state_tensor(0)), ref.xA)
+        assert np.array_equal(to_np(layer.state_tensor(1)), ref.xT)
+        if want.count:
+            saw.add("upd")
+        if want.count < d.count:
+            saw.add("trunc")
+    assert saw == {"upd", "trunc"}
+
+
+@pytest.mark.parametrize("S", ["f32", "f16"])
+@pytest.mark.parametrize("act", ["relu", "none"])
+def test_add_act(S, act):
+    rng = np.random.default_rng(17)
+    shape = (2, 31, 30, 64)
+    n, h, w, c = shape
+    eps = 0.4
+    radd, ract = orc.Add(S), orc.ActTrunc(act, eps, S)
+    ctx = pkg.Context(n * h * w)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.ACT, DT[S], n, h, w, c, act=pkg.ACT_CODES[act], eps=eps, n_in=2))
+    a0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
+    b0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
+    r0 = radd.init(a0, b0)
+    if act != "none":
+        r0 = ract.init(r0)
+    g0 = layer.init([torch.from_numpy(a0).cuda(), torch.from_numpy(b0).cuda()])
+    ctx.sync()
+    assert np.array_equal(to_np(g0), r0)
+    for t in range(3):
+        da = _rand_delta(rng, shape, 0.2, S, 0.3)
+        db = _rand_delta(rng, shape, 0.1, S, 0.3)
+        want = radd.step(da, db).poisoned()
+        if act != "none":
+            want = ract.step(want).poisoned()
+        out = layer.step([_upload(da), _upload(db)])
+        ctx.sync()
+        check_delta(out, want, S, f"add+{act} frame {t}", exact_values=True)
+        if act != "none":
+            assert np.array_equal(to_np(layer.state_tensor(0)), ract.xA)
+            assert np.array_equal(to_np(layer.state_tensor(1)), ract.xT)
+
+
+# ---- convolution: linear (values within tolerance; masks and lists bit-exact) -------------------
+CONV_CASES = [
+    # S, k, stride, pad, cin, cout, (n,h,w)
+    ("f32", 3, 1, 1, 32, 32, (1, 64, 64)),
+    ("f32", 1, 1, 0, 32, 64, (2, 20, 23)),
+    ("f32", 3, 2, 1, 16, 48, (1, 31, 33)),
+    ("f32", 3, 1, 1, 3, 32, (1, 30, 30)),
+    ("f16", 1, 1, 0, 64, 64, (2, 40, 40)),
+    ("f16", 3, 1, 1, 64, 64, (2, 40, 37)),
+    ("f16", 1, 1, 0, 64, 256, (1, 48, 48)),
+    ("f16", 3, 2, 1, 3, 32, (1, 50, 50)),
+    ("f16", 7, 2, 3, 3, 64, (1, 40, 40)),
+    ("f16", 1, 1, 0, 48, 96, (1, 25, 25)),
+    ("f16", 3, 1, 1, 32, 160, (1, 21, 20)),
+    ("f16", 1, 2, 0, 64, 128, (1, 30, 30)),
+    ("f16", 3, 1, 1, 64, 16, (1, 24, 24)),
+]
+
+
+def _conv_layers(S, k, stride, pad, cin, cout, nhw, rng, act=pkg.ACT_NONE, eps=0.0, n_in=1, depthwise=False):
+    n, h, w = nhw
+    if depthwise:
+        wgt = (rng.normal(0, 1, (k, k, cin)) * np.sqrt(2.0 / (k * k))).astype(NP_DTYPE[S])
+    else:
+        wgt = (rng.normal(0, 1, (k, k, cin, cout)) * np.sqrt(2.0 / (k * k * cin))).astype(NP_DTYPE[S])
+    bias = rng.normal(0, 0.1, cout).astype(NP_DTYPE[S])
+    ref = orc.Conv(wgt, bias, stride, pad, depthwise, S)
+    ctx = pkg.Context(n * h * w)
+    desc = pkg.make_desc(pkg.DWCONV if depthwise else pkg.CONV, DT[S], n, h, w, cin, k=k, stride=stride, pad=pad,
+                         cout=cout, act=act, eps=eps, n_in=n_in)
+    layer = pkg.Layer(ctx, desc, torch.from_numpy(wgt).cuda(), torch.from_numpy(bias).cuda())
+    return ctx, layer, ref
+
+
+@pytest.mark.parametrize("S,k,stride,pad,cin,cout,nhw", CONV_CASES)
+def test_conv_linear(S, k, stride, pad, cin, cout, nhw):
+    rng = np.random.default_rng(k * 100 + cin + cout)
+    n, h, w = nhw
+    ctx, layer, ref = _conv_layers(S, k, stride, pad, cin, cout, nhw, rng)
+    x0 = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
+    r0 = ref.init(x0)
+    g0 = layer.init([torch.from_numpy(x0).cuda()])
+    ctx.sync()
+    assert rel_err(to_np(g0), r0) <= TOL[S], "dense first frame"
+    for t, dens in enumerate([0.05, 0.4, 1.0, 0.0]):
+        d = _rand_delta(rng, (n, h, w, cin), dens, S)
+        want = ref.step(d).poisoned()
+        out = layer.step([_upload(d)])
+        ctx.sync()
+        check_delta(out, want, S, f"conv frame {t} density {dens}")
+        st = layer.stats()
+        assert st["pixels_in"] == d.count and st["pixels_out"] == want.count
+
+
+@pytest.mark.parametrize("S,k,stride,cin,cout,nhw,res", [
+    ("f32", 3, 1, 32, 32, (1, 64, 64), False),
+    ("f16", 1, 1, 64, 64, (2, 32, 32), False),
+    ("f16", 3, 1, 64, 64, (2, 33, 35), False),
+    ("f16", 1, 1, 64, 256, (1, 40, 40), True),
+    ("f16", 3, 2, 64, 128, (1, 30, 30), False),
+    ("f16", 3, 2, 3, 32, (1, 40, 40), False),
+    ("f32", 1, 1, 16, 16, (1, 20, 20), True),
+])
+def test_conv_fused_act(S, k, stride, cin, cout, nhw, res):
+    """conv (+ residual) + activation/truncation in one layer == oracle conv -> add -> act."""
+    rng = np.random.default_rng(k + cin * 3 + cout)
+    n, h, w = nhw
+    eps = 0.3
+    pad = k // 2
+    ctx, layer, rconv = _conv_layers(S, k, stride, pad, cin, cout, nhw, rng, act=pkg.ACT_RELU, eps=eps,
+                                     n_in=2 if res else 1)
+    radd, ract = orc.Add(S), orc.ActTrunc("relu", eps, S)
+    oh, ow = layer.out_shape[1:3]
+    x0 = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
+    y0 = rconv.init(x0)
+    ins0 = [torch.from_numpy(x0).cuda()]
+    if res:
+        s0 = rng.normal(0, 1, (n, oh, ow, cout)).astype(NP_DTYPE[S])
+        y0 = radd.init(y0, s0)
+        ins0.append(torch.from_numpy(s0).cuda())
+    r0 = ract.init(y0)
+    g0 = layer.init(ins0)
+    ctx.sync()
+    assert rel_err(to_np(g0), r0) <= TOL[S]
+    assert rel_err(to_np(layer.state_tensor(0)), ract.xA) <= TOL[S]
+    ties = 0
+    for t, dens in enumerate([0.05, 0.3, 1.0, 0.0, 0.1]):
+        # teacher forcing: the layer starts every frame from the oracle's state
+        layer.state_tensor(0).copy_(torch.from_numpy(ract.xA).cuda())
+        layer.state_tensor(1).copy_(torch.from_numpy(ract.xT).cuda())
+        d = _rand_delta(rng, (n, h, w, cin), dens, S, 0.5)
+        mid = rconv.step(d).poisoned()
+        ins = [_upload(d)]
+        if res:
+            ds = _rand_delta(rng, (n, oh, ow, cout), dens / 2, S, 0.5)
+            mid = radd.step(mid, ds).poisoned()
+            ins.append(_upload(ds))
+        want = ract.step(mid).poisoned()
+        out = layer.step(ins)
+        ctx.sync()
+        near = np.abs(np.nan_to_num(ract.last_u, nan=np.inf) - eps) <= TOL[S] * eps
+        ties += check_delta(out, want, S, f"fused frame {t}", allow_mask_diff=near)
+        # state: equal to the oracle's where the decision agreed
+        agree = to_np(out.mask) == want.mask
+        assert rel_err(to_np(layer.state_tensor(0))[agree], ract.xA[agree]) <= TOL[S]
+        xt_g, xt_r = to_np(layer.state_tensor(1))[agree], ract.xT[agree]
+        assert np.abs(xt_g.astype(np.float64) - xt_r).max(initial=0) <= TOL[S] * max(1.0, np.abs(xt_r).max(initial=0))
+    assert ties <= 3
+
+
+@pytest.mark.parametrize("S", ["f32", "f16"])
+@pytest.mark.parametrize("stride,c", [(1, 32), (2, 192), (1, 960), (2, 20)])
+def test_depthwise(S, stride, c):
+    rng = np.random.default_rng(stride + c)
+    nhw = (1, 28, 27)
+    eps = 0.3
+    ctx, layer, rconv = _conv_layers(S, 3, stride, 1, c, c, nhw, rng, act=pkg.ACT_RELU6, eps=eps, depthwise=True)
+    ract = orc.ActTrunc("relu6", eps, S)
+    x0 = rng.normal(0, 1, nhw + (c,)).astype(NP_DTYPE[S])
+    r0 = ract.init(rconv.init(x0))
+    g0 = layer.init([torch.from_numpy(x0).cuda()])
+    ctx.sync()
+    assert rel_err(to_np(g0), r0) <= TOL[S]
+    ties = 0
+    for t, dens in enumerate([0.1, 0.5, 0.0]):
+        layer.state_tensor(0).copy_(torch.from_numpy(ract.xA).cuda())
+        layer.state_tensor(1).copy_(torch.from_numpy(ract.xT).cuda())
+        d = _rand_delta(rng, nhw + (c,), dens, S, 0.5)
+        want = ract.step(rconv.step(d).poisoned()).poisoned()
+        out = layer.step([_upload(d)])
+        ctx.sync()
+        near = np.abs(np.nan_to_num(ract.last_u, nan=np.inf) - eps) <= TOL[S] * eps
+        ties += check_delta(out, want, S, f"depthwise frame {t}", allow_mask_diff=near)
+    assert ties <= 3
+
+
+# ---- pooling, upsampling, accumulation (bit-exact) -----------------------------------------------
+@pytest.mark.parametrize("S", ["f32", "f16"])
+def test_maxpool(S):
+    rng = np.random.default_rng(3)
+    shape = (2, 33, 30, 64)
+    n, h, w, c = shape
+    ref = orc.MaxPool(3, 2, 1, S)
+    ctx = pkg.Context(n * h * w)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.MAXPOOL, DT[S], n, h, w, c, k=3, stride=2, pad=1))
+    x0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
+    r0 = ref.init(x0)
+    g0 = layer.init([torch.from_numpy(x0).cuda()])
+    ctx.sync()
+    assert np.array_equal(to_np(g0), r0)
+    for t, dens in enumerate([0.1, 0.6, 0.0]):
+        d = _rand_delta(rng, shape, dens, S, 0.7)
+        want = ref.step(d).poisoned()
+        out = layer.step([_upload(d)])
+        ctx.sync()
+        check_delta(out, want, S, f"maxpool frame {t}", exact_values=True)
+        assert np.array_equal(to_np(layer.state_tensor(0)), ref.xA)
+
+
+@pytest.mark.parametrize("S", ["f32", "f16"])
+@pytest.mark.parametrize("factor", [2, 4])
+def test_upsample(S, factor):
+    rng = np.random.default_rng(factor)
+    shape = (2, 9, 12, 32)
+    n, h, w, c = shape
+    ref = orc.Upsample(factor, S)
+    ctx = pkg.Context(n * h * w * factor * factor)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.UPSAMPLE, DT[S], n, h, w, c, factor=factor))
+    x0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
+    g0 = layer.init([torch.from_numpy(x0).cuda()])
+    ctx.sync()
+    assert np.array_equal(to_np(g0), ref.init(x0))
+    for t, dens in enumerate([0.1, 1.0, 0.0]):
+        d = _rand_delta(rng, shape, dens, S)
+        want = ref.step(d).poisoned()
+        out = layer.step([_upload(d)])
+        ctx.sync()
+        check_delta(out, want, S, f"upsample frame {t}", exact_values=True)
+
+
+@pytest.mark.parametrize("S", ["f32", "f16"])
+def test_accumulate(S):
+    rng = np.random.default_rng(8)
+    shape = (2, 21, 19, 256)
+    n, h, w, c = shape
+    ref = orc.Accumulate(S)
+    ctx = pkg.Context(n * h * w)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.ACCUM, DT[S], n, h, w, c))
+    y0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
+    ref.init(y0)
+    layer.init([torch.from_numpy(y0).cuda()])
+    for t, dens in enumerate([0.1, 0.7, 0.0]):
+        d = _rand_delta(rng, shape, dens, S)
+        want = ref.step(d)
+        out = layer.step([_upload(d)])
+        ctx.sync()
+        assert np.array_equal(to_np(out.data), want)
+
+
+# ---- error paths through the ABI ------------------------------------------------------------------
+def test_error_paths():
+    ctx = pkg.Context(16 * 16)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.ACT, pkg.F32, 1, 16, 16, 8, act=pkg.ACT_RELU, eps=0.1))
+    d = _upload(ODelta(np.zeros((1, 16, 16, 8), np.float32), np.zeros((1, 16, 16), np.uint8)))
+    with pytest.raises(pkg.DcnnError) as e:
+        layer.step([d])                                   # step before the first frame
+    assert e.value.status == 4
+    layer.init([torch.zeros((1, 16, 16, 8), device="cuda")])
+    bad = _upload(ODelta(np.zeros((1, 8, 16, 8), np.float32), np.zeros((1, 8, 16), np.uint8)))
+    with pytest.raises(pkg.DcnnError) as e:
+        layer.step([bad])
+    assert e.value.status == 2
+    half = _upload(ODelta(np.zeros((1, 16, 16, 8), np.float16), np.zeros((1, 16, 16), np.uint8)))
+    with pytest.raises(pkg.DcnnError) as e:
+        layer.step([half])
+    assert e.value.status == 3
+    layer.reset()
+    with pytest.raises(pkg.DcnnError):
+        layer.step([d])
+    small = pkg.Context(64)                               # workspace too small for this layer
+    l2 = pkg.Layer(small, pkg.make_desc(pkg.ACT, pkg.F32, 1, 64, 64, 8, act=pkg.ACT_RELU, eps=0.1, n_in=2))
+    l2.init([torch.zeros((1, 64, 64, 8), device="cuda")] * 2)
+    big = _upload(ODelta(np.zeros((1, 64, 64, 8), np.float32), np.zeros((1, 64, 64), np.uint8)))
+    with pytest.raises(pkg.DcnnError) as e:
+        l2.step([big, big])
+    assert e.value.status == 5
+    with pytest.raises(pkg.DcnnError) as e:               # weights too large for the LDS-resident kernel
+        pkg.Layer(ctx, pkg.make_desc(pkg.CONV, pkg.F16, 1, 16, 16, 512, k=3, stride=1, pad=1, cout=512),
+                  torch.zeros((3, 3, 512, 512), dtype=torch.float16, device="cuda"))
+    assert e.value.status == 7

@@ -1,0 +1,192 @@
+"""GPU parity of whole networks run free (no teacher forcing) through dcnn_net_*.
+
+The library's convolution sums differ from the oracle's in rounding order, so a pixel whose
+max |dy| lands within rounding of the threshold may be decided differently ("threshold tie");
+from then on the two delta streams legitimately differ while both keep tracking dense
+inference.  The checks are therefore:
+  * until the first tie: every mask identical, every index list the oracle's, the dense
+    output within the value tolerance;
+  * a mask difference is only accepted at pixels whose oracle max-norm is within the value
+    tolerance of the threshold;
+  * always: the dense output stays as close to plain dense inference as the oracle's does
+    (truncation error does not accumulate), and with negative thresholds it equals it.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2203_03996_amd as pkg
+import workloads as wl
+from oracle import deltacnn_oracle as orc
+from oracle.deltacnn_oracle import Delta as ODelta
+from tests.helpers import NP_DTYPE, TOL, rel_err, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_net(spec, seed, n_streams, flags=3, frames=None, check_dense=True):
+    S = spec["dtype"]
+    wts = wl.make_weights(spec, seed)
+    vid = wl.make_batch(spec["video"], seed, n_streams)
+    if frames:
+        vid = vid[:frames]
+    oracle = orc.OracleNet(spec, wts, S)
+    # dense reference uses the weights as stored (rounded to S), like both implementations
+    wts_s = {i: (w.astype(NP_DTYPE[S]).astype(np.float64), b.astype(NP_DTYPE[S]).astype(np.float64))
+             for i, (w, b) in wts.items()}
+    shapes = wl.node_shapes(spec)
+    max_px = n_streams * max(h * w for h, w, _ in shapes)
+    ctx = pkg.Context(max_px)
+    net = pkg.Net(ctx, spec, wts, n_streams, flags)
+    oh, ow, oc = shapes[-1]
+    out = torch.empty((n_streams, oh, ow, oc), dtype=torch.float16 if S == "f16" else torch.float32, device="cuda")
+    eps_of = {i: nd["eps"] for i, nd in enumerate(spec["nodes"]) if nd["kind"] in ("act", "deltagen")}
+    diverged = False
+    ties = 0
+    report = []
+    for t in range(vid.shape[0]):
+        fr = vid[t].astype(NP_DTYPE[S])
+        frame = torch.from_numpy(fr).cuda()
+        (net.init if t == 0 else net.step)(frame, out)
+        ctx.sync()
+        ref = oracle.frame(fr)
+        got = to_np(out)
+        assert not np.isnan(got.astype(np.float64)).any(), f"frame {t}: NaN in the dense output"
+        if t > 0:
+            for li in range(net.num_layers):
+                nid, view, _ = net.layer_output(li)
+                o = oracle.outs[nid]
+                if not isinstance(o, ODelta) or view.mask is None:
+                    continue
+                gm = to_np(view.mask)
+                diff = gm != o.mask
+                if diff.any() and not diverged:
+                    # the first difference of the run must sit on a threshold tie of this very layer
+                    ly = oracle.layers[nid]
+                    assert getattr(ly, "last_u", None) is not None, f"frame {t} node {nid}: mask differs"
+                    eps = eps_of[nid]
+                    near = np.abs(np.nan_to_num(ly.last_u, nan=np.inf) - eps) <= TOL[S] * abs(eps)
+                    assert np.all(near[diff]), f"frame {t} node {nid}: mask differs away from a threshold tie"
+                    ties += int(diff.sum())
+                    diverged = True
+                if not diverged:
+                    if view.count is not None and (flags & 2):
+                        cnt = int(to_np(view.count)[0])
+                        assert cnt == o.count, f"frame {t} node {nid}: count {cnt} vs {o.count}"
+                        assert np.array_equal(to_np(view.idx)[:cnt], o.idx), f"frame {t} node {nid}: index list"
+                    sel = o.mask == 1
+                    e = rel_err(to_np(view.data)[sel], o.data[sel])
+                    assert e <= TOL[S], f"frame {t} node {nid}: delta values off by {e:.2e}"
+                else:
+                    assert diff.mean() < 0.02, f"frame {t} node {nid}: masks drifted apart ({diff.mean():.3f})"
+        if not diverged:
+            e = rel_err(got, ref)
+            assert e <= TOL[S], f"frame {t}: dense output off by {e:.2e}"
+        if check_dense:
+            dense = orc.dense_reference(spec, wts_s, fr.astype(np.float64))
+            scale = np.abs(dense).max()
+            err_o = np.abs(ref.astype(np.float64) - dense).max() / scale
+            err_g = np.abs(got.astype(np.float64) - dense).max() / scale
+            report.append((err_o, err_g))
+            assert err_g <= 2.0 * err_o + 4 * TOL[S], f"frame {t}: library drifts from dense inference ({err_g:.2e} vs oracle {err_o:.2e})"
+    return {"ties": ties, "diverged": diverged, "errs": report, "net": net, "ctx": ctx, "oracle": oracle}
+
+
+def test_config1_single_conv_fp32_full_size():
+    """BASELINE config 1: 3x3 conv + ReLU, 32 channels, 64x64, fp32, 4 frames, eps 0.05."""
+    r = _run_net(wl.single_conv_relu(), wl.CONFIG_SEEDS[1], 1)
+    assert r["ties"] == 0
+
+
+@pytest.mark.parametrize("flags", [1, 3, 2])
+def test_config2_bottleneck_fp16_full_size(flags):
+    """BASELINE config 2 at its real size (128x128, 64->64->256, fp16), 6 of its 16 frames."""
+    r = _run_net(wl.bottleneck_block(eps=0.1), wl.CONFIG_SEEDS[2], 1, flags=flags, frames=6)
+    assert r["ties"] <= 20
+
+
+def test_config2_batched_streams():
+    _run_net(wl.bottleneck_block(eps=0.1, h=64, w=48), wl.CONFIG_SEEDS[2], 3, frames=5)
+
+
+@pytest.mark.parametrize("S", ["f32", "f16"])
+@pytest.mark.parametrize("flags", [3, 2])
+def test_tiny_mixed_net_all_layer_kinds(S, flags):
+    _run_net(wl.tiny_mixed_net(eps=0.05, dtype=S), 11, 2, flags=flags)
+
+
+@pytest.mark.parametrize("spec_fn", [lambda: wl.single_conv_relu(eps=-1.0), lambda: wl.bottleneck_block(eps=-1.0, h=32, w=32, frames=4),
+                                     lambda: wl.tiny_mixed_net(eps=-1.0, dtype="f16")])
+def test_dense_mode_matches_dense_inference(spec_fn):
+    """Negative thresholds: every pixel is reprocessed and the output is plain dense inference."""
+    spec = spec_fn()
+    r = _run_net(spec, 5, 1)
+    assert not r["diverged"]
+    for err_o, err_g in r["errs"]:
+        assert err_g <= 8 * TOL[spec["dtype"]]
+
+
+def test_identical_frames_and_infinite_threshold_do_nothing():
+    spec = wl.bottleneck_block(eps=0.05, h=32, w=32, frames=3)
+    wts = wl.make_weights(spec, 2)
+    vid = wl.make_batch(spec["video"], 2, 1).astype(np.float16)
+    ctx = pkg.Context(32 * 32)
+    net = pkg.Net(ctx, spec, wts, 1, 3)
+    out = torch.empty((1, 32, 32, 256), dtype=torch.float16, device="cuda")
+    f0 = torch.from_numpy(vid[0]).cuda()
+    net.init(f0, out)
+    ctx.sync()
+    o1 = out.clone()
+    arena1 = net.arena.clone()
+    net.step(f0, out)
+    ctx.sync()
+    assert torch.equal(out, o1)
+    for s in net.stats():
+        assert s["pixels_out"] == 0 and s["pixels_work"] == 0
+    spec_inf = wl.bottleneck_block(eps=float("inf"), h=32, w=32, frames=3)
+    net2 = pkg.Net(ctx, spec_inf, wts, 1, 3)
+    net2.init(f0, out)
+    net2.step(torch.from_numpy(vid[1]).cuda(), out)
+    ctx.sync()
+    assert torch.equal(out, o1)
+    assert all(s["pixels_out"] == 0 for s in net2.stats())
+    del arena1
+
+
+def test_reset_restarts_from_a_dense_frame():
+    spec = wl.single_conv_relu(h=32, w=32)
+    wts = wl.make_weights(spec, 3)
+    vid = wl.make_batch(spec["video"], 3, 1).astype(np.float32)
+    ctx = pkg.Context(32 * 32)
+    net = pkg.Net(ctx, spec, wts, 1)
+    out = torch.empty((1, 32, 32, 32), device="cuda")
+    with pytest.raises(pkg.DcnnError):
+        net.step(torch.from_numpy(vid[0]).cuda(), out)
+    net.init(torch.from_numpy(vid[0]).cuda(), out)
+    net.step(torch.from_numpy(vid[1]).cuda(), out)
+    net.reset()
+    with pytest.raises(pkg.DcnnError):
+        net.step(torch.from_numpy(vid[2]).cuda(), out)
+    net.init(torch.from_numpy(vid[3]).cuda(), out)
+    ctx.sync()
+    fresh = pkg.Net(ctx, spec, wts, 1)
+    out2 = torch.empty_like(out)
+    fresh.init(torch.from_numpy(vid[3]).cuda(), out2)
+    ctx.sync()
+    assert torch.equal(out, out2)
+
+
+def test_run_to_run_determinism():
+    spec = wl.bottleneck_block(eps=0.1, h=64, w=64, frames=4)
+    wts = wl.make_weights(spec, 9)
+    vid = wl.make_batch(spec["video"], 9, 2).astype(np.float16)
+    outs = []
+    for _ in range(2):
+        ctx = pkg.Context(2 * 64 * 64)
+        net = pkg.Net(ctx, spec, wts, 2)
+        out = torch.empty((2, 64, 64, 256), dtype=torch.float16, device="cuda")
+        for t in range(4):
+            (net.init if t == 0 else net.step)(torch.from_numpy(vid[t]).cuda(), out)
+        ctx.sync()
+        outs.append(out.clone())
+    assert torch.equal(outs[0], outs[1])
