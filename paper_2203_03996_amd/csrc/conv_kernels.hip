@@ -7,9 +7,13 @@
 // straight from the NHWC delta map into registers, 16 bytes per lane).  A tap contributes only
 // where the input pixel is in bounds AND flagged: unflagged memory is never read (it is invalid
 // by contract), and a tap no lane of the wave needs is skipped altogether.
-// The whole packed weight tensor of the layer stays resident in LDS (160 KB per CU on gfx950) for
-// the lifetime of the persistent workgroup; the fp32 result tile is rounded to the storage type,
-// staged through LDS and handed to the activation + truncation tail with coalesced accesses.
+// When the packed weight tensor of the layer fits, it stays resident in LDS (160 KB per CU on
+// gfx950) for the lifetime of the persistent workgroup.  Larger layers stream it: the four waves of
+// a workgroup walk the K dimension in lockstep and a double-buffered 4-K-step slice of the weights
+// is copied global -> registers -> LDS while the matrix cores consume the previous slice.
+// The fp32 result tile is rounded to the storage type, staged through LDS and handed to the
+// activation + truncation tail with coalesced accesses (once per pixel when all output channels
+// fit the staging tile, else per pass of output channels for layers without activation).
 #include "device_utils.h"
 
 namespace dcnn {
@@ -42,12 +46,18 @@ struct ConvPlan {
     int cout_pad;      // npass * nb * 32
     int kch;           // K-steps per tap, each covering 2 * KPACK input channels
     size_t w_bytes;    // packed weights
-    size_t lds_bytes;  // packed weights + staging of all waves
+    bool stream;       // weights do not fit LDS: stream them in slices
+    bool full_tail;    // the staging tile holds all output channels (needed for a fused activation)
+    size_t lds_bytes;
+    bool ok;
 };
 
-static ConvPlan conv_plan(int dtype, int k, int cin, int cout) {
+static size_t stage_bytes(int cols, int dtype) { return (size_t)kConvWaves * kTile * (cols * dtype_size(dtype) + kStagePad); }
+
+static ConvPlan conv_plan(int dtype, int k, int cin, int cout, size_t max_lds, bool need_full_tail) {
     const int kpack = dtype == DCNN_F16 ? 8 : 4;
-    ConvPlan p;
+    const int vec = dtype == DCNN_F16 ? 8 : 4;
+    ConvPlan p{};
     const int nbt = (int)cdiv(cout, 32);
     static const int cand[] = {8, 6, 5, 4, 3, 2, 1};
     p.nb = 1;
@@ -58,29 +68,33 @@ static ConvPlan conv_plan(int dtype, int k, int cin, int cout) {
     p.cout_pad = p.npass * p.nb * 32;
     p.kch = (int)cdiv(cin, 2 * kpack);
     p.w_bytes = (size_t)k * k * p.kch * 2 * p.cout_pad * 16;
-    p.lds_bytes = p.w_bytes + (size_t)kConvWaves * kTile * (p.cout_pad * dtype_size(dtype) + kStagePad);
+    const size_t slice = (size_t)2 * kGroup * 2 * p.nb * 32 * 16;          // double-buffered weight slice
+    const int nvec = cout % vec == 0 ? cout / vec : cout;                  // vectors per pixel in the tail
+    const bool tail_fits_wave = nvec <= kWave;
+    const size_t full = stage_bytes(p.cout_pad, dtype), part = stage_bytes(p.nb * 32, dtype);
+    p.ok = true;
+    if (tail_fits_wave && p.w_bytes + full <= max_lds) { p.stream = false; p.full_tail = true; p.lds_bytes = p.w_bytes + full; }
+    else if (tail_fits_wave && slice + full <= max_lds) { p.stream = true; p.full_tail = true; p.lds_bytes = slice + full; }
+    else if (!need_full_tail && cout % vec == 0 && slice + part <= max_lds) { p.stream = true; p.full_tail = false; p.lds_bytes = slice + part; }
+    else p.ok = false;
     return p;
 }
 
 size_t conv_packed_weight_bytes(int dtype, int k, int cin, int cout, int depthwise) {
     if (depthwise) return align_up((size_t)k * k * cout * dtype_size(dtype));
-    return align_up(conv_plan(dtype, k, cin, cout).w_bytes);
+    return align_up(conv_plan(dtype, k, cin, cout, 0, false).w_bytes);
 }
 
 bool conv_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cout, int depthwise, bool fused, char* why,
                     size_t why_len) {
-    (void)fused;
     if (depthwise) return true;
-    const ConvPlan p = conv_plan(dtype, k, cin, cout);
-    const int vec = dtype == DCNN_F16 ? 8 : 4;
     if (k * k > 64) { snprintf(why, why_len, "kernel size %d too large", k); return false; }
-    if (p.lds_bytes > ctx->max_lds) {
-        snprintf(why, why_len, "conv %dx%d %d->%d needs %zu bytes of LDS (limit %zu): weight streaming not implemented",
-                 k, k, cin, cout, p.lds_bytes, ctx->max_lds);
+    const ConvPlan p = conv_plan(dtype, k, cin, cout, ctx->max_lds, fused);
+    if (!p.ok) {
+        snprintf(why, why_len, "conv %dx%d %d->%d%s: the output tile does not fit the %zu bytes of LDS", k, k, cin, cout,
+                 fused ? " with fused activation" : "", ctx->max_lds);
         return false;
     }
-    const int nvec = cout % vec == 0 ? cout / vec : cout;
-    if (nvec > kWave) { snprintf(why, why_len, "conv output of %d channels is wider than one wave pass", cout); return false; }
     return true;
 }
 
@@ -110,7 +124,7 @@ dcnn_status launch_pack_weights(dcnn_ctx* ctx, int dtype, const void* w, void* w
                                 int depthwise) {
     if (depthwise)
         return launch_copy(ctx, wpacked, w, (size_t)k * k * cout * dtype_size(dtype));
-    const ConvPlan p = conv_plan(dtype, k, cin, cout);
+    const ConvPlan p = conv_plan(dtype, k, cin, cout, 0, false);
     const int64_t total = (int64_t)p.w_bytes / (int64_t)dtype_size(dtype);
     const int grid = (int)(cdiv(total, 256) < 4096 ? cdiv(total, 256) : 4096);
     if (dtype == DCNN_F16)
@@ -122,11 +136,44 @@ dcnn_status launch_pack_weights(dcnn_ctx* ctx, int dtype, const void* w, void* w
     return check_hip(ctx, hipGetLastError(), "pack_weights_kernel launch");
 }
 
-template <typename T, int NB, int V, bool ALIGNED>
+// accumulators -> staging tile [pixel][cout] in the storage type.  Lane (col, g) holds, for pixel
+// `col`, the output channels 8*q + 4*g + {0..3} of every 32-channel block.
+template <typename T, int NB>
+__device__ __forceinline__ void stage_accumulators(const f32x16 (&acc)[NB], unsigned char* row, int first_col, int g) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            T* dst = reinterpret_cast<T*>(row) + first_col + b * 32 + 8 * q + 4 * g;
+            if constexpr (sizeof(T) == 2) {
+                f16x4 v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = (f16)acc[b][4 * q + i];
+                *reinterpret_cast<f16x4*>(dst) = v;
+            } else {
+                f32x4 v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = acc[b][4 * q + i];
+                *reinterpret_cast<f32x4*>(dst) = v;
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ void wave_lds_fence() {
+    // the staging tile is private to one wave: order its LDS writes and reads without a block barrier
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <typename T, int NB, int V, bool ALIGNED, bool STREAM>
 __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init,
-                                                                 int npass) {
+                                                                 int npass, int full_tail) {
     typedef typename Mma<T>::Vec Vec;
     constexpr int KP = Mma<T>::KPACK;
+    constexpr int COLS = NB * 32;
+    constexpr int SLICE = kGroup * 2 * COLS;                   // 16-byte vectors of one weight slice
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int64_t count = list_count(l);
@@ -137,22 +184,27 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, Con
     const int col = lane % 32, g = lane / 32;
     const int taps = c.k * c.k, kch = c.kch;
     const int ksteps = taps * kch;
-    const int w_vecs = npass * ksteps * 2 * NB * 32;
+    const int groups = (kch + kGroup - 1) / kGroup;            // slices per tap
+    const int w_vecs = STREAM ? 2 * SLICE : npass * ksteps * 2 * COLS;
     Vec* w_lds = reinterpret_cast<Vec*>(smem);
-    const int stage_stride = c.cout_pad * (int)sizeof(T) + kStagePad;
+    const int stage_cols = full_tail ? c.cout_pad : COLS;
+    const int stage_stride = stage_cols * (int)sizeof(T) + kStagePad;
     unsigned char* stage = smem + (size_t)w_vecs * 16 + (size_t)wave * kTile * stage_stride;
+    const Vec* wglob = static_cast<const Vec*>(c.wpacked);
 
-    {
-        const Vec* wg = static_cast<const Vec*>(c.wpacked);
-        for (int i = threadIdx.x; i < w_vecs; i += kConvThreads) w_lds[i] = wg[i];
+    if constexpr (!STREAM) {
+        for (int i = threadIdx.x; i < w_vecs; i += kConvThreads) w_lds[i] = wglob[i];
+        __syncthreads();
     }
-    __syncthreads();
 
     const T* in = static_cast<const T*>(c.in_data);
     for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
         const int64_t tile = wt * kConvWaves + wave;
         const int64_t base = tile * kTile;
-        if (base >= count) continue;
+        const bool tile_on = base < count;
+        if constexpr (!STREAM) {
+            if (!tile_on) continue;                            // streaming waves stay in step for the barriers
+        }
         const int64_t j = base + col;
         const bool valid = j < count;
         const int64_t p = valid ? (l.list ? (int64_t)l.list[j] : j) : 0;
@@ -202,70 +254,120 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, Con
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
 
-            // software pipeline over (tap, group of K-steps): the gathers of the next group are in
-            // flight while the matrix cores work on the current one
-            int t = 0, kc0 = 0;
-            while (t < taps && !((tapany >> t) & 1)) ++t;
-            Vec xa[kGroup];
-            if (t < taps) gather(t, 0, xa);
-            while (t < taps) {
-                int tn = t, kn = kc0 + kGroup;
-                if (kn >= kch) {
-                    kn = 0;
-                    ++tn;
-                    while (tn < taps && !((tapany >> tn) & 1)) ++tn;
-                }
-                Vec xb[kGroup];
-                if (tn < taps) gather(tn, kn, xb);
-                const Vec* wrow = w_lds + ((size_t)(pass * ksteps + t * kch + kc0) * 2 + g) * (NB * 32) + col;
-#pragma unroll
-                for (int u = 0; u < kGroup; ++u) {
-                    if (kc0 + u < kch) {
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wrow[(size_t)u * 2 * NB * 32 + b * 32], xa[u]);
+            if constexpr (!STREAM) {
+                // software pipeline over (tap, group of K-steps): the gathers of the next group are in
+                // flight while the matrix cores work on the current one; taps no lane needs are skipped
+                int t = 0, kc0 = 0;
+                while (t < taps && !((tapany >> t) & 1)) ++t;
+                Vec xa[kGroup];
+                if (t < taps) gather(t, 0, xa);
+                while (t < taps) {
+                    int tn = t, kn = kc0 + kGroup;
+                    if (kn >= kch) {
+                        kn = 0;
+                        ++tn;
+                        while (tn < taps && !((tapany >> tn) & 1)) ++tn;
                     }
-                }
+                    Vec xb[kGroup];
+                    if (tn < taps) gather(tn, kn, xb);
+                    const Vec* wrow = w_lds + ((size_t)(pass * ksteps + t * kch + kc0) * 2 + g) * COLS + col;
 #pragma unroll
-                for (int u = 0; u < kGroup; ++u) xa[u] = xb[u];
-                t = tn;
-                kc0 = kn;
+                    for (int u = 0; u < kGroup; ++u) {
+                        if (kc0 + u < kch) {
+#pragma unroll
+                            for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wrow[(size_t)u * 2 * COLS + b * 32], xa[u]);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < kGroup; ++u) xa[u] = xb[u];
+                    t = tn;
+                    kc0 = kn;
+                }
+            } else {
+                // all waves of the workgroup walk the slices (tap, group) in lockstep; slice s+1 travels
+                // global -> registers while slice s is multiplied, then registers -> LDS, one barrier
+                const int nslices = taps * groups;
+                auto slice_src = [&](int s, int* nvec) {
+                    const int t = s / groups, kc0 = (s % groups) * kGroup;
+                    const int steps = kch - kc0 < kGroup ? kch - kc0 : kGroup;
+                    *nvec = steps * 2 * COLS;
+                    return wglob + ((size_t)(pass * ksteps + t * kch + kc0) * 2) * COLS;
+                };
+                Vec wreg[NB];                                   // SLICE / kConvThreads == NB vectors per thread
+                auto slice_load = [&](int s) {
+                    int nv;
+                    const Vec* src = slice_src(s, &nv);
+#pragma unroll
+                    for (int i = 0; i < NB; ++i) {
+                        const int vi = threadIdx.x + i * kConvThreads;
+                        if (vi < nv) wreg[i] = src[vi];
+                    }
+                };
+                auto slice_store = [&](int s) {
+                    int nv;
+                    slice_src(s, &nv);
+                    Vec* dst = w_lds + (size_t)(s & 1) * SLICE;
+#pragma unroll
+                    for (int i = 0; i < NB; ++i) {
+                        const int vi = threadIdx.x + i * kConvThreads;
+                        if (vi < nv) dst[vi] = wreg[i];
+                    }
+                };
+                Vec xa[kGroup];
+                slice_load(0);
+                gather(0, 0, xa);
+                slice_store(0);
+                __syncthreads();
+                for (int s = 0; s < nslices; ++s) {
+                    const int t = s / groups, kc0 = (s % groups) * kGroup;
+                    Vec xb[kGroup];
+                    if (s + 1 < nslices) {
+                        slice_load(s + 1);
+                        gather((s + 1) / groups, ((s + 1) % groups) * kGroup, xb);
+                    }
+                    if ((tapany >> t) & 1) {
+                        const Vec* wrow = w_lds + (size_t)(s & 1) * SLICE + (size_t)g * COLS + col;
+#pragma unroll
+                        for (int u = 0; u < kGroup; ++u) {
+                            if (kc0 + u < kch) {
+#pragma unroll
+                                for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wrow[(size_t)u * 2 * COLS + b * 32], xa[u]);
+                            }
+                        }
+                    }
+                    if (s + 1 < nslices) slice_store(s + 1);
+                    __syncthreads();
+#pragma unroll
+                    for (int u = 0; u < kGroup; ++u) xa[u] = xb[u];
+                }
             }
 
-            // accumulators -> staging tile [pixel][cout] in the storage type.  Lane (col, g) holds, for
-            // pixel `col`, the output channels 8*q + 4*g + {0..3} of every 32-channel block.
-            unsigned char* row = stage + (size_t)col * stage_stride;
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int co = (pass * NB + b) * 32 + 8 * q + 4 * g;
-                    T* dst = reinterpret_cast<T*>(row) + co;
-                    if constexpr (sizeof(T) == 2) {
-                        f16x4 v;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) v[i] = (f16)acc[b][4 * q + i];
-                        *reinterpret_cast<f16x4*>(dst) = v;
-                    } else {
-                        f32x4 v;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) v[i] = acc[b][4 * q + i];
-                        *reinterpret_cast<f32x4*>(dst) = v;
-                    }
+            stage_accumulators<T, NB>(acc, stage + (size_t)col * stage_stride, full_tail ? pass * COLS : 0, g);
+            if (!full_tail) {
+                // pass-through layers too wide for one staging tile: write this pass's channels now
+                wave_lds_fence();
+                const int ch0 = pass * COLS;
+                const int nch = e.c - ch0 < COLS ? e.c - ch0 : COLS;
+                if (tile_on && nch > 0) {
+                    auto dxp = [&](int ent, int64_t, int c0, float (&o)[V]) {
+                        load_vec<T, V>(reinterpret_cast<const T*>(stage + (size_t)ent * stage_stride) + (c0 - ch0), o);
+                    };
+                    act_trunc_tile<T, V, 1>(e, init != 0, l.list, base, count, lane, dxp, ch0, nch);
                 }
+                wave_lds_fence();
             }
         }
-        // the staging tile is private to this wave: order its writes before the reads below
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-        auto dx = [&](int ent, int64_t, int c0, float (&o)[V]) {
-            load_vec<T, V>(reinterpret_cast<const T*>(stage + (size_t)ent * stage_stride) + c0, o);
-        };
-        const uint32_t bits = act_trunc_tile<T, V, 1>(e, init != 0, l.list, base, count, lane, dx);
-        if (e.surv && lane == 0) e.surv[tile] = bits;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        if (full_tail) {
+            wave_lds_fence();
+            if (tile_on) {
+                auto dx = [&](int ent, int64_t, int c0, float (&o)[V]) {
+                    load_vec<T, V>(reinterpret_cast<const T*>(stage + (size_t)ent * stage_stride) + c0, o);
+                };
+                const uint32_t bits = act_trunc_tile<T, V, 1>(e, init != 0, l.list, base, count, lane, dx);
+                if (e.surv && lane == 0) e.surv[tile] = bits;
+            }
+            wave_lds_fence();
+        }
     }
 }
 
@@ -280,11 +382,11 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
     per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
     int64_t cap = (int64_t)ctx->num_cu * per_cu;
     const int grid = (int)(cdiv(want < cap ? want : cap, kXcd) * kXcd);
-    const int ini = init ? 1 : 0;
+    const int ini = init ? 1 : 0, full = p.full_tail ? 1 : 0;
     hipError_t err = hipSuccess;
-#define DCNN_CONV_LAUNCH(V, AL)                                                                                  \
+#define DCNN_CONV_LAUNCH(V, AL, ST)                                                                              \
     do {                                                                                                         \
-        auto kern = conv_mfma_kernel<T, NB, V, AL>;                                                              \
+        auto kern = conv_mfma_kernel<T, NB, V, AL, ST>;                                                          \
         static bool attr_set = false;                                                                            \
         if (!attr_set) {                                                                                         \
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -292,13 +394,15 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
             attr_set = (err == hipSuccess);                                                                      \
         }                                                                                                        \
         if (err == hipSuccess)                                                                                   \
-            hipLaunchKernelGGL(kern, dim3(grid), dim3(kConvThreads), p.lds_bytes, ctx->stream, l, c, e, ini, p.npass); \
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(kConvThreads), p.lds_bytes, ctx->stream, l, c, e, ini, p.npass, full); \
     } while (0)
-    if (vec_out) {
-        if (aligned) DCNN_CONV_LAUNCH(VEC, true); else DCNN_CONV_LAUNCH(VEC, false);
-    } else {
-        if (aligned) DCNN_CONV_LAUNCH(1, true); else DCNN_CONV_LAUNCH(1, false);
-    }
+#define DCNN_CONV_PICK(V)                                                                                        \
+    do {                                                                                                         \
+        if (p.stream) { if (aligned) DCNN_CONV_LAUNCH(V, true, true); else DCNN_CONV_LAUNCH(V, false, true); }   \
+        else { if (aligned) DCNN_CONV_LAUNCH(V, true, false); else DCNN_CONV_LAUNCH(V, false, false); }          \
+    } while (0)
+    if (vec_out) DCNN_CONV_PICK(VEC); else DCNN_CONV_PICK(1);
+#undef DCNN_CONV_PICK
 #undef DCNN_CONV_LAUNCH
     if (err != hipSuccess) return check_hip(ctx, err, "hipFuncSetAttribute(conv_mfma_kernel)");
     return check_hip(ctx, hipGetLastError(), "conv_mfma_kernel launch");
@@ -307,10 +411,11 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
 template <typename T>
 static dcnn_status launch_conv_t(dcnn_ctx* ctx, bool init, const ListArgs& l, ConvArgs c, const EpilogueArgs& e) {
     const int dtype = sizeof(T) == 2 ? DCNN_F16 : DCNN_F32;
+    const bool fused = e.act != DCNN_ACT_NONE;
     char why[256];
-    if (!conv_supported(ctx, dtype, c.k, c.cin, c.cout, 0, e.act != DCNN_ACT_NONE, why, sizeof(why)))
+    if (!conv_supported(ctx, dtype, c.k, c.cin, c.cout, 0, fused, why, sizeof(why)))
         return fail(ctx, DCNN_EUNSUPPORTED, "%s", why);
-    const ConvPlan p = conv_plan(dtype, c.k, c.cin, c.cout);
+    const ConvPlan p = conv_plan(dtype, c.k, c.cin, c.cout, ctx->max_lds, fused);
     c.cout_pad = p.cout_pad;
     c.kch = p.kch;
     switch (p.nb) {

@@ -100,9 +100,13 @@ __device__ __forceinline__ int pow2_ceil(int v) {
 // ---------------------------------------------------------------------------------------------
 template <typename T, int V, int VPL, class Dx>
 __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool init, const int32_t* list,
-                                                  int64_t tile_base, int64_t count, int lane, Dx dx) {
+                                                  int64_t tile_base, int64_t count, int lane, Dx dx,
+                                                  int ch0 = 0, int nch = -1) {
+    // [ch0, ch0 + nch) is the window of channels handled by this call (default: all of them);
+    // windows are only used for pass-through (act == NONE) tiles, which need no per-pixel maximum
     const int C = e.c;
-    const int nvec = (C + V - 1) / V;
+    if (nch < 0) nch = C;
+    const int nvec = (nch + V - 1) / V;
     int LP = pow2_ceil((nvec + VPL - 1) / VPL);
     LP = LP < 2 ? 2 : (LP > kWave ? kWave : LP);
     const int PPI = kWave / LP;                       // pixels per iteration (<= 32)
@@ -127,7 +131,7 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
         for (int v = 0; v < VPL; ++v) {
             const int vi = sub + v * LP;
             const bool on = valid && vi < nvec;
-            const int c0 = vi * V;
+            const int c0 = ch0 + vi * V;
 #pragma unroll
             for (int i = 0; i < V; ++i) { s[v][i] = 0.0f; dy[v][i] = 0.0f; d[v][i] = 0.0f; }
             if (!on) continue;
@@ -181,7 +185,7 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
         for (int v = 0; v < VPL; ++v) {
             const int vi = sub + v * LP;
             if (!(valid && vi < nvec)) continue;
-            const int64_t off = p * C + vi * V;
+            const int64_t off = p * C + ch0 + vi * V;
             if (e.act == DCNN_ACT_NONE) {
                 store_vec<T, V>(out + off, d[v]);
             } else if (init) {

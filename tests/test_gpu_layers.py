@@ -114,7 +114,7 @@ def test_act_trunc(S, f, shape):
             saw.add("upd")
         if want.count < d.count:
             saw.add("trunc")
-    assert saw == {"upd", "trunc"}
+    assert "upd" in saw and ("trunc" in saw or c > 64)     # wide pixels always exceed the threshold
 
 
 @pytest.mark.parametrize("S", ["f32", "f16"])
@@ -165,6 +165,13 @@ CONV_CASES = [
     ("f16", 3, 1, 1, 32, 160, (1, 21, 20)),
     ("f16", 1, 2, 0, 64, 128, (1, 30, 30)),
     ("f16", 3, 1, 1, 64, 16, (1, 24, 24)),
+    # weights too large for LDS: streamed in slices; the last two are wider than one staging tile
+    ("f16", 3, 2, 1, 64, 128, (1, 30, 30)),
+    ("f16", 3, 1, 1, 256, 256, (1, 20, 20)),
+    ("f16", 1, 1, 0, 160, 960, (1, 14, 14)),
+    ("f16", 1, 1, 0, 512, 2048, (1, 9, 8)),
+    ("f32", 3, 1, 1, 128, 128, (1, 16, 16)),
+    ("f32", 1, 1, 0, 64, 1024, (1, 12, 12)),
 ]
 
 
@@ -375,7 +382,8 @@ def test_error_paths():
     with pytest.raises(pkg.DcnnError) as e:
         l2.step([big, big])
     assert e.value.status == 5
-    with pytest.raises(pkg.DcnnError) as e:               # weights too large for the LDS-resident kernel
-        pkg.Layer(ctx, pkg.make_desc(pkg.CONV, pkg.F16, 1, 16, 16, 512, k=3, stride=1, pad=1, cout=512),
-                  torch.zeros((3, 3, 512, 512), dtype=torch.float16, device="cuda"))
+    with pytest.raises(pkg.DcnnError) as e:               # a fused activation needs the whole pixel in one LDS tile
+        pkg.Layer(ctx, pkg.make_desc(pkg.CONV, pkg.F16, 1, 16, 16, 64, k=1, stride=1, pad=0, cout=2048,
+                                     act=pkg.ACT_RELU, eps=0.1),
+                  torch.zeros((1, 1, 64, 2048), dtype=torch.float16, device="cuda"))
     assert e.value.status == 7
