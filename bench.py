@@ -1,0 +1,369 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse frame-difference inference path on one MI355X.
+
+Workload (benchmark configs[1]): ResNet bottleneck block (1x1 64->64, 3x3 64->64, 1x1 64->256,
+projection shortcut 1x1 64->256, add, ReLU), 128x128 NHWC fp16, 16-frame synthetic video with 4
+moving objects per stream, `--streams` independent camera streams batched on the GPU.  A "step" is
+one frame of every stream through the whole path (delta generation -> ... -> accumulated dense
+output); inputs are resident in HBM before the timed region.  Update density is set by a single
+global threshold found by bisection.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
+MFMA_F16_PEAK_TFLOPS = 2500.0   # dense fp16 matrix peak
+DENSITIES = [0.05, 0.10, 0.20, 0.50]
+HEADLINE_DENSITY = 0.10
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+# ---- algorithmic work of one layer step, from the layer's own counters -----------------------------
+def layer_bytes(s: dict, b: int) -> float:
+    """Bytes the method itself must move for one step of a layer (delta / state / weights / masks)."""
+    from paper_2203_03996_amd import DELTAGEN, CONV, DWCONV, ACT, MAXPOOL, UPSAMPLE, ACCUM, ACT_NONE
+    kind, cin, cout = s["kind"], s["c_in"], s["c_out"]
+    work, out, pin, pin2 = s["pixels_work"], s["pixels_out"], s["pixels_in"], s["pixels_in2"]
+    if kind == DELTAGEN:
+        return 2.0 * s["pixels_total"] * cin * b + 2.0 * out * cin * b + s["pixels_total"]
+    if kind == ACCUM:
+        return 3.0 * pin * cin * b
+    total = 0.0
+    if kind in (CONV, DWCONV):
+        total += pin * cin * b                                            # every flagged input once
+        total += s["k"] ** 2 * (cout if kind == DWCONV else cin * cout) * b   # weights once per launch
+    elif kind == ACT:
+        total += pin * cin * b
+    elif kind == MAXPOOL:
+        return 3.0 * pin * cin * b + work * cout * b
+    elif kind == UPSAMPLE:
+        return pin * cin * b + work * cout * b
+    if s["n_in"] == 2:
+        total += pin2 * cout * b                                          # residual stream
+    if s["act"] != ACT_NONE:
+        total += work * 2 * cout * b                                      # read x^A, x^T
+        total += out * 3 * cout * b + (work - out) * cout * b             # write x^A, x^T, delta | x^T
+        total += 2 * work                                                 # mask bytes
+    else:
+        total += work * cout * b
+    return total
+
+
+def layer_flops(s: dict) -> tuple[float, float]:
+    """(needed, issued) FLOPs of one step of a convolution layer (1 multiply-add = 2 FLOP)."""
+    from paper_2203_03996_amd import CONV, DWCONV
+    if s["kind"] not in (CONV, DWCONV):
+        return 0.0, 0.0
+    per = s["c_out"] if s["kind"] == DWCONV else s["c_in"] * s["c_out"]
+    taps = s["k"] ** 2
+    return 2.0 * s["pixels_in"] * taps / s["stride"] ** 2 * per, 2.0 * s["pixels_work"] * taps * per
+
+
+class Workload:
+    def __init__(self, streams: int, frames: int = 16):
+        import workloads as wl
+        self.wl = wl
+        self.streams, self.frames = streams, frames
+        self.seed = wl.CONFIG_SEEDS[2]
+        base = wl.bottleneck_block(frames=frames)
+        self.weights = wl.make_weights(base, self.seed)
+        t0 = time.time()
+        vid = wl.make_batch(base["video"], self.seed, streams).astype(np.float16)     # [T,B,H,W,C]
+        self.video_np = vid
+        self.video = [torch.from_numpy(vid[t]).cuda() for t in range(frames)]
+        # consecutive steps always see neighbouring frames: play the clip forwards, then backwards
+        self.order = list(range(1, frames)) + list(range(frames - 2, -1, -1))
+        self.dense_flops = wl.dense_flops(base)
+        log(f"[bench] synthetic video {vid.shape} fp16 generated in {time.time() - t0:.1f}s")
+
+    def spec(self, eps: float):
+        return self.wl.bottleneck_block(eps=eps, frames=self.frames)
+
+
+def make_net(work: Workload, eps: float, streams: int):
+    import paper_2203_03996_amd as pkg
+    ctx = pkg.Context(streams * 128 * 128)
+    net = pkg.Net(ctx, work.spec(eps), work.weights, streams, 1)
+    return ctx, net
+
+
+def conv_density(stats) -> float:
+    """Mean over convolution layers of flagged input pixels / input pixels (Section 5 statistic)."""
+    from paper_2203_03996_amd import CONV, DWCONV
+    d = [s["pixels_in"] / s["pixels_in_total"] for s in stats if s["kind"] in (CONV, DWCONV)]
+    return float(np.mean(d)) if d else 0.0
+
+
+def measure_density(work: Workload, eps: float, streams: int = 2) -> float:
+    ctx, net = make_net(work, eps, streams)
+    frames = [f[:streams].contiguous() for f in work.video]
+    net.init(frames[0])
+    dens = []
+    for t in range(1, work.frames):
+        net.step(frames[t])
+        dens.append(conv_density(net.stats()))
+    return float(np.mean(dens))
+
+
+def calibrate(work: Workload, target: float) -> tuple[float, float]:
+    """Bisection on one global threshold until the mean conv-input density hits the target."""
+    lo, hi = 1e-4, 2.0                      # density falls as the threshold rises
+    best = None
+    for _ in range(22):
+        mid = float(np.sqrt(lo * hi))
+        d = measure_density(work, mid)
+        if best is None or abs(d - target) < abs(best[1] - target):
+            best = (mid, d)
+        if abs(d - target) <= 0.005:
+            break
+        if d > target:
+            lo = mid
+        else:
+            hi = mid
+    return best
+
+
+def run_timed(work: Workload, eps: float, steps: int, warmup: int, streams: int, time_layer: int | None = None,
+              collect_stats: bool = False):
+    """Init + warm-up + `steps` timed steps.  Returns ms/step, optional kernel timing of one layer,
+    optional per-step per-layer counters (collected in an identical, untimed replay)."""
+    ctx, net = make_net(work, eps, streams)
+    frames = work.video if streams == work.streams else [f[:streams].contiguous() for f in work.video]
+    order = work.order
+    per_step_stats = None
+    if collect_stats:
+        net.init(frames[0])
+        per_step_stats = []
+        for k in range(warmup + steps):
+            net.step(frames[order[k % len(order)]])
+            if k >= warmup:
+                per_step_stats.append(net.stats())
+        net.reset()
+    net.init(frames[0])
+    for k in range(warmup):
+        net.step(frames[order[k % len(order)]])
+    if time_layer is not None:
+        net.set_timing(time_layer, steps)
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for k in range(warmup, warmup + steps):
+        net.step(frames[order[k % len(order)]])
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    kern = net.timing(time_layer) if time_layer is not None else None
+    return ms, kern, per_step_stats, net
+
+
+def profile_layers(work: Workload, eps: float, steps: int, warmup: int, streams: int):
+    """Per-layer kernel time (HIP events around each layer's main kernel) in a separate pass."""
+    ctx, net = make_net(work, eps, streams)
+    frames = work.video if streams == work.streams else [f[:streams].contiguous() for f in work.video]
+    net.init(frames[0])
+    for k in range(warmup):
+        net.step(frames[work.order[k % len(work.order)]])
+    for i in range(1, net.num_layers):
+        net.set_timing(i, steps)
+    for k in range(warmup, warmup + steps):
+        net.step(frames[work.order[k % len(work.order)]])
+    out = []
+    for i in range(net.num_layers):
+        if i == 0:
+            out.append(0.0)
+            continue
+        ms, n = net.timing(i)
+        out.append(ms / max(n, 1))
+    return out
+
+
+def dense_baseline(work: Workload, steps: int, warmup: int, streams: int):
+    """Ordinary dense inference of the same block on the same GPU through PyTorch-ROCm (MIOpen /
+    hipBLASLt), fp16 channels-last: the analogue of the paper's cuDNN row.  Comparison only."""
+    import torch.nn.functional as F
+    spec = work.spec(0.0)
+    tw = {}
+    for i, (w, b) in work.weights.items():
+        wt = torch.from_numpy(np.ascontiguousarray(w)).permute(3, 2, 0, 1).contiguous().half().cuda()
+        tw[i] = (wt.contiguous(memory_format=torch.channels_last), torch.from_numpy(b).half().cuda())
+    nodes = spec["nodes"]
+    frames = [f[:streams].permute(0, 3, 1, 2) for f in work.video]       # NHWC storage viewed as NCHW channels-last
+
+    def forward(x):
+        outs = []
+        for i, nd in enumerate(nodes):
+            k = nd["kind"]
+            if k == "deltagen":
+                y = x
+            elif k == "conv":
+                y = F.conv2d(outs[nd["in"][0]], tw[i][0], tw[i][1], stride=nd["stride"], padding=nd["pad"])
+            elif k == "act":
+                y = F.relu(outs[nd["in"][0]])
+            elif k == "add":
+                y = outs[nd["in"][0]] + outs[nd["in"][1]]
+            else:
+                y = outs[nd["in"][0]]
+            outs.append(y)
+        return outs[-1]
+
+    with torch.no_grad():
+        for k in range(warmup):
+            forward(frames[work.order[k % len(work.order)]])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for k in range(steps):
+            forward(frames[work.order[k % len(work.order)]])
+        e1.record()
+        torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def cpu_baseline(work: Workload, eps: float, budget_s: float = 12.0):
+    """The CPU oracle as it stands, timed on this machine's host cores on one stream of the same video."""
+    from oracle import deltacnn_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    spec = work.spec(eps)
+    vid = work.video_np[:, :1]
+    net = orc.OracleNet(spec, work.weights, "f16")
+    net.frame(vid[0])
+    done, t0 = 0, time.time()
+    k = 0
+    while time.time() - t0 < budget_s or done < 4:
+        net.frame(vid[work.order[k % len(work.order)]])
+        k += 1
+        done += 1
+    dt = time.time() - t0
+    return {"value": done / dt, "unit": "frames/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"1 stream, {done} sparse frames (frames >= 2) of the same clip at the headline threshold, "
+                      f"numpy fp16-storage oracle, {dt:.1f} s", "host_cpus": os.cpu_count()}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--streams", type=int, default=64, help="independent camera streams batched on the GPU")
+    ap.add_argument("--quick", action="store_true", help="headline measurement only (no sweep, no baselines)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (streams are independent; see DESIGN.md for how the "
+              "path would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    import paper_2203_03996_amd as pkg
+    pkg.load_library()
+    B, K, W = args.streams, args.steps, args.warmup
+    work = Workload(B)
+    b = 2                                                    # bytes per element (fp16)
+
+    # thresholds for the density sweep
+    eps_of = {}
+    for d in DENSITIES if not args.quick else [HEADLINE_DENSITY]:
+        eps, got = calibrate(work, d)
+        eps_of[d] = (eps, got)
+        log(f"[bench] density target {d:.2f}: eps {eps:.5f} -> measured {got:.4f}")
+
+    # headline: per-layer kernel profile picks the dominant kernel, then the timed region
+    eps_h = eps_of[HEADLINE_DENSITY][0]
+    prof = profile_layers(work, eps_h, min(K, 30), W, B)
+    dominant = int(np.argmax(prof))
+    ms, kern, stats, net = run_timed(work, eps_h, K, W, B, time_layer=dominant, collect_stats=True)
+    fps = B * 1e3 / ms
+    kern_ms = kern[0] / max(kern[1], 1)
+    dom_bytes = float(np.mean([layer_bytes(st[dominant], b) for st in stats]))
+    dom_need, dom_issued = [float(np.mean(x)) for x in zip(*[layer_flops(st[dominant]) for st in stats])]
+    achieved_gbs = dom_bytes / (kern_ms * 1e-3) / 1e9
+    step_bytes = float(np.mean([sum(layer_bytes(s, b) for s in st) for st in stats]))
+    dens_h = float(np.mean([conv_density(st) for st in stats]))
+    layer_names = []
+    for i in range(net.num_layers):
+        s = stats[0][i]
+        layer_names.append(f"{['deltagen','conv','dwconv','act','maxpool','upsample','accum'][s['kind']]}"
+                           f"{s['k']}x{s['k']}:{s['c_in']}->{s['c_out']}" + ("+res" if s["n_in"] == 2 else "") +
+                           ("+act" if s["act"] else ""))
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"streams{B}_density{HEADLINE_DENSITY}", {}).get("bytes_per_launch")
+        except Exception:
+            traffic = None
+    result = {
+        "metric": "frames/sec + dense-equiv GFLOP/s vs update density; HBM GB/s % peak",
+        "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "configs[1]: ResNet bottleneck block 64->64->256 (+1x1 projection shortcut), 128x128 "
+                               "NHWC fp16, 16-frame synthetic video, 4 moving objects per stream",
+                   "streams": B, "update_density": dens_h, "eps": eps_h, "frames_per_step": B,
+                   "density_definition": "mean over frames>=2 and conv layers of flagged input pixels / pixels"},
+        "dense_equiv_gflops": fps * work.dense_flops / 1e9,
+        "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": layer_names[dominant], "kernel_ms": kern_ms, "algorithmic_bytes_per_launch": dom_bytes,
+                     "needed_gflop_per_launch": dom_need / 1e9, "issued_gflop_per_launch": dom_issued / 1e9,
+                     "mfma_frac_of_fp16_peak": dom_issued / (kern_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS},
+        "whole_step": {"algorithmic_bytes": step_bytes, "achieved_gbs": step_bytes / (ms * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "layer_kernel_ms": dict(zip(layer_names, [round(x, 5) for x in prof]))},
+    }
+    if not args.quick:
+        sweep = []
+        for d in DENSITIES:
+            eps = eps_of[d][0]
+            ms_d, _, st_d, _ = run_timed(work, eps, K, W, B, collect_stats=True)
+            by = float(np.mean([sum(layer_bytes(s, b) for s in st) for st in st_d]))
+            sweep.append({"density_target": d, "density": float(np.mean([conv_density(st) for st in st_d])), "eps": eps,
+                          "ms_per_step": ms_d, "frames_per_s": B * 1e3 / ms_d,
+                          "dense_equiv_gflops": B * 1e3 / ms_d * work.dense_flops / 1e9,
+                          "algorithmic_gbs": by / (ms_d * 1e-3) / 1e9})
+            log(f"[bench] density {d}: {ms_d:.3f} ms/step, {B * 1e3 / ms_d:.0f} frames/s")
+        for name, eps in (("ours_dense_eps<0", -1.0), ("eps=inf", float("inf"))):
+            ms_d, _, _, _ = run_timed(work, eps, K, W, B)
+            sweep.append({"density_target": name, "eps": eps if np.isfinite(eps) else "inf", "ms_per_step": ms_d,
+                          "frames_per_s": B * 1e3 / ms_d, "dense_equiv_gflops": B * 1e3 / ms_d * work.dense_flops / 1e9})
+            log(f"[bench] {name}: {ms_d:.3f} ms/step")
+        ms1, _, _, _ = run_timed(work, eps_h, K, W, 1)
+        result["single_stream"] = {"streams": 1, "ms_per_step": ms1, "frames_per_s": 1e3 / ms1}
+        md = dense_baseline(work, K, W, B)
+        md1 = dense_baseline(work, K, W, 1)
+        result["dense_baseline"] = {"kind": "PyTorch-ROCm conv2d/relu/add fp16 channels-last, same GPU",
+                                    "streams": B, "ms_per_step": md, "frames_per_s": B * 1e3 / md,
+                                    "gflops": B * 1e3 / md * work.dense_flops / 1e9,
+                                    "single_stream_frames_per_s": 1e3 / md1}
+        result["sweep"] = sweep
+        result["speedup_vs_dense_at_headline"] = fps / (B * 1e3 / md)
+        result["cpu_baseline"] = cpu_baseline(work, eps_h)
+    else:
+        result["cpu_baseline"] = cpu_baseline(work, eps_h, budget_s=3.0)
+    result["paper_context"] = "paper reports up to 7x over cuDNN on Jetson Nano / GTX 1050 / RTX 3090 (other hardware; context only)"
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -104,9 +104,17 @@ typedef struct {
 /* Counters of the last step of a layer (Section 5 reports the same quantities per network). */
 typedef struct {
     int64_t pixels_in;      /* flagged pixels of input 0                       */
+    int64_t pixels_in2;     /* flagged pixels of input 1 (0 if there is none)  */
     int64_t pixels_work;    /* pixels the layer visited (its work list)        */
     int64_t pixels_out;     /* flagged pixels of the output                    */
     int64_t pixels_total;   /* n*h*w of the output                             */
+    int64_t pixels_in_total;/* n*h*w of input 0                                */
+    int32_t kind;           /* dcnn_kind of the layer                          */
+    int32_t act;            /* fused activation (dcnn_act)                     */
+    int32_t n_in;
+    int32_t c_in, c_out;    /* channels                                        */
+    int32_t k, stride;      /* window (convolutions, pooling), else 1          */
+    int32_t reserved;
 } dcnn_stats;
 
 typedef struct dcnn_ctx dcnn_ctx;
@@ -159,6 +167,12 @@ dcnn_status dcnn_layer_reset(dcnn_layer* layer);
 dcnn_status dcnn_layer_state(const dcnn_layer* layer, int32_t which, void** ptr_dev, size_t* bytes);
 /* Counters of the last step; synchronises the stream. */
 dcnn_status dcnn_layer_stats(dcnn_layer* layer, dcnn_stats* stats_host);
+/* Kernel timing for measurements: with max_steps > 0 the layer brackets its main compute kernel
+ * (not its mask passes) with HIP events on the context's stream for up to max_steps steps;
+ * 0 switches it off.  dcnn_layer_timing synchronises, reports the summed kernel time and the
+ * number of timed launches since the last call, and starts over. */
+dcnn_status dcnn_layer_set_timing(dcnn_layer* layer, int32_t max_steps);
+dcnn_status dcnn_layer_timing(dcnn_layer* layer, float* total_ms_host, int32_t* launches_host);
 
 /* ---- networks ------------------------------------------------------------------------------ */
 /* A network is a DAG of plain nodes (kinds above with act/n_in unfused: CONV has no activation,

@@ -29,7 +29,7 @@ EXPORTS = [
     "dcnn_workspace_bytes", "dcnn_ctx_create", "dcnn_ctx_destroy", "dcnn_ctx_sync", "dcnn_status_str",
     "dcnn_last_error", "dcnn_mask_compact", "dcnn_layer_query", "dcnn_layer_create", "dcnn_layer_destroy",
     "dcnn_layer_init", "dcnn_layer_step", "dcnn_layer_output", "dcnn_layer_reset", "dcnn_layer_state",
-    "dcnn_layer_stats", "dcnn_net_create", "dcnn_net_destroy", "dcnn_net_add", "dcnn_net_finalize",
+    "dcnn_layer_stats", "dcnn_layer_set_timing", "dcnn_layer_timing", "dcnn_net_create", "dcnn_net_destroy", "dcnn_net_add", "dcnn_net_finalize",
     "dcnn_net_bind", "dcnn_net_init", "dcnn_net_step", "dcnn_net_reset", "dcnn_net_output",
     "dcnn_net_num_layers", "dcnn_net_layer", "dcnn_net_stats",
 ]
@@ -53,8 +53,13 @@ class LayerSizes(C.Structure):
 
 
 class Stats(C.Structure):
-    _fields_ = [("pixels_in", C.c_int64), ("pixels_work", C.c_int64), ("pixels_out", C.c_int64),
-                ("pixels_total", C.c_int64)]
+    _fields_ = [("pixels_in", C.c_int64), ("pixels_in2", C.c_int64), ("pixels_work", C.c_int64),
+                ("pixels_out", C.c_int64), ("pixels_total", C.c_int64), ("pixels_in_total", C.c_int64),
+                ("kind", C.c_int32), ("act", C.c_int32), ("n_in", C.c_int32), ("c_in", C.c_int32),
+                ("c_out", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32), ("reserved", C.c_int32)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_ if name != "reserved"}
 
 
 class DcnnError(RuntimeError):
@@ -98,6 +103,8 @@ def load_library() -> C.CDLL:
     lib.dcnn_layer_reset.argtypes = [vp]
     lib.dcnn_layer_state.argtypes = [vp, i32, P(vp), P(sz)]
     lib.dcnn_layer_stats.argtypes = [vp, P(Stats)]
+    lib.dcnn_layer_set_timing.argtypes = [vp, i32]
+    lib.dcnn_layer_timing.argtypes = [vp, P(C.c_float), P(i32)]
     lib.dcnn_net_create.argtypes = [vp, i32, i32, i32, i32, i32, P(vp)]
     lib.dcnn_net_destroy.argtypes = [vp]
     lib.dcnn_net_destroy.restype = None
@@ -274,8 +281,7 @@ class Layer:
     def stats(self) -> dict:
         s = Stats()
         self.ctx.check(self.ctx.lib.dcnn_layer_stats(self.handle, C.byref(s)))
-        return {"pixels_in": s.pixels_in, "pixels_work": s.pixels_work, "pixels_out": s.pixels_out,
-                "pixels_total": s.pixels_total}
+        return s.as_dict()
 
     def __del__(self):
         try:
@@ -375,8 +381,20 @@ class Net:
     def stats(self):
         arr = (Stats * self.num_layers)()
         self.ctx.check(self.ctx.lib.dcnn_net_stats(self.handle, arr))
-        return [{"pixels_in": s.pixels_in, "pixels_work": s.pixels_work, "pixels_out": s.pixels_out,
-                 "pixels_total": s.pixels_total} for s in arr]
+        return [s.as_dict() for s in arr]
+
+    def set_timing(self, i: int, max_steps: int):
+        lh, nid = C.c_void_p(), C.c_int32()
+        self.ctx.check(self.ctx.lib.dcnn_net_layer(self.handle, i, C.byref(lh), C.byref(nid)))
+        self.ctx.check(self.ctx.lib.dcnn_layer_set_timing(lh, max_steps))
+
+    def timing(self, i: int):
+        """(summed kernel milliseconds, launches) of layer i since the last call."""
+        lh, nid = C.c_void_p(), C.c_int32()
+        self.ctx.check(self.ctx.lib.dcnn_net_layer(self.handle, i, C.byref(lh), C.byref(nid)))
+        ms, n = C.c_float(), C.c_int32()
+        self.ctx.check(self.ctx.lib.dcnn_layer_timing(lh, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     def __del__(self):
         try:

@@ -10,24 +10,31 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libdeltacnn.so")
-SOURCES = ["ctx.hip", "mask_kernels.hip", "tile_kernels.hip", "conv_kernels.hip", "layer.hip", "net.hip"]
+SOURCES = [("ctx.hip", "ctx.o", []), ("mask_kernels.hip", "mask_kernels.o", []), ("tile_kernels.hip", "tile_kernels.o", []),
+           ("conv_kernels.hip", "conv_kernels.o", []), ("layer.hip", "layer.o", []), ("net.hip", "net.o", [])]
+# the MFMA convolution kernels: one object per (element type, accumulator block count), built in parallel
+for _t, _tn in (("f16", "f16"), ("float", "f32")):
+    for _nb in (4, 3, 2, 1):
+        SOURCES.append(("conv_inst.hip", f"conv_{_tn}_nb{_nb}.o",
+                        [f"-DDCNN_CONV_T={_t}", f"-DDCNN_CONV_TNAME={_tn}", f"-DDCNN_CONV_NB={_nb}"]))
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build(verbose: bool = False, jobs: int = 6) -> str:
+def build(verbose: bool = False, jobs: int = 8) -> str:
     os.makedirs(LIBDIR, exist_ok=True)
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-    def compile_one(src: str) -> str:
-        obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    def compile_one(item) -> str:
+        src, objname, extra = item
+        obj = os.path.join(objdir, objname)
+        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+            raise RuntimeError(f"hipcc failed on {src} {extra}:\n{err}")
         if verbose and err.strip():
             print(err, file=sys.stderr)
         return obj

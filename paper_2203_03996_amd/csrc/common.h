@@ -56,6 +56,7 @@ struct MaskPassArgs {
     int32_t* count_out;
     int n, h, w, oh, ow, k, stride, pad;
     int up;                      // > 1: nearest upsampling of the input mask by this factor (k = 1)
+    int32_t* zero_count;         // optional counter the pass resets to 0 (survivor count of the layer)
     int emit_only;               // 1: mask_in is final and its chunk counts are in the workspace already
 };
 dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& a);
@@ -79,6 +80,7 @@ struct EpilogueArgs {
     void* out_data;
     uint8_t* out_mask;           // written at every visited pixel (0 or 1); nullptr: not written
     uint32_t* surv;              // survivor word per tile; nullptr: not written
+    int32_t* out_count;          // when surv is null: survivors are added here (zeroed by the mask pass)
 };
 
 struct ListArgs {
@@ -92,14 +94,15 @@ struct ConvArgs {
     const void* in_data;
     const uint8_t* in_mask;      // nullptr: every in-bounds pixel is flagged (first frame)
     const void* wpacked;
+    const void* zero_page;       // >= 16 bytes of zeros: what lanes read instead of an unflagged / padded input
     int n, h, w, cin, oh, ow, cout, cout_pad, k, stride, pad, kch;
     int depthwise;
 };
 dcnn_status launch_conv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const ConvArgs& c,
                         const EpilogueArgs& e);
-size_t conv_packed_weight_bytes(int dtype, int k, int cin, int cout, int depthwise);
+size_t conv_packed_weight_bytes(int dtype, int k, int cin, int cout, int depthwise, bool fused);
 dcnn_status launch_pack_weights(dcnn_ctx* ctx, int dtype, const void* w, void* wpacked, int k, int cin, int cout,
-                                int depthwise);
+                                int depthwise, bool fused);
 bool conv_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cout, int depthwise, bool fused,
                     char* why, size_t why_len);
 

@@ -1,0 +1,308 @@
+// Sparse delta convolution with dense weights as a gather-GEMM on the matrix cores.
+//
+// The work list holds the flagged OUTPUT pixels in ascending order.  A tile of 32 consecutive list
+// entries is owned by `cs` wavefronts, each computing nb*32 of the output channels:
+//     D[cout][pixel] += W_tap[cout][cin] * X_tap[cin][pixel]        for every window tap
+// with MFMA 32x32 blocks (A operand = weights from LDS, B operand = the pixel's channels gathered
+// straight from the NHWC delta map into registers, 16 bytes per lane).  A tap contributes only
+// where the input pixel is in bounds AND flagged; every other lane reads a page of zeros instead,
+// so the inner loop has no branches and unflagged memory (invalid by contract) is never touched.
+// When the packed weight tensor of the layer fits, it stays resident in LDS (160 KB per CU on
+// gfx950) for the lifetime of the persistent workgroup.  Larger layers stream it: the waves of a
+// workgroup walk the K dimension in lockstep and a double-buffered 4-K-step slice of the weights
+// is copied global -> registers -> LDS while the matrix cores consume the previous slice.
+// The fp32 result tile is rounded to the storage type, staged through LDS (private to the wave)
+// and handed to the activation + truncation tail with coalesced accesses; waves that share a tile
+// agree on the per-pixel maximum through LDS.
+#pragma once
+
+#include "conv_plan.h"
+
+namespace dcnn {
+
+// accumulators -> staging tile [pixel][nb*32 channels] in the storage type.  Lane (col, g) holds,
+// for pixel `col`, the output channels 8*q + 4*g + {0..3} of every 32-channel block.
+template <typename T, int NB>
+__device__ __forceinline__ void stage_accumulators(const f32x16 (&acc)[NB], unsigned char* row, int g) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            T* dst = reinterpret_cast<T*>(row) + b * 32 + 8 * q + 4 * g;
+            if constexpr (sizeof(T) == 2) {
+                f16x4 v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = (f16)acc[b][4 * q + i];
+                *reinterpret_cast<f16x4*>(dst) = v;
+            } else {
+                f32x4 v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = acc[b][4 * q + i];
+                *reinterpret_cast<f32x4*>(dst) = v;
+            }
+        }
+    }
+}
+
+template <typename T, int NB, int V, bool ALIGNED, bool STREAM, int KS>
+__global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init,
+                                                                 int npass, int cs) {
+    typedef typename Mma<T>::Vec Vec;
+    typedef typename RawOf<T, V>::type Raw;
+    constexpr int KP = Mma<T>::KPACK;
+    constexpr int COLS = NB * 32;
+    constexpr int GK = 4;                                      // K-steps whose gathers are in flight together
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tiles_per_iter = kConvWaves / cs;
+    const int64_t count = list_count(l);
+    const WgTileRange r = wg_tile_range((count + tiles_per_iter * kTile - 1) / (tiles_per_iter * kTile));
+    if (r.begin >= r.end) return;                              // nothing for this workgroup: skip the weight load
+
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int col = lane % 32, g = lane / 32;
+    const int slot = wave / cs, part = wave % cs;              // which tile of the iteration, which channel slice
+    const int ksz = KS ? KS : c.k;
+    const int taps = ksz * ksz, kch = c.kch;
+    const int ksteps = taps * kch;
+    const bool full_tail = npass == 1;
+    const int slice_vecs = cs * kGroup * 2 * COLS;             // one streamed slice (all channel slices)
+    const int w_vecs = STREAM ? 2 * slice_vecs : npass * cs * ksteps * 2 * COLS;
+    Vec* w_lds = reinterpret_cast<Vec*>(smem);
+    constexpr int stage_stride = COLS * (int)sizeof(T) + kStagePad;
+    unsigned char* stage = smem + (size_t)w_vecs * 16 + (size_t)wave * kTile * stage_stride;
+    float* xchg = reinterpret_cast<float*>(smem + (size_t)w_vecs * 16 + (size_t)kConvWaves * kTile * stage_stride) +
+                  (size_t)slot * 2 * cs * kTile;
+    const Vec* wglob = static_cast<const Vec*>(c.wpacked);
+    const T* in = static_cast<const T*>(c.in_data);
+    const T* zeros = static_cast<const T*>(c.zero_page);
+
+    if constexpr (!STREAM) {
+        for (int i = threadIdx.x; i < w_vecs; i += kConvThreads) w_lds[i] = wglob[i];
+        lds_block_sync();
+    }
+
+    for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
+        // ---- the tile: pixel of this lane's column, window origin, which taps are needed ---------
+        const int64_t tile = wt * tiles_per_iter + slot;
+        const int64_t base = tile * kTile;
+        const int p32 = list_pixel(l.list, base + col, count);
+        const bool valid = p32 >= 0;
+        const int64_t p = valid ? p32 : 0;
+        const int ox = (int)(p % c.ow);
+        const int64_t t1 = p / c.ow;
+        const int oy = (int)(t1 % c.oh);
+        const int64_t n = t1 / c.oh;
+        const int iy0 = oy * c.stride - c.pad, ix0 = ox * c.stride - c.pad;
+        uint64_t tapbits = 0;
+        if constexpr (KS != 0) {
+            // fixed window: all update flags of the window are requested at once, then tested
+            uint8_t flag[KS * KS];
+#pragma unroll
+            for (int t = 0; t < KS * KS; ++t) {
+                const int iy = iy0 + t / KS, ix = ix0 + t % KS;
+                const bool inb = valid && iy >= 0 && iy < c.h && ix >= 0 && ix < c.w;
+                const int64_t q = inb ? (n * c.h + iy) * c.w + ix : 0;
+                flag[t] = c.in_mask ? c.in_mask[q] : (uint8_t)1;
+                if (!inb) flag[t] = 0;
+            }
+#pragma unroll
+            for (int t = 0; t < KS * KS; ++t)
+                if (flag[t]) tapbits |= 1ull << t;
+        } else {
+            for (int t = 0; t < taps; ++t) {
+                const int iy = iy0 + t / ksz, ix = ix0 + t % ksz;
+                bool ok = valid && iy >= 0 && iy < c.h && ix >= 0 && ix < c.w;
+                if (ok && c.in_mask) ok = c.in_mask[(n * c.h + iy) * c.w + ix] != 0;
+                if (ok) tapbits |= 1ull << t;
+            }
+        }
+
+        // 16 bytes of input channels of K-step s = t*kch + kc for this lane's pixel; lanes that do not
+        // need the tap (or whose channels are padding) read the zero page
+        auto gather_one = [&](int s) -> Vec {
+            const int t = s / kch, kc = s - t * kch;
+            const int ch = (2 * kc + g) * KP;
+            const bool ok = s < ksteps && ((tapbits >> t) & 1) && ch < c.cin;
+            const int iy = iy0 + t / ksz, ix = ix0 + t % ksz;
+            const T* src = ok ? in + ((n * c.h + iy) * c.w + ix) * c.cin + ch : zeros;
+            if constexpr (ALIGNED) {
+                return *reinterpret_cast<const Vec*>(src);
+            } else {
+                Vec v;
+#pragma unroll
+                for (int i = 0; i < KP; ++i) v[i] = (ok && ch + i < c.cin) ? src[i] : (T)0.0f;
+                return v;
+            }
+        };
+
+        for (int pass = 0; pass < npass; ++pass) {
+            const int cgroup = pass * cs + part;               // which group of COLS output channels
+            f32x16 acc[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+
+            if constexpr (!STREAM) {
+                // weights resident: waves run independently; the gathers of the next GK K-steps are in
+                // flight while the matrix cores work on the current ones
+                const Vec* wbase = w_lds + ((size_t)cgroup * ksteps * 2 + g) * COLS + col;
+                Vec xa[GK], xb[GK];
+#pragma unroll
+                for (int u = 0; u < GK; ++u) xa[u] = gather_one(u);
+                for (int s0 = 0; s0 < ksteps; s0 += GK) {
+                    if (s0 + GK < ksteps) {
+#pragma unroll
+                        for (int u = 0; u < GK; ++u) xb[u] = gather_one(s0 + GK + u);
+                    }
+#pragma unroll
+                    for (int u = 0; u < GK; ++u) {
+                        if (s0 + u < ksteps) {
+                            const Vec* wrow = wbase + (size_t)(s0 + u) * 2 * COLS;
+#pragma unroll
+                            for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wrow[b * 32], xa[u]);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < GK; ++u) xa[u] = xb[u];
+                }
+            } else {
+                // weights streamed: all waves walk the slices (tap, group of 4 K-steps) in lockstep;
+                // slice i+1 travels global -> registers while slice i is multiplied, then registers ->
+                // LDS, one barrier per slice.  A slice holds the weights of all `cs` channel slices.
+                const int groups = (kch + kGroup - 1) / kGroup;
+                const int nslices = taps * groups;
+                constexpr int WREG = 4 * NB / 2;               // >= cs * kGroup * 2 * COLS / kConvThreads for cs <= 4
+                Vec wreg[WREG];
+                auto slice_load = [&](int si) {
+                    const int t = si / groups, kc0 = (si % groups) * kGroup;
+                    const int steps = kch - kc0 < kGroup ? kch - kc0 : kGroup;
+                    const int per_part = steps * 2 * COLS;
+#pragma unroll
+                    for (int i = 0; i < WREG; ++i) {
+                        const int vi = threadIdx.x + i * kConvThreads;
+                        const int q = vi / (kGroup * 2 * COLS), o = vi - q * (kGroup * 2 * COLS);
+                        if (q < cs && o < per_part)
+                            wreg[i] = wglob[((size_t)((pass * cs + q) * ksteps + t * kch + kc0) * 2) * COLS + o];
+                    }
+                };
+                auto slice_store = [&](int si) {
+                    const int kc0 = (si % groups) * kGroup;
+                    const int steps = kch - kc0 < kGroup ? kch - kc0 : kGroup;
+                    const int per_part = steps * 2 * COLS;
+                    Vec* dst = w_lds + (size_t)(si & 1) * slice_vecs;
+#pragma unroll
+                    for (int i = 0; i < WREG; ++i) {
+                        const int vi = threadIdx.x + i * kConvThreads;
+                        const int q = vi / (kGroup * 2 * COLS), o = vi - q * (kGroup * 2 * COLS);
+                        if (q < cs && o < per_part) dst[vi] = wreg[i];
+                    }
+                };
+                auto gather_slice = [&](int si, Vec (&x)[kGroup]) {
+                    const int t = si / groups, kc0 = (si % groups) * kGroup;
+#pragma unroll
+                    for (int u = 0; u < kGroup; ++u) x[u] = gather_one(kc0 + u < kch ? t * kch + kc0 + u : ksteps);
+                };
+                Vec xa[kGroup], xb[kGroup];
+                slice_load(0);
+                gather_slice(0, xa);
+                slice_store(0);
+                lds_block_sync();
+                for (int si = 0; si < nslices; ++si) {
+                    const int kc0 = (si % groups) * kGroup;
+                    if (si + 1 < nslices) {
+                        slice_load(si + 1);
+                        gather_slice(si + 1, xb);
+                    }
+                    const Vec* wrow = w_lds + (size_t)(si & 1) * slice_vecs + (size_t)part * (kGroup * 2 * COLS) +
+                                      (size_t)g * COLS + col;
+#pragma unroll
+                    for (int u = 0; u < kGroup; ++u) {
+                        if (kc0 + u < kch) {
+#pragma unroll
+                            for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wrow[(size_t)u * 2 * COLS + b * 32], xa[u]);
+                        }
+                    }
+                    if (si + 1 < nslices) slice_store(si + 1);
+                    lds_block_sync();
+#pragma unroll
+                    for (int u = 0; u < kGroup; ++u) xa[u] = xb[u];
+                }
+            }
+
+            // ---- tail: this wave's channel slice of the tile ------------------------------------
+            stage_accumulators<T, NB>(acc, stage + (size_t)col * stage_stride, g);
+            lds_wave_sync();
+            const int ch0 = cgroup * COLS;
+            int nch = e.c - ch0;
+            nch = nch < 0 ? 0 : (nch > COLS ? COLS : nch);
+            auto dx = [&](int ent, int64_t, int c0) -> Raw {
+                return raw_load<T, V>(reinterpret_cast<const T*>(stage + (size_t)ent * stage_stride) + (c0 - ch0));
+            };
+            const MaxExchange mx{xchg, cs, part};
+            uint32_t bits;
+            if (cs > 1 && full_tail && e.act != DCNN_ACT_NONE && !init)
+                bits = act_trunc_tile<T, V, 1, 4, true>(e, false, p32, lane, dx, ch0, nch, COLS, mx);
+            else
+                bits = act_trunc_tile<T, V, 1, 4, false>(e, init != 0, p32, lane, dx, ch0, nch, COLS, mx);
+            if (full_tail && lane == 0 && part == 0 && base < count) {
+                if (e.surv) e.surv[tile] = bits;
+                else if (e.out_count) atomicAdd(e.out_count, __popc(bits));
+            }
+            lds_wave_sync();
+        }
+    }
+}
+
+template <typename T, int NB>
+static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, const ConvArgs& c, const EpilogueArgs& e,
+                                  const ConvPlan& p) {
+    constexpr int VEC = Elem<T>::VEC;
+    const bool vec_out = (e.c % VEC) == 0;
+    const bool aligned = ((size_t)c.cin * sizeof(T)) % 16 == 0;
+    const int tiles_per_iter = kConvWaves / p.cs;
+    int64_t want = cdiv(l.max_count > 0 ? l.max_count : 1, tiles_per_iter * kTile);
+    int64_t per_cu = (int64_t)(kLdsBytes / p.lds_bytes);
+    per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
+    int64_t cap = (int64_t)ctx->num_cu * per_cu;
+    const int grid = (int)(cdiv(want < cap ? want : cap, kXcd) * kXcd);
+    const int ini = init ? 1 : 0;
+    hipError_t err = hipSuccess;
+    bool launched = false;
+#define DCNN_CONV_LAUNCH(V, AL, ST, KS)                                                                          \
+    do {                                                                                                         \
+        auto kern = conv_mfma_kernel<T, NB, V, AL, ST, KS>;                                                      \
+        static bool attr_set = false;                                                                            \
+        if (!attr_set) {                                                                                         \
+            err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                      (int)kLdsBytes);                                                           \
+            attr_set = (err == hipSuccess);                                                                      \
+        }                                                                                                        \
+        if (err == hipSuccess)                                                                                   \
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(kConvThreads), p.lds_bytes, ctx->stream, l, c, e, ini, p.npass, p.cs); \
+        launched = true;                                                                                         \
+    } while (0)
+    // instantiated combinations: the common case (16-byte aligned input pixels, vector-width output
+    // channels) is specialised on the window size; odd shapes take the generic-window kernels
+    if (vec_out && aligned) {
+        if (p.stream) DCNN_CONV_LAUNCH(VEC, true, true, 0);
+        else if (c.k == 1) DCNN_CONV_LAUNCH(VEC, true, false, 1);
+        else if (c.k == 3) DCNN_CONV_LAUNCH(VEC, true, false, 3);
+        else DCNN_CONV_LAUNCH(VEC, true, false, 0);
+    } else if (vec_out && !p.stream) {
+        DCNN_CONV_LAUNCH(VEC, false, false, 0);
+    } else if (!vec_out && !p.stream) {
+        if constexpr (NB <= 2) {
+            if (aligned) DCNN_CONV_LAUNCH(1, true, false, 0); else DCNN_CONV_LAUNCH(1, false, false, 0);
+        }
+    }
+#undef DCNN_CONV_LAUNCH
+    if (!launched)
+        return fail(ctx, DCNN_EUNSUPPORTED, "conv %dx%d %d->%d: no kernel for this combination of channel alignment and size",
+                    c.k, c.k, c.cin, c.cout);
+    if (err != hipSuccess) return check_hip(ctx, err, "hipFuncSetAttribute(conv_mfma_kernel)");
+    return check_hip(ctx, hipGetLastError(), "conv_mfma_kernel launch");
+}
+
+}  // namespace dcnn

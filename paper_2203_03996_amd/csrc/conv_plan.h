@@ -1,0 +1,90 @@
+// Shared by the convolution translation units: launch constants, MFMA traits and the plan that
+// packing, sizing and launching agree on.
+#pragma once
+
+#include "device_utils.h"
+
+namespace dcnn {
+
+constexpr int kConvWaves = 8;                       // waves per workgroup; they share the weights in LDS
+constexpr int kConvThreads = kConvWaves * kWave;
+constexpr int kStagePad = 16;                       // bytes added to a staging row against bank conflicts
+constexpr int kGroup = 4;                           // K-steps per streamed weight slice
+constexpr size_t kLdsBytes = 160 * 1024;            // LDS of one gfx950 compute unit; the context refuses less
+
+template <typename T> struct Mma;
+template <> struct Mma<f16> {
+    typedef f16x8 Vec;
+    static constexpr int KPACK = 8;
+    static __device__ __forceinline__ void run(f32x16& acc, const Vec& w, const Vec& x) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(w, x, acc, 0, 0, 0);
+    }
+};
+template <> struct Mma<float> {
+    typedef f32x4 Vec;
+    static constexpr int KPACK = 4;
+    static __device__ __forceinline__ void run(f32x16& acc, const Vec& w, const Vec& x) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w[j], x[j], acc, 0, 0, 0);
+    }
+};
+
+// How the output channels of a layer are spread: every wave holds `nb` MFMA column blocks (32
+// output channels each) in its accumulators, `cs` waves share one tile of 32 pixels and split its
+// channels between them, and `npass` passes cover layers wider than nb*cs*32 channels.
+struct ConvPlan {
+    int nb, cs, npass;
+    int cout_pad;      // npass * cs * nb * 32
+    int kch;           // K-steps per tap, each covering 2 * KPACK input channels
+    size_t w_bytes;    // packed weights
+    bool stream;       // weights do not fit LDS: stream them in slices
+    bool full_tail;    // one pass: the activation tail sees the whole pixel
+    size_t lds_bytes;
+    bool ok;
+};
+
+inline size_t conv_stage_bytes(int nb, int dtype) { return (size_t)kConvWaves * kTile * (nb * 32 * dtype_size(dtype) + kStagePad); }
+inline size_t conv_xchg_bytes() { return (size_t)2 * kConvWaves * kTile * sizeof(float); }
+
+// The plan depends only on the layer's description, so packing, sizing and launching agree on it.
+inline ConvPlan conv_plan(int dtype, int k, int cin, int cout, bool need_full_tail) {
+    const int kpack = dtype == DCNN_F16 ? 8 : 4;
+    const int vec = dtype == DCNN_F16 ? 8 : 4;
+    const bool vec_out = cout % vec == 0;
+    const int nbt = (int)cdiv(cout, 32);
+    ConvPlan best{};
+    best.ok = false;
+    long best_score = -1;
+    // preference among equally padded layouts: two blocks per wave first (small accumulators, one
+    // cache line per pixel and array in the tail), then three, four, one
+    static const int nb_pref[] = {2, 3, 4, 1};
+    static const int cs_list[] = {1, 2, 4};
+    for (int pi = 0; pi < 4; ++pi) {
+        const int nb = nb_pref[pi];
+        for (int cs : cs_list) {
+            if (!vec_out && (nb > 2 || cs > 1)) continue;          // element-wise tail: one wave, <= 64 channels
+            const int cap = nb * cs;
+            const int npass = (int)cdiv(nbt, cap);
+            if (need_full_tail && npass > 1) continue;
+            if (!vec_out && npass > 1) continue;
+            ConvPlan p{};
+            p.nb = nb; p.cs = cs; p.npass = npass;
+            p.cout_pad = npass * cap * 32;
+            p.kch = (int)cdiv(cin, 2 * kpack);
+            p.w_bytes = (size_t)k * k * p.kch * 2 * p.cout_pad * 16;
+            p.full_tail = npass == 1;
+            const size_t fixed = conv_stage_bytes(nb, dtype) + conv_xchg_bytes();
+            const size_t slice = (size_t)2 * cs * kGroup * 2 * nb * 32 * 16;   // double-buffered weight slice
+            if (p.w_bytes + fixed <= kLdsBytes) { p.stream = false; p.lds_bytes = p.w_bytes + fixed; }
+            else if (slice + fixed <= kLdsBytes) { p.stream = true; p.lds_bytes = slice + fixed; }
+            else continue;
+            p.ok = true;
+            // fewer padded blocks first, then fewer passes, then fewer waves per tile, then preference
+            const long score = (long)npass * cap * 100000L + (long)npass * 1000L + cs * 10L + pi;
+            if (best_score < 0 || score < best_score) { best = p; best_score = score; }
+        }
+    }
+    return best;
+}
+
+}  // namespace dcnn

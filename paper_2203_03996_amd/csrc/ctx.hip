@@ -1,4 +1,6 @@
 // Context, error reporting and workspace carve-up (host code).
+#include <new>
+
 #include "common.h"
 
 namespace dcnn {
@@ -56,13 +58,14 @@ dcnn_status dcnn_ctx_create(void* hip_stream, void* workspace_dev, size_t worksp
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return DCNN_EHIP;
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return DCNN_EUNSUPPORTED;   // kernels are built for CDNA4 only
+    if (prop.sharedMemPerBlock < 160 * 1024) return DCNN_EUNSUPPORTED;           // the conv plans assume 160 KB of LDS
     dcnn_ctx* c = new (std::nothrow) dcnn_ctx();
     if (!c) return DCNN_ENOMEM;
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->ws = static_cast<char*>(workspace_dev);
     c->ws_bytes = workspace_bytes;
     c->num_cu = prop.multiProcessorCount;
-    c->max_lds = prop.sharedMemPerBlock;
+    c->max_lds = prop.sharedMemPerBlock;                // 160 KB on gfx950; the conv plans rely on it
     c->err[0] = 0;
     *out = c;
     return DCNN_OK;

@@ -83,8 +83,62 @@ __device__ __forceinline__ int pow2_ceil(int v) {
     return p;
 }
 
+// Raw storage-typed vector of V channels (one 16-byte register quad, or a single element).
+template <typename T, int V> struct RawOf;
+template <> struct RawOf<f16, 8> { typedef f16x8 type; };
+template <> struct RawOf<float, 4> { typedef f32x4 type; };
+template <> struct RawOf<f16, 1> { typedef f16 type; };
+template <> struct RawOf<float, 1> { typedef float type; };
+
+template <typename T, int V> __device__ __forceinline__ typename RawOf<T, V>::type raw_load(const T* p) {
+    return *reinterpret_cast<const typename RawOf<T, V>::type*>(p);
+}
+template <typename T, int V> __device__ __forceinline__ void raw_store(T* p, typename RawOf<T, V>::type v) {
+    *reinterpret_cast<typename RawOf<T, V>::type*>(p) = v;
+}
+template <typename T, int V> __device__ __forceinline__ typename RawOf<T, V>::type raw_zero() {
+    typename RawOf<T, V>::type v;
+    if constexpr (V == 1) v = (T)0.0f;
+    else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) v[i] = (T)0.0f;
+    }
+    return v;
+}
+template <typename T, int V> __device__ __forceinline__ float raw_get(const typename RawOf<T, V>::type& v, int i) {
+    if constexpr (V == 1) return (float)v;
+    else return (float)v[i];
+}
+// round-to-nearest-even into the storage type
+template <typename T, int V> __device__ __forceinline__ void raw_set(typename RawOf<T, V>::type& v, int i, float x) {
+    if constexpr (V == 1) v = (T)x;
+    else v[i] = (T)x;
+}
+
+// LDS-only synchronisation: orders shared-memory traffic without waiting for outstanding global
+// loads and stores (a generic fence would drain them and stall the memory pipeline).
+__device__ __forceinline__ void lds_wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+__device__ __forceinline__ void lds_block_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// How several waves that hold different channel slices of the same pixels agree on the
+// per-pixel maximum: each writes its partial maxima to LDS, one block barrier, each reads all.
+struct MaxExchange {
+    float* buf;      // [2][parts][32] floats in LDS (double-buffered by batch parity)
+    int parts;       // waves per pixel tile (1: no exchange)
+    int part;        // this wave's slice
+};
+
 // ---------------------------------------------------------------------------------------------
-// Activation + truncation of one tile of 32 work-list entries, executed by one wavefront.
+// Activation + truncation of one tile of 32 work-list entries, executed by one wavefront (or by
+// `parts` wavefronts that each own a slice of the channels).
 //
 // Per pixel (Section 3.1, Eqs. 4-6):  s = (x^A + x^T) + dx;  dy = f(s) - f(x^A);
 //   max_c |dy_c| >= eps : x^A <- s, x^T <- 0, emit dy, flag the pixel
@@ -92,128 +146,162 @@ __device__ __forceinline__ int pow2_ceil(int v) {
 // First frame (init): v = dx (+ bias) (+ dense residual); x^A <- v, x^T <- 0, emit f(v).
 // act == NONE: the (summed) delta is passed through, no state.
 //
-// LP consecutive lanes share one pixel (each lane owns up to VPL vectors of V channels), so a
-// wave visits 64/LP pixels per iteration with fully coalesced 16-byte accesses; the per-pixel
-// maximum is an LP-lane butterfly.  `dx(e, p, c0, out, valid_out)` delivers V channels of the
-// first delta stream for tile entry e / pixel p, already rounded to the storage type.
+// The call handles the channel window [ch0, ch0+nch) of every pixel.  LP consecutive lanes share
+// one pixel (each lane owns up to VPL vectors of V channels), so a wave visits 64/LP pixels per
+// iteration with coalesced 16-byte accesses; the per-pixel maximum is an LP-lane butterfly,
+// followed by the LDS exchange when the pixel's channels are spread over several waves.  The
+// kernel is bound by memory latency, not arithmetic: the loads of UB iterations (delta, residual,
+// x^A, x^T) are issued back to back before any of them is consumed.  `p_mine` is the pixel of
+// entry lane%32 (or -1), so no index-list load sits in front of the address computation.
+// `dx(ent, p, c0)` delivers V channels of the first delta stream for tile entry `ent` / pixel p
+// as a raw vector already rounded to the storage type.
 // Returns the survivor word of the tile (bit e set iff entry e stays flagged) in every lane.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int V, int VPL, class Dx>
-__device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool init, const int32_t* list,
-                                                  int64_t tile_base, int64_t count, int lane, Dx dx,
-                                                  int ch0 = 0, int nch = -1) {
-    // [ch0, ch0 + nch) is the window of channels handled by this call (default: all of them);
-    // windows are only used for pass-through (act == NONE) tiles, which need no per-pixel maximum
+template <typename T, int V, int VPL, int UB, bool XCHG, class Dx>
+__device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool init, int p_mine, int lane, Dx dx,
+                                                  int ch0, int nch, int span, MaxExchange mx) {
+    // `span` >= nch fixes how lanes are laid out over a pixel's channels; waves that exchange maxima
+    // must use the same span so that they run the same number of batches (and barriers)
+    typedef typename RawOf<T, V>::type Raw;
     const int C = e.c;
-    if (nch < 0) nch = C;
     const int nvec = (nch + V - 1) / V;
-    int LP = pow2_ceil((nvec + VPL - 1) / VPL);
+    int LP = pow2_ceil(((span + V - 1) / V + VPL - 1) / VPL);
     LP = LP < 2 ? 2 : (LP > kWave ? kWave : LP);
     const int PPI = kWave / LP;                       // pixels per iteration (<= 32)
     const int sub = lane % LP, grp = lane / LP;
+    const int iters = kTile / PPI;
     const T* bias = static_cast<const T*>(e.bias);
     const T* res = static_cast<const T*>(e.res_data);
     T* xA = static_cast<T*>(e.xA);
     T* xT = static_cast<T*>(e.xT);
     T* out = static_cast<T*>(e.out_data);
+    const bool stateful = e.act != DCNN_ACT_NONE;
     uint32_t bits = 0;
+    int batch = 0;
 
-    for (int it = 0; it < kTile / PPI; ++it) {
-        const int ent = it * PPI + grp;
-        const int64_t j = tile_base + ent;
-        const bool valid = j < count;
-        const int64_t p = valid ? (list ? (int64_t)list[j] : j) : 0;
-        const bool res_ok = valid && res && (e.res_mask == nullptr || e.res_mask[p] != 0);
-
-        float s[VPL][V], dy[VPL][V], d[VPL][V];
-        float u = 0.0f;
+    for (int it0 = 0; it0 < iters; it0 += UB, ++batch) {
+        int pix[UB];
+        Raw rd[UB][VPL], rr[UB][VPL], ra[UB][VPL], rt[UB][VPL];
+        // ---- phase 1: issue every load of the batch ---------------------------------------------
 #pragma unroll
-        for (int v = 0; v < VPL; ++v) {
-            const int vi = sub + v * LP;
-            const bool on = valid && vi < nvec;
-            const int c0 = ch0 + vi * V;
+        for (int ub = 0; ub < UB; ++ub) {
+            const int ent = (it0 + ub) * PPI + grp;
+            const int p32 = (it0 + ub) < iters ? __shfl(p_mine, ent & (kTile - 1), kWave) : -1;
+            pix[ub] = p32;
+            const int64_t p = p32;
+            const bool valid = p32 >= 0;
+            const bool res_ok = valid && res && (init || e.res_mask == nullptr || e.res_mask[p] != 0);
 #pragma unroll
-            for (int i = 0; i < V; ++i) { s[v][i] = 0.0f; dy[v][i] = 0.0f; d[v][i] = 0.0f; }
-            if (!on) continue;
-            dx(ent, p, c0, d[v]);
-            if (init) {
-                if (bias) {
-                    float b[V];
-                    load_vec<T, V>(bias + c0, b);
-#pragma unroll
-                    for (int i = 0; i < V; ++i) d[v][i] = round_store<T>(d[v][i] + b[i]);
+            for (int v = 0; v < VPL; ++v) {
+                const int vi = sub + v * LP;
+                const bool on = valid && vi < nvec;
+                const int c0 = ch0 + vi * V;
+                rd[ub][v] = raw_zero<T, V>(); rr[ub][v] = raw_zero<T, V>();
+                ra[ub][v] = raw_zero<T, V>(); rt[ub][v] = raw_zero<T, V>();
+                if (!on) continue;
+                rd[ub][v] = dx(ent, p, c0);
+                if (res_ok) rr[ub][v] = raw_load<T, V>(res + p * C + c0);
+                if (stateful && !init) {
+                    ra[ub][v] = raw_load<T, V>(xA + p * C + c0);
+                    rt[ub][v] = raw_load<T, V>(xT + p * C + c0);
                 }
-                if (res) {
-                    float r[V];
-                    load_vec<T, V>(res + p * C + c0, r);
-#pragma unroll
-                    for (int i = 0; i < V; ++i) d[v][i] = round_store<T>(d[v][i] + r[i]);
-                }
-#pragma unroll
-                for (int i = 0; i < V; ++i) { s[v][i] = d[v][i]; dy[v][i] = act_apply(e.act, d[v][i]); }
-                continue;
+                if (init && bias) ra[ub][v] = raw_load<T, V>(bias + c0);      // slot reused for the bias
             }
-            if (res) {
-                float r[V];
+        }
+        // ---- phase 2: arithmetic and the per-pixel maximum ---------------------------------------
+        Raw o_a[UB][VPL], o_t[UB][VPL], o_y[UB][VPL];
+        float umax[UB];
 #pragma unroll
-                for (int i = 0; i < V; ++i) r[i] = 0.0f;
-                if (res_ok) load_vec<T, V>(res + p * C + c0, r);
+        for (int ub = 0; ub < UB; ++ub) {
+            float u = 0.0f;
 #pragma unroll
-                for (int i = 0; i < V; ++i) d[v][i] = round_store<T>(d[v][i] + r[i]);
-            }
-            if (e.act != DCNN_ACT_NONE) {
-                float a[V], t[V];
-                load_vec<T, V>(xA + p * C + c0, a);
-                load_vec<T, V>(xT + p * C + c0, t);
+            for (int v = 0; v < VPL; ++v) {
 #pragma unroll
                 for (int i = 0; i < V; ++i) {
-                    s[v][i] = (a[i] + t[i]) + d[v][i];
-                    dy[v][i] = act_apply(e.act, s[v][i]) - act_apply(e.act, a[i]);
-                    u = fmaxf(u, fabsf(dy[v][i]));
-                    d[v][i] = t[i] + d[v][i];            // what x^T becomes if the pixel is truncated
+                    float d = raw_get<T, V>(rd[ub][v], i);
+                    if (init) {
+                        if (bias) d = round_store<T>(d + raw_get<T, V>(ra[ub][v], i));
+                        if (res) d = round_store<T>(d + raw_get<T, V>(rr[ub][v], i));
+                        raw_set<T, V>(o_a[ub][v], i, d);
+                        raw_set<T, V>(o_t[ub][v], i, 0.0f);
+                        raw_set<T, V>(o_y[ub][v], i, stateful ? act_apply(e.act, d) : d);
+                    } else {
+                        if (res) d = round_store<T>(d + raw_get<T, V>(rr[ub][v], i));
+                        if (stateful) {
+                            const float a = raw_get<T, V>(ra[ub][v], i), t = raw_get<T, V>(rt[ub][v], i);
+                            const float s = (a + t) + d;
+                            const float dy = act_apply(e.act, s) - act_apply(e.act, a);
+                            u = fmaxf(u, fabsf(dy));
+                            raw_set<T, V>(o_a[ub][v], i, s);
+                            raw_set<T, V>(o_t[ub][v], i, t + d);       // x^T if the pixel is truncated
+                            raw_set<T, V>(o_y[ub][v], i, dy);
+                        } else {
+                            raw_set<T, V>(o_a[ub][v], i, 0.0f);
+                            raw_set<T, V>(o_t[ub][v], i, 0.0f);
+                            raw_set<T, V>(o_y[ub][v], i, d);
+                        }
+                    }
                 }
             }
+            if (!init && stateful)
+                for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
+            umax[ub] = u;
         }
-
-        bool upd = true;
-        if (!init && e.act != DCNN_ACT_NONE) {
-            for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
-            upd = u >= e.eps;
-        }
-
+        if constexpr (XCHG) {
+            // every wave of the workgroup passes here the same number of times
+            float* slot = mx.buf + (size_t)(batch & 1) * mx.parts * kTile;
 #pragma unroll
-        for (int v = 0; v < VPL; ++v) {
-            const int vi = sub + v * LP;
-            if (!(valid && vi < nvec)) continue;
-            const int64_t off = p * C + ch0 + vi * V;
-            if (e.act == DCNN_ACT_NONE) {
-                store_vec<T, V>(out + off, d[v]);
-            } else if (init) {
-                store_vec<T, V>(xA + off, s[v]);
-                float z[V];
+            for (int ub = 0; ub < UB; ++ub) {
+                const int ent = (it0 + ub) * PPI + grp;
+                if (sub == 0 && (it0 + ub) < iters) slot[mx.part * kTile + ent] = umax[ub];
+            }
+            lds_block_sync();
 #pragma unroll
-                for (int i = 0; i < V; ++i) z[i] = 0.0f;
-                store_vec<T, V>(xT + off, z);
-                store_vec<T, V>(out + off, dy[v]);
-            } else if (upd) {
-                store_vec<T, V>(xA + off, s[v]);
-                float z[V];
-#pragma unroll
-                for (int i = 0; i < V; ++i) z[i] = 0.0f;
-                store_vec<T, V>(xT + off, z);
-                store_vec<T, V>(out + off, dy[v]);
-            } else {
-                store_vec<T, V>(xT + off, d[v]);
+            for (int ub = 0; ub < UB; ++ub) {
+                const int ent = ((it0 + ub) * PPI + grp) & (kTile - 1);
+                float u = 0.0f;
+                for (int q = 0; q < mx.parts; ++q) u = fmaxf(u, slot[q * kTile + ent]);
+                umax[ub] = u;
             }
         }
-        if (valid && sub == 0) {
-            if (e.out_mask && !init) e.out_mask[p] = upd ? 1 : 0;
-            if (upd) bits |= 1u << ent;
+        // ---- phase 3: decision and stores --------------------------------------------------------
+#pragma unroll
+        for (int ub = 0; ub < UB; ++ub) {
+            const int64_t p = pix[ub];
+            const bool valid = pix[ub] >= 0;
+            const int ent = (it0 + ub) * PPI + grp;
+            const bool upd = (init || !stateful) ? true : (umax[ub] >= e.eps);
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) {
+                const int vi = sub + v * LP;
+                if (!(valid && vi < nvec)) continue;
+                const int64_t off = p * C + ch0 + vi * V;
+                if (!stateful) {
+                    raw_store<T, V>(out + off, o_y[ub][v]);
+                } else if (upd) {
+                    raw_store<T, V>(xA + off, o_a[ub][v]);
+                    raw_store<T, V>(xT + off, raw_zero<T, V>());
+                    raw_store<T, V>(out + off, o_y[ub][v]);
+                } else {
+                    raw_store<T, V>(xT + off, o_t[ub][v]);
+                }
+            }
+            if (valid && sub == 0) {
+                if (e.out_mask && !init && mx.part == 0) e.out_mask[p] = upd ? 1 : 0;
+                if (upd) bits |= 1u << ent;
+            }
         }
     }
+    if constexpr (XCHG) lds_block_sync();             // the exchange buffers are free again for the next tile
 #pragma unroll
     for (int m = kWave >> 1; m >= 1; m >>= 1) bits |= __shfl_xor(bits, m, kWave);
     return bits;
+}
+
+// Pixel of work-list entry `j` for the lane that owns it (-1 beyond the end of the list).
+__device__ __forceinline__ int list_pixel(const int32_t* list, int64_t j, int64_t count) {
+    if (j >= count) return -1;
+    return list ? list[j] : (int)j;
 }
 
 }  // namespace dcnn

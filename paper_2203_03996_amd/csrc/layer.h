@@ -1,6 +1,9 @@
 // Internal layout of a layer object (shared by layer.hip and net.hip).
 #pragma once
 
+#include <utility>
+#include <vector>
+
 #include "common.h"
 
 struct dcnn_layer {
@@ -28,4 +31,8 @@ struct dcnn_layer {
     dcnn_delta view;
     const int32_t* last_in_count;
     const int32_t* last_work_count;
+    const int32_t* last_in2_count;
+    // optional kernel timing
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+    size_t events_used = 0;
 };

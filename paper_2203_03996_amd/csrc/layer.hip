@@ -91,7 +91,7 @@ static void carve(dcnn_layer* L, void* state) {
     L->buf0 = L->buf1 = nullptr; L->buf0_bytes = L->buf1_bytes = 0;
     L->out_data = nullptr; L->out_mask = nullptr; L->out_idx = nullptr; L->out_count = nullptr;
     L->list = nullptr; L->list_count = nullptr; L->wpacked = nullptr; L->bias = nullptr;
-    L->counters = static_cast<int32_t*>(cv.take(kAlign));
+    L->counters = static_cast<int32_t*>(cv.take(kAlign));      // stays all zero: doubles as the zero page of the gathers
     switch (d.kind) {
         case DCNN_DELTAGEN:
             L->buf0 = cv.take(in_map); L->buf0_bytes = in_map;
@@ -135,7 +135,7 @@ static void carve(dcnn_layer* L, void* state) {
         L->alias_mask = true;
     }
     if (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV) {
-        L->wpacked = cv.take(conv_packed_weight_bytes(d.dtype, d.kh, d.c, L->oc, d.kind == DCNN_DWCONV));
+        L->wpacked = cv.take(conv_packed_weight_bytes(d.dtype, d.kh, d.c, L->oc, d.kind == DCNN_DWCONV, act));
         L->bias = cv.take((size_t)L->oc * es);
     }
     L->state_bytes = cv.off;
@@ -224,7 +224,7 @@ dcnn_status dcnn_layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const 
             return fail(ctx, DCNN_EUNSUPPORTED, "layer_create: %s", why);
         }
         st = launch_pack_weights(ctx, desc->dtype, weights_dev, L->wpacked, desc->kh, desc->c, L->oc,
-                                 desc->kind == DCNN_DWCONV);
+                                 desc->kind == DCNN_DWCONV, has_act(*desc));
         if (st == DCNN_OK && bias_dev) st = launch_copy(ctx, L->bias, bias_dev, (size_t)L->oc * dtype_size(desc->dtype));
         if (st != DCNN_OK) { delete L; return st; }
         L->has_bias = bias_dev != nullptr;
@@ -240,7 +240,49 @@ dcnn_status dcnn_layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const 
     return DCNN_OK;
 }
 
-void dcnn_layer_destroy(dcnn_layer* layer) { delete layer; }
+static void drop_events(dcnn_layer* L) {
+    for (auto& e : L->events) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
+    L->events.clear();
+    L->events_used = 0;
+}
+
+void dcnn_layer_destroy(dcnn_layer* layer) {
+    if (!layer) return;
+    drop_events(layer);
+    delete layer;
+}
+
+dcnn_status dcnn_layer_set_timing(dcnn_layer* L, int32_t max_steps) {
+    if (!L) return DCNN_EINVAL;
+    if (max_steps < 0 || max_steps > 65536) return fail(L->ctx, DCNN_EINVAL, "set_timing: max_steps out of range");
+    drop_events(L);
+    for (int i = 0; i < max_steps; ++i) {
+        hipEvent_t a, b;
+        dcnn_status st = check_hip(L->ctx, hipEventCreate(&a), "hipEventCreate");
+        if (st != DCNN_OK) return st;
+        st = check_hip(L->ctx, hipEventCreate(&b), "hipEventCreate");
+        if (st != DCNN_OK) { (void)hipEventDestroy(a); return st; }
+        L->events.emplace_back(a, b);
+    }
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_layer_timing(dcnn_layer* L, float* total_ms, int32_t* launches) {
+    if (!L || !total_ms || !launches) return DCNN_EINVAL;
+    dcnn_status st = check_hip(L->ctx, hipStreamSynchronize(L->ctx->stream), "hipStreamSynchronize");
+    if (st != DCNN_OK) return st;
+    float sum = 0.0f;
+    for (size_t i = 0; i < L->events_used; ++i) {
+        float ms = 0.0f;
+        st = check_hip(L->ctx, hipEventElapsedTime(&ms, L->events[i].first, L->events[i].second), "hipEventElapsedTime");
+        if (st != DCNN_OK) return st;
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = (int32_t)L->events_used;
+    L->events_used = 0;
+    return DCNN_OK;
+}
 
 dcnn_status dcnn_layer_reset(dcnn_layer* layer) {
     if (!layer) return DCNN_EINVAL;
@@ -267,7 +309,7 @@ dcnn_status dcnn_layer_init(dcnn_layer* L, const void* const* dense_in, int32_t 
         case DCNN_CONV:
         case DCNN_DWCONV: {
             ConvArgs c{};
-            c.in_data = dense_in[0]; c.in_mask = nullptr; c.wpacked = L->wpacked;
+            c.in_data = dense_in[0]; c.in_mask = nullptr; c.wpacked = L->wpacked; c.zero_page = L->counters;
             c.n = d.n; c.h = d.h; c.w = d.w; c.cin = d.c; c.oh = L->oh; c.ow = L->ow; c.cout = L->oc;
             c.k = d.kh; c.stride = d.stride; c.pad = d.pad; c.depthwise = d.kind == DCNN_DWCONV;
             EpilogueArgs e{};
@@ -311,6 +353,8 @@ dcnn_status dcnn_layer_init(dcnn_layer* L, const void* const* dense_in, int32_t 
     if (st != DCNN_OK) return st;
     L->inited = true;
     L->last_in_count = nullptr;
+    L->last_in2_count = nullptr;
+    L->last_work_count = nullptr;
     L->view = dcnn_delta{};
     return DCNN_OK;
 }
@@ -341,6 +385,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
     v.idx = L->alias_mask ? in[0]->idx : L->out_idx;
     v.count = L->alias_mask ? in[0]->count : L->out_count;
     L->last_in_count = in[0]->count;
+    L->last_in2_count = n_in == 2 ? in[1]->count : nullptr;
 
     if (d.kind == DCNN_DELTAGEN) {
         DeltaGenArgs a{};
@@ -361,6 +406,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         m.mask_out = L->out_mask; m.idx_out = L->list; m.count_out = L->list_count;
         m.n = d.n; m.h = d.h; m.w = d.w; m.oh = L->oh; m.ow = L->ow;
         m.k = 1; m.stride = 1; m.pad = 0; m.up = 1; m.emit_only = 0;
+        m.zero_count = (act && !d.want_idx) ? L->out_count : nullptr;
         if (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV || d.kind == DCNN_MAXPOOL) { m.k = d.kh; m.stride = d.stride; m.pad = d.pad; }
         if (d.kind == DCNN_UPSAMPLE) m.up = d.factor;
         st = launch_mask_compact(ctx, m);
@@ -373,6 +419,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             MaskPassArgs m{};
             m.mask_in = in[0]->mask; m.mask_out = L->out_mask; m.idx_out = nullptr;
             m.n = d.n; m.h = d.h; m.w = d.w; m.oh = L->oh; m.ow = L->ow; m.k = 1; m.stride = 1; m.pad = 0; m.up = 1;
+            m.zero_count = !d.want_idx ? L->out_count : nullptr;
             st = launch_mask_compact(ctx, m);
             if (st != DCNN_OK) return st;
         }
@@ -380,11 +427,16 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
     L->last_work_count = l.count;
 
     // ---- compute -------------------------------------------------------------------------------
+    const bool timed = L->events_used < L->events.size();
+    if (timed) {
+        st = check_hip(ctx, hipEventRecord(L->events[L->events_used].first, ctx->stream), "hipEventRecord");
+        if (st != DCNN_OK) return st;
+    }
     switch (d.kind) {
         case DCNN_CONV:
         case DCNN_DWCONV: {
             ConvArgs c{};
-            c.in_data = in[0]->data; c.in_mask = in[0]->mask; c.wpacked = L->wpacked;
+            c.in_data = in[0]->data; c.in_mask = in[0]->mask; c.wpacked = L->wpacked; c.zero_page = L->counters;
             c.n = d.n; c.h = d.h; c.w = d.w; c.cin = d.c; c.oh = L->oh; c.ow = L->ow; c.cout = L->oc;
             c.k = d.kh; c.stride = d.stride; c.pad = d.pad; c.depthwise = d.kind == DCNN_DWCONV;
             EpilogueArgs e{};
@@ -393,6 +445,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             e.xA = L->buf0; e.xT = L->buf1; e.out_data = L->out_data;
             e.out_mask = act ? L->out_mask : nullptr;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;
+            e.out_count = (act && !d.want_idx) ? L->out_count : nullptr;
             st = launch_conv(ctx, d.dtype, false, l, c, e);
             break;
         }
@@ -404,6 +457,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             e.xA = L->buf0; e.xT = L->buf1; e.out_data = L->out_data;
             e.out_mask = act ? L->out_mask : nullptr;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;
+            e.out_count = (act && !d.want_idx) ? L->out_count : nullptr;
             st = launch_act(ctx, d.dtype, false, l, a, e);
             break;
         }
@@ -432,6 +486,11 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         default: return fail(ctx, DCNN_EINVAL, "step: bad layer kind");
     }
     if (st != DCNN_OK) return st;
+    if (timed) {
+        st = check_hip(ctx, hipEventRecord(L->events[L->events_used].second, ctx->stream), "hipEventRecord");
+        if (st != DCNN_OK) return st;
+        ++L->events_used;
+    }
     // ---- ordered list of the pixels that stayed flagged ------------------------------------------
     if (act && d.want_idx && (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV || d.kind == DCNN_ACT))
         st = launch_emit_sublist(ctx, l.list, l.count, L->out_pixels, ws.surv, L->out_idx, L->out_count);
@@ -474,9 +533,15 @@ dcnn_status dcnn_layer_stats(dcnn_layer* L, dcnn_stats* s) {
         return r;
     };
     st = read(L->last_in_count, &s->pixels_in);
+    if (st == DCNN_OK) st = read(L->last_in2_count, &s->pixels_in2);
     if (st == DCNN_OK) st = read(L->last_work_count, &s->pixels_work);
     if (st == DCNN_OK) st = read(L->view.count, &s->pixels_out);
     s->pixels_total = L->out_pixels;
+    s->pixels_in_total = L->in_pixels;
+    s->kind = L->d.kind; s->act = L->d.act; s->n_in = L->d.n_in;
+    s->c_in = L->d.c; s->c_out = L->oc;
+    const bool window = L->d.kind == DCNN_CONV || L->d.kind == DCNN_DWCONV || L->d.kind == DCNN_MAXPOOL;
+    s->k = window ? L->d.kh : 1; s->stride = window ? L->d.stride : 1; s->reserved = 0;
     return st;
 }
 

@@ -51,6 +51,7 @@ struct MaskKernelArgs {
     const uint8_t* mask_b;
     uint8_t* mask_out;
     int32_t* chunk_counts;
+    int32_t* zero_count;
     int64_t out_pixels;
     int n, h, w, oh, ow, k, stride, pad, up;
 };
@@ -97,7 +98,10 @@ __global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs 
         }
     }
     const int total = block_sum(cnt, s_red);
-    if (threadIdx.x == 0) a.chunk_counts[blockIdx.x] = total;
+    if (threadIdx.x == 0) {
+        a.chunk_counts[blockIdx.x] = total;
+        if (blockIdx.x == 0 && a.zero_count) *a.zero_count = 0;
+    }
 }
 
 struct EmitArgs {
@@ -145,6 +149,7 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
         a.mask_in = m.mask_in; a.mask_b = m.mask_b;
         a.mask_out = m.mask_out ? m.mask_out : ws.scratch_mask;
         a.chunk_counts = ws.chunk_counts;
+        a.zero_count = m.zero_count;
         a.out_pixels = out_pixels;
         a.n = m.n; a.h = m.h; a.w = m.w; a.oh = m.oh; a.ow = m.ow;
         a.k = m.k; a.stride = m.stride; a.pad = m.pad;

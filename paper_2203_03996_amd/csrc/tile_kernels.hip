@@ -19,21 +19,28 @@ static int list_grid(const dcnn_ctx* ctx, int64_t max_count, int entries_per_wg,
 // ---- activation + truncation (+ add) ----------------------------------------------------------
 template <typename T, int V, int VPL>
 __global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a, EpilogueArgs e, int init) {
+    typedef typename RawOf<T, V>::type Raw;
+    constexpr int UB = (V * VPL >= 16) ? 2 : 4;
     const int64_t count = list_count(l);
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int C = e.c;
     const T* in = static_cast<const T*>(a.in_data);
     const uint8_t* in_mask = a.in_mask;
-    auto dx = [&](int, int64_t p, int c0, float (&o)[V]) {
-        if (in_mask == nullptr || in_mask[p] != 0) load_vec<T, V>(in + p * C + c0, o);
+    auto dx = [&](int, int64_t p, int c0) -> Raw {
+        if (in_mask == nullptr || in_mask[p] != 0) return raw_load<T, V>(in + p * C + c0);
+        return raw_zero<T, V>();
     };
     const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
     for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
         const int64_t tile = wt * kTileWaves + wave;
         const int64_t base = tile * kTile;
         if (base >= count) continue;
-        const uint32_t bits = act_trunc_tile<T, V, VPL>(e, init != 0, l.list, base, count, lane, dx);
-        if (e.surv && lane == 0) e.surv[tile] = bits;
+        const int p_mine = list_pixel(l.list, base + lane % kTile, count);
+        const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
+        if (lane == 0) {
+            if (e.surv) e.surv[tile] = bits;
+            else if (e.out_count) atomicAdd(e.out_count, __popc(bits));
+        }
     }
 }
 
@@ -72,12 +79,14 @@ dcnn_status launch_act(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, c
 // read (unflagged memory is invalid), load and multiply are fused per pixel.
 template <typename T, int V, int VPL>
 __global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init) {
+    typedef typename RawOf<T, V>::type Raw;
+    constexpr int UB = 2;
     const int64_t count = list_count(l);
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int C = e.c;
     const T* in = static_cast<const T*>(c.in_data);
     const T* wgt = static_cast<const T*>(c.wpacked);           // [k][k][C], unpacked
-    auto dx = [&](int, int64_t p, int c0, float (&o)[V]) {
+    auto dx = [&](int, int64_t p, int c0) -> Raw {
         const int ox = (int)(p % c.ow);
         const int64_t t = p / c.ow;
         const int oy = (int)(t % c.oh);
@@ -93,23 +102,28 @@ __global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvAr
                 if (ix < 0 || ix >= c.w) continue;
                 const int64_t q = (n * c.h + iy) * c.w + ix;
                 if (c.in_mask && c.in_mask[q] == 0) continue;
-                float xv[V], wv[V];
-                load_vec<T, V>(in + q * C + c0, xv);
-                load_vec<T, V>(wgt + (int64_t)(ky * c.k + kx) * C + c0, wv);
+                const Raw xv = raw_load<T, V>(in + q * C + c0);
+                const Raw wv = raw_load<T, V>(wgt + (int64_t)(ky * c.k + kx) * C + c0);
 #pragma unroll
-                for (int i = 0; i < V; ++i) acc[i] = fmaf(xv[i], wv[i], acc[i]);
+                for (int i = 0; i < V; ++i) acc[i] = fmaf(raw_get<T, V>(xv, i), raw_get<T, V>(wv, i), acc[i]);
             }
         }
+        Raw o;
 #pragma unroll
-        for (int i = 0; i < V; ++i) o[i] = round_store<T>(acc[i]);
+        for (int i = 0; i < V; ++i) raw_set<T, V>(o, i, acc[i]);
+        return o;
     };
     const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
     for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
         const int64_t tile = wt * kTileWaves + wave;
         const int64_t base = tile * kTile;
         if (base >= count) continue;
-        const uint32_t bits = act_trunc_tile<T, V, VPL>(e, init != 0, l.list, base, count, lane, dx);
-        if (e.surv && lane == 0) e.surv[tile] = bits;
+        const int p_mine = list_pixel(l.list, base + lane % kTile, count);
+        const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
+        if (lane == 0) {
+            if (e.surv) e.surv[tile] = bits;
+            else if (e.out_count) atomicAdd(e.out_count, __popc(bits));
+        }
     }
 }
 
