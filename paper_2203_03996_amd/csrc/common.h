@@ -21,6 +21,20 @@ inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t dtype_size(int dt) { return dt == DCNN_F16 ? 2 : 4; }
 
+// Division of a 31-bit unsigned number by a constant known on the host: q = (mulhi(n, m) + n) >> s
+// with s = ceil(log2 d), m = ceil(2^(32+s) / d) - 2^32.  Exact for 0 <= n < 2^31.
+struct FastDiv {
+    uint32_t m, s, d;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    f.s = 0;
+    while ((1ull << f.s) < d) ++f.s;
+    f.m = (uint32_t)((((1ull << (32 + f.s)) + d - 1) / d) - (1ull << 32));
+    return f;
+}
+
 }  // namespace dcnn
 
 struct dcnn_ctx {
@@ -97,6 +111,8 @@ struct ConvArgs {
     const void* zero_page;       // >= 16 bytes of zeros: what lanes read instead of an unflagged / padded input
     int n, h, w, cin, oh, ow, cout, cout_pad, k, stride, pad, kch;
     int depthwise;
+    FastDiv div_ow, div_oh;      // filled by launch_conv
+    int dbg;                     // experiment knobs (0 in normal operation)
 };
 dcnn_status launch_conv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const ConvArgs& c,
                         const EpilogueArgs& e);

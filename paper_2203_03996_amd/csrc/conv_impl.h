@@ -44,8 +44,11 @@ __device__ __forceinline__ void stage_accumulators(const f32x16 (&acc)[NB], unsi
     }
 }
 
+#ifndef DCNN_CONV_BOUNDS
+#define DCNN_CONV_BOUNDS (STREAM ? 512 : (NB <= 2 ? 768 : 512))
+#endif
 template <typename T, int NB, int V, bool ALIGNED, bool STREAM, int KS>
-__global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init,
+__global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init,
                                                                  int npass, int cs) {
     typedef typename Mma<T>::Vec Vec;
     typedef typename RawOf<T, V>::type Raw;
@@ -54,7 +57,8 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, Con
     constexpr int GK = 4;                                      // K-steps whose gathers are in flight together
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tiles_per_iter = kConvWaves / cs;
+    const int nwaves = blockDim.x / kWave, nthreads = blockDim.x;
+    const int tiles_per_iter = nwaves / cs;
     const int64_t count = list_count(l);
     const WgTileRange r = wg_tile_range((count + tiles_per_iter * kTile - 1) / (tiles_per_iter * kTile));
     if (r.begin >= r.end) return;                              // nothing for this workgroup: skip the weight load
@@ -71,68 +75,83 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, Con
     Vec* w_lds = reinterpret_cast<Vec*>(smem);
     constexpr int stage_stride = COLS * (int)sizeof(T) + kStagePad;
     unsigned char* stage = smem + (size_t)w_vecs * 16 + (size_t)wave * kTile * stage_stride;
-    float* xchg = reinterpret_cast<float*>(smem + (size_t)w_vecs * 16 + (size_t)kConvWaves * kTile * stage_stride) +
+    float* xchg = reinterpret_cast<float*>(smem + (size_t)w_vecs * 16 + (size_t)nwaves * kTile * stage_stride) +
                   (size_t)slot * 2 * cs * kTile;
     const Vec* wglob = static_cast<const Vec*>(c.wpacked);
     const T* in = static_cast<const T*>(c.in_data);
     const T* zeros = static_cast<const T*>(c.zero_page);
 
     if constexpr (!STREAM) {
-        for (int i = threadIdx.x; i < w_vecs; i += kConvThreads) w_lds[i] = wglob[i];
+        for (int i = threadIdx.x; i < w_vecs; i += nthreads) w_lds[i] = wglob[i];
         lds_block_sync();
     }
 
+    int survivors = 0;                                         // per-wave count, added to the layer's counter once
     for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
         // ---- the tile: pixel of this lane's column, window origin, which taps are needed ---------
+        // (pixel indices fit 31 bits; only the final element offset is 64-bit)
         const int64_t tile = wt * tiles_per_iter + slot;
         const int64_t base = tile * kTile;
         const int p32 = list_pixel(l.list, base + col, count);
         const bool valid = p32 >= 0;
-        const int64_t p = valid ? p32 : 0;
-        const int ox = (int)(p % c.ow);
-        const int64_t t1 = p / c.ow;
-        const int oy = (int)(t1 % c.oh);
-        const int64_t n = t1 / c.oh;
+        const uint32_t pu = valid ? (uint32_t)p32 : 0u;
+        const uint32_t t1 = fast_div(pu, c.div_ow);
+        const int ox = (int)(pu - t1 * (uint32_t)c.ow);
+        const uint32_t n = fast_div(t1, c.div_oh);
+        const int oy = (int)(t1 - n * (uint32_t)c.oh);
         const int iy0 = oy * c.stride - c.pad, ix0 = ox * c.stride - c.pad;
+        const int q00 = ((int)n * c.h + iy0) * c.w + ix0;      // pixel index of tap (0,0); only used when in bounds
         uint64_t tapbits = 0;
         if constexpr (KS != 0) {
             // fixed window: all update flags of the window are requested at once, then tested
             uint8_t flag[KS * KS];
 #pragma unroll
             for (int t = 0; t < KS * KS; ++t) {
-                const int iy = iy0 + t / KS, ix = ix0 + t % KS;
-                const bool inb = valid && iy >= 0 && iy < c.h && ix >= 0 && ix < c.w;
-                const int64_t q = inb ? (n * c.h + iy) * c.w + ix : 0;
-                flag[t] = c.in_mask ? c.in_mask[q] : (uint8_t)1;
+                const int dy = t / KS, dx = t % KS;
+                const bool inb = valid && (unsigned)(iy0 + dy) < (unsigned)c.h && (unsigned)(ix0 + dx) < (unsigned)c.w;
+                const int q = inb ? q00 + dy * c.w + dx : 0;
+                flag[t] = (c.in_mask && !(c.dbg & 8)) ? c.in_mask[q] : (uint8_t)1;
                 if (!inb) flag[t] = 0;
             }
 #pragma unroll
             for (int t = 0; t < KS * KS; ++t)
                 if (flag[t]) tapbits |= 1ull << t;
         } else {
-            for (int t = 0; t < taps; ++t) {
-                const int iy = iy0 + t / ksz, ix = ix0 + t % ksz;
-                bool ok = valid && iy >= 0 && iy < c.h && ix >= 0 && ix < c.w;
-                if (ok && c.in_mask) ok = c.in_mask[(n * c.h + iy) * c.w + ix] != 0;
+            for (int t = 0, dy = 0, dx = 0; t < taps; ++t) {
+                bool ok = valid && (unsigned)(iy0 + dy) < (unsigned)c.h && (unsigned)(ix0 + dx) < (unsigned)c.w;
+                if (ok && c.in_mask) ok = c.in_mask[q00 + dy * c.w + dx] != 0;
                 if (ok) tapbits |= 1ull << t;
+                if (++dx == ksz) { dx = 0; ++dy; }
             }
         }
 
-        // 16 bytes of input channels of K-step s = t*kch + kc for this lane's pixel; lanes that do not
-        // need the tap (or whose channels are padding) read the zero page
-        auto gather_one = [&](int s) -> Vec {
-            const int t = s / kch, kc = s - t * kch;
-            const int ch = (2 * kc + g) * KP;
-            const bool ok = s < ksteps && ((tapbits >> t) & 1) && ch < c.cin;
-            const int iy = iy0 + t / ksz, ix = ix0 + t % ksz;
-            const T* src = ok ? in + ((n * c.h + iy) * c.w + ix) * c.cin + ch : zeros;
-            if constexpr (ALIGNED) {
-                return *reinterpret_cast<const Vec*>(src);
-            } else {
-                Vec v;
+        // Wave-uniform cursor over groups of GK K-steps: tap t = (dy, dx), first K-step kc0 of the group.
+        struct Cursor { int t, dy, dx, kc0; };
+        auto advance = [&](Cursor& cu) {
+            cu.kc0 += GK;
+            if (cu.kc0 >= kch) {
+                cu.kc0 = 0; ++cu.t;
+                if (++cu.dx == ksz) { cu.dx = 0; ++cu.dy; }
+            }
+        };
+        // 16 bytes of input channels per K-step for this lane's pixel; lanes that do not need the tap
+        // (or whose channels are padding) read the zero page instead: no branches, no invalid reads
+        auto gather_group = [&](const Cursor& cu, Vec (&x)[GK]) {
+            const bool tap_ok = cu.t < taps && ((tapbits >> cu.t) & 1) && !(c.dbg & 2);
+            const T* src = in + (int64_t)(q00 + cu.dy * c.w + cu.dx) * c.cin;
 #pragma unroll
-                for (int i = 0; i < KP; ++i) v[i] = (ok && ch + i < c.cin) ? src[i] : (T)0.0f;
-                return v;
+            for (int u = 0; u < GK; ++u) {
+                const int ch = (2 * (cu.kc0 + u) + g) * KP;
+                const bool ok = tap_ok && cu.kc0 + u < kch && ch < c.cin;
+                const T* ptr = ok ? src + ch : zeros;
+                if constexpr (ALIGNED) {
+                    x[u] = *reinterpret_cast<const Vec*>(ptr);
+                } else {
+                    Vec v;
+#pragma unroll
+                    for (int i = 0; i < KP; ++i) v[i] = (ok && ch + i < c.cin) ? ptr[i] : (T)0.0f;
+                    x[u] = v;
+                }
             }
         };
 
@@ -145,27 +164,30 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, Con
                 for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
 
             if constexpr (!STREAM) {
-                // weights resident: waves run independently; the gathers of the next GK K-steps are in
-                // flight while the matrix cores work on the current ones
+                // weights resident: waves run independently; the gathers of the next group of K-steps
+                // are in flight while the matrix cores work on the current group (two register sets)
                 const Vec* wbase = w_lds + ((size_t)cgroup * ksteps * 2 + g) * COLS + col;
-                Vec xa[GK], xb[GK];
-#pragma unroll
-                for (int u = 0; u < GK; ++u) xa[u] = gather_one(u);
-                for (int s0 = 0; s0 < ksteps; s0 += GK) {
-                    if (s0 + GK < ksteps) {
-#pragma unroll
-                        for (int u = 0; u < GK; ++u) xb[u] = gather_one(s0 + GK + u);
-                    }
+                auto mma_group = [&](const Cursor& cu, const Vec (&x)[GK]) {
+                    const Vec* wrow = wbase + (size_t)(cu.t * kch + cu.kc0) * 2 * COLS;
 #pragma unroll
                     for (int u = 0; u < GK; ++u) {
-                        if (s0 + u < ksteps) {
-                            const Vec* wrow = wbase + (size_t)(s0 + u) * 2 * COLS;
+                        if (cu.kc0 + u < kch) {
 #pragma unroll
-                            for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wrow[b * 32], xa[u]);
+                            for (int b = 0; b < NB; ++b) { if (!(c.dbg & 1)) Mma<T>::run(acc[b], wrow[(size_t)u * 2 * COLS + b * 32], x[u]); else acc[b][0] += (float)x[u][0]; }
                         }
                     }
-#pragma unroll
-                    for (int u = 0; u < GK; ++u) xa[u] = xb[u];
+                };
+                Vec xa[GK], xb[GK];
+                Cursor ca{0, 0, 0, 0}, cb;
+                gather_group(ca, xa);
+                while (ca.t < taps) {
+                    cb = ca; advance(cb);
+                    if (cb.t < taps) gather_group(cb, xb);
+                    mma_group(ca, xa);
+                    if (cb.t >= taps) break;
+                    ca = cb; advance(ca);
+                    if (ca.t < taps) gather_group(ca, xa);
+                    mma_group(cb, xb);
                 }
             } else {
                 // weights streamed: all waves walk the slices (tap, group of 4 K-steps) in lockstep;
@@ -173,6 +195,7 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, Con
                 // LDS, one barrier per slice.  A slice holds the weights of all `cs` channel slices.
                 const int groups = (kch + kGroup - 1) / kGroup;
                 const int nslices = taps * groups;
+                constexpr int kConvThreads = 8 * kWave;         // streaming workgroups always have 8 waves
                 constexpr int WREG = 4 * NB / 2;               // >= cs * kGroup * 2 * COLS / kConvThreads for cs <= 4
                 Vec wreg[WREG];
                 auto slice_load = [&](int si) {
@@ -199,10 +222,11 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, Con
                         if (q < cs && o < per_part) dst[vi] = wreg[i];
                     }
                 };
+                static_assert(GK == kGroup, "the streamed slice is one group of K-steps");
                 auto gather_slice = [&](int si, Vec (&x)[kGroup]) {
-                    const int t = si / groups, kc0 = (si % groups) * kGroup;
-#pragma unroll
-                    for (int u = 0; u < kGroup; ++u) x[u] = gather_one(kc0 + u < kch ? t * kch + kc0 + u : ksteps);
+                    const int t = si / groups;
+                    Cursor cu{t, t / ksz, t % ksz, (si % groups) * kGroup};
+                    gather_group(cu, x);
                 };
                 Vec xa[kGroup], xb[kGroup];
                 slice_load(0);
@@ -241,18 +265,21 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(ListArgs l, Con
                 return raw_load<T, V>(reinterpret_cast<const T*>(stage + (size_t)ent * stage_stride) + (c0 - ch0));
             };
             const MaxExchange mx{xchg, cs, part};
-            uint32_t bits;
-            if (cs > 1 && full_tail && e.act != DCNN_ACT_NONE && !init)
-                bits = act_trunc_tile<T, V, 1, 4, true>(e, false, p32, lane, dx, ch0, nch, COLS, mx);
+            uint32_t bits = 0;
+            if (c.dbg & 4) { if (acc[0][0] == 12345.0f) e.out_mask[0] = 1; }
+            else if (cs > 1 && full_tail && e.act != DCNN_ACT_NONE && !init)
+                bits = act_trunc_tile<T, V, 1, 2, true>(e, false, p32, lane, dx, ch0, nch, COLS, mx);
             else
-                bits = act_trunc_tile<T, V, 1, 4, false>(e, init != 0, p32, lane, dx, ch0, nch, COLS, mx);
-            if (full_tail && lane == 0 && part == 0 && base < count) {
-                if (e.surv) e.surv[tile] = bits;
-                else if (e.out_count) atomicAdd(e.out_count, __popc(bits));
+                bits = act_trunc_tile<T, V, 1, 2, false>(e, init != 0, p32, lane, dx, ch0, nch, COLS, mx);
+            if (full_tail && part == 0 && base < count) {
+                if (e.surv) { if (lane == 0) e.surv[tile] = bits; }
+                else survivors += __popc(bits);
             }
             lds_wave_sync();
         }
     }
+    // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
+    if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
 }
 
 template <typename T, int NB>
@@ -261,7 +288,7 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
     constexpr int VEC = Elem<T>::VEC;
     const bool vec_out = (e.c % VEC) == 0;
     const bool aligned = ((size_t)c.cin * sizeof(T)) % 16 == 0;
-    const int tiles_per_iter = kConvWaves / p.cs;
+    const int tiles_per_iter = p.waves / p.cs;
     int64_t want = cdiv(l.max_count > 0 ? l.max_count : 1, tiles_per_iter * kTile);
     int64_t per_cu = (int64_t)(kLdsBytes / p.lds_bytes);
     per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
@@ -280,7 +307,7 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
             attr_set = (err == hipSuccess);                                                                      \
         }                                                                                                        \
         if (err == hipSuccess)                                                                                   \
-            hipLaunchKernelGGL(kern, dim3(grid), dim3(kConvThreads), p.lds_bytes, ctx->stream, l, c, e, ini, p.npass, p.cs); \
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(p.waves * kWave), p.lds_bytes, ctx->stream, l, c, e, ini, p.npass, p.cs); \
         launched = true;                                                                                         \
     } while (0)
     // instantiated combinations: the common case (16-byte aligned input pixels, vector-width output

@@ -6,8 +6,7 @@
 
 namespace dcnn {
 
-constexpr int kConvWaves = 8;                       // waves per workgroup; they share the weights in LDS
-constexpr int kConvThreads = kConvWaves * kWave;
+constexpr int kConvWavesMax = 12;                   // waves per workgroup (8 or 12); they share the weights in LDS
 constexpr int kStagePad = 16;                       // bytes added to a staging row against bank conflicts
 constexpr int kGroup = 4;                           // K-steps per streamed weight slice
 constexpr size_t kLdsBytes = 160 * 1024;            // LDS of one gfx950 compute unit; the context refuses less
@@ -34,6 +33,7 @@ template <> struct Mma<float> {
 // channels between them, and `npass` passes cover layers wider than nb*cs*32 channels.
 struct ConvPlan {
     int nb, cs, npass;
+    int waves;         // wavefronts per workgroup
     int cout_pad;      // npass * cs * nb * 32
     int kch;           // K-steps per tap, each covering 2 * KPACK input channels
     size_t w_bytes;    // packed weights
@@ -43,8 +43,8 @@ struct ConvPlan {
     bool ok;
 };
 
-inline size_t conv_stage_bytes(int nb, int dtype) { return (size_t)kConvWaves * kTile * (nb * 32 * dtype_size(dtype) + kStagePad); }
-inline size_t conv_xchg_bytes() { return (size_t)2 * kConvWaves * kTile * sizeof(float); }
+inline size_t conv_stage_bytes(int waves, int nb, int dtype) { return (size_t)waves * kTile * (nb * 32 * dtype_size(dtype) + kStagePad); }
+inline size_t conv_xchg_bytes(int waves) { return (size_t)2 * waves * kTile * sizeof(float); }
 
 // The plan depends only on the layer's description, so packing, sizing and launching agree on it.
 inline ConvPlan conv_plan(int dtype, int k, int cin, int cout, bool need_full_tail) {
@@ -73,14 +73,24 @@ inline ConvPlan conv_plan(int dtype, int k, int cin, int cout, bool need_full_ta
             p.kch = (int)cdiv(cin, 2 * kpack);
             p.w_bytes = (size_t)k * k * p.kch * 2 * p.cout_pad * 16;
             p.full_tail = npass == 1;
-            const size_t fixed = conv_stage_bytes(nb, dtype) + conv_xchg_bytes();
-            const size_t slice = (size_t)2 * cs * kGroup * 2 * nb * 32 * 16;   // double-buffered weight slice
-            if (p.w_bytes + fixed <= kLdsBytes) { p.stream = false; p.lds_bytes = p.w_bytes + fixed; }
-            else if (slice + fixed <= kLdsBytes) { p.stream = true; p.lds_bytes = slice + fixed; }
-            else continue;
+            // narrow accumulators leave room for 12 waves per workgroup (168 registers each): more loads
+            // in flight per compute unit; otherwise 8 waves with up to 256 registers
+            bool placed = false;
+            for (int waves : {12, 8}) {
+                if (waves == 12 && nb > 2) continue;
+                const size_t fixed = conv_stage_bytes(waves, nb, dtype) + conv_xchg_bytes(waves);
+                const size_t slice = (size_t)2 * cs * kGroup * 2 * nb * 32 * 16;   // double-buffered weight slice
+                if (p.w_bytes + fixed <= kLdsBytes) { p.stream = false; p.lds_bytes = p.w_bytes + fixed; }
+                else if (waves == 8 && slice + fixed <= kLdsBytes) { p.stream = true; p.lds_bytes = slice + fixed; }
+                else continue;
+                p.waves = waves;
+                placed = true;
+                break;
+            }
+            if (!placed) continue;
             p.ok = true;
             // fewer padded blocks first, then fewer passes, then fewer waves per tile, then preference
-            const long score = (long)npass * cap * 100000L + (long)npass * 1000L + cs * 10L + pi;
+            const long score = (long)npass * cap * 100000L + (long)npass * 1000L + (nb > 2 ? 500L : 0L) + cs * 10L + pi;
             if (best_score < 0 || score < best_score) { best = p; best_score = score; }
         }
     }

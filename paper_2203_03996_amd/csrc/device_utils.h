@@ -77,6 +77,10 @@ __device__ __forceinline__ WgTileRange wg_tile_range(int64_t n_wg_tiles) {
     return r;
 }
 
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv& f) {
+    return (__umulhi(n, f.m) + n) >> f.s;
+}
+
 __device__ __forceinline__ int pow2_ceil(int v) {
     int p = 1;
     while (p < v) p <<= 1;

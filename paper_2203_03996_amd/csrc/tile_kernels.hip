@@ -30,6 +30,7 @@ __global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a
         if (in_mask == nullptr || in_mask[p] != 0) return raw_load<T, V>(in + p * C + c0);
         return raw_zero<T, V>();
     };
+    int survivors = 0;
     const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
     for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
         const int64_t tile = wt * kTileWaves + wave;
@@ -37,11 +38,11 @@ __global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a
         if (base >= count) continue;
         const int p_mine = list_pixel(l.list, base + lane % kTile, count);
         const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
-        if (lane == 0) {
-            if (e.surv) e.surv[tile] = bits;
-            else if (e.out_count) atomicAdd(e.out_count, __popc(bits));
-        }
+        if (e.surv) { if (lane == 0) e.surv[tile] = bits; }
+        else survivors += __popc(bits);
     }
+    // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
+    if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
 }
 
 template <typename T>
@@ -113,6 +114,7 @@ __global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvAr
         for (int i = 0; i < V; ++i) raw_set<T, V>(o, i, acc[i]);
         return o;
     };
+    int survivors = 0;
     const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
     for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
         const int64_t tile = wt * kTileWaves + wave;
@@ -120,11 +122,11 @@ __global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvAr
         if (base >= count) continue;
         const int p_mine = list_pixel(l.list, base + lane % kTile, count);
         const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
-        if (lane == 0) {
-            if (e.surv) e.surv[tile] = bits;
-            else if (e.out_count) atomicAdd(e.out_count, __popc(bits));
-        }
+        if (e.surv) { if (lane == 0) e.surv[tile] = bits; }
+        else survivors += __popc(bits);
     }
+    // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
+    if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
 }
 
 template <typename T>
