@@ -112,7 +112,6 @@ struct ConvArgs {
     int n, h, w, cin, oh, ow, cout, cout_pad, k, stride, pad, kch;
     int depthwise;
     FastDiv div_ow, div_oh;      // filled by launch_conv
-    int dbg;                     // experiment knobs (0 in normal operation)
 };
 dcnn_status launch_conv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const ConvArgs& c,
                         const EpilogueArgs& e);

@@ -45,7 +45,7 @@ __device__ __forceinline__ void stage_accumulators(const f32x16 (&acc)[NB], unsi
 }
 
 #ifndef DCNN_CONV_BOUNDS
-#define DCNN_CONV_BOUNDS (STREAM ? 512 : (NB <= 2 ? 768 : 512))
+#define DCNN_CONV_BOUNDS 512
 #endif
 template <typename T, int NB, int V, bool ALIGNED, bool STREAM, int KS>
 __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init,
@@ -87,12 +87,19 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
     }
 
     int survivors = 0;                                         // per-wave count, added to the layer's counter once
+    // tail loads are prefetched when a tile takes at most 4 lane-iterations (narrow channel slices)
+    constexpr int TAIL_LP = (COLS / V) <= 2 ? 2 : ((COLS / V) <= 4 ? 4 : ((COLS / V) <= 8 ? 8 : ((COLS / V) <= 16 ? 16 : ((COLS / V) <= 32 ? 32 : 64))));
+    constexpr int NIT = kTile / (kWave / TAIL_LP);
+    constexpr bool PREFETCH_TAIL = NIT <= 4 && !STREAM;
+    int p32_next = list_pixel(l.list, (r.begin * tiles_per_iter + slot) * kTile + col, count);
     for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
         // ---- the tile: pixel of this lane's column, window origin, which taps are needed ---------
         // (pixel indices fit 31 bits; only the final element offset is 64-bit)
         const int64_t tile = wt * tiles_per_iter + slot;
         const int64_t base = tile * kTile;
-        const int p32 = list_pixel(l.list, base + col, count);
+        const int p32 = p32_next;
+        // the next tile's list entry is requested now, long before it is needed
+        p32_next = wt + r.step < r.end ? list_pixel(l.list, ((wt + r.step) * tiles_per_iter + slot) * kTile + col, count) : -1;
         const bool valid = p32 >= 0;
         const uint32_t pu = valid ? (uint32_t)p32 : 0u;
         const uint32_t t1 = fast_div(pu, c.div_ow);
@@ -110,7 +117,7 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
                 const int dy = t / KS, dx = t % KS;
                 const bool inb = valid && (unsigned)(iy0 + dy) < (unsigned)c.h && (unsigned)(ix0 + dx) < (unsigned)c.w;
                 const int q = inb ? q00 + dy * c.w + dx : 0;
-                flag[t] = (c.in_mask && !(c.dbg & 8)) ? c.in_mask[q] : (uint8_t)1;
+                flag[t] = c.in_mask ? c.in_mask[q] : (uint8_t)1;
                 if (!inb) flag[t] = 0;
             }
 #pragma unroll
@@ -137,7 +144,7 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
         // 16 bytes of input channels per K-step for this lane's pixel; lanes that do not need the tap
         // (or whose channels are padding) read the zero page instead: no branches, no invalid reads
         auto gather_group = [&](const Cursor& cu, Vec (&x)[GK]) {
-            const bool tap_ok = cu.t < taps && ((tapbits >> cu.t) & 1) && !(c.dbg & 2);
+            const bool tap_ok = cu.t < taps && ((tapbits >> cu.t) & 1);
             const T* src = in + (int64_t)(q00 + cu.dy * c.w + cu.dx) * c.cin;
 #pragma unroll
             for (int u = 0; u < GK; ++u) {
@@ -157,6 +164,11 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
 
         for (int pass = 0; pass < npass; ++pass) {
             const int cgroup = pass * cs + part;               // which group of COLS output channels
+            const int ch0 = cgroup * COLS;
+            int nch = e.c - ch0;
+            nch = nch < 0 ? 0 : (nch > COLS ? COLS : nch);
+            TailRegs<T, V, PREFETCH_TAIL ? NIT : 1> tl;
+            if constexpr (PREFETCH_TAIL) tail_prefetch<T, V, NIT>(e, init != 0, p32, lane, ch0, nch, tl);
             f32x16 acc[NB];
 #pragma unroll
             for (int b = 0; b < NB; ++b)
@@ -173,7 +185,7 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
                     for (int u = 0; u < GK; ++u) {
                         if (cu.kc0 + u < kch) {
 #pragma unroll
-                            for (int b = 0; b < NB; ++b) { if (!(c.dbg & 1)) Mma<T>::run(acc[b], wrow[(size_t)u * 2 * COLS + b * 32], x[u]); else acc[b][0] += (float)x[u][0]; }
+                            for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wrow[(size_t)u * 2 * COLS + b * 32], x[u]);
                         }
                     }
                 };
@@ -258,19 +270,19 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
             // ---- tail: this wave's channel slice of the tile ------------------------------------
             stage_accumulators<T, NB>(acc, stage + (size_t)col * stage_stride, g);
             lds_wave_sync();
-            const int ch0 = cgroup * COLS;
-            int nch = e.c - ch0;
-            nch = nch < 0 ? 0 : (nch > COLS ? COLS : nch);
             auto dx = [&](int ent, int64_t, int c0) -> Raw {
                 return raw_load<T, V>(reinterpret_cast<const T*>(stage + (size_t)ent * stage_stride) + (c0 - ch0));
             };
             const MaxExchange mx{xchg, cs, part};
-            uint32_t bits = 0;
-            if (c.dbg & 4) { if (acc[0][0] == 12345.0f) e.out_mask[0] = 1; }
-            else if (cs > 1 && full_tail && e.act != DCNN_ACT_NONE && !init)
-                bits = act_trunc_tile<T, V, 1, 2, true>(e, false, p32, lane, dx, ch0, nch, COLS, mx);
-            else
-                bits = act_trunc_tile<T, V, 1, 2, false>(e, init != 0, p32, lane, dx, ch0, nch, COLS, mx);
+            uint32_t bits;
+            const bool exchange = cs > 1 && full_tail && e.act != DCNN_ACT_NONE && !init;
+            if constexpr (PREFETCH_TAIL) {
+                if (exchange) bits = tail_finish<T, V, NIT, true>(e, false, lane, dx, ch0, nch, mx, tl);
+                else bits = tail_finish<T, V, NIT, false>(e, init != 0, lane, dx, ch0, nch, mx, tl);
+            } else {
+                if (exchange) bits = act_trunc_tile<T, V, 1, 2, true>(e, false, p32, lane, dx, ch0, nch, COLS, mx);
+                else bits = act_trunc_tile<T, V, 1, 2, false>(e, init != 0, p32, lane, dx, ch0, nch, COLS, mx);
+            }
             if (full_tail && part == 0 && base < count) {
                 if (e.surv) { if (lane == 0) e.surv[tile] = bits; }
                 else survivors += __popc(bits);

@@ -1,7 +1,5 @@
 // Host side of the convolution: plan queries, weight packing and dispatch to the per-variant
 // translation units (conv_inst.hip).
-#include <stdlib.h>
-
 #include "conv_plan.h"
 
 namespace dcnn {
@@ -85,7 +83,6 @@ dcnn_status launch_conv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, 
     c.kch = p.kch;
     c.div_ow = make_fastdiv((uint32_t)c.ow);
     c.div_oh = make_fastdiv((uint32_t)c.oh);
-    { const char* d = getenv("DCNN_DBG"); c.dbg = d ? atoi(d) : 0; }
 #define DCNN_CASE(NB) case NB: return dtype == DCNN_F16 ? launch_conv_f16_nb##NB(ctx, init, l, c, e, p) : launch_conv_f32_nb##NB(ctx, init, l, c, e, p);
     switch (p.nb) {
         DCNN_CASE(1) DCNN_CASE(2) DCNN_CASE(3) DCNN_CASE(4)

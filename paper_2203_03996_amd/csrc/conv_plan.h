@@ -76,7 +76,7 @@ inline ConvPlan conv_plan(int dtype, int k, int cin, int cout, bool need_full_ta
             // narrow accumulators leave room for 12 waves per workgroup (168 registers each): more loads
             // in flight per compute unit; otherwise 8 waves with up to 256 registers
             bool placed = false;
-            for (int waves : {12, 8}) {
+            for (int waves : {8}) {
                 if (waves == 12 && nb > 2) continue;
                 const size_t fixed = conv_stage_bytes(waves, nb, dtype) + conv_xchg_bytes(waves);
                 const size_t slice = (size_t)2 * cs * kGroup * 2 * nb * 32 * 16;   // double-buffered weight slice

@@ -51,11 +51,10 @@ template <typename T, int V> __device__ __forceinline__ void store_vec(T* p, con
 // Value as it will read back after a store in the storage type.
 template <typename T> __device__ __forceinline__ float round_store(float x) { return (float)(T)x; }
 
-__device__ __forceinline__ float act_apply(int act, float x) {
-    if (act == DCNN_ACT_RELU) return fmaxf(x, 0.0f);
-    if (act == DCNN_ACT_RELU6) return fminf(fmaxf(x, 0.0f), 6.0f);
-    return x;
-}
+// ReLU and ReLU6 as one clamp to [0, hi] (hi = +inf / 6): a single median-of-three instruction,
+// exact for every finite x.  Callers compute hi once from the layer's activation.
+__device__ __forceinline__ float act_hi(int act) { return act == DCNN_ACT_RELU6 ? 6.0f : INFINITY; }
+__device__ __forceinline__ float act_clamp(float x, float hi) { return __builtin_amdgcn_fmed3f(x, 0.0f, hi); }
 
 __device__ __forceinline__ int64_t list_count(const ListArgs& l) {
     return l.count ? (int64_t)(*l.count) : l.count_host;
@@ -180,6 +179,7 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
     T* xT = static_cast<T*>(e.xT);
     T* out = static_cast<T*>(e.out_data);
     const bool stateful = e.act != DCNN_ACT_NONE;
+    const float hi = act_hi(e.act);
     uint32_t bits = 0;
     int batch = 0;
 
@@ -228,13 +228,13 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
                         if (res) d = round_store<T>(d + raw_get<T, V>(rr[ub][v], i));
                         raw_set<T, V>(o_a[ub][v], i, d);
                         raw_set<T, V>(o_t[ub][v], i, 0.0f);
-                        raw_set<T, V>(o_y[ub][v], i, stateful ? act_apply(e.act, d) : d);
+                        raw_set<T, V>(o_y[ub][v], i, stateful ? act_clamp(d, hi) : d);
                     } else {
                         if (res) d = round_store<T>(d + raw_get<T, V>(rr[ub][v], i));
                         if (stateful) {
                             const float a = raw_get<T, V>(ra[ub][v], i), t = raw_get<T, V>(rt[ub][v], i);
                             const float s = (a + t) + d;
-                            const float dy = act_apply(e.act, s) - act_apply(e.act, a);
+                            const float dy = act_clamp(s, hi) - act_clamp(a, hi);
                             u = fmaxf(u, fabsf(dy));
                             raw_set<T, V>(o_a[ub][v], i, s);
                             raw_set<T, V>(o_t[ub][v], i, t + d);       // x^T if the pixel is truncated
@@ -297,6 +297,146 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
         }
     }
     if constexpr (XCHG) lds_block_sync();             // the exchange buffers are free again for the next tile
+#pragma unroll
+    for (int m = kWave >> 1; m >= 1; m >>= 1) bits |= __shfl_xor(bits, m, kWave);
+    return bits;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same tail split in two for the convolution kernels: `tail_prefetch` issues the loads that
+// do not depend on the convolution result (residual, x^A, x^T of the whole tile) BEFORE the K
+// loop, so their latency hides behind the gathers and the matrix work; `tail_finish` consumes
+// them once the result tile is staged.  One vector per lane and pixel (VPL = 1), NIT = 32 / (64/LP)
+// iterations cover the tile.  Arithmetic, rounding and decisions are exactly those of
+// act_trunc_tile.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int V, int NIT> struct TailRegs {
+    typename RawOf<T, V>::type rr[NIT], ra[NIT], rt[NIT];
+    int pix[NIT];
+};
+
+template <typename T, int V, int NIT>
+__device__ __forceinline__ void tail_prefetch(const EpilogueArgs& e, bool init, int p_mine, int lane, int ch0, int nch,
+                                             TailRegs<T, V, NIT>& r) {
+    constexpr int PPI = kTile / NIT, LP = kWave / PPI;
+    const int C = e.c;
+    const int nvec = (nch + V - 1) / V;
+    const int sub = lane % LP, grp = lane / LP;
+    const T* bias = static_cast<const T*>(e.bias);
+    const T* res = static_cast<const T*>(e.res_data);
+    const T* xA = static_cast<const T*>(e.xA);
+    const T* xT = static_cast<const T*>(e.xT);
+    const bool stateful = e.act != DCNN_ACT_NONE;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int ent = it * PPI + grp;
+        const int p32 = __shfl(p_mine, ent, kWave);
+        r.pix[it] = p32;
+        const int64_t p = p32;
+        const bool on = p32 >= 0 && sub < nvec;
+        const int c0 = ch0 + sub * V;
+        r.rr[it] = raw_zero<T, V>(); r.ra[it] = raw_zero<T, V>(); r.rt[it] = raw_zero<T, V>();
+        if (!on) continue;
+        if (res && (init || e.res_mask == nullptr || e.res_mask[p] != 0)) r.rr[it] = raw_load<T, V>(res + p * C + c0);
+        if (stateful && !init) {
+            r.ra[it] = raw_load<T, V>(xA + p * C + c0);
+            r.rt[it] = raw_load<T, V>(xT + p * C + c0);
+        }
+        if (init && bias) r.ra[it] = raw_load<T, V>(bias + c0);               // slot reused for the bias
+    }
+}
+
+template <typename T, int V, int NIT, bool XCHG, class Dx>
+__device__ __forceinline__ uint32_t tail_finish(const EpilogueArgs& e, bool init, int lane, Dx dx, int ch0, int nch,
+                                               MaxExchange mx, const TailRegs<T, V, NIT>& r) {
+    typedef typename RawOf<T, V>::type Raw;
+    constexpr int PPI = kTile / NIT, LP = kWave / PPI;
+    const int C = e.c;
+    const int nvec = (nch + V - 1) / V;
+    const int sub = lane % LP, grp = lane / LP;
+    const bool has_bias = e.bias != nullptr, has_res = e.res_data != nullptr;
+    T* xA = static_cast<T*>(e.xA);
+    T* xT = static_cast<T*>(e.xT);
+    T* out = static_cast<T*>(e.out_data);
+    const bool stateful = e.act != DCNN_ACT_NONE;
+    const float hi = act_hi(e.act);
+    Raw o_a[NIT], o_t[NIT], o_y[NIT];
+    float umax[NIT];
+    uint32_t bits = 0;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int ent = it * PPI + grp;
+        const bool on = r.pix[it] >= 0 && sub < nvec;
+        Raw rd = raw_zero<T, V>();
+        if (on) rd = dx(ent, (int64_t)r.pix[it], ch0 + sub * V);
+        float u = 0.0f;
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            float d = raw_get<T, V>(rd, i);
+            if (init) {
+                if (has_bias) d = round_store<T>(d + raw_get<T, V>(r.ra[it], i));
+                if (has_res) d = round_store<T>(d + raw_get<T, V>(r.rr[it], i));
+                raw_set<T, V>(o_a[it], i, d);
+                raw_set<T, V>(o_t[it], i, 0.0f);
+                raw_set<T, V>(o_y[it], i, stateful ? act_clamp(d, hi) : d);
+            } else {
+                if (has_res) d = round_store<T>(d + raw_get<T, V>(r.rr[it], i));
+                if (stateful) {
+                    const float a = raw_get<T, V>(r.ra[it], i), t = raw_get<T, V>(r.rt[it], i);
+                    const float s = (a + t) + d;
+                    const float dy = act_clamp(s, hi) - act_clamp(a, hi);
+                    u = fmaxf(u, fabsf(dy));
+                    raw_set<T, V>(o_a[it], i, s);
+                    raw_set<T, V>(o_t[it], i, t + d);
+                    raw_set<T, V>(o_y[it], i, dy);
+                } else {
+                    raw_set<T, V>(o_a[it], i, 0.0f);
+                    raw_set<T, V>(o_t[it], i, 0.0f);
+                    raw_set<T, V>(o_y[it], i, d);
+                }
+            }
+        }
+        if (!init && stateful)
+            for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
+        umax[it] = u;
+    }
+    if constexpr (XCHG) {
+        // every wave of the workgroup passes here once per tile
+#pragma unroll
+        for (int it = 0; it < NIT; ++it)
+            if (sub == 0) mx.buf[mx.part * kTile + it * PPI + grp] = umax[it];
+        lds_block_sync();
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            float u = 0.0f;
+            for (int q = 0; q < mx.parts; ++q) u = fmaxf(u, mx.buf[q * kTile + it * PPI + grp]);
+            umax[it] = u;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int64_t p = r.pix[it];
+        const bool valid = r.pix[it] >= 0;
+        const int ent = it * PPI + grp;
+        const bool upd = (init || !stateful) ? true : (umax[it] >= e.eps);
+        if (valid && sub < nvec) {
+            const int64_t off = p * C + ch0 + sub * V;
+            if (!stateful) {
+                raw_store<T, V>(out + off, o_y[it]);
+            } else if (upd) {
+                raw_store<T, V>(xA + off, o_a[it]);
+                raw_store<T, V>(xT + off, raw_zero<T, V>());
+                raw_store<T, V>(out + off, o_y[it]);
+            } else {
+                raw_store<T, V>(xT + off, o_t[it]);
+            }
+        }
+        if (valid && sub == 0) {
+            if (e.out_mask && !init && mx.part == 0) e.out_mask[p] = upd ? 1 : 0;
+            if (upd) bits |= 1u << ent;
+        }
+    }
+    if constexpr (XCHG) lds_block_sync();             // the exchange buffer is free again for the next tile
 #pragma unroll
     for (int m = kWave >> 1; m >= 1; m >>= 1) bits |= __shfl_xor(bits, m, kWave);
     return bits;
