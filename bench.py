@@ -268,6 +268,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--streams", type=int, default=64, help="independent camera streams batched on the GPU")
     ap.add_argument("--quick", action="store_true", help="headline measurement only (no sweep, no baselines)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the measurement run one plain 1 GiB device-to-device copy kernel (reference for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (streams are independent; see DESIGN.md for how the "
@@ -361,6 +364,13 @@ def main():
         result["cpu_baseline"] = cpu_baseline(work, eps_h)
     else:
         result["cpu_baseline"] = cpu_baseline(work, eps_h, budget_s=3.0)
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                        # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        result["calibration_copy_bytes"] = int(src.numel() * 4)
     result["paper_context"] = "paper reports up to 7x over cuDNN on Jetson Nano / GTX 1050 / RTX 3090 (other hardware; context only)"
     print(json.dumps(result))
 
