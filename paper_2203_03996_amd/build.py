@@ -26,11 +26,12 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    extra_env = os.environ.get("DCNN_EXTRA_FLAGS", "").split()
 
     def compile_one(item) -> str:
         src, objname, extra = item
         obj = os.path.join(objdir, objname)
-        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *extra_env, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:

@@ -91,38 +91,58 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
     constexpr int TAIL_LP = (COLS / V) <= 2 ? 2 : ((COLS / V) <= 4 ? 4 : ((COLS / V) <= 8 ? 8 : ((COLS / V) <= 16 ? 16 : ((COLS / V) <= 32 ? 32 : 64))));
     constexpr int NIT = kTile / (kWave / TAIL_LP);
     constexpr bool PREFETCH_TAIL = NIT <= 4 && !STREAM;
-    int p32_next = list_pixel(l.list, (r.begin * tiles_per_iter + slot) * kTile + col, count);
+    // Software pipeline over tiles: the list entry of tile n+2 and the update flags of tile n+1 are
+    // requested while tile n is processed, so neither round trip sits on a tile's critical path.
+    struct TileGeom { int p32; bool valid; int iy0, ix0, q00; };
+    auto geometry = [&](int p32) {
+        TileGeom gm;
+        gm.p32 = p32;
+        gm.valid = p32 >= 0;
+        const uint32_t pu = gm.valid ? (uint32_t)p32 : 0u;
+        const uint32_t t1 = fast_div(pu, c.div_ow);
+        const int ox = (int)(pu - t1 * (uint32_t)c.ow);
+        const uint32_t n = fast_div(t1, c.div_oh);
+        const int oy = (int)(t1 - n * (uint32_t)c.oh);
+        gm.iy0 = oy * c.stride - c.pad;
+        gm.ix0 = ox * c.stride - c.pad;
+        gm.q00 = ((int)n * c.h + gm.iy0) * c.w + gm.ix0;       // pixel index of tap (0,0); only used when in bounds
+        return gm;
+    };
+    constexpr int NFLAG = KS ? KS * KS : 1;
+    auto request_flags = [&](const TileGeom& gm, uint8_t (&flag)[NFLAG]) {
+        // fixed window: all update flags of the window are requested at once (tested one tile later)
+        if constexpr (KS != 0) {
+#pragma unroll
+            for (int t = 0; t < KS * KS; ++t) {
+                const int dy = t / KS, dx = t % KS;
+                const bool inb = gm.valid && (unsigned)(gm.iy0 + dy) < (unsigned)c.h && (unsigned)(gm.ix0 + dx) < (unsigned)c.w;
+                const int q = inb ? gm.q00 + dy * c.w + dx : 0;
+                flag[t] = c.in_mask ? c.in_mask[q] : (uint8_t)1;
+                if (!inb) flag[t] = 0;
+            }
+        }
+    };
+    auto entry = [&](int64_t wt_) {
+        return wt_ < r.end ? list_pixel(l.list, (wt_ * tiles_per_iter + slot) * kTile + col, count) : -1;
+    };
+    TileGeom g_next = geometry(entry(r.begin));
+    int p32_next2 = entry(r.begin + r.step);
+    uint8_t flag_next[NFLAG];
+    request_flags(g_next, flag_next);
     for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
         // ---- the tile: pixel of this lane's column, window origin, which taps are needed ---------
         // (pixel indices fit 31 bits; only the final element offset is 64-bit)
         const int64_t tile = wt * tiles_per_iter + slot;
         const int64_t base = tile * kTile;
-        const int p32 = p32_next;
-        // the next tile's list entry is requested now, long before it is needed
-        p32_next = wt + r.step < r.end ? list_pixel(l.list, ((wt + r.step) * tiles_per_iter + slot) * kTile + col, count) : -1;
-        const bool valid = p32 >= 0;
-        const uint32_t pu = valid ? (uint32_t)p32 : 0u;
-        const uint32_t t1 = fast_div(pu, c.div_ow);
-        const int ox = (int)(pu - t1 * (uint32_t)c.ow);
-        const uint32_t n = fast_div(t1, c.div_oh);
-        const int oy = (int)(t1 - n * (uint32_t)c.oh);
-        const int iy0 = oy * c.stride - c.pad, ix0 = ox * c.stride - c.pad;
-        const int q00 = ((int)n * c.h + iy0) * c.w + ix0;      // pixel index of tap (0,0); only used when in bounds
+        const TileGeom gm = g_next;
+        const int p32 = gm.p32;
+        const bool valid = gm.valid;
+        const int iy0 = gm.iy0, ix0 = gm.ix0, q00 = gm.q00;
         uint64_t tapbits = 0;
         if constexpr (KS != 0) {
-            // fixed window: all update flags of the window are requested at once, then tested
-            uint8_t flag[KS * KS];
-#pragma unroll
-            for (int t = 0; t < KS * KS; ++t) {
-                const int dy = t / KS, dx = t % KS;
-                const bool inb = valid && (unsigned)(iy0 + dy) < (unsigned)c.h && (unsigned)(ix0 + dx) < (unsigned)c.w;
-                const int q = inb ? q00 + dy * c.w + dx : 0;
-                flag[t] = c.in_mask ? c.in_mask[q] : (uint8_t)1;
-                if (!inb) flag[t] = 0;
-            }
 #pragma unroll
             for (int t = 0; t < KS * KS; ++t)
-                if (flag[t]) tapbits |= 1ull << t;
+                if (flag_next[t]) tapbits |= 1ull << t;
         } else {
             for (int t = 0, dy = 0, dx = 0; t < taps; ++t) {
                 bool ok = valid && (unsigned)(iy0 + dy) < (unsigned)c.h && (unsigned)(ix0 + dx) < (unsigned)c.w;
@@ -131,6 +151,10 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
                 if (++dx == ksz) { dx = 0; ++dy; }
             }
         }
+        // requests for the tiles to come
+        g_next = geometry(p32_next2);
+        p32_next2 = entry(wt + 2 * r.step);
+        request_flags(g_next, flag_next);
 
         // Wave-uniform cursor over groups of GK K-steps: tap t = (dy, dx), first K-step kc0 of the group.
         struct Cursor { int t, dy, dx, kc0; };
@@ -180,12 +204,21 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
                 // are in flight while the matrix cores work on the current group (two register sets)
                 const Vec* wbase = w_lds + ((size_t)cgroup * ksteps * 2 + g) * COLS + col;
                 auto mma_group = [&](const Cursor& cu, const Vec (&x)[GK]) {
+                    // all weight operands of the group are requested from LDS before the first MFMA issues,
+                    // so their latency is paid once per group instead of once per instruction
                     const Vec* wrow = wbase + (size_t)(cu.t * kch + cu.kc0) * 2 * COLS;
+                    Vec wv[GK][NB];
+#pragma unroll
+                    for (int u = 0; u < GK; ++u)
+#pragma unroll
+                        for (int b = 0; b < NB; ++b)
+                            wv[u][b] = (cu.kc0 + u < kch) ? wrow[(size_t)u * 2 * COLS + b * 32] : wrow[b * 32];
+                    asm volatile("" ::: "memory");
 #pragma unroll
                     for (int u = 0; u < GK; ++u) {
                         if (cu.kc0 + u < kch) {
 #pragma unroll
-                            for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wrow[(size_t)u * 2 * COLS + b * 32], x[u]);
+                            for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wv[u][b], x[u]);
                         }
                     }
                 };
