@@ -17,32 +17,9 @@
 #pragma once
 
 #include "conv_plan.h"
+#include "conv_ws_impl.h"
 
 namespace dcnn {
-
-// accumulators -> staging tile [pixel][nb*32 channels] in the storage type.  Lane (col, g) holds,
-// for pixel `col`, the output channels 8*q + 4*g + {0..3} of every 32-channel block.
-template <typename T, int NB>
-__device__ __forceinline__ void stage_accumulators(const f32x16 (&acc)[NB], unsigned char* row, int g) {
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            T* dst = reinterpret_cast<T*>(row) + b * 32 + 8 * q + 4 * g;
-            if constexpr (sizeof(T) == 2) {
-                f16x4 v;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = (f16)acc[b][4 * q + i];
-                *reinterpret_cast<f16x4*>(dst) = v;
-            } else {
-                f32x4 v;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = acc[b][4 * q + i];
-                *reinterpret_cast<f32x4*>(dst) = v;
-            }
-        }
-    }
-}
 
 #ifndef DCNN_CONV_BOUNDS
 #define DCNN_CONV_BOUNDS 512
@@ -355,6 +332,33 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
             hipLaunchKernelGGL(kern, dim3(grid), dim3(p.waves * kWave), p.lds_bytes, ctx->stream, l, c, e, ini, p.npass, p.cs); \
         launched = true;                                                                                         \
     } while (0)
+    // resident weights, vector-aligned channels, one pass, sparse step: the wave-specialised kernel
+    const size_t ws_lds = conv_ws_lds_bytes(p, sizeof(T) == 2 ? DCNN_F16 : DCNN_F32, c.k, e.c);
+    const uint64_t in_bytes = (uint64_t)c.n * c.h * c.w * c.cin * sizeof(T);
+    const uint64_t out_bytes = (uint64_t)c.n * c.oh * c.ow * e.c * sizeof(T);
+    if (vec_out && aligned && ws_lds != 0 && !init && in_bytes <= kWsMaxBytes && out_bytes <= kWsMaxBytes) {
+        const int64_t ws_want = cdiv(l.max_count > 0 ? l.max_count : 1, (kWsProducers / p.cs) * kTile);
+        const int64_t ws_cap = ctx->num_cu;                    // 16 waves of up to 128 registers fill a compute unit
+        const int ws_grid = (int)(cdiv(ws_want < ws_cap ? ws_want : ws_cap, kXcd) * kXcd);
+#define DCNN_WS_LAUNCH(KS, RES)                                                                                  \
+    do {                                                                                                         \
+        auto kern = conv_ws_kernel<T, NB, KS, RES>;                                                              \
+        static bool attr_set = false;                                                                            \
+        if (!attr_set) {                                                                                         \
+            err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                      (int)kLdsBytes);                                                           \
+            attr_set = (err == hipSuccess);                                                                      \
+        }                                                                                                        \
+        if (err == hipSuccess)                                                                                   \
+            hipLaunchKernelGGL(kern, dim3(ws_grid), dim3(kWsWaves * kWave), ws_lds, ctx->stream, l, c, e, p.cs); \
+    } while (0)
+        const bool has_res = e.res_data != nullptr;
+        if (c.k == 1) { if (has_res) DCNN_WS_LAUNCH(1, true); else DCNN_WS_LAUNCH(1, false); }
+        else { if (has_res) DCNN_WS_LAUNCH(3, true); else DCNN_WS_LAUNCH(3, false); }
+#undef DCNN_WS_LAUNCH
+        if (err != hipSuccess) return check_hip(ctx, err, "hipFuncSetAttribute(conv_ws_kernel)");
+        return check_hip(ctx, hipGetLastError(), "conv_ws_kernel launch");
+    }
     // instantiated combinations: the common case (16-byte aligned input pixels, vector-width output
     // channels) is specialised on the window size; odd shapes take the generic-window kernels
     if (vec_out && aligned) {

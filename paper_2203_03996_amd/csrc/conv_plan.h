@@ -28,6 +28,30 @@ template <> struct Mma<float> {
     }
 };
 
+// accumulators -> staging tile [pixel][nb*32 channels] in the storage type.  Lane (col, g) holds,
+// for pixel `col`, the output channels 8*q + 4*g + {0..3} of every 32-channel block.
+template <typename T, int NB>
+__device__ __forceinline__ void stage_accumulators(const f32x16 (&acc)[NB], unsigned char* row, int g) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            T* dst = reinterpret_cast<T*>(row) + b * 32 + 8 * q + 4 * g;
+            if constexpr (sizeof(T) == 2) {
+                f16x4 v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = (f16)acc[b][4 * q + i];
+                *reinterpret_cast<f16x4*>(dst) = v;
+            } else {
+                f32x4 v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = acc[b][4 * q + i];
+                *reinterpret_cast<f32x4*>(dst) = v;
+            }
+        }
+    }
+}
+
 // How the output channels of a layer are spread: every wave holds `nb` MFMA column blocks (32
 // output channels each) in its accumulators, `cs` waves share one tile of 32 pixels and split its
 // channels between them, and `npass` passes cover layers wider than nb*cs*32 channels.

@@ -1,0 +1,379 @@
+// Sparse delta convolution with resident weights, wave-specialised.
+//
+// A tile of the sparse convolution has two halves with opposite needs.  The gather-GEMM wants many
+// short cache-hit loads and the matrix cores; the activation + truncation tail wants a few long
+// loads of layer state that come from HBM, and plain vector arithmetic.  One wave that does both in
+// turn waits for each memory system in turn, and the registers of both halves limit the compute
+// unit to two waves per SIMD.  Here a workgroup of 16 waves splits the roles:
+//   producers (waves 0-7)   gather the flagged taps of a tile, multiply on the matrix cores and
+//                           leave the rounded result tile in LDS;
+//   consumers (waves 8-15)  pick the tile of the PREVIOUS round up from LDS, apply residual /
+//                           activation / truncation (Section 3.1, Eqs. 4-6), and write state, output
+//                           delta, update mask and survivor word with coalesced 16-byte accesses.
+// The result tiles are double-buffered, so one workgroup barrier per round is the only coupling.
+// Each role needs at most 128 registers: four waves per SIMD, and while the consumers wait for
+// HBM the producers keep the matrix cores and the L2 busy.
+//
+// The channels of a tile are split over `cs` producers (nb*32 output channels each); the consumers
+// split the same tile by PIXELS instead (32/cs pixels, all channels), so the per-pixel maximum
+// stays inside one wave.
+//
+// All global traffic uses buffer addressing (32-bit byte offsets against a descriptor): address
+// arithmetic is one add per access, and a lane that must not touch memory (tap not flagged, pixel
+// beyond the list, pixel truncated) simply gets an offset beyond the descriptor's range, for which
+// the hardware returns zeros on loads and drops stores.  No branches, no unflagged memory read.
+// Every tensor therefore has to stay below 2 GiB; larger ones run on the plain kernel, as does the
+// dense first frame (bias, no truncation).
+#pragma once
+
+#include "conv_plan.h"
+
+namespace dcnn {
+
+constexpr int kWsProducers = 8;
+constexpr int kWsWaves = 16;
+constexpr uint32_t kOob = 0x80000000u;                         // byte offset no descriptor here reaches
+constexpr uint64_t kWsMaxBytes = 0x7fffffffull;
+
+constexpr int ws_pow2_ceil(int v) { int p = 1; while (p < v) p <<= 1; return p; }
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// LDS needed by the wave-specialised kernel; 0 when the shape is not covered by it.
+inline size_t conv_ws_lds_bytes(const ConvPlan& p, int dtype, int k, int cout) {
+    const int vec = dtype == DCNN_F16 ? 8 : 4;
+    if (p.stream || p.npass != 1 || cout % vec != 0 || (k != 1 && k != 3)) return 0;
+    const int lpb = ws_pow2_ceil(p.nb * 32 / vec);
+    if (p.cs * lpb > kWave) return 0;
+    const size_t bytes = p.w_bytes + 2 * conv_stage_bytes(kWsProducers, p.nb, dtype);
+    return bytes <= kLdsBytes ? bytes : 0;
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t ws_rsrc(const void* p, uint64_t bytes) {
+    // raw buffer (stride 0), 32-bit data format; a null pointer gives an empty range
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, p ? (int)bytes : 0, 0x00020000);
+}
+template <typename Raw> __device__ __forceinline__ Raw ws_load16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    return __builtin_bit_cast(Raw, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0));
+}
+template <typename Raw> __device__ __forceinline__ void ws_store16(__amdgpu_buffer_rsrc_t r, uint32_t off, Raw v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)off, 0, 0);
+}
+
+template <typename T, int NB, int KS, bool RES>
+__global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int cs) {
+    typedef typename Mma<T>::Vec Vec;
+    constexpr int V = Elem<T>::VEC;
+    typedef typename RawOf<T, V>::type Raw;
+    constexpr int COLS = NB * 32;
+    constexpr int GK = 4;                                      // K-steps whose gathers are in flight together
+    constexpr int NP = kWsProducers;
+    constexpr int ES = (int)sizeof(T);
+    static_assert(sizeof(Vec) == 16 && sizeof(Raw) == 16, "16-byte channel vectors");
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tiles_per_iter = NP / cs;
+    const int64_t count = list_count(l);
+    const WgTileRange r = wg_tile_range((count + tiles_per_iter * kTile - 1) / (tiles_per_iter * kTile));
+    if (r.begin >= r.end) return;                              // nothing for this workgroup: skip the weight load
+    const int rounds = (int)((r.end - r.begin + r.step - 1) / r.step);
+
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const bool producer = wave < NP;
+    const int ww = producer ? wave : wave - NP;
+    const int slot = ww / cs, part = ww % cs;                  // which tile of the round; channel slice / pixel slice
+    const int taps = KS * KS, kch = c.kch;
+    const int ksteps = taps * kch;
+    const int w_vecs = cs * ksteps * 2 * COLS;
+    Vec* w_lds = reinterpret_cast<Vec*>(smem);
+    constexpr int stage_stride = COLS * ES + kStagePad;
+    constexpr int stage_tile = kTile * stage_stride;
+    unsigned char* stage0 = smem + (size_t)w_vecs * 16;        // [2][NP][32 pixels][stage_stride]
+    // pixel of entry `j` of the work list of round `rd` (this wave's tile), -1 beyond the list
+    auto tile_of = [&](int rd) { return (r.begin + (int64_t)rd * r.step) * tiles_per_iter + slot; };
+    auto list_entry = [&](int rd, int j) { return rd < rounds ? list_pixel(l.list, tile_of(rd) * kTile + j, count) : -1; };
+
+    {
+        const Vec* wglob = static_cast<const Vec*>(c.wpacked);
+        for (int i = threadIdx.x; i < w_vecs; i += kWsWaves * kWave) w_lds[i] = wglob[i];
+    }
+    lds_block_sync();
+
+    // Both roles pass the same number of workgroup barriers: one per round 0..rounds.
+    if (producer) {
+        // =====================================================================================
+        // producer: tile -> gathered taps x weights -> rounded result tile in LDS
+        // =====================================================================================
+        const int col = lane % 32, g = lane / 32;
+        const uint64_t in_pixels = (uint64_t)c.n * c.h * c.w;
+        const __amdgpu_buffer_rsrc_t rs_in = ws_rsrc(c.in_data, in_pixels * c.cin * ES);
+        const __amdgpu_buffer_rsrc_t rs_mask = ws_rsrc(c.in_mask, in_pixels);
+        const bool has_mask = c.in_mask != nullptr;
+        const int cin_bytes = c.cin * ES;
+        const bool cin_full = kch * 32 == cin_bytes;           // no K-step reaches past the pixel's channels
+        // Software pipeline over tiles: the list entry of tile n+2 and the update flags of tile n+1
+        // are requested while tile n is processed.
+        struct TileGeom { bool valid; int iy0, ix0, q00; };
+        auto geometry = [&](int p32) {
+            TileGeom gm;
+            gm.valid = p32 >= 0;
+            const uint32_t pu = gm.valid ? (uint32_t)p32 : 0u;
+            const uint32_t t1 = fast_div(pu, c.div_ow);
+            const int ox = (int)(pu - t1 * (uint32_t)c.ow);
+            const uint32_t n = fast_div(t1, c.div_oh);
+            const int oy = (int)(t1 - n * (uint32_t)c.oh);
+            gm.iy0 = oy * c.stride - c.pad;
+            gm.ix0 = ox * c.stride - c.pad;
+            gm.q00 = ((int)n * c.h + gm.iy0) * c.w + gm.ix0;   // pixel index of tap (0,0); only used when in bounds
+            return gm;
+        };
+        // update flag of every window tap (0 outside the image or beyond the list)
+        auto request_flags = [&](const TileGeom& gm, uint8_t (&flag)[KS * KS]) {
+#pragma unroll
+            for (int t = 0; t < KS * KS; ++t) {
+                const int dy = t / KS, dx = t % KS;
+                const bool inb = gm.valid && (unsigned)(gm.iy0 + dy) < (unsigned)c.h && (unsigned)(gm.ix0 + dx) < (unsigned)c.w;
+                const uint32_t off = inb ? (uint32_t)(gm.q00 + dy * c.w + dx) : kOob;
+                flag[t] = has_mask ? __builtin_amdgcn_raw_buffer_load_b8(rs_mask, (int)off, 0, 0) : (uint8_t)inb;
+            }
+        };
+        TileGeom g_next = geometry(list_entry(0, col));
+        int p32_next2 = list_entry(1, col);
+        uint8_t flag_next[KS * KS];
+        request_flags(g_next, flag_next);
+        const Vec* wbase = w_lds + ((size_t)part * ksteps * 2 + g) * COLS + col;
+
+        for (int rd = 0; rd <= rounds; ++rd) {
+            if (rd < rounds) {
+                // byte offset of this lane's 16 bytes in tap (0,0), K-step 0
+                const uint32_t base00 = (uint32_t)g_next.q00 * (uint32_t)cin_bytes + (uint32_t)g * 16u;
+                uint32_t tapbits = 0;
+#pragma unroll
+                for (int t = 0; t < KS * KS; ++t)
+                    if (flag_next[t]) tapbits |= 1u << t;
+                g_next = geometry(p32_next2);
+                p32_next2 = list_entry(rd + 2, col);
+                request_flags(g_next, flag_next);
+
+                // Wave-uniform cursor over groups of GK K-steps: tap t = (dy, dx), first K-step kc0.
+                struct Cursor { int t, dy, dx, kc0; };
+                auto advance = [&](Cursor& cu) {
+                    cu.kc0 += GK;
+                    if (cu.kc0 >= kch) {
+                        cu.kc0 = 0; ++cu.t;
+                        if (++cu.dx == KS) { cu.dx = 0; ++cu.dy; }
+                    }
+                };
+                // 16 bytes of input channels per K-step for this lane's pixel; lanes that do not need
+                // the tap (or whose channels are padding) get zeros from an out-of-range offset
+                auto gather_group = [&](const Cursor& cu, Vec (&x)[GK]) {
+                    const bool tap_ok = (tapbits >> cu.t) & 1;
+                    const uint32_t uni = (uint32_t)((cu.dy * c.w + cu.dx) * cin_bytes + cu.kc0 * 32);
+                    const uint32_t off = tap_ok ? base00 + uni : kOob;
+#pragma unroll
+                    for (int u = 0; u < GK; ++u) {
+                        uint32_t o = off + (uint32_t)u * 32u;
+                        if (!cin_full && (2 * (cu.kc0 + u) + g) * 16 >= cin_bytes) o = kOob;
+                        x[u] = ws_load16<Vec>(rs_in, o);
+                    }
+                };
+                f32x16 acc[NB];
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+                auto mma_group = [&](const Cursor& cu, const Vec (&x)[GK]) {
+                    const Vec* wrow = wbase + (size_t)(cu.t * kch + cu.kc0) * 2 * COLS;
+#pragma unroll
+                    for (int u = 0; u < GK; ++u) {
+                        if (cu.kc0 + u < kch) {
+#pragma unroll
+                            for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wrow[(size_t)u * 2 * COLS + b * 32], x[u]);
+                        }
+                    }
+                };
+                Vec xa[GK], xb[GK];
+                Cursor ca{0, 0, 0, 0}, cb;
+                gather_group(ca, xa);
+                while (ca.t < taps) {
+                    cb = ca; advance(cb);
+                    if (cb.t < taps) gather_group(cb, xb);
+                    mma_group(ca, xa);
+                    if (cb.t >= taps) break;
+                    ca = cb; advance(ca);
+                    if (ca.t < taps) gather_group(ca, xa);
+                    mma_group(cb, xb);
+                }
+                unsigned char* tile_stage = stage0 + (size_t)((rd & 1) * NP + ww) * stage_tile;
+                stage_accumulators<T, NB>(acc, tile_stage + (size_t)col * stage_stride, g);
+            }
+            lds_block_sync();
+        }
+    } else {
+        // =====================================================================================
+        // consumer: result tile of the previous round -> residual / activation / truncation
+        // =====================================================================================
+        constexpr int LPB = ws_pow2_ceil(COLS / V);            // lanes per pixel and producer slice
+        constexpr int NIT = LPB / 2;                           // lane-iterations over this wave's 32/cs pixels
+        constexpr int H = NIT >= 4 ? 2 : 1;                    // iterations per register set
+        constexpr int NS = NIT / H;                            // sets per tile; two register sets alternate
+        static_assert(NIT >= 2 && NS * H == NIT && NS % 2 == 0, "tile iterations split into an even number of sets");
+        const int LP = cs * LPB;                               // lanes per pixel (all channels), <= 64
+        const int PPI = kWave / LP;                            // pixels per iteration
+        const int sub = lane % LP, grp = lane / LP;
+        const int spart = sub / LPB, vi = sub % LPB;
+        const int c0 = spart * COLS + vi * V;                  // first of this lane's V channels
+        const bool ch_on = vi * V < COLS && c0 < e.c;
+        const int ent0 = part * (kTile / cs) + grp;            // tile entry of iteration 0
+        const uint32_t row_bytes = (uint32_t)e.c * ES;
+        const uint32_t ch_bytes = (uint32_t)c0 * ES;
+        const uint64_t out_pixels = (uint64_t)c.n * c.oh * c.ow;
+        const uint64_t out_bytes = out_pixels * row_bytes;
+        const bool stateful = e.act != DCNN_ACT_NONE;
+        const __amdgpu_buffer_rsrc_t rs_xA = ws_rsrc(e.xA, out_bytes), rs_xT = ws_rsrc(e.xT, out_bytes);
+        const __amdgpu_buffer_rsrc_t rs_out = ws_rsrc(e.out_data, out_bytes);
+        const __amdgpu_buffer_rsrc_t rs_res = ws_rsrc(e.res_data, out_bytes);
+        const __amdgpu_buffer_rsrc_t rs_rmask = ws_rsrc(e.res_mask, out_pixels);
+        const __amdgpu_buffer_rsrc_t rs_omask = ws_rsrc(e.out_mask, out_pixels);
+        const bool has_rmask = e.res_mask != nullptr;
+        const float hi = act_hi(e.act);
+        // this lane's 16 bytes in row 0 of the producer slice that holds its channels (lanes without
+        // channels read slot 0: harmless, their stores go nowhere)
+        const unsigned char* my_stage = stage0 + (size_t)(slot * cs + spart) * stage_tile + (size_t)(ch_on ? vi : 0) * V * ES;
+        int survivors = 0;
+
+        struct Tile {
+            int pix[NIT];          // pixel of iteration it (-1 beyond the list)
+            uint32_t off[NIT];     // byte offset of this lane's channels (out of range: nothing to do)
+            uint8_t rflag[NIT];    // update flag of the residual stream
+        };
+        // derived values of a tile whose list entries have arrived; requests its residual flags
+        auto prepare = [&](Tile& t) {
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int p = t.pix[it];
+                t.off[it] = (p >= 0 && ch_on) ? (uint32_t)p * row_bytes + ch_bytes : kOob;
+                t.rflag[it] = 1;
+                if constexpr (RES) {
+                    if (has_rmask) t.rflag[it] = __builtin_amdgcn_raw_buffer_load_b8(rs_rmask, p >= 0 ? p : (int)kOob, 0, 0);
+                }
+            }
+        };
+        struct Set { Raw ra[H], rt[H], rr[RES ? H : 1]; };
+        // loads that do not depend on the convolution result, for the H iterations of set s
+        auto load_set = [&](const Tile& t, int s, Set& st) {
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const uint32_t o = t.off[s * H + h];
+                if constexpr (RES) st.rr[h] = ws_load16<Raw>(rs_res, t.rflag[s * H + h] ? o : kOob);
+                if (stateful) {
+                    st.ra[h] = ws_load16<Raw>(rs_xA, o);
+                    st.rt[h] = ws_load16<Raw>(rs_xT, o);
+                }
+            }
+        };
+        // arithmetic, decision and stores of set s; returns the survivor bits of its pixels
+        auto finish_set = [&](const Tile& t, int s, const Set& st, const unsigned char* tile_stage) -> uint32_t {
+            uint32_t bits = 0;
+            Raw rd[H];
+#pragma unroll
+            for (int h = 0; h < H; ++h)
+                rd[h] = raw_load<T, V>(reinterpret_cast<const T*>(tile_stage + (size_t)(ent0 + (s * H + h) * PPI) * stage_stride));
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const int it = s * H + h;
+                const uint32_t o = t.off[it];
+                Raw d = rd[h];
+                if constexpr (RES) {
+#pragma unroll
+                    for (int i = 0; i < V; ++i) raw_set<T, V>(d, i, raw_get<T, V>(rd[h], i) + raw_get<T, V>(st.rr[h], i));
+                }
+                bool upd = true;
+                if (stateful) {
+                    Raw o_a, o_t, o_y;
+                    float u = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < V; ++i) {
+                        const float dd = raw_get<T, V>(d, i);
+                        const float a = raw_get<T, V>(st.ra[h], i), tt = raw_get<T, V>(st.rt[h], i);
+                        const float sum = (a + tt) + dd;
+                        const float dy = act_clamp(sum, hi) - act_clamp(a, hi);
+                        u = fmaxf(u, fabsf(dy));
+                        raw_set<T, V>(o_a, i, sum);
+                        raw_set<T, V>(o_t, i, tt + dd);             // x^T if the pixel is truncated
+                        raw_set<T, V>(o_y, i, dy);
+                    }
+                    for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
+                    upd = u >= e.eps;
+                    const uint32_t o_upd = upd ? o : kOob;
+                    ws_store16<Raw>(rs_xA, o_upd, o_a);
+                    ws_store16<Raw>(rs_xT, o, upd ? raw_zero<T, V>() : o_t);
+                    ws_store16<Raw>(rs_out, o_upd, o_y);
+                } else {
+                    ws_store16<Raw>(rs_out, o, d);
+                }
+                const bool lead = t.pix[it] >= 0 && sub == 0;
+                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)(upd ? 1 : 0), rs_omask, lead ? t.pix[it] : (int)kOob, 0, 0);
+                if (lead && upd) bits |= 1u << (ent0 + it * PPI);
+            }
+            return bits;
+        };
+
+        // Software pipeline.  List entries are requested two tiles ahead, residual flags one tile ahead,
+        // and over the sets of consecutive tiles: while set s is finished, the loads of set s+1 (issued
+        // one step earlier) and of set s+2 (issued right after) are in flight.
+        Tile cur, nxt;
+        int pix_nn[NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            cur.pix[it] = list_entry(0, ent0 + it * PPI);
+            nxt.pix[it] = list_entry(1, ent0 + it * PPI);
+            pix_nn[it] = list_entry(2, ent0 + it * PPI);
+        }
+        prepare(cur);
+        prepare(nxt);
+        Set set0, set1;
+        load_set(cur, 0, set0);
+        load_set(cur, 1, set1);
+        lds_block_sync();                                      // round 0: the producers fill the first tiles
+        for (int rd = 1; rd <= rounds; ++rd) {
+            // `cur` is the tile produced in round rd-1, `nxt` the one being produced now
+            const unsigned char* tile_stage = my_stage + (size_t)(((rd - 1) & 1) * NP) * stage_tile;
+            uint32_t bits = 0;
+#pragma unroll
+            for (int s = 0; s < NS; s += 2) {
+                bits |= finish_set(cur, s, set0, tile_stage);
+                if (s + 2 < NS) load_set(cur, s + 2, set0); else load_set(nxt, s + 2 - NS, set0);
+                bits |= finish_set(cur, s + 1, set1, tile_stage);
+                if (s + 3 < NS) load_set(cur, s + 3, set1); else load_set(nxt, s + 3 - NS, set1);
+            }
+#pragma unroll
+            for (int m = kWave >> 1; m >= 1; m >>= 1) bits |= __shfl_xor(bits, m, kWave);
+            const int64_t tile = tile_of(rd - 1);
+            if (tile * kTile < count) {
+                if (e.surv) {
+                    // this wave owns bits [part*32/cs, (part+1)*32/cs) of the tile's survivor word
+                    if (lane == 0) {
+                        if (cs == 1) e.surv[tile] = bits;
+                        else if (cs == 2) reinterpret_cast<uint16_t*>(e.surv)[tile * 2 + part] = (uint16_t)(bits >> (16 * part));
+                        else reinterpret_cast<uint8_t*>(e.surv)[tile * 4 + part] = (uint8_t)(bits >> (8 * part));
+                    }
+                } else {
+                    survivors += __popc(bits);
+                }
+            }
+            cur = nxt;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                nxt.pix[it] = pix_nn[it];
+                pix_nn[it] = list_entry(rd + 2, ent0 + it * PPI);
+            }
+            prepare(nxt);
+            lds_block_sync();
+        }
+        // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
+        if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
+    }
+}
+
+}  // namespace dcnn
