@@ -72,6 +72,7 @@ struct MaskPassArgs {
     int up;                      // > 1: nearest upsampling of the input mask by this factor (k = 1)
     int32_t* zero_count;         // optional counter the pass resets to 0 (survivor count of the layer)
     int emit_only;               // 1: mask_in is final and its chunk counts are in the workspace already
+    uint32_t* taps_out;          // optional [n*oh*ow]: per list entry, which window taps are flagged (k*k <= 25 bits)
 };
 dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& a);
 
@@ -102,6 +103,8 @@ struct ListArgs {
     const int32_t* count;        // nullptr: use count_host
     int64_t count_host;
     int64_t max_count;           // upper bound used to size the grid
+    const uint32_t* taps;        // optional, per entry: bit t set iff window tap t of the entry's pixel is in
+                                 // bounds and flagged in the input mask (written with the list by the mask pass)
 };
 
 struct ConvArgs {

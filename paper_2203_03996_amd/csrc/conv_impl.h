@@ -336,7 +336,9 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
     const size_t ws_lds = conv_ws_lds_bytes(p, sizeof(T) == 2 ? DCNN_F16 : DCNN_F32, c.k, e.c);
     const uint64_t in_bytes = (uint64_t)c.n * c.h * c.w * c.cin * sizeof(T);
     const uint64_t out_bytes = (uint64_t)c.n * c.oh * c.ow * e.c * sizeof(T);
-    if (vec_out && aligned && ws_lds != 0 && !init && in_bytes <= kWsMaxBytes && out_bytes <= kWsMaxBytes) {
+    // (a window wider than 1x1, or a 1x1 walk over a list that is not the input's own, needs the tap words)
+    const bool ws_taps = l.taps != nullptr || (c.k == 1 && c.stride == 1 && l.list != nullptr && c.in_mask != nullptr);
+    if (vec_out && aligned && ws_lds != 0 && !init && ws_taps && in_bytes <= kWsMaxBytes && out_bytes <= kWsMaxBytes) {
         const int64_t ws_want = cdiv(l.max_count > 0 ? l.max_count : 1, (kWsProducers / p.cs) * kTile);
         const int64_t ws_cap = ctx->num_cu;                    // 16 waves of up to 128 registers fill a compute unit
         const int ws_grid = (int)(cdiv(ws_want < ws_cap ? ws_want : ws_cap, kXcd) * kXcd);

@@ -26,6 +26,8 @@
 // dense first frame (bias, no truncation).
 #pragma once
 
+#include <type_traits>
+
 #include "conv_plan.h"
 
 namespace dcnn {
@@ -107,102 +109,108 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         const int col = lane % 32, g = lane / 32;
         const uint64_t in_pixels = (uint64_t)c.n * c.h * c.w;
         const __amdgpu_buffer_rsrc_t rs_in = ws_rsrc(c.in_data, in_pixels * c.cin * ES);
-        const __amdgpu_buffer_rsrc_t rs_mask = ws_rsrc(c.in_mask, in_pixels);
-        const bool has_mask = c.in_mask != nullptr;
         const int cin_bytes = c.cin * ES;
-        const bool cin_full = kch * 32 == cin_bytes;           // no K-step reaches past the pixel's channels
-        // Software pipeline over tiles: the list entry of tile n+2 and the update flags of tile n+1
-        // are requested while tile n is processed.
-        struct TileGeom { bool valid; int iy0, ix0, q00; };
-        auto geometry = [&](int p32) {
-            TileGeom gm;
-            gm.valid = p32 >= 0;
-            const uint32_t pu = gm.valid ? (uint32_t)p32 : 0u;
+        const int kgroups = (kch + GK - 1) / GK;               // groups of GK K-steps per tap
+        const bool k_exact = kgroups * GK * 32 == cin_bytes;   // no K-step of a group reaches past the pixel's channels
+        constexpr int kNoTap = 31;                             // cursor sentinel: no tap has this number
+        // Which window taps of a list entry are in bounds and flagged comes with the work list (one
+        // word per entry); a 1x1 layer that walks its input's own list has exactly its one tap.
+        // Software pipeline over tiles: list entry and tap word of tile n+2 are requested while tile
+        // n is processed.
+        auto origin = [&](int p32) {
+            // pixel index of tap (0,0) of the entry's window (only used when that tap is in bounds)
+            const uint32_t pu = p32 >= 0 ? (uint32_t)p32 : 0u;
             const uint32_t t1 = fast_div(pu, c.div_ow);
             const int ox = (int)(pu - t1 * (uint32_t)c.ow);
             const uint32_t n = fast_div(t1, c.div_oh);
             const int oy = (int)(t1 - n * (uint32_t)c.oh);
-            gm.iy0 = oy * c.stride - c.pad;
-            gm.ix0 = ox * c.stride - c.pad;
-            gm.q00 = ((int)n * c.h + gm.iy0) * c.w + gm.ix0;   // pixel index of tap (0,0); only used when in bounds
-            return gm;
+            return ((int)n * c.h + oy * c.stride - c.pad) * c.w + ox * c.stride - c.pad;
         };
-        // update flag of every window tap (0 outside the image or beyond the list)
-        auto request_flags = [&](const TileGeom& gm, uint8_t (&flag)[KS * KS]) {
-#pragma unroll
-            for (int t = 0; t < KS * KS; ++t) {
-                const int dy = t / KS, dx = t % KS;
-                const bool inb = gm.valid && (unsigned)(gm.iy0 + dy) < (unsigned)c.h && (unsigned)(gm.ix0 + dx) < (unsigned)c.w;
-                const uint32_t off = inb ? (uint32_t)(gm.q00 + dy * c.w + dx) : kOob;
-                flag[t] = has_mask ? __builtin_amdgcn_raw_buffer_load_b8(rs_mask, (int)off, 0, 0) : (uint8_t)inb;
-            }
+        auto tap_word = [&](int rd, int p32) -> uint32_t {
+            if (l.taps == nullptr) return p32 >= 0 ? 1u : 0u;
+            const int64_t j = tile_of(rd) * kTile + col;
+            return (rd < rounds && j < count) ? l.taps[j] : 0u;
         };
-        TileGeom g_next = geometry(list_entry(0, col));
-        int p32_next2 = list_entry(1, col);
-        uint8_t flag_next[KS * KS];
-        request_flags(g_next, flag_next);
+        int p32_next = list_entry(0, col), p32_next2 = list_entry(1, col);
+        uint32_t taps_next = tap_word(0, p32_next), taps_next2 = tap_word(1, p32_next2);
         const Vec* wbase = w_lds + ((size_t)part * ksteps * 2 + g) * COLS + col;
 
         for (int rd = 0; rd <= rounds; ++rd) {
             if (rd < rounds) {
                 // byte offset of this lane's 16 bytes in tap (0,0), K-step 0
-                const uint32_t base00 = (uint32_t)g_next.q00 * (uint32_t)cin_bytes + (uint32_t)g * 16u;
-                uint32_t tapbits = 0;
+                const uint32_t base00 = (uint32_t)origin(p32_next) * (uint32_t)cin_bytes + (uint32_t)g * 16u;
+                const uint32_t tapbits = taps_next;                // taps this lane needs
+                uint32_t wave_taps = 0;                            // taps any lane of the wave needs
 #pragma unroll
                 for (int t = 0; t < KS * KS; ++t)
-                    if (flag_next[t]) tapbits |= 1u << t;
-                g_next = geometry(p32_next2);
+                    if (__ballot((tapbits >> t) & 1)) wave_taps |= 1u << t;
+                p32_next = p32_next2; taps_next = taps_next2;
                 p32_next2 = list_entry(rd + 2, col);
-                request_flags(g_next, flag_next);
+                taps_next2 = tap_word(rd + 2, p32_next2);
 
-                // Wave-uniform cursor over groups of GK K-steps: tap t = (dy, dx), first K-step kc0.
-                struct Cursor { int t, dy, dx, kc0; };
+                // Wave-uniform cursor over the (tap, group of GK K-steps) pairs that matter: a tap no
+                // lane of the wave needs is skipped altogether.  t == kNoTap once the pairs run out.
+                struct Cursor { uint32_t rest; int t, kg; };
+                auto first_tap = [](uint32_t m) { return m ? __builtin_ctz(m) : kNoTap; };
                 auto advance = [&](Cursor& cu) {
-                    cu.kc0 += GK;
-                    if (cu.kc0 >= kch) {
-                        cu.kc0 = 0; ++cu.t;
-                        if (++cu.dx == KS) { cu.dx = 0; ++cu.dy; }
+                    if (++cu.kg >= kgroups) {
+                        cu.kg = 0;
+                        cu.rest &= cu.rest - 1;
+                        cu.t = first_tap(cu.rest);
                     }
                 };
                 // 16 bytes of input channels per K-step for this lane's pixel; lanes that do not need
-                // the tap (or whose channels are padding) get zeros from an out-of-range offset
+                // the tap (or whose channels are padding) get zeros from an out-of-range offset.  Every
+                // load is issued unconditionally, so the number in flight is known at compile time and
+                // a group's wait never includes the group requested after it.
                 auto gather_group = [&](const Cursor& cu, Vec (&x)[GK]) {
                     const bool tap_ok = (tapbits >> cu.t) & 1;
-                    const uint32_t uni = (uint32_t)((cu.dy * c.w + cu.dx) * cin_bytes + cu.kc0 * 32);
+                    const int dy = cu.t / KS, dx = cu.t % KS;
+                    const uint32_t uni = (uint32_t)((dy * c.w + dx) * cin_bytes + cu.kg * (GK * 32));
                     const uint32_t off = tap_ok ? base00 + uni : kOob;
 #pragma unroll
                     for (int u = 0; u < GK; ++u) {
                         uint32_t o = off + (uint32_t)u * 32u;
-                        if (!cin_full && (2 * (cu.kc0 + u) + g) * 16 >= cin_bytes) o = kOob;
+                        if (!k_exact && (2 * (cu.kg * GK + u) + g) * 16 >= cin_bytes) o = kOob;
                         x[u] = ws_load16<Vec>(rs_in, o);
                     }
+                    __builtin_amdgcn_sched_barrier(0);             // the scheduler must not sink the loads below the MFMAs
                 };
                 f32x16 acc[NB];
 #pragma unroll
                 for (int b = 0; b < NB; ++b)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+                // The weight operands of K-step u+1 are requested from LDS before the MFMAs of step u
+                // issue; a K-step past the end multiplies the (valid) last step's weights with zeros.
                 auto mma_group = [&](const Cursor& cu, const Vec (&x)[GK]) {
-                    const Vec* wrow = wbase + (size_t)(cu.t * kch + cu.kc0) * 2 * COLS;
+                    Vec wv[2][NB];
+                    auto request = [&](int u) {
+                        const int kc = cu.kg * GK + u;
+                        const Vec* wrow = wbase + (size_t)(cu.t * kch + (kc < kch ? kc : kch - 1)) * 2 * COLS;
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) wv[u & 1][b] = wrow[b * 32];
+                    };
+                    request(0);
 #pragma unroll
                     for (int u = 0; u < GK; ++u) {
-                        if (cu.kc0 + u < kch) {
+                        if (u + 1 < GK) request(u + 1);
+                        __builtin_amdgcn_sched_barrier(0);         // keep the requests ahead of the matrix work
 #pragma unroll
-                            for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wrow[(size_t)u * 2 * COLS + b * 32], x[u]);
-                        }
+                        for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wv[u & 1][b], x[u]);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 };
                 Vec xa[GK], xb[GK];
-                Cursor ca{0, 0, 0, 0}, cb;
-                gather_group(ca, xa);
-                while (ca.t < taps) {
-                    cb = ca; advance(cb);
-                    if (cb.t < taps) gather_group(cb, xb);
-                    mma_group(ca, xa);
-                    if (cb.t >= taps) break;
-                    ca = cb; advance(ca);
-                    if (ca.t < taps) gather_group(ca, xa);
-                    mma_group(cb, xb);
+                Cursor cg{wave_taps, first_tap(wave_taps), 0};     // gathers run one group ahead of the matrix work
+                Cursor cm = cg;
+                gather_group(cg, xa); advance(cg);
+                while (cm.t != kNoTap) {
+                    gather_group(cg, xb); advance(cg);
+                    mma_group(cm, xa); advance(cm);
+                    if (cm.t == kNoTap) break;
+                    gather_group(cg, xa); advance(cg);
+                    mma_group(cm, xb); advance(cm);
                 }
                 unsigned char* tile_stage = stage0 + (size_t)((rd & 1) * NP + ww) * stage_tile;
                 stage_accumulators<T, NB>(acc, tile_stage + (size_t)col * stage_stride, g);
@@ -261,19 +269,19 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         };
         struct Set { Raw ra[H], rt[H], rr[RES ? H : 1]; };
         // loads that do not depend on the convolution result, for the H iterations of set s
-        auto load_set = [&](const Tile& t, int s, Set& st) {
+        auto load_set = [&](auto sf, const Tile& t, int s, Set& st) {
 #pragma unroll
             for (int h = 0; h < H; ++h) {
                 const uint32_t o = t.off[s * H + h];
                 if constexpr (RES) st.rr[h] = ws_load16<Raw>(rs_res, t.rflag[s * H + h] ? o : kOob);
-                if (stateful) {
+                if constexpr (decltype(sf)::value) {
                     st.ra[h] = ws_load16<Raw>(rs_xA, o);
                     st.rt[h] = ws_load16<Raw>(rs_xT, o);
                 }
             }
         };
         // arithmetic, decision and stores of set s; returns the survivor bits of its pixels
-        auto finish_set = [&](const Tile& t, int s, const Set& st, const unsigned char* tile_stage) -> uint32_t {
+        auto finish_set = [&](auto sf, const Tile& t, int s, const Set& st, const unsigned char* tile_stage) -> uint32_t {
             uint32_t bits = 0;
             Raw rd[H];
 #pragma unroll
@@ -289,7 +297,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     for (int i = 0; i < V; ++i) raw_set<T, V>(d, i, raw_get<T, V>(rd[h], i) + raw_get<T, V>(st.rr[h], i));
                 }
                 bool upd = true;
-                if (stateful) {
+                if constexpr (decltype(sf)::value) {
                     Raw o_a, o_t, o_y;
                     float u = 0.0f;
 #pragma unroll
@@ -319,58 +327,62 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
             return bits;
         };
 
-        // Software pipeline.  List entries are requested two tiles ahead, residual flags one tile ahead,
-        // and over the sets of consecutive tiles: while set s is finished, the loads of set s+1 (issued
-        // one step earlier) and of set s+2 (issued right after) are in flight.
-        Tile cur, nxt;
-        int pix_nn[NIT];
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            cur.pix[it] = list_entry(0, ent0 + it * PPI);
-            nxt.pix[it] = list_entry(1, ent0 + it * PPI);
-            pix_nn[it] = list_entry(2, ent0 + it * PPI);
-        }
-        prepare(cur);
-        prepare(nxt);
-        Set set0, set1;
-        load_set(cur, 0, set0);
-        load_set(cur, 1, set1);
-        lds_block_sync();                                      // round 0: the producers fill the first tiles
-        for (int rd = 1; rd <= rounds; ++rd) {
-            // `cur` is the tile produced in round rd-1, `nxt` the one being produced now
-            const unsigned char* tile_stage = my_stage + (size_t)(((rd - 1) & 1) * NP) * stage_tile;
-            uint32_t bits = 0;
-#pragma unroll
-            for (int s = 0; s < NS; s += 2) {
-                bits |= finish_set(cur, s, set0, tile_stage);
-                if (s + 2 < NS) load_set(cur, s + 2, set0); else load_set(nxt, s + 2 - NS, set0);
-                bits |= finish_set(cur, s + 1, set1, tile_stage);
-                if (s + 3 < NS) load_set(cur, s + 3, set1); else load_set(nxt, s + 3 - NS, set1);
-            }
-#pragma unroll
-            for (int m = kWave >> 1; m >= 1; m >>= 1) bits |= __shfl_xor(bits, m, kWave);
-            const int64_t tile = tile_of(rd - 1);
-            if (tile * kTile < count) {
-                if (e.surv) {
-                    // this wave owns bits [part*32/cs, (part+1)*32/cs) of the tile's survivor word
-                    if (lane == 0) {
-                        if (cs == 1) e.surv[tile] = bits;
-                        else if (cs == 2) reinterpret_cast<uint16_t*>(e.surv)[tile * 2 + part] = (uint16_t)(bits >> (16 * part));
-                        else reinterpret_cast<uint8_t*>(e.surv)[tile * 4 + part] = (uint8_t)(bits >> (8 * part));
-                    }
-                } else {
-                    survivors += __popc(bits);
-                }
-            }
-            cur = nxt;
-#pragma unroll
+        auto run = [&](auto sf) {
+            // Software pipeline.  List entries are requested two tiles ahead, residual flags one tile ahead,
+            // and over the sets of consecutive tiles: while set s is finished, the loads of set s+1 (issued
+            // one step earlier) and of set s+2 (issued right after) are in flight.
+            Tile cur, nxt;
+            int pix_nn[NIT];
+    #pragma unroll
             for (int it = 0; it < NIT; ++it) {
-                nxt.pix[it] = pix_nn[it];
-                pix_nn[it] = list_entry(rd + 2, ent0 + it * PPI);
+                cur.pix[it] = list_entry(0, ent0 + it * PPI);
+                nxt.pix[it] = list_entry(1, ent0 + it * PPI);
+                pix_nn[it] = list_entry(2, ent0 + it * PPI);
             }
+            prepare(cur);
             prepare(nxt);
-            lds_block_sync();
-        }
+            Set set0, set1;
+            load_set(sf, cur, 0, set0);
+            load_set(sf, cur, 1, set1);
+            lds_block_sync();                                      // round 0: the producers fill the first tiles
+            for (int rd = 1; rd <= rounds; ++rd) {
+                // `cur` is the tile produced in round rd-1, `nxt` the one being produced now
+                const unsigned char* tile_stage = my_stage + (size_t)(((rd - 1) & 1) * NP) * stage_tile;
+                uint32_t bits = 0;
+    #pragma unroll
+                for (int s = 0; s < NS; s += 2) {
+                    bits |= finish_set(sf, cur, s, set0, tile_stage);
+                    if (s + 2 < NS) load_set(sf, cur, s + 2, set0); else load_set(sf, nxt, s + 2 - NS, set0);
+                    bits |= finish_set(sf, cur, s + 1, set1, tile_stage);
+                    if (s + 3 < NS) load_set(sf, cur, s + 3, set1); else load_set(sf, nxt, s + 3 - NS, set1);
+                }
+    #pragma unroll
+                for (int m = kWave >> 1; m >= 1; m >>= 1) bits |= __shfl_xor(bits, m, kWave);
+                const int64_t tile = tile_of(rd - 1);
+                if (tile * kTile < count) {
+                    if (e.surv) {
+                        // this wave owns bits [part*32/cs, (part+1)*32/cs) of the tile's survivor word
+                        if (lane == 0) {
+                            if (cs == 1) e.surv[tile] = bits;
+                            else if (cs == 2) reinterpret_cast<uint16_t*>(e.surv)[tile * 2 + part] = (uint16_t)(bits >> (16 * part));
+                            else reinterpret_cast<uint8_t*>(e.surv)[tile * 4 + part] = (uint8_t)(bits >> (8 * part));
+                        }
+                    } else {
+                        survivors += __popc(bits);
+                    }
+                }
+                cur = nxt;
+    #pragma unroll
+                for (int it = 0; it < NIT; ++it) {
+                    nxt.pix[it] = pix_nn[it];
+                    pix_nn[it] = list_entry(rd + 2, ent0 + it * PPI);
+                }
+                prepare(nxt);
+                lds_block_sync();
+            }
+        };
+        // layers with an activation keep state (x^A, x^T) and truncate; linear ones pass the delta on
+        if (stateful) run(std::true_type{}); else run(std::false_type{});
         // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
         if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
     }

@@ -24,6 +24,7 @@ struct dcnn_layer {
     int32_t* out_count;
     int32_t* list;                      // work list when the layer builds its own
     int32_t* list_count;
+    uint32_t* taps;                     // per work-list entry: flagged window taps (dense convolutions, 1x1 / 3x3)
     void* wpacked;
     void* bias;
     int32_t* counters;

@@ -90,7 +90,7 @@ static void carve(dcnn_layer* L, void* state) {
     const bool act = has_act(d), own = own_list(d);
     L->buf0 = L->buf1 = nullptr; L->buf0_bytes = L->buf1_bytes = 0;
     L->out_data = nullptr; L->out_mask = nullptr; L->out_idx = nullptr; L->out_count = nullptr;
-    L->list = nullptr; L->list_count = nullptr; L->wpacked = nullptr; L->bias = nullptr;
+    L->list = nullptr; L->list_count = nullptr; L->taps = nullptr; L->wpacked = nullptr; L->bias = nullptr;
     L->counters = static_cast<int32_t*>(cv.take(kAlign));      // stays all zero: doubles as the zero page of the gathers
     switch (d.kind) {
         case DCNN_DELTAGEN:
@@ -130,6 +130,8 @@ static void carve(dcnn_layer* L, void* state) {
                 L->list = L->out_idx;
                 L->list_count = L->out_count;
             }
+            if (d.kind == DCNN_CONV && (d.kh == 1 || d.kh == 3))
+                L->taps = static_cast<uint32_t*>(cv.take((size_t)L->out_pixels * sizeof(uint32_t)));
         }
     } else {
         L->alias_mask = true;
@@ -409,9 +411,10 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         m.zero_count = (act && !d.want_idx) ? L->out_count : nullptr;
         if (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV || d.kind == DCNN_MAXPOOL) { m.k = d.kh; m.stride = d.stride; m.pad = d.pad; }
         if (d.kind == DCNN_UPSAMPLE) m.up = d.factor;
+        m.taps_out = L->taps;
         st = launch_mask_compact(ctx, m);
         if (st != DCNN_OK) return st;
-        l.list = L->list; l.count = L->list_count;
+        l.list = L->list; l.count = L->list_count; l.taps = L->taps;
     } else {
         l.list = in[0]->idx; l.count = in[0]->count;
         if (act) {

@@ -5,6 +5,8 @@
 // emit       : pixel space; exclusive prefix over the chunk counts + an in-chunk scan turn the
 //              mask into the ascending list of flagged pixels.  No atomics: the list order is
 //              fixed, so results are identical from run to run.
+//              Optionally also writes, per list entry, the word of window taps that are in bounds and
+//              flagged, so the convolution does not have to test the window again.
 // emit_sublist: list space; keeps the entries of a work list whose survivor bit is set.
 #include "device_utils.h"
 
@@ -110,6 +112,9 @@ struct EmitArgs {
     int32_t* idx_out;
     int32_t* count_out;
     int64_t pixels;
+    const uint8_t* tap_mask;      // input mask the window taps are tested against (with taps_out)
+    uint32_t* taps_out;
+    int h, w, oh, ow, k, stride, pad;
 };
 
 __global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
@@ -132,8 +137,31 @@ __global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
     }
     int total;
     int pos = prefix + block_exclusive_scan(__popcll(word), s_red, &total);
-    for (int i = 0; i < kPxPerThread; ++i)
-        if ((word >> (8 * i)) & 1) a.idx_out[pos++] = (int32_t)(p0 + i);
+    if (a.taps_out == nullptr) {
+        for (int i = 0; i < kPxPerThread; ++i)
+            if ((word >> (8 * i)) & 1) a.idx_out[pos++] = (int32_t)(p0 + i);
+        return;
+    }
+    int ox = (int)(p0 % a.ow);
+    int64_t t = p0 / a.ow;
+    int oy = (int)(t % a.oh);
+    int64_t n = t / a.oh;
+    for (int i = 0; i < kPxPerThread; ++i) {
+        if ((word >> (8 * i)) & 1) {
+            uint32_t taps = 0;
+            for (int ky = 0, tap = 0; ky < a.k; ++ky) {
+                const int iy = oy * a.stride - a.pad + ky;
+                for (int kx = 0; kx < a.k; ++kx, ++tap) {
+                    const int ix = ox * a.stride - a.pad + kx;
+                    if (iy >= 0 && iy < a.h && ix >= 0 && ix < a.w && a.tap_mask[(n * a.h + iy) * a.w + ix]) taps |= 1u << tap;
+                }
+            }
+            a.idx_out[pos] = (int32_t)(p0 + i);
+            a.taps_out[pos] = taps;
+            ++pos;
+        }
+        if (++ox == a.ow) { ox = 0; if (++oy == a.oh) { oy = 0; ++n; } }
+    }
 }
 
 dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
@@ -161,6 +189,8 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
     }
     if (m.idx_out == nullptr) return DCNN_OK;
     EmitArgs e{emit_mask, ws.chunk_counts, m.idx_out, m.count_out, out_pixels};
+    e.tap_mask = m.mask_in; e.taps_out = (m.emit_only || m.up > 1 || m.k * m.k > 25) ? nullptr : m.taps_out;
+    e.h = m.h; e.w = m.w; e.oh = m.oh; e.ow = m.ow; e.k = m.k; e.stride = m.stride; e.pad = m.pad;
     hipLaunchKernelGGL(emit_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, e);
     return check_hip(ctx, hipGetLastError(), "emit_kernel launch");
 }
