@@ -48,6 +48,30 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* s_red, int* tota
     return base + inc - v;
 }
 
+// Every non-zero byte of the word becomes 1.
+__device__ __forceinline__ uint64_t bytes01(uint64_t w) {
+    w |= w >> 4; w |= w >> 2; w |= w >> 1;
+    return w & 0x0101010101010101ull;
+}
+
+// Flags of input row iy at columns x0-1 .. x0+8 as a bit string (bit j = column x0-1+j), zero outside
+// the image.  x0 is a multiple of 8 and the row width a multiple of 8, so the middle is one word.
+__device__ __forceinline__ uint32_t row_flags10(const uint8_t* mask, int64_t n, int iy, int x0, int h, int w) {
+    if (iy < 0 || iy >= h) return 0;
+    const uint8_t* row = mask + (n * h + iy) * w;
+    const uint64_t word = bytes01(*reinterpret_cast<const uint64_t*>(row + x0));
+    uint32_t bits = (uint32_t)((word * 0x0102040810204080ull) >> 56) << 1;      // byte i -> bit i+1
+    if (x0 > 0 && row[x0 - 1]) bits |= 1u;
+    if (x0 + 8 < w && row[x0 + 8]) bits |= 1u << 9;
+    return bits;
+}
+
+// 3x3 window, stride 1, padding 1, rows a multiple of 8 pixels wide: the common dilation, done on
+// bit strings instead of byte by byte.
+__device__ __forceinline__ bool window3_fast(int k, int stride, int pad, int up, int h, int w, int oh, int ow) {
+    return k == 3 && stride == 1 && pad == 1 && up == 1 && (w % 8) == 0 && oh == h && ow == w;
+}
+
 struct MaskKernelArgs {
     const uint8_t* mask_in;
     const uint8_t* mask_b;
@@ -67,6 +91,16 @@ __global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs 
         if (a.k == 1 && a.stride == 1 && a.up == 1 && p0 + kPxPerThread <= a.out_pixels) {
             word = *reinterpret_cast<const uint64_t*>(a.mask_in + p0);
             if (a.mask_b) word |= *reinterpret_cast<const uint64_t*>(a.mask_b + p0);
+        } else if (window3_fast(a.k, a.stride, a.pad, a.up, a.h, a.w, a.oh, a.ow)) {
+            const int x0 = (int)(p0 % a.w);
+            const int64_t t = p0 / a.w;
+            const int y = (int)(t % a.h);
+            const int64_t n = t / a.h;
+            uint32_t any = 0;                                   // bit j: some row has a flag at column x0-1+j
+            for (int r = -1; r <= 1; ++r) any |= row_flags10(a.mask_in, n, y + r, x0, a.h, a.w);
+            const uint32_t hit = (any | (any >> 1) | (any >> 2)) & 0xffu;   // bit i: window of pixel x0+i has a flag
+            for (int i = 0; i < kPxPerThread; ++i) word |= (uint64_t)((hit >> i) & 1u) << (8 * i);
+            if (a.mask_b) word |= bytes01(*reinterpret_cast<const uint64_t*>(a.mask_b + p0));
         } else {
             int ox = (int)(p0 % a.ow);
             int64_t t = p0 / a.ow;
@@ -140,6 +174,23 @@ __global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
     if (a.taps_out == nullptr) {
         for (int i = 0; i < kPxPerThread; ++i)
             if ((word >> (8 * i)) & 1) a.idx_out[pos++] = (int32_t)(p0 + i);
+        return;
+    }
+    if (word == 0) return;
+    if (window3_fast(a.k, a.stride, a.pad, 1, a.h, a.w, a.oh, a.ow) && p0 + kPxPerThread <= a.pixels) {
+        const int x0 = (int)(p0 % a.w);
+        const int64_t t = p0 / a.w;
+        const int y = (int)(t % a.h);
+        const int64_t n = t / a.h;
+        uint32_t rows[3];
+        for (int r = 0; r < 3; ++r) rows[r] = row_flags10(a.tap_mask, n, y + r - 1, x0, a.h, a.w);
+        for (int i = 0; i < kPxPerThread; ++i) {
+            if ((word >> (8 * i)) & 1) {
+                a.idx_out[pos] = (int32_t)(p0 + i);
+                a.taps_out[pos] = ((rows[0] >> i) & 7u) | (((rows[1] >> i) & 7u) << 3) | (((rows[2] >> i) & 7u) << 6);
+                ++pos;
+            }
+        }
         return;
     }
     int ox = (int)(p0 % a.ow);

@@ -162,8 +162,9 @@ dcnn_status launch_dwconv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l
 // ---- input delta generation (dense pass over the frame) ---------------------------------------
 // Per pixel: d = frame - P (P = value last propagated); flagged iff max_c |d_c| >= eps;
 // flagged: delta <- d, P <- frame.  Writes the whole mask and one count per chunk of pixels.
+constexpr int kDeltaGenThreads = 1024;                       // 16 waves per chunk of pixels: enough loads in flight per compute unit
 template <typename T, int V, int VPL>
-__global__ __launch_bounds__(256) void deltagen_kernel(DeltaGenArgs a, int32_t* chunk_counts) {
+__global__ __launch_bounds__(kDeltaGenThreads) void deltagen_kernel(DeltaGenArgs a, int32_t* chunk_counts) {
     __shared__ int s_count;
     if (threadIdx.x == 0) s_count = 0;
     __syncthreads();
@@ -179,40 +180,57 @@ __global__ __launch_bounds__(256) void deltagen_kernel(DeltaGenArgs a, int32_t* 
     const int64_t chunk_begin = (int64_t)blockIdx.x * kChunk;
     const int64_t chunk_end = min(chunk_begin + kChunk, a.pixels);
     int mine = 0;
-    for (int64_t p0 = chunk_begin + (int64_t)wave * PPI; p0 < chunk_end; p0 += 4 * PPI) {
-        const int64_t p = p0 + grp;
-        const bool valid = p < chunk_end;
-        float f[VPL][V], d[VPL][V];
-        float u = 0.0f;
+    constexpr int NW = kDeltaGenThreads / kWave;
+    typedef typename RawOf<T, V>::type Raw;
+    constexpr int UB = VPL == 1 ? 4 : (VPL == 2 ? 2 : 1);      // pixel groups whose loads are in flight together
+    // The pass is bound by memory latency: the loads of UB pixel groups (frame and P) are issued back
+    // to back before any of them is consumed.
+    for (int64_t p0 = chunk_begin + (int64_t)wave * PPI; p0 < chunk_end; p0 += (int64_t)UB * NW * PPI) {
+        Raw rf[UB][VPL], rq[UB][VPL];
 #pragma unroll
-        for (int v = 0; v < VPL; ++v) {
-            const int vi = sub + v * LP;
-            if (valid && vi < nvec) {
-                float q[V];
-                load_vec<T, V>(frame + p * C + vi * V, f[v]);
-                load_vec<T, V>(P + p * C + vi * V, q);
-#pragma unroll
-                for (int i = 0; i < V; ++i) {
-                    d[v][i] = f[v][i] - q[i];
-                    u = fmaxf(u, fabsf(d[v][i]));
-                }
-            }
-        }
-        for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
-        const bool flag = valid && (u >= a.eps);
-        if (flag) {
+        for (int ub = 0; ub < UB; ++ub) {
+            const int64_t p = p0 + (int64_t)ub * NW * PPI + grp;
 #pragma unroll
             for (int v = 0; v < VPL; ++v) {
                 const int vi = sub + v * LP;
-                if (vi < nvec) {
-                    store_vec<T, V>(out + p * C + vi * V, d[v]);
-                    store_vec<T, V>(P + p * C + vi * V, f[v]);
+                rf[ub][v] = raw_zero<T, V>(); rq[ub][v] = raw_zero<T, V>();
+                if (p < chunk_end && vi < nvec) {
+                    rf[ub][v] = raw_load<T, V>(frame + p * C + vi * V);
+                    rq[ub][v] = raw_load<T, V>(P + p * C + vi * V);
                 }
             }
         }
-        if (valid && sub == 0) {
-            a.out_mask[p] = flag ? 1 : 0;
-            mine += flag ? 1 : 0;
+#pragma unroll
+        for (int ub = 0; ub < UB; ++ub) {
+            const int64_t p = p0 + (int64_t)ub * NW * PPI + grp;
+            const bool valid = p < chunk_end;
+            Raw rd[VPL];
+            float u = 0.0f;
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) {
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    const float d = raw_get<T, V>(rf[ub][v], i) - raw_get<T, V>(rq[ub][v], i);
+                    u = fmaxf(u, fabsf(d));
+                    raw_set<T, V>(rd[v], i, d);
+                }
+            }
+            for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
+            const bool flag = valid && (u >= a.eps);
+            if (flag) {
+#pragma unroll
+                for (int v = 0; v < VPL; ++v) {
+                    const int vi = sub + v * LP;
+                    if (vi < nvec) {
+                        raw_store<T, V>(out + p * C + vi * V, rd[v]);
+                        raw_store<T, V>(P + p * C + vi * V, rf[ub][v]);
+                    }
+                }
+            }
+            if (valid && sub == 0) {
+                a.out_mask[p] = flag ? 1 : 0;
+                mine += flag ? 1 : 0;
+            }
         }
     }
     if (mine) atomicAdd(&s_count, mine);
@@ -390,7 +408,7 @@ dcnn_status launch_deltagen(dcnn_ctx* ctx, int dtype, const DeltaGenArgs& a) {
     dcnn_status st = workspace_view(ctx, a.pixels, &ws);
     if (st != DCNN_OK) return st;
     const int nchunks = (int)cdiv(a.pixels, kChunk);
-    dim3 g(nchunks), b(256);
+    dim3 g(nchunks), b(kDeltaGenThreads);
 #define DCNN_DG_LAUNCH(T, V, VPL) hipLaunchKernelGGL((deltagen_kernel<T, V, VPL>), g, b, 0, ctx->stream, a, ws.chunk_counts)
 #define DCNN_DG_PICK(T, V)                                                                       \
     do {                                                                                         \
