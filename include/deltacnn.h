@@ -94,6 +94,12 @@ typedef struct {
     int32_t dilate_r;
     int32_t factor;
     int32_t want_idx;       /* 0: the output's idx/count need not be produced (no consumer reads them) */
+    /* Optional fused projection shortcut (CONV with activation and n_in == 2 only; 0 = none): input 1 is
+     * then not a residual of the output shape but the [n, proj_h, proj_w, proj_c] input of a 1x1
+     * convolution (stride proj_stride, no padding, proj_c -> cout) whose result is added before the
+     * activation -- conv_a(x) + conv_b(z) is linear in both deltas (Section 3.1, Eq. 1).  Each of the two
+     * results is rounded to the storage type before the addition, as if it had been stored. */
+    int32_t proj_c, proj_h, proj_w, proj_stride;
 } dcnn_layer_desc;
 
 typedef struct {
@@ -144,7 +150,8 @@ dcnn_status dcnn_mask_compact(dcnn_ctx* ctx, const uint8_t* mask_in_dev, int32_t
 
 /* ---- layers -------------------------------------------------------------------------------- */
 dcnn_status dcnn_layer_query(const dcnn_layer_desc* desc, dcnn_layer_sizes* out);
-/* weights_dev: CONV [kh][kw][cin][cout], DWCONV [kh][kw][c]; bias_dev [cout] or NULL; both of the
+/* weights_dev: CONV [kh][kw][cin][cout], DWCONV [kh][kw][c]; bias_dev [cout] or NULL; with a fused
+ * projection the [proj_c][cout] weights follow the main ones and bias_dev is [2][cout].  Both of the
  * layer's dtype, read once here (packed into state memory) -- they may be freed after
  * dcnn_ctx_sync.  state_dev: at least state_bytes from dcnn_layer_query, zero-filled or not. */
 dcnn_status dcnn_layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const void* weights_dev,

@@ -44,7 +44,8 @@ class LayerDesc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("dtype", C.c_int32), ("n", C.c_int32), ("h", C.c_int32), ("w", C.c_int32),
                 ("c", C.c_int32), ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32),
                 ("cout", C.c_int32), ("act", C.c_int32), ("eps", C.c_float), ("n_in", C.c_int32),
-                ("dilate_r", C.c_int32), ("factor", C.c_int32), ("want_idx", C.c_int32)]
+                ("dilate_r", C.c_int32), ("factor", C.c_int32), ("want_idx", C.c_int32),
+                ("proj_c", C.c_int32), ("proj_h", C.c_int32), ("proj_w", C.c_int32), ("proj_stride", C.c_int32)]
 
 
 class LayerSizes(C.Structure):

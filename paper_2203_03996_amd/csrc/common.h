@@ -72,7 +72,9 @@ struct MaskPassArgs {
     int up;                      // > 1: nearest upsampling of the input mask by this factor (k = 1)
     int32_t* zero_count;         // optional counter the pass resets to 0 (survivor count of the layer)
     int emit_only;               // 1: mask_in is final and its chunk counts are in the workspace already
-    uint32_t* taps_out;          // optional [n*oh*ow]: per list entry, which window taps are flagged (k*k <= 25 bits)
+    uint32_t* taps_out;          // optional [n*oh*ow]: per list entry, which window taps are flagged (k*k <= 25 bits);
+                                 // bit 30: the entry's pixel is flagged in mask_b
+    int b_stride, b_h, b_w;      // b_stride > 0: mask_b is [n,b_h,b_w] and output pixel (y,x) looks at (y,x)*b_stride
 };
 dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& a);
 
@@ -115,6 +117,11 @@ struct ConvArgs {
     int n, h, w, cin, oh, ow, cout, cout_pad, k, stride, pad, kch;
     int depthwise;
     FastDiv div_ow, div_oh;      // filled by launch_conv
+    // optional projection: a 1x1 convolution (stride2, no padding) of a second input [n,h2,w2,cin2] whose
+    // result is added to this one's before the epilogue; its update flag is bit 30 of the list's tap words
+    const void* in2_data;        // nullptr: none
+    const void* wpacked2;
+    int h2, w2, cin2, stride2, kch2;
 };
 dcnn_status launch_conv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const ConvArgs& c,
                         const EpilogueArgs& e);
@@ -123,6 +130,14 @@ dcnn_status launch_pack_weights(dcnn_ctx* ctx, int dtype, const void* w, void* w
                                 int depthwise, bool fused);
 bool conv_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cout, int depthwise, bool fused,
                     char* why, size_t why_len);
+// Convolution + activation with a fused 1x1 projection of a second input (cin2 channels): supported when the
+// sparse step can run on the wave-specialised kernel with both weight tensors resident in LDS.
+bool conv_proj_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cin2, int cout, int64_t in_elems,
+                         int64_t in2_elems, int64_t out_elems);
+size_t conv_proj_weight_bytes(int dtype, int k, int cin, int cin2, int cout);
+// Packs the projection's [cin2][cout] weights in the column grouping of the main convolution's plan.
+dcnn_status launch_pack_weights_proj(dcnn_ctx* ctx, int dtype, const void* w2, void* wpacked2, int k, int cin, int cin2,
+                                     int cout);
 
 struct ActArgs {
     const void* in_data;         // first delta stream

@@ -333,18 +333,25 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
         launched = true;                                                                                         \
     } while (0)
     // resident weights, vector-aligned channels, one pass, sparse step: the wave-specialised kernel
-    const size_t ws_lds = conv_ws_lds_bytes(p, sizeof(T) == 2 ? DCNN_F16 : DCNN_F32, c.k, e.c);
+    const bool dual = c.in2_data != nullptr;
+    const size_t ws_lds = conv_ws_lds_bytes(p, sizeof(T) == 2 ? DCNN_F16 : DCNN_F32, c.k, e.c, dual ? c.cin2 : 0);
     const uint64_t in_bytes = (uint64_t)c.n * c.h * c.w * c.cin * sizeof(T);
+    const uint64_t in2_bytes = dual ? (uint64_t)c.n * c.h2 * c.w2 * c.cin2 * sizeof(T) : 0;
     const uint64_t out_bytes = (uint64_t)c.n * c.oh * c.ow * e.c * sizeof(T);
     // (a window wider than 1x1, or a 1x1 walk over a list that is not the input's own, needs the tap words)
     const bool ws_taps = l.taps != nullptr || (c.k == 1 && c.stride == 1 && l.list != nullptr && c.in_mask != nullptr);
-    if (vec_out && aligned && ws_lds != 0 && !init && ws_taps && in_bytes <= kWsMaxBytes && out_bytes <= kWsMaxBytes) {
+    const bool ws_ok = vec_out && aligned && ws_lds != 0 && !init && ws_taps && in_bytes <= kWsMaxBytes &&
+                       in2_bytes <= kWsMaxBytes && out_bytes <= kWsMaxBytes;
+    if (dual && (!ws_ok || l.taps == nullptr || e.res_data != nullptr || ((size_t)c.cin2 * sizeof(T)) % 16 != 0))
+        return fail(ctx, DCNN_EUNSUPPORTED, "conv %dx%d %d->%d with a fused projection of %d channels: shape not covered", c.k,
+                    c.k, c.cin, c.cout, c.cin2);
+    if (ws_ok) {
         const int64_t ws_want = cdiv(l.max_count > 0 ? l.max_count : 1, (kWsProducers / p.cs) * kTile);
         const int64_t ws_cap = ctx->num_cu;                    // 16 waves of up to 128 registers fill a compute unit
         const int ws_grid = (int)(cdiv(ws_want < ws_cap ? ws_want : ws_cap, kXcd) * kXcd);
-#define DCNN_WS_LAUNCH(KS, RES)                                                                                  \
+#define DCNN_WS_LAUNCH(KS, RES, DUAL)                                                                            \
     do {                                                                                                         \
-        auto kern = conv_ws_kernel<T, NB, KS, RES>;                                                              \
+        auto kern = conv_ws_kernel<T, NB, KS, RES, DUAL>;                                                        \
         static bool attr_set = false;                                                                            \
         if (!attr_set) {                                                                                         \
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -355,8 +362,15 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
             hipLaunchKernelGGL(kern, dim3(ws_grid), dim3(kWsWaves * kWave), ws_lds, ctx->stream, l, c, e, p.cs); \
     } while (0)
         const bool has_res = e.res_data != nullptr;
-        if (c.k == 1) { if (has_res) DCNN_WS_LAUNCH(1, true); else DCNN_WS_LAUNCH(1, false); }
-        else { if (has_res) DCNN_WS_LAUNCH(3, true); else DCNN_WS_LAUNCH(3, false); }
+        if (c.k == 1) {
+            if (dual) DCNN_WS_LAUNCH(1, false, true);
+            else if (has_res) DCNN_WS_LAUNCH(1, true, false);
+            else DCNN_WS_LAUNCH(1, false, false);
+        } else {
+            if (dual) DCNN_WS_LAUNCH(3, false, true);
+            else if (has_res) DCNN_WS_LAUNCH(3, true, false);
+            else DCNN_WS_LAUNCH(3, false, false);
+        }
 #undef DCNN_WS_LAUNCH
         if (err != hipSuccess) return check_hip(ctx, err, "hipFuncSetAttribute(conv_ws_kernel)");
         return check_hip(ctx, hipGetLastError(), "conv_ws_kernel launch");

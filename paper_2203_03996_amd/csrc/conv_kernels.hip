@@ -1,6 +1,6 @@
 // Host side of the convolution: plan queries, weight packing and dispatch to the per-variant
 // translation units (conv_inst.hip).
-#include "conv_plan.h"
+#include "conv_ws_impl.h"
 
 namespace dcnn {
 
@@ -63,6 +63,39 @@ dcnn_status launch_pack_weights(dcnn_ctx* ctx, int dtype, const void* w, void* w
     return check_hip(ctx, hipGetLastError(), "pack_weights_kernel launch");
 }
 
+bool conv_proj_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cin2, int cout, int64_t in_elems,
+                         int64_t in2_elems, int64_t out_elems) {
+    const size_t es = dtype_size(dtype);
+    if (ctx->max_lds < kLdsBytes || (k != 1 && k != 3)) return false;
+    if (((size_t)cin * es) % 16 != 0 || ((size_t)cin2 * es) % 16 != 0) return false;
+    const ConvPlan p = conv_plan(dtype, k, cin, cout, true);
+    if (!p.ok || conv_ws_lds_bytes(p, dtype, k, cout, cin2) == 0) return false;
+    const uint64_t lim = kWsMaxBytes / es;
+    return (uint64_t)in_elems <= lim && (uint64_t)in2_elems <= lim && (uint64_t)out_elems <= lim;
+}
+
+size_t conv_proj_weight_bytes(int dtype, int k, int cin, int cin2, int cout) {
+    const ConvPlan p = conv_plan(dtype, k, cin, cout, true);
+    const int kch2 = (int)cdiv(cin2, dtype == DCNN_F16 ? 16 : 8);
+    return align_up((size_t)kch2 * 2 * (p.ok ? p.cout_pad : (int)cdiv(cout, 512) * 512) * 16);
+}
+
+dcnn_status launch_pack_weights_proj(dcnn_ctx* ctx, int dtype, const void* w2, void* wpacked2, int k, int cin, int cin2,
+                                     int cout) {
+    const ConvPlan p = conv_plan(dtype, k, cin, cout, true);
+    if (!p.ok) return fail(ctx, DCNN_EUNSUPPORTED, "pack_weights: unsupported convolution shape");
+    const int kch2 = (int)cdiv(cin2, dtype == DCNN_F16 ? 16 : 8);
+    const int64_t total = (int64_t)kch2 * 2 * p.cout_pad * 16 / (int64_t)dtype_size(dtype);
+    const int grid = (int)(cdiv(total, 256) < 4096 ? cdiv(total, 256) : 4096);
+    if (dtype == DCNN_F16)
+        hipLaunchKernelGGL((pack_weights_kernel<f16>), dim3(grid), dim3(256), 0, ctx->stream, static_cast<const f16*>(w2),
+                           static_cast<f16*>(wpacked2), 1, cin2, cout, p.nb, p.npass * p.cs, kch2);
+    else
+        hipLaunchKernelGGL((pack_weights_kernel<float>), dim3(grid), dim3(256), 0, ctx->stream,
+                           static_cast<const float*>(w2), static_cast<float*>(wpacked2), 1, cin2, cout, p.nb, p.npass * p.cs, kch2);
+    return check_hip(ctx, hipGetLastError(), "pack_weights_kernel launch");
+}
+
 #define DCNN_DECL(TN, NB) dcnn_status launch_conv_##TN##_nb##NB(dcnn_ctx*, bool, const ListArgs&, const ConvArgs&, const EpilogueArgs&, const ConvPlan&);
 #define DCNN_DECL_ALL(TN) DCNN_DECL(TN, 1) DCNN_DECL(TN, 2) DCNN_DECL(TN, 3) DCNN_DECL(TN, 4)
 DCNN_DECL_ALL(f16)
@@ -81,6 +114,7 @@ dcnn_status launch_conv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, 
     const ConvPlan p = conv_plan(dtype, c.k, c.cin, c.cout, fused);
     c.cout_pad = p.cout_pad;
     c.kch = p.kch;
+    c.kch2 = c.in2_data ? (int)cdiv(c.cin2, dtype == DCNN_F16 ? 16 : 8) : 0;
     c.div_ow = make_fastdiv((uint32_t)c.ow);
     c.div_oh = make_fastdiv((uint32_t)c.oh);
 #define DCNN_CASE(NB) case NB: return dtype == DCNN_F16 ? launch_conv_f16_nb##NB(ctx, init, l, c, e, p) : launch_conv_f32_nb##NB(ctx, init, l, c, e, p);

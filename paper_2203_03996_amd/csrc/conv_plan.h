@@ -29,8 +29,9 @@ template <> struct Mma<float> {
 };
 
 // accumulators -> staging tile [pixel][nb*32 channels] in the storage type.  Lane (col, g) holds,
-// for pixel `col`, the output channels 8*q + 4*g + {0..3} of every 32-channel block.
-template <typename T, int NB>
+// for pixel `col`, the output channels 8*q + 4*g + {0..3} of every 32-channel block.  With ADD the
+// rounded accumulators are added to what the tile holds (and the sum is rounded again).
+template <typename T, int NB, bool ADD = false>
 __device__ __forceinline__ void stage_accumulators(const f32x16 (&acc)[NB], unsigned char* row, int g) {
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -41,11 +42,21 @@ __device__ __forceinline__ void stage_accumulators(const f32x16 (&acc)[NB], unsi
                 f16x4 v;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[i] = (f16)acc[b][4 * q + i];
+                if constexpr (ADD) {
+                    const f16x4 old = *reinterpret_cast<const f16x4*>(dst);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = (f16)((float)old[i] + (float)v[i]);
+                }
                 *reinterpret_cast<f16x4*>(dst) = v;
             } else {
                 f32x4 v;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[i] = acc[b][4 * q + i];
+                if constexpr (ADD) {
+                    const f32x4 old = *reinterpret_cast<const f32x4*>(dst);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = old[i] + v[i];
+                }
                 *reinterpret_cast<f32x4*>(dst) = v;
             }
         }

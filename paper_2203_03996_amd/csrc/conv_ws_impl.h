@@ -22,6 +22,9 @@
 // arithmetic is one add per access, and a lane that must not touch memory (tap not flagged, pixel
 // beyond the list, pixel truncated) simply gets an offset beyond the descriptor's range, for which
 // the hardware returns zeros on loads and drops stores.  No branches, no unflagged memory read.
+// A layer may carry a second, 1x1 convolution of another input whose result is added before the
+// activation (the projection shortcut of a residual block): the producer runs it as a second short
+// K loop on the same tile, so its result never travels through memory.
 // Every tensor therefore has to stay below 2 GiB; larger ones run on the plain kernel, as does the
 // dense first frame (bias, no truncation).
 #pragma once
@@ -36,18 +39,20 @@ constexpr int kWsProducers = 8;
 constexpr int kWsWaves = 16;
 constexpr uint32_t kOob = 0x80000000u;                         // byte offset no descriptor here reaches
 constexpr uint64_t kWsMaxBytes = 0x7fffffffull;
+constexpr int kTapProj = 30;                                   // bit of a tap word: the projection's input pixel is flagged
 
 constexpr int ws_pow2_ceil(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // LDS needed by the wave-specialised kernel; 0 when the shape is not covered by it.
-inline size_t conv_ws_lds_bytes(const ConvPlan& p, int dtype, int k, int cout) {
+inline size_t conv_ws_lds_bytes(const ConvPlan& p, int dtype, int k, int cout, int cin2 = 0) {
     const int vec = dtype == DCNN_F16 ? 8 : 4;
     if (p.stream || p.npass != 1 || cout % vec != 0 || (k != 1 && k != 3)) return 0;
     const int lpb = ws_pow2_ceil(p.nb * 32 / vec);
     if (p.cs * lpb > kWave) return 0;
-    const size_t bytes = p.w_bytes + 2 * conv_stage_bytes(kWsProducers, p.nb, dtype);
+    const size_t w2_bytes = (size_t)cdiv(cin2, dtype == DCNN_F16 ? 16 : 8) * 2 * p.cout_pad * 16;   // projection weights
+    const size_t bytes = p.w_bytes + w2_bytes + 2 * conv_stage_bytes(kWsProducers, p.nb, dtype);
     return bytes <= kLdsBytes ? bytes : 0;
 }
 
@@ -62,7 +67,7 @@ template <typename Raw> __device__ __forceinline__ void ws_store16(__amdgpu_buff
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)off, 0, 0);
 }
 
-template <typename T, int NB, int KS, bool RES>
+template <typename T, int NB, int KS, bool RES, bool DUAL>
 __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int cs) {
     typedef typename Mma<T>::Vec Vec;
     constexpr int V = Elem<T>::VEC;
@@ -86,7 +91,9 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
     const int slot = ww / cs, part = ww % cs;                  // which tile of the round; channel slice / pixel slice
     const int taps = KS * KS, kch = c.kch;
     const int ksteps = taps * kch;
-    const int w_vecs = cs * ksteps * 2 * COLS;
+    const int w1_vecs = cs * ksteps * 2 * COLS;
+    const int w2_vecs = DUAL ? cs * c.kch2 * 2 * COLS : 0;     // the projection's weights follow the main ones
+    const int w_vecs = w1_vecs + w2_vecs;
     Vec* w_lds = reinterpret_cast<Vec*>(smem);
     constexpr int stage_stride = COLS * ES + kStagePad;
     constexpr int stage_tile = kTile * stage_stride;
@@ -97,7 +104,11 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
 
     {
         const Vec* wglob = static_cast<const Vec*>(c.wpacked);
-        for (int i = threadIdx.x; i < w_vecs; i += kWsWaves * kWave) w_lds[i] = wglob[i];
+        for (int i = threadIdx.x; i < w1_vecs; i += kWsWaves * kWave) w_lds[i] = wglob[i];
+        if constexpr (DUAL) {
+            const Vec* wglob2 = static_cast<const Vec*>(c.wpacked2);
+            for (int i = threadIdx.x; i < w2_vecs; i += kWsWaves * kWave) w_lds[w1_vecs + i] = wglob2[i];
+        }
     }
     lds_block_sync();
 
@@ -126,6 +137,19 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
             const int oy = (int)(t1 - n * (uint32_t)c.oh);
             return ((int)n * c.h + oy * c.stride - c.pad) * c.w + ox * c.stride - c.pad;
         };
+        // the projection's input: pixel (oy*stride2, ox*stride2) of a [n, h2, w2, cin2] map
+        const __amdgpu_buffer_rsrc_t rs_in2 = ws_rsrc(c.in2_data, (uint64_t)c.n * c.h2 * c.w2 * c.cin2 * ES);
+        const int cin2_bytes = c.cin2 * ES;
+        auto origin2 = [&](int p32) {
+            const uint32_t pu = p32 >= 0 ? (uint32_t)p32 : 0u;
+            const uint32_t t1 = fast_div(pu, c.div_ow);
+            const int ox = (int)(pu - t1 * (uint32_t)c.ow);
+            const uint32_t n = fast_div(t1, c.div_oh);
+            const int oy = (int)(t1 - n * (uint32_t)c.oh);
+            return ((int)n * c.h2 + oy * c.stride2) * c.w2 + ox * c.stride2;
+        };
+        const int kgroups2 = DUAL ? (c.kch2 + GK - 1) / GK : 1;
+        (void)rs_in2; (void)cin2_bytes; (void)origin2; (void)kgroups2;
         auto tap_word = [&](int rd, int p32) -> uint32_t {
             if (l.taps == nullptr) return p32 >= 0 ? 1u : 0u;
             const int64_t j = tile_of(rd) * kTile + col;
@@ -134,26 +158,35 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         int p32_next = list_entry(0, col), p32_next2 = list_entry(1, col);
         uint32_t taps_next = tap_word(0, p32_next), taps_next2 = tap_word(1, p32_next2);
         const Vec* wbase = w_lds + ((size_t)part * ksteps * 2 + g) * COLS + col;
+        const Vec* wbase2 = w_lds + w1_vecs + ((size_t)part * (DUAL ? c.kch2 : 0) * 2 + g) * COLS + col;
 
         for (int rd = 0; rd <= rounds; ++rd) {
             if (rd < rounds) {
                 // byte offset of this lane's 16 bytes in tap (0,0), K-step 0
-                const uint32_t base00 = (uint32_t)origin(p32_next) * (uint32_t)cin_bytes + (uint32_t)g * 16u;
+                const int p32_cur = p32_next;
+                const uint32_t base00 = (uint32_t)origin(p32_cur) * (uint32_t)cin_bytes + (uint32_t)g * 16u;
                 const uint32_t tapbits = taps_next;                // taps this lane needs
                 uint32_t wave_taps = 0;                            // taps any lane of the wave needs
 #pragma unroll
                 for (int t = 0; t < KS * KS; ++t)
                     if (__ballot((tapbits >> t) & 1)) wave_taps |= 1u << t;
+                uint32_t base2 = 0;                                // the same for the projection's pixel
+                if constexpr (DUAL) {
+                    if (__ballot((tapbits >> kTapProj) & 1)) wave_taps |= 1u << kTapProj;
+                    base2 = (uint32_t)origin2(p32_cur) * (uint32_t)cin2_bytes + (uint32_t)g * 16u;
+                }
                 p32_next = p32_next2; taps_next = taps_next2;
                 p32_next2 = list_entry(rd + 2, col);
                 taps_next2 = tap_word(rd + 2, p32_next2);
 
                 // Wave-uniform cursor over the (tap, group of GK K-steps) pairs that matter: a tap no
-                // lane of the wave needs is skipped altogether.  t == kNoTap once the pairs run out.
+                // lane of the wave needs is skipped altogether.  With a projection, its K groups follow
+                // as "tap" kTapProj of the same sequence, so its gathers are in flight while the last
+                // main group is multiplied.  t == kNoTap once the pairs run out.
                 struct Cursor { uint32_t rest; int t, kg; };
                 auto first_tap = [](uint32_t m) { return m ? __builtin_ctz(m) : kNoTap; };
                 auto advance = [&](Cursor& cu) {
-                    if (++cu.kg >= kgroups) {
+                    if (++cu.kg >= ((DUAL && cu.t == kTapProj) ? kgroups2 : kgroups)) {
                         cu.kg = 0;
                         cu.rest &= cu.rest - 1;
                         cu.t = first_tap(cu.rest);
@@ -164,15 +197,20 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 // load is issued unconditionally, so the number in flight is known at compile time and
                 // a group's wait never includes the group requested after it.
                 auto gather_group = [&](const Cursor& cu, Vec (&x)[GK]) {
+                    const bool proj = DUAL && cu.t == kTapProj;
                     const bool tap_ok = (tapbits >> cu.t) & 1;
                     const int dy = cu.t / KS, dx = cu.t % KS;
-                    const uint32_t uni = (uint32_t)((dy * c.w + dx) * cin_bytes + cu.kg * (GK * 32));
-                    const uint32_t off = tap_ok ? base00 + uni : kOob;
+                    const uint32_t uni = proj ? (uint32_t)(cu.kg * (GK * 32))
+                                              : (uint32_t)((dy * c.w + dx) * cin_bytes + cu.kg * (GK * 32));
+                    const uint32_t off = tap_ok ? (proj ? base2 : base00) + uni : kOob;
+                    const int limit = proj ? cin2_bytes : cin_bytes;
+                    const bool exact = proj ? false : k_exact;
+                    const __amdgpu_buffer_rsrc_t rs = proj ? rs_in2 : rs_in;
 #pragma unroll
                     for (int u = 0; u < GK; ++u) {
                         uint32_t o = off + (uint32_t)u * 32u;
-                        if (!k_exact && (2 * (cu.kg * GK + u) + g) * 16 >= cin_bytes) o = kOob;
-                        x[u] = ws_load16<Vec>(rs_in, o);
+                        if (!exact && (2 * (cu.kg * GK + u) + g) * 16 >= limit) o = kOob;
+                        x[u] = ws_load16<Vec>(rs, o);
                     }
                     __builtin_amdgcn_sched_barrier(0);             // the scheduler must not sink the loads below the MFMAs
                 };
@@ -181,13 +219,31 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 for (int b = 0; b < NB; ++b)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+                unsigned char* tile_row = stage0 + (size_t)((rd & 1) * NP + ww) * stage_tile + (size_t)col * stage_stride;
+                bool main_staged = false;
                 // The weight operands of K-step u+1 are requested from LDS before the MFMAs of step u
                 // issue; a K-step past the end multiplies the (valid) last step's weights with zeros.
                 auto mma_group = [&](const Cursor& cu, const Vec (&x)[GK]) {
+                    const bool proj = DUAL && cu.t == kTapProj;
+                    if constexpr (DUAL) {
+                        if (proj && !main_staged) {
+                            // The main result waits, rounded to the storage type, in the staging tile while
+                            // the accumulators are reused: both results are rounded before they are added,
+                            // as if each had been stored.
+                            stage_accumulators<T, NB, false>(acc, tile_row, g);
+#pragma unroll
+                            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                                for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+                            main_staged = true;
+                        }
+                    }
+                    const int steps = proj ? c.kch2 : kch;
+                    const Vec* wtap = proj ? wbase2 : wbase + (size_t)(cu.t * kch) * 2 * COLS;
                     Vec wv[2][NB];
                     auto request = [&](int u) {
                         const int kc = cu.kg * GK + u;
-                        const Vec* wrow = wbase + (size_t)(cu.t * kch + (kc < kch ? kc : kch - 1)) * 2 * COLS;
+                        const Vec* wrow = wtap + (size_t)(kc < steps ? kc : steps - 1) * 2 * COLS;
 #pragma unroll
                         for (int b = 0; b < NB; ++b) wv[u & 1][b] = wrow[b * 32];
                     };
@@ -212,8 +268,8 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     gather_group(cg, xa); advance(cg);
                     mma_group(cm, xb); advance(cm);
                 }
-                unsigned char* tile_stage = stage0 + (size_t)((rd & 1) * NP + ww) * stage_tile;
-                stage_accumulators<T, NB>(acc, tile_stage + (size_t)col * stage_stride, g);
+                if (main_staged) stage_accumulators<T, NB, true>(acc, tile_row, g);
+                else stage_accumulators<T, NB, false>(acc, tile_row, g);
             }
             lds_block_sync();
         }

@@ -14,6 +14,7 @@ struct dcnn_layer {
     bool inited;
     bool alias_mask;            // output mask / index list are those of input 0
     bool has_bias;
+    bool has_bias2 = false;     // bias of the fused projection
     size_t state_bytes;
     // pieces of the caller-provided state memory
     void* buf0; size_t buf0_bytes;      // x^A | stored input frame | dense output
@@ -27,6 +28,9 @@ struct dcnn_layer {
     uint32_t* taps;                     // per work-list entry: flagged window taps (dense convolutions, 1x1 / 3x3)
     void* wpacked;
     void* bias;
+    void* wpacked2;                     // fused projection: weights in the main plan's column grouping (sparse steps)
+    void* wpacked2_dense;               // ... and packed as a convolution of its own (dense first frame)
+    void* bias2;
     int32_t* counters;
     // bookkeeping of the last step
     dcnn_delta view;
@@ -37,3 +41,10 @@ struct dcnn_layer {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
     size_t events_used = 0;
 };
+
+namespace dcnn {
+// dcnn_layer_create with the weights and bias of a fused projection passed on their own.
+dcnn_status layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const void* weights_dev, const void* bias_dev,
+                         const void* proj_weights_dev, const void* proj_bias_dev, void* state_dev, size_t state_bytes,
+                         dcnn_layer** out);
+}  // namespace dcnn

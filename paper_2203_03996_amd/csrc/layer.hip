@@ -9,6 +9,7 @@ using namespace dcnn;
 namespace dcnn {
 
 static bool has_act(const dcnn_layer_desc& d) { return d.act != DCNN_ACT_NONE; }
+static bool has_proj(const dcnn_layer_desc& d) { return d.proj_c > 0; }
 
 // Does the layer build a work list of its own (window dilation / union of two masks), or does
 // it walk the index list of its first input as it is?
@@ -66,7 +67,15 @@ static dcnn_status validate_desc(const dcnn_layer_desc& d) {
         default: if (d.n_in != 1) return DCNN_EINVAL;
     }
     int oh, ow, oc;
-    return out_shape(d, &oh, &ow, &oc);
+    const dcnn_status st = out_shape(d, &oh, &ow, &oc);
+    if (st != DCNN_OK) return st;
+    if (d.proj_c < 0) return DCNN_EINVAL;
+    if (has_proj(d)) {
+        if (d.kind != DCNN_CONV || d.n_in != 2 || d.act == DCNN_ACT_NONE) return DCNN_EINVAL;
+        if (d.proj_stride < 1 || d.proj_stride > 2 || d.proj_h < 1 || d.proj_w < 1) return DCNN_EINVAL;
+        if ((d.proj_h - 1) / d.proj_stride + 1 != oh || (d.proj_w - 1) / d.proj_stride + 1 != ow) return DCNN_ESHAPE;
+    }
+    return DCNN_OK;
 }
 
 // Walks the state memory and hands out aligned pieces; with base == nullptr it only measures.
@@ -91,6 +100,7 @@ static void carve(dcnn_layer* L, void* state) {
     L->buf0 = L->buf1 = nullptr; L->buf0_bytes = L->buf1_bytes = 0;
     L->out_data = nullptr; L->out_mask = nullptr; L->out_idx = nullptr; L->out_count = nullptr;
     L->list = nullptr; L->list_count = nullptr; L->taps = nullptr; L->wpacked = nullptr; L->bias = nullptr;
+    L->wpacked2 = nullptr; L->wpacked2_dense = nullptr; L->bias2 = nullptr;
     L->counters = static_cast<int32_t*>(cv.take(kAlign));      // stays all zero: doubles as the zero page of the gathers
     switch (d.kind) {
         case DCNN_DELTAGEN:
@@ -139,6 +149,11 @@ static void carve(dcnn_layer* L, void* state) {
     if (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV) {
         L->wpacked = cv.take(conv_packed_weight_bytes(d.dtype, d.kh, d.c, L->oc, d.kind == DCNN_DWCONV, act));
         L->bias = cv.take((size_t)L->oc * es);
+        if (has_proj(d)) {
+            L->wpacked2 = cv.take(conv_proj_weight_bytes(d.dtype, d.kh, d.c, d.proj_c, L->oc));
+            L->wpacked2_dense = cv.take(conv_packed_weight_bytes(d.dtype, 1, d.proj_c, L->oc, 0, false));
+            L->bias2 = cv.take((size_t)L->oc * es);
+        }
     }
     L->state_bytes = cv.off;
 }
@@ -197,6 +212,24 @@ dcnn_status dcnn_layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const 
                               void* state_dev, size_t state_bytes, dcnn_layer** out) {
     if (!ctx) return DCNN_EINVAL;
     if (!desc || !out) return fail(ctx, DCNN_EINVAL, "layer_create: null argument");
+    // a fused projection's weights and bias follow the main ones
+    const void* w2 = nullptr;
+    const void* b2 = nullptr;
+    if (desc->proj_c > 0 && desc->kind == DCNN_CONV && desc->cout > 0 && desc->kh > 0 && desc->c > 0 && weights_dev) {
+        const size_t es = dtype_size(desc->dtype);
+        w2 = static_cast<const char*>(weights_dev) + (size_t)desc->kh * desc->kh * desc->c * desc->cout * es;
+        if (bias_dev) b2 = static_cast<const char*>(bias_dev) + (size_t)desc->cout * es;
+    }
+    return dcnn::layer_create(ctx, desc, weights_dev, bias_dev, w2, b2, state_dev, state_bytes, out);
+}
+
+}  // extern "C"
+
+namespace dcnn {
+
+dcnn_status layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const void* weights_dev, const void* bias_dev,
+                         const void* proj_weights_dev, const void* proj_bias_dev, void* state_dev, size_t state_bytes,
+                         dcnn_layer** out) {
     *out = nullptr;
     dcnn_status st = validate_desc(*desc);
     if (st != DCNN_OK) return fail(ctx, st, "layer_create: invalid descriptor (kind %d)", desc->kind);
@@ -228,6 +261,22 @@ dcnn_status dcnn_layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const 
         st = launch_pack_weights(ctx, desc->dtype, weights_dev, L->wpacked, desc->kh, desc->c, L->oc,
                                  desc->kind == DCNN_DWCONV, has_act(*desc));
         if (st == DCNN_OK && bias_dev) st = launch_copy(ctx, L->bias, bias_dev, (size_t)L->oc * dtype_size(desc->dtype));
+        if (st == DCNN_OK && has_proj(*desc)) {
+            const size_t es = dtype_size(desc->dtype);
+            if (!conv_proj_supported(ctx, desc->dtype, desc->kh, desc->c, desc->proj_c, L->oc, L->in_pixels * desc->c,
+                                     (int64_t)desc->n * desc->proj_h * desc->proj_w * desc->proj_c, L->out_pixels * L->oc) ||
+                !conv_supported(ctx, desc->dtype, 1, desc->proj_c, L->oc, 0, false, why, sizeof(why))) {
+                delete L;
+                return fail(ctx, DCNN_EUNSUPPORTED, "layer_create: conv %dx%d %d->%d with a fused projection of %d channels is not covered",
+                            desc->kh, desc->kh, desc->c, L->oc, desc->proj_c);
+            }
+            if (!proj_weights_dev) { delete L; return fail(ctx, DCNN_EINVAL, "layer_create: fused projection without weights"); }
+            const void* w2 = proj_weights_dev;
+            st = launch_pack_weights_proj(ctx, desc->dtype, w2, L->wpacked2, desc->kh, desc->c, desc->proj_c, L->oc);
+            if (st == DCNN_OK) st = launch_pack_weights(ctx, desc->dtype, w2, L->wpacked2_dense, 1, desc->proj_c, L->oc, 0, false);
+            if (st == DCNN_OK && proj_bias_dev) st = launch_copy(ctx, L->bias2, proj_bias_dev, (size_t)L->oc * es);
+            L->has_bias2 = proj_bias_dev != nullptr;
+        }
         if (st != DCNN_OK) { delete L; return st; }
         L->has_bias = bias_dev != nullptr;
     }
@@ -241,6 +290,10 @@ dcnn_status dcnn_layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const 
     *out = L;
     return DCNN_OK;
 }
+
+}  // namespace dcnn
+
+extern "C" {
 
 static void drop_events(dcnn_layer* L) {
     for (auto& e : L->events) { (void)hipEventDestroy(e.first); (void)hipEventDestroy(e.second); }
@@ -310,13 +363,26 @@ dcnn_status dcnn_layer_init(dcnn_layer* L, const void* const* dense_in, int32_t 
             break;
         case DCNN_CONV:
         case DCNN_DWCONV: {
+            if (has_proj(d)) {
+                // the projection runs as a dense convolution of its own into the output buffer, which the
+                // main convolution then reads as its residual (each pixel is read before it is rewritten)
+                ConvArgs c2{};
+                c2.in_data = dense_in[1]; c2.in_mask = nullptr; c2.wpacked = L->wpacked2_dense; c2.zero_page = L->counters;
+                c2.n = d.n; c2.h = d.proj_h; c2.w = d.proj_w; c2.cin = d.proj_c; c2.oh = L->oh; c2.ow = L->ow; c2.cout = L->oc;
+                c2.k = 1; c2.stride = d.proj_stride; c2.pad = 0; c2.depthwise = 0;
+                EpilogueArgs e2{};
+                e2.c = L->oc; e2.act = DCNN_ACT_NONE; e2.eps = 0.0f; e2.bias = L->has_bias2 ? L->bias2 : nullptr;
+                e2.out_data = dense_out;
+                st = launch_conv(ctx, d.dtype, true, full_list(L->out_pixels), c2, e2);
+                if (st != DCNN_OK) break;
+            }
             ConvArgs c{};
             c.in_data = dense_in[0]; c.in_mask = nullptr; c.wpacked = L->wpacked; c.zero_page = L->counters;
             c.n = d.n; c.h = d.h; c.w = d.w; c.cin = d.c; c.oh = L->oh; c.ow = L->ow; c.cout = L->oc;
             c.k = d.kh; c.stride = d.stride; c.pad = d.pad; c.depthwise = d.kind == DCNN_DWCONV;
             EpilogueArgs e{};
             e.c = L->oc; e.act = d.act; e.eps = d.eps; e.bias = L->has_bias ? L->bias : nullptr;
-            e.res_data = d.n_in == 2 ? dense_in[1] : nullptr; e.res_mask = nullptr;
+            e.res_data = d.n_in == 2 ? (has_proj(d) ? dense_out : dense_in[1]) : nullptr; e.res_mask = nullptr;
             e.xA = L->buf0; e.xT = L->buf1; e.out_data = dense_out; e.out_mask = nullptr; e.surv = nullptr;
             st = launch_conv(ctx, d.dtype, true, full_list(L->out_pixels), c, e);
             break;
@@ -372,7 +438,8 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
     dcnn_status st = check_input(L, in[0], 0, d.h, d.w, d.c, !own || d.kind == DCNN_MAXPOOL);
     if (st != DCNN_OK) return st;
     if (n_in == 2) {
-        st = check_input(L, in[1], 1, L->oh, L->ow, L->oc, false);
+        st = has_proj(d) ? check_input(L, in[1], 1, d.proj_h, d.proj_w, d.proj_c, false)
+                         : check_input(L, in[1], 1, L->oh, L->ow, L->oc, false);
         if (st != DCNN_OK) return st;
     }
     Workspace ws;
@@ -412,6 +479,9 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         if (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV || d.kind == DCNN_MAXPOOL) { m.k = d.kh; m.stride = d.stride; m.pad = d.pad; }
         if (d.kind == DCNN_UPSAMPLE) m.up = d.factor;
         m.taps_out = L->taps;
+        if (has_proj(d) && !(d.proj_stride == 1 && d.proj_h == L->oh && d.proj_w == L->ow)) {
+            m.b_stride = d.proj_stride; m.b_h = d.proj_h; m.b_w = d.proj_w;
+        }
         st = launch_mask_compact(ctx, m);
         if (st != DCNN_OK) return st;
         l.list = L->list; l.count = L->list_count; l.taps = L->taps;
@@ -445,6 +515,11 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             EpilogueArgs e{};
             e.c = L->oc; e.act = d.act; e.eps = d.eps; e.bias = nullptr;
             e.res_data = n_in == 2 ? in[1]->data : nullptr; e.res_mask = n_in == 2 ? in[1]->mask : nullptr;
+            if (has_proj(d)) {
+                c.in2_data = in[1]->data; c.wpacked2 = L->wpacked2;
+                c.h2 = d.proj_h; c.w2 = d.proj_w; c.cin2 = d.proj_c; c.stride2 = d.proj_stride;
+                e.res_data = nullptr; e.res_mask = nullptr;
+            }
             e.xA = L->buf0; e.xT = L->buf1; e.out_data = L->out_data;
             e.out_mask = act ? L->out_mask : nullptr;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;

@@ -72,6 +72,16 @@ __device__ __forceinline__ bool window3_fast(int k, int stride, int pad, int up,
     return k == 3 && stride == 1 && pad == 1 && up == 1 && (w % 8) == 0 && oh == h && ow == w;
 }
 
+// Flag of the second mask for output pixel p (same shape as the output, or sampled with a stride).
+__device__ __forceinline__ bool mask_b_flag(const uint8_t* mask_b, int64_t p, int b_stride, int b_h, int b_w, int oh, int ow) {
+    if (b_stride <= 0) return mask_b[p] != 0;
+    const int x = (int)(p % ow);
+    const int64_t t = p / ow;
+    const int y = (int)(t % oh);
+    const int64_t n = t / oh;
+    return mask_b[(n * b_h + (int64_t)y * b_stride) * b_w + (int64_t)x * b_stride] != 0;
+}
+
 struct MaskKernelArgs {
     const uint8_t* mask_in;
     const uint8_t* mask_b;
@@ -80,6 +90,7 @@ struct MaskKernelArgs {
     int32_t* zero_count;
     int64_t out_pixels;
     int n, h, w, oh, ow, k, stride, pad, up;
+    int b_stride, b_h, b_w;       // > 0: mask_b is sampled at (y, x) * b_stride of an [n, b_h, b_w] map
 };
 
 __global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs a) {
@@ -88,10 +99,11 @@ __global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs 
     uint64_t word = 0;
     int cnt = 0;
     if (p0 < a.out_pixels) {
-        if (a.k == 1 && a.stride == 1 && a.up == 1 && p0 + kPxPerThread <= a.out_pixels) {
+        const bool b_same = a.mask_b == nullptr || a.b_stride <= 0;
+        if (a.k == 1 && a.stride == 1 && a.up == 1 && b_same && p0 + kPxPerThread <= a.out_pixels) {
             word = *reinterpret_cast<const uint64_t*>(a.mask_in + p0);
             if (a.mask_b) word |= *reinterpret_cast<const uint64_t*>(a.mask_b + p0);
-        } else if (window3_fast(a.k, a.stride, a.pad, a.up, a.h, a.w, a.oh, a.ow)) {
+        } else if (b_same && window3_fast(a.k, a.stride, a.pad, a.up, a.h, a.w, a.oh, a.ow)) {
             const int x0 = (int)(p0 % a.w);
             const int64_t t = p0 / a.w;
             const int y = (int)(t % a.h);
@@ -121,7 +133,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs 
                         }
                     }
                 }
-                if (a.mask_b) f |= a.mask_b[p0 + i];
+                if (a.mask_b && mask_b_flag(a.mask_b, p0 + i, a.b_stride, a.b_h, a.b_w, a.oh, a.ow)) f |= 1;
                 word |= (uint64_t)(f ? 1 : 0) << (8 * i);
                 if (++ox == a.ow) { ox = 0; if (++oy == a.oh) { oy = 0; ++n; } }
             }
@@ -147,8 +159,10 @@ struct EmitArgs {
     int32_t* count_out;
     int64_t pixels;
     const uint8_t* tap_mask;      // input mask the window taps are tested against (with taps_out)
+    const uint8_t* mask_b;        // second mask: bit 30 of the tap word
     uint32_t* taps_out;
     int h, w, oh, ow, k, stride, pad;
+    int b_stride, b_h, b_w;
 };
 
 __global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
@@ -187,7 +201,9 @@ __global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
         for (int i = 0; i < kPxPerThread; ++i) {
             if ((word >> (8 * i)) & 1) {
                 a.idx_out[pos] = (int32_t)(p0 + i);
-                a.taps_out[pos] = ((rows[0] >> i) & 7u) | (((rows[1] >> i) & 7u) << 3) | (((rows[2] >> i) & 7u) << 6);
+                uint32_t taps = ((rows[0] >> i) & 7u) | (((rows[1] >> i) & 7u) << 3) | (((rows[2] >> i) & 7u) << 6);
+                if (a.mask_b && mask_b_flag(a.mask_b, p0 + i, a.b_stride, a.b_h, a.b_w, a.oh, a.ow)) taps |= 1u << 30;
+                a.taps_out[pos] = taps;
                 ++pos;
             }
         }
@@ -207,6 +223,7 @@ __global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
                     if (iy >= 0 && iy < a.h && ix >= 0 && ix < a.w && a.tap_mask[(n * a.h + iy) * a.w + ix]) taps |= 1u << tap;
                 }
             }
+            if (a.mask_b && mask_b_flag(a.mask_b, p0 + i, a.b_stride, a.b_h, a.b_w, a.oh, a.ow)) taps |= 1u << 30;
             a.idx_out[pos] = (int32_t)(p0 + i);
             a.taps_out[pos] = taps;
             ++pos;
@@ -233,6 +250,7 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
         a.n = m.n; a.h = m.h; a.w = m.w; a.oh = m.oh; a.ow = m.ow;
         a.k = m.k; a.stride = m.stride; a.pad = m.pad;
         a.up = m.up > 1 ? m.up : 1;
+        a.b_stride = m.b_stride; a.b_h = m.b_h; a.b_w = m.b_w;
         hipLaunchKernelGGL(mask_pass_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, a);
         st = check_hip(ctx, hipGetLastError(), "mask_pass_kernel launch");
         if (st != DCNN_OK) return st;
@@ -242,6 +260,7 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
     EmitArgs e{emit_mask, ws.chunk_counts, m.idx_out, m.count_out, out_pixels};
     e.tap_mask = m.mask_in; e.taps_out = (m.emit_only || m.up > 1 || m.k * m.k > 25) ? nullptr : m.taps_out;
     e.h = m.h; e.w = m.w; e.oh = m.oh; e.ow = m.ow; e.k = m.k; e.stride = m.stride; e.pad = m.pad;
+    e.mask_b = m.mask_b; e.b_stride = m.b_stride; e.b_h = m.b_h; e.b_w = m.b_w;
     hipLaunchKernelGGL(emit_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, e);
     return check_hip(ctx, hipGetLastError(), "emit_kernel launch");
 }

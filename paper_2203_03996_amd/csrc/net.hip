@@ -1,5 +1,6 @@
 // Network executor: a DAG of plain nodes is fused into layers (conv -> add -> activation chains
-// become one launch sequence), the layers' state is planned into one caller-provided arena, and
+// become one launch sequence; a 1x1 projection convolution on the other arm of the add is pulled in
+// as well), the layers' state is planned into one caller-provided arena, and
 // a frame is run by stepping the layers in topological order on the context's stream.
 #include <new>
 #include <vector>
@@ -25,6 +26,8 @@ struct Planned {
     int out_node;                   // node whose output this layer produces
     const void* w;
     const void* b;
+    const void* w2;                 // fused projection
+    const void* b2;
     size_t state_off, state_bytes;
     dcnn_layer* layer;
 };
@@ -132,12 +135,13 @@ dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t fuse, size_t* arena_bytes) 
         if (absorbed[i]) continue;
         const Node& nd = net->nodes[i];
         Planned p{};
-        p.d = nd.d; p.in_nodes = nd.in; p.out_node = i; p.w = nd.w; p.b = nd.b; p.layer = nullptr;
+        p.d = nd.d; p.in_nodes = nd.in; p.out_node = i; p.w = nd.w; p.b = nd.b; p.w2 = nullptr; p.b2 = nullptr; p.layer = nullptr;
         if ((fuse & 1) && is_conv(nd.d)) {
             int cur = i;
             dcnn_layer_desc d = nd.d;
             std::vector<int> ins = nd.in, taken;
             int j = sole_consumer(cur);
+            int proj = -1;                       // convolution on the other arm of the add that is pulled in
             if (j >= 0 && !absorbed[j] && is_add(net->nodes[j].d)) {
                 const Node& add = net->nodes[j];
                 const int other = add.in[0] == cur ? add.in[1] : add.in[0];
@@ -146,6 +150,12 @@ dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t fuse, size_t* arena_bytes) 
                     ins.push_back(other);
                     taken.push_back(j);
                     cur = j;
+                    // the other arm: an unfused 1x1 convolution without padding that feeds only this add and
+                    // has not been planned yet (it comes later in node order, or it would be a layer already)
+                    const Node& o = net->nodes[other];
+                    if (other > i && !absorbed[other] && o.d.kind == DCNN_CONV && o.d.kh == 1 && o.d.pad == 0 &&
+                        o.consumers.size() == 1 && o.in.size() == 1)
+                        proj = other;
                 }
             }
             int k = sole_consumer(cur);
@@ -158,6 +168,18 @@ dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t fuse, size_t* arena_bytes) 
             if (cur != i && conv_supported(ctx, d.dtype, d.kh, d.c, nd.oc, d.kind == DCNN_DWCONV, true, why, sizeof(why))) {
                 for (int a : taken) absorbed[a] = 1;
                 p.d = d; p.in_nodes = ins; p.out_node = cur;
+                if (proj >= 0 && d.act != DCNN_ACT_NONE && d.kind == DCNN_CONV) {
+                    const Node& o = net->nodes[proj];
+                    const int64_t px_in = (int64_t)d.n * d.h * d.w, px_in2 = (int64_t)d.n * o.d.h * o.d.w;
+                    const int64_t px_out = (int64_t)d.n * nd.oh * nd.ow;
+                    if (conv_proj_supported(ctx, d.dtype, d.kh, d.c, o.d.c, nd.oc, px_in * d.c, px_in2 * o.d.c, px_out * nd.oc) &&
+                        conv_supported(ctx, d.dtype, 1, o.d.c, nd.oc, 0, false, why, sizeof(why))) {
+                        absorbed[proj] = 1;
+                        p.d.proj_c = o.d.c; p.d.proj_h = o.d.h; p.d.proj_w = o.d.w; p.d.proj_stride = o.d.stride;
+                        p.in_nodes[1] = o.in[0];
+                        p.w2 = o.w; p.b2 = o.b;
+                    }
+                }
             }
         } else if ((fuse & 1) && is_add(nd.d)) {
             int k = sole_consumer(i);
@@ -212,7 +234,7 @@ dcnn_status dcnn_net_bind(dcnn_net* net, void* arena_dev, size_t arena_bytes) {
         return fail(ctx, DCNN_EINVAL, "net_bind: arena missing or not 256-byte aligned");
     if (arena_bytes < net->arena_bytes) return fail(ctx, DCNN_ENOMEM, "net_bind: arena of %zu bytes, need %zu", arena_bytes, net->arena_bytes);
     for (auto& p : net->plan) {
-        dcnn_status st = dcnn_layer_create(ctx, &p.d, p.w, p.b, static_cast<char*>(arena_dev) + p.state_off, p.state_bytes, &p.layer);
+        dcnn_status st = dcnn::layer_create(ctx, &p.d, p.w, p.b, p.w2, p.b2, static_cast<char*>(arena_dev) + p.state_off, p.state_bytes, &p.layer);
         if (st != DCNN_OK) {
             for (auto& q : net->plan) { dcnn_layer_destroy(q.layer); q.layer = nullptr; }
             return st;
