@@ -223,9 +223,11 @@ class Context:
 
 
 def make_desc(kind, dtype, n, h, w, c, k=1, stride=1, pad=0, cout=0, act=ACT_NONE, eps=0.0, n_in=1, dilate_r=0,
-              factor=1, want_idx=1) -> LayerDesc:
+              factor=1, want_idx=1, proj=None) -> LayerDesc:
+    """proj = (channels, height, width, stride) of the input of a fused 1x1 projection shortcut, or None."""
+    pc, ph, pw, ps = proj if proj is not None else (0, 0, 0, 0)
     return LayerDesc(kind, dtype, n, h, w, c, k, k, stride, pad, cout, act, float(eps), n_in, dilate_r, factor,
-                     want_idx)
+                     want_idx, pc, ph, pw, ps)
 
 
 class Layer:

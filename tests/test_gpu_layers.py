@@ -266,6 +266,64 @@ def test_conv_fused_act(S, k, stride, cin, cout, nhw, res):
     assert ties <= 3
 
 
+@pytest.mark.parametrize("S,k,cin,cin2,cout,nhw,stride2", [
+    ("f16", 1, 64, 64, 256, (2, 24, 40), 1),
+    ("f16", 1, 64, 32, 128, (1, 19, 23), 2),
+    ("f16", 3, 32, 48, 64, (1, 33, 35), 1),
+    ("f32", 1, 16, 8, 32, (1, 20, 20), 1),
+    ("f32", 3, 16, 16, 32, (1, 17, 21), 2),
+])
+def test_conv_fused_projection(S, k, cin, cin2, cout, nhw, stride2):
+    """conv_a(x) + conv_b(z) + activation/truncation in one layer (the 1x1 projection conv_b of the other
+    arm of a residual add runs inside the same kernel) == oracle conv, conv, add, act."""
+    rng = np.random.default_rng(7 * k + cin + cin2 + cout + stride2)
+    n, oh, ow = nhw
+    h, w = oh, ow                                           # main convolution: stride 1, same padding
+    h2, w2 = (oh - 1) * stride2 + 1 + (stride2 - 1), (ow - 1) * stride2 + 1      # ragged: an unused last row
+    if (h2 - 1) // stride2 + 1 != oh:
+        h2 = (oh - 1) * stride2 + 1
+    eps = 0.3
+    wa = (rng.normal(0, 1, (k, k, cin, cout)) * np.sqrt(2.0 / (k * k * cin))).astype(NP_DTYPE[S])
+    wb = (rng.normal(0, 1, (1, 1, cin2, cout)) * np.sqrt(2.0 / cin2)).astype(NP_DTYPE[S])
+    ba = rng.normal(0, 0.1, cout).astype(NP_DTYPE[S])
+    bb = rng.normal(0, 0.1, cout).astype(NP_DTYPE[S])
+    ra, rb = orc.Conv(wa, ba, 1, k // 2, False, S), orc.Conv(wb, bb, stride2, 0, False, S)
+    radd, ract = orc.Add(S), orc.ActTrunc("relu", eps, S)
+    ctx = pkg.Context(n * max(h * w, h2 * w2))
+    desc = pkg.make_desc(pkg.CONV, DT[S], n, h, w, cin, k=k, stride=1, pad=k // 2, cout=cout, act=pkg.ACT_RELU, eps=eps,
+                         n_in=2, proj=(cin2, h2, w2, stride2))
+    wcat = torch.from_numpy(np.concatenate([wa.ravel(), wb.ravel()])).cuda()
+    bcat = torch.from_numpy(np.concatenate([ba, bb])).cuda()
+    layer = pkg.Layer(ctx, desc, wcat, bcat)
+    assert layer.out_shape == (n, oh, ow, cout)
+    x0 = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
+    z0 = rng.normal(0, 1, (n, h2, w2, cin2)).astype(NP_DTYPE[S])
+    r0 = ract.init(radd.init(ra.init(x0), rb.init(z0)))
+    g0 = layer.init([torch.from_numpy(x0).cuda(), torch.from_numpy(z0).cuda()])
+    ctx.sync()
+    assert rel_err(to_np(g0), r0) <= TOL[S], "dense first frame"
+    assert rel_err(to_np(layer.state_tensor(0)), ract.xA) <= TOL[S]
+    ties = 0
+    for t, (dx, dz) in enumerate([(0.05, 0.1), (0.3, 0.0), (0.0, 0.2), (1.0, 1.0), (0.0, 0.0), (0.1, 0.02)]):
+        layer.state_tensor(0).copy_(torch.from_numpy(ract.xA).cuda())
+        layer.state_tensor(1).copy_(torch.from_numpy(ract.xT).cuda())
+        d = _rand_delta(rng, (n, h, w, cin), dx, S, 0.5)
+        z = _rand_delta(rng, (n, h2, w2, cin2), dz, S, 0.5)
+        mid = radd.step(ra.step(d).poisoned(), rb.step(z).poisoned()).poisoned()
+        want = ract.step(mid).poisoned()
+        out = layer.step([_upload(d), _upload(z)])
+        ctx.sync()
+        near = np.abs(np.nan_to_num(ract.last_u, nan=np.inf) - eps) <= TOL[S] * eps
+        ties += check_delta(out, want, S, f"projection frame {t}", allow_mask_diff=near)
+        agree = to_np(out.mask) == want.mask
+        assert rel_err(to_np(layer.state_tensor(0))[agree], ract.xA[agree]) <= TOL[S]
+        xt_g, xt_r = to_np(layer.state_tensor(1))[agree], ract.xT[agree]
+        assert np.abs(xt_g.astype(np.float64) - xt_r).max(initial=0) <= TOL[S] * max(1.0, np.abs(xt_r).max(initial=0))
+        st = layer.stats()
+        assert st["pixels_in"] == d.count and st["pixels_in2"] == z.count and st["pixels_work"] == mid.count
+    assert ties <= 3
+
+
 @pytest.mark.parametrize("S", ["f32", "f16"])
 @pytest.mark.parametrize("stride,c", [(1, 32), (2, 192), (1, 960), (2, 20)])
 def test_depthwise(S, stride, c):
