@@ -55,7 +55,9 @@ def layer_bytes(s: dict, b: int) -> float:
         return 3.0 * pin * cin * b + work * cout * b
     elif kind == UPSAMPLE:
         return pin * cin * b + work * cout * b
-    if s["n_in"] == 2:
+    if s.get("proj_c", 0):
+        total += pin2 * s["proj_c"] * b + s["proj_c"] * cout * b           # projection: its flagged inputs, its weights
+    elif s["n_in"] == 2:
         total += pin2 * cout * b                                          # residual stream
     if s["act"] != ACT_NONE:
         total += work * 2 * cout * b                                      # read x^A, x^T
@@ -73,7 +75,11 @@ def layer_flops(s: dict) -> tuple[float, float]:
         return 0.0, 0.0
     per = s["c_out"] if s["kind"] == DWCONV else s["c_in"] * s["c_out"]
     taps = s["k"] ** 2
-    return 2.0 * s["pixels_in"] * taps / s["stride"] ** 2 * per, 2.0 * s["pixels_work"] * taps * per
+    needed, issued = 2.0 * s["pixels_in"] * taps / s["stride"] ** 2 * per, 2.0 * s["pixels_work"] * taps * per
+    if s.get("proj_c", 0):                                                # fused 1x1 projection of input 1
+        needed += 2.0 * s["pixels_in2"] * s["proj_c"] * s["c_out"]
+        issued += 2.0 * s["pixels_work"] * s["proj_c"] * s["c_out"]
+    return needed, issued
 
 
 class Workload:
@@ -108,6 +114,8 @@ def conv_density(stats) -> float:
     """Mean over convolution layers of flagged input pixels / input pixels (Section 5 statistic)."""
     from paper_2203_03996_amd import CONV, DWCONV
     d = [s["pixels_in"] / s["pixels_in_total"] for s in stats if s["kind"] in (CONV, DWCONV)]
+    # a fused projection is a convolution of the network too (its input is the layer's input 1)
+    d += [s["pixels_in2"] / s["pixels_in2_total"] for s in stats if s["kind"] == CONV and s.get("proj_c", 0)]
     return float(np.mean(d)) if d else 0.0
 
 
@@ -308,7 +316,8 @@ def main():
     for i in range(net.num_layers):
         s = stats[0][i]
         layer_names.append(f"{['deltagen','conv','dwconv','act','maxpool','upsample','accum'][s['kind']]}"
-                           f"{s['k']}x{s['k']}:{s['c_in']}->{s['c_out']}" + ("+res" if s["n_in"] == 2 else "") +
+                           f"{s['k']}x{s['k']}:{s['c_in']}->{s['c_out']}" +
+                           (f"+proj1x1:{s['proj_c']}->{s['c_out']}" if s.get("proj_c", 0) else ("+res" if s["n_in"] == 2 else "")) +
                            ("+act" if s["act"] else ""))
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")

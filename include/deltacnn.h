@@ -115,12 +115,13 @@ typedef struct {
     int64_t pixels_out;     /* flagged pixels of the output                    */
     int64_t pixels_total;   /* n*h*w of the output                             */
     int64_t pixels_in_total;/* n*h*w of input 0                                */
+    int64_t pixels_in2_total;/* n*h*w of input 1 (0 if there is none)           */
     int32_t kind;           /* dcnn_kind of the layer                          */
     int32_t act;            /* fused activation (dcnn_act)                     */
     int32_t n_in;
     int32_t c_in, c_out;    /* channels                                        */
     int32_t k, stride;      /* window (convolutions, pooling), else 1          */
-    int32_t reserved;
+    int32_t proj_c;         /* channels of the fused projection's input (input 1), 0 if none */
 } dcnn_stats;
 
 typedef struct dcnn_ctx dcnn_ctx;

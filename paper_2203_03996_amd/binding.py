@@ -56,11 +56,12 @@ class LayerSizes(C.Structure):
 class Stats(C.Structure):
     _fields_ = [("pixels_in", C.c_int64), ("pixels_in2", C.c_int64), ("pixels_work", C.c_int64),
                 ("pixels_out", C.c_int64), ("pixels_total", C.c_int64), ("pixels_in_total", C.c_int64),
+                ("pixels_in2_total", C.c_int64),
                 ("kind", C.c_int32), ("act", C.c_int32), ("n_in", C.c_int32), ("c_in", C.c_int32),
-                ("c_out", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32), ("reserved", C.c_int32)]
+                ("c_out", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32), ("proj_c", C.c_int32)]
 
     def as_dict(self) -> dict:
-        return {name: getattr(self, name) for name, _ in self._fields_ if name != "reserved"}
+        return {name: getattr(self, name) for name, _ in self._fields_}
 
 
 class DcnnError(RuntimeError):

@@ -616,10 +616,11 @@ dcnn_status dcnn_layer_stats(dcnn_layer* L, dcnn_stats* s) {
     if (st == DCNN_OK) st = read(L->view.count, &s->pixels_out);
     s->pixels_total = L->out_pixels;
     s->pixels_in_total = L->in_pixels;
+    s->pixels_in2_total = L->d.n_in == 2 ? (L->d.proj_c > 0 ? (int64_t)L->d.n * L->d.proj_h * L->d.proj_w : L->out_pixels) : 0;
     s->kind = L->d.kind; s->act = L->d.act; s->n_in = L->d.n_in;
     s->c_in = L->d.c; s->c_out = L->oc;
     const bool window = L->d.kind == DCNN_CONV || L->d.kind == DCNN_DWCONV || L->d.kind == DCNN_MAXPOOL;
-    s->k = window ? L->d.kh : 1; s->stride = window ? L->d.stride : 1; s->reserved = 0;
+    s->k = window ? L->d.kh : 1; s->stride = window ? L->d.stride : 1; s->proj_c = L->d.proj_c;
     return st;
 }
 
