@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         const bool has_rmask = e.res_mask != nullptr;
         const float hi = act_hi(e.act);
         // this lane's 16 bytes in row 0 of the producer slice that holds its channels (lanes without
-        // channels read slot 0: harmless, their stores go nowhere)
+        // channels read slot 0 and discard it; their stores go nowhere)
         const unsigned char* my_stage = stage0 + (size_t)(slot * cs + spart) * stage_tile + (size_t)(ch_on ? vi : 0) * V * ES;
         int survivors = 0;
 
@@ -341,8 +341,10 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
             uint32_t bits = 0;
             Raw rd[H];
 #pragma unroll
-            for (int h = 0; h < H; ++h)
+            for (int h = 0; h < H; ++h) {
                 rd[h] = raw_load<T, V>(reinterpret_cast<const T*>(tile_stage + (size_t)(ent0 + (s * H + h) * PPI) * stage_stride));
+                if (!ch_on) rd[h] = raw_zero<T, V>();              // lanes without channels must not raise the maximum
+            }
 #pragma unroll
             for (int h = 0; h < H; ++h) {
                 const int it = s * H + h;

@@ -218,6 +218,20 @@ def test_conv_linear(S, k, stride, pad, cin, cout, nhw):
     ("f16", 3, 2, 64, 128, (1, 30, 30), False),
     ("f16", 3, 2, 3, 32, (1, 40, 40), False),
     ("f32", 1, 1, 16, 16, (1, 20, 20), True),
+    # further shapes of the wave-specialised kernel: strided resident 3x3, channels that do not fill the
+    # last K-step, three column blocks per wave, two and four waves per tile with a residual, fp32 wide
+    ("f16", 3, 2, 32, 32, (2, 41, 37), False),
+    ("f16", 1, 1, 24, 96, (1, 33, 31), False),
+    ("f16", 3, 1, 16, 96, (1, 31, 29), True),
+    ("f16", 1, 1, 64, 128, (1, 45, 40), True),
+    ("f16", 1, 2, 32, 256, (1, 50, 44), True),
+    ("f32", 1, 1, 32, 64, (1, 37, 30), True),
+    ("f32", 3, 1, 16, 64, (3, 21, 22), False),
+    ("f16", 1, 1, 64, 64, (4, 96, 96), False),
+    # output channels that do not fill the last column block (padded lanes must stay out of the maximum)
+    ("f16", 1, 1, 32, 72, (1, 29, 33), True),
+    ("f16", 3, 1, 32, 40, (1, 23, 27), False),
+    ("f32", 1, 1, 16, 44, (1, 23, 27), False),
 ])
 def test_conv_fused_act(S, k, stride, cin, cout, nhw, res):
     """conv (+ residual) + activation/truncation in one layer == oracle conv -> add -> act."""
