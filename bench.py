@@ -63,6 +63,8 @@ def layer_bytes(s: dict, b: int) -> float:
         total += work * 2 * cout * b                                      # read x^A, x^T
         total += out * 3 * cout * b + (work - out) * cout * b             # write x^A, x^T, delta | x^T
         total += 2 * work                                                 # mask bytes
+        if s.get("fuse_accum", 0):
+            total += out * cout * b                                       # read O where updated (its write replaces the delta's)
     else:
         total += work * cout * b
     return total
@@ -318,7 +320,7 @@ def main():
         layer_names.append(f"{['deltagen','conv','dwconv','act','maxpool','upsample','accum'][s['kind']]}"
                            f"{s['k']}x{s['k']}:{s['c_in']}->{s['c_out']}" +
                            (f"+proj1x1:{s['proj_c']}->{s['c_out']}" if s.get("proj_c", 0) else ("+res" if s["n_in"] == 2 else "")) +
-                           ("+act" if s["act"] else ""))
+                           ("+act" if s["act"] else "") + ("+accum" if s.get("fuse_accum", 0) else ""))
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):

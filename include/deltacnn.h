@@ -100,6 +100,10 @@ typedef struct {
      * activation -- conv_a(x) + conv_b(z) is linear in both deltas (Section 3.1, Eq. 1).  Each of the two
      * results is rounded to the storage type before the addition, as if it had been stored. */
     int32_t proj_c, proj_h, proj_w, proj_stride;
+    /* 1: the layer also is the network's output layer (Fig. 2): it keeps the dense accumulated output O
+     * (state buffer 2, dcnn_layer_output's data) and adds every delta it emits to it instead of storing
+     * the delta.  CONV with activation and without a residual input only. */
+    int32_t fuse_accum;
 } dcnn_layer_desc;
 
 typedef struct {
@@ -122,6 +126,8 @@ typedef struct {
     int32_t c_in, c_out;    /* channels                                        */
     int32_t k, stride;      /* window (convolutions, pooling), else 1          */
     int32_t proj_c;         /* channels of the fused projection's input (input 1), 0 if none */
+    int32_t fuse_accum;     /* 1: the layer also accumulates the dense output             */
+    int32_t reserved;
 } dcnn_stats;
 
 typedef struct dcnn_ctx dcnn_ctx;
@@ -170,7 +176,8 @@ dcnn_status dcnn_layer_step(dcnn_layer* layer, const dcnn_delta* const* in, int3
 dcnn_status dcnn_layer_output(const dcnn_layer* layer, dcnn_delta* out_view);
 /* Forget the buffers: the next call must be dcnn_layer_init (supplementary Section 1.4). */
 dcnn_status dcnn_layer_reset(dcnn_layer* layer);
-/* which: 0 = x^A (ACT/CONV+act/MAXPOOL), stored frame (DELTAGEN), dense output (ACCUM); 1 = x^T.
+/* which: 0 = x^A (ACT/CONV+act/MAXPOOL), stored frame (DELTAGEN), dense output (ACCUM); 1 = x^T;
+ * 2 = dense output of a layer with fuse_accum.
  * Returns the device pointer and byte size of that buffer inside the state memory. */
 dcnn_status dcnn_layer_state(const dcnn_layer* layer, int32_t which, void** ptr_dev, size_t* bytes);
 /* Counters of the last step; synchronises the stream. */

@@ -45,7 +45,8 @@ class LayerDesc(C.Structure):
                 ("c", C.c_int32), ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32),
                 ("cout", C.c_int32), ("act", C.c_int32), ("eps", C.c_float), ("n_in", C.c_int32),
                 ("dilate_r", C.c_int32), ("factor", C.c_int32), ("want_idx", C.c_int32),
-                ("proj_c", C.c_int32), ("proj_h", C.c_int32), ("proj_w", C.c_int32), ("proj_stride", C.c_int32)]
+                ("proj_c", C.c_int32), ("proj_h", C.c_int32), ("proj_w", C.c_int32), ("proj_stride", C.c_int32),
+                ("fuse_accum", C.c_int32)]
 
 
 class LayerSizes(C.Structure):
@@ -58,10 +59,11 @@ class Stats(C.Structure):
                 ("pixels_out", C.c_int64), ("pixels_total", C.c_int64), ("pixels_in_total", C.c_int64),
                 ("pixels_in2_total", C.c_int64),
                 ("kind", C.c_int32), ("act", C.c_int32), ("n_in", C.c_int32), ("c_in", C.c_int32),
-                ("c_out", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32), ("proj_c", C.c_int32)]
+                ("c_out", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32), ("proj_c", C.c_int32), ("fuse_accum", C.c_int32),
+                ("reserved", C.c_int32)]
 
     def as_dict(self) -> dict:
-        return {name: getattr(self, name) for name, _ in self._fields_}
+        return {name: getattr(self, name) for name, _ in self._fields_ if name != "reserved"}
 
 
 class DcnnError(RuntimeError):
@@ -224,11 +226,11 @@ class Context:
 
 
 def make_desc(kind, dtype, n, h, w, c, k=1, stride=1, pad=0, cout=0, act=ACT_NONE, eps=0.0, n_in=1, dilate_r=0,
-              factor=1, want_idx=1, proj=None) -> LayerDesc:
+              factor=1, want_idx=1, proj=None, fuse_accum=0) -> LayerDesc:
     """proj = (channels, height, width, stride) of the input of a fused 1x1 projection shortcut, or None."""
     pc, ph, pw, ps = proj if proj is not None else (0, 0, 0, 0)
     return LayerDesc(kind, dtype, n, h, w, c, k, k, stride, pad, cout, act, float(eps), n_in, dilate_r, factor,
-                     want_idx, pc, ph, pw, ps)
+                     want_idx, pc, ph, pw, ps, fuse_accum)
 
 
 class Layer:

@@ -98,6 +98,8 @@ struct EpilogueArgs {
     uint8_t* out_mask;           // written at every visited pixel (0 or 1); nullptr: not written
     uint32_t* surv;              // survivor word per tile; nullptr: not written
     int32_t* out_count;          // when surv is null: survivors are added here (zeroed by the mask pass)
+    void* accum_O;               // fused final accumulation: dense output O (output shape); the emitted delta is
+                                 // added to it and not stored (sparse steps of layers with an activation only)
 };
 
 struct ListArgs {
@@ -132,6 +134,9 @@ bool conv_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cout, in
                     char* why, size_t why_len);
 // Convolution + activation with a fused 1x1 projection of a second input (cin2 channels): supported when the
 // sparse step can run on the wave-specialised kernel with both weight tensors resident in LDS.
+// Convolution + activation whose sparse step runs on the wave-specialised kernel (needed for a fused final
+// accumulation).
+bool conv_ws_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cout, int64_t in_elems, int64_t out_elems);
 bool conv_proj_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cin2, int cout, int64_t in_elems,
                          int64_t in2_elems, int64_t out_elems);
 size_t conv_proj_weight_bytes(int dtype, int k, int cin, int cin2, int cout);

@@ -342,16 +342,20 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
     const bool ws_taps = l.taps != nullptr || (c.k == 1 && c.stride == 1 && l.list != nullptr && c.in_mask != nullptr);
     const bool ws_ok = vec_out && aligned && ws_lds != 0 && !init && ws_taps && in_bytes <= kWsMaxBytes &&
                        in2_bytes <= kWsMaxBytes && out_bytes <= kWsMaxBytes;
+    const bool accum = e.accum_O != nullptr;
     if (dual && (!ws_ok || l.taps == nullptr || e.res_data != nullptr || ((size_t)c.cin2 * sizeof(T)) % 16 != 0))
         return fail(ctx, DCNN_EUNSUPPORTED, "conv %dx%d %d->%d with a fused projection of %d channels: shape not covered", c.k,
                     c.k, c.cin, c.cout, c.cin2);
+    if (accum && (!ws_ok || e.res_data != nullptr || e.act == DCNN_ACT_NONE))
+        return fail(ctx, DCNN_EUNSUPPORTED, "conv %dx%d %d->%d with a fused final accumulation: shape not covered", c.k, c.k,
+                    c.cin, c.cout);
     if (ws_ok) {
         const int64_t ws_want = cdiv(l.max_count > 0 ? l.max_count : 1, (kWsProducers / p.cs) * kTile);
         const int64_t ws_cap = ctx->num_cu;                    // 16 waves of up to 128 registers fill a compute unit
         const int ws_grid = (int)(cdiv(ws_want < ws_cap ? ws_want : ws_cap, kXcd) * kXcd);
-#define DCNN_WS_LAUNCH(KS, RES, DUAL)                                                                            \
+#define DCNN_WS_LAUNCH(KS, AUX, DUAL)                                                                            \
     do {                                                                                                         \
-        auto kern = conv_ws_kernel<T, NB, KS, RES, DUAL>;                                                        \
+        auto kern = conv_ws_kernel<T, NB, KS, AUX, DUAL>;                                                        \
         static bool attr_set = false;                                                                            \
         if (!attr_set) {                                                                                         \
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -361,16 +365,15 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
         if (err == hipSuccess)                                                                                   \
             hipLaunchKernelGGL(kern, dim3(ws_grid), dim3(kWsWaves * kWave), ws_lds, ctx->stream, l, c, e, p.cs); \
     } while (0)
-        const bool has_res = e.res_data != nullptr;
-        if (c.k == 1) {
-            if (dual) DCNN_WS_LAUNCH(1, false, true);
-            else if (has_res) DCNN_WS_LAUNCH(1, true, false);
-            else DCNN_WS_LAUNCH(1, false, false);
-        } else {
-            if (dual) DCNN_WS_LAUNCH(3, false, true);
-            else if (has_res) DCNN_WS_LAUNCH(3, true, false);
-            else DCNN_WS_LAUNCH(3, false, false);
-        }
+#define DCNN_WS_PICK(KS)                                                                                         \
+    do {                                                                                                         \
+        if (dual) { if (accum) DCNN_WS_LAUNCH(KS, 2, true); else DCNN_WS_LAUNCH(KS, 0, true); }                  \
+        else if (accum) DCNN_WS_LAUNCH(KS, 2, false);                                                            \
+        else if (e.res_data != nullptr) DCNN_WS_LAUNCH(KS, 1, false);                                            \
+        else DCNN_WS_LAUNCH(KS, 0, false);                                                                       \
+    } while (0)
+        if (c.k == 1) DCNN_WS_PICK(1); else DCNN_WS_PICK(3);
+#undef DCNN_WS_PICK
 #undef DCNN_WS_LAUNCH
         if (err != hipSuccess) return check_hip(ctx, err, "hipFuncSetAttribute(conv_ws_kernel)");
         return check_hip(ctx, hipGetLastError(), "conv_ws_kernel launch");

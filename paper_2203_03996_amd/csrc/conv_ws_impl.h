@@ -67,11 +67,14 @@ template <typename Raw> __device__ __forceinline__ void ws_store16(__amdgpu_buff
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)off, 0, 0);
 }
 
-template <typename T, int NB, int KS, bool RES, bool DUAL>
+// AUX: third per-pixel stream of the tail -- 0 none, 1 residual delta (added before the activation),
+// 2 dense accumulated output O of a final layer (O += emitted delta; the delta itself is not stored).
+template <typename T, int NB, int KS, int AUX, bool DUAL>
 __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int cs) {
     typedef typename Mma<T>::Vec Vec;
     constexpr int V = Elem<T>::VEC;
     typedef typename RawOf<T, V>::type Raw;
+    constexpr bool RES = AUX == 1, ACC = AUX == 2;
     constexpr int COLS = NB * 32;
     constexpr int GK = 4;                                      // K-steps whose gathers are in flight together
     constexpr int NP = kWsProducers;
@@ -296,7 +299,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         const bool stateful = e.act != DCNN_ACT_NONE;
         const __amdgpu_buffer_rsrc_t rs_xA = ws_rsrc(e.xA, out_bytes), rs_xT = ws_rsrc(e.xT, out_bytes);
         const __amdgpu_buffer_rsrc_t rs_out = ws_rsrc(e.out_data, out_bytes);
-        const __amdgpu_buffer_rsrc_t rs_res = ws_rsrc(e.res_data, out_bytes);
+        const __amdgpu_buffer_rsrc_t rs_res = ws_rsrc(ACC ? e.accum_O : e.res_data, out_bytes);   // the third stream
         const __amdgpu_buffer_rsrc_t rs_rmask = ws_rsrc(e.res_mask, out_pixels);
         const __amdgpu_buffer_rsrc_t rs_omask = ws_rsrc(e.out_mask, out_pixels);
         const bool has_rmask = e.res_mask != nullptr;
@@ -323,13 +326,14 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 }
             }
         };
-        struct Set { Raw ra[H], rt[H], rr[RES ? H : 1]; };
+        struct Set { Raw ra[H], rt[H], rr[AUX ? H : 1]; };
         // loads that do not depend on the convolution result, for the H iterations of set s
         auto load_set = [&](auto sf, const Tile& t, int s, Set& st) {
 #pragma unroll
             for (int h = 0; h < H; ++h) {
                 const uint32_t o = t.off[s * H + h];
                 if constexpr (RES) st.rr[h] = ws_load16<Raw>(rs_res, t.rflag[s * H + h] ? o : kOob);
+                if constexpr (ACC) st.rr[h] = ws_load16<Raw>(rs_res, o);   // O, read before the decision is known
                 if constexpr (decltype(sf)::value) {
                     st.ra[h] = ws_load16<Raw>(rs_xA, o);
                     st.rt[h] = ws_load16<Raw>(rs_xT, o);
@@ -374,7 +378,15 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     const uint32_t o_upd = upd ? o : kOob;
                     ws_store16<Raw>(rs_xA, o_upd, o_a);
                     ws_store16<Raw>(rs_xT, o, upd ? raw_zero<T, V>() : o_t);
-                    ws_store16<Raw>(rs_out, o_upd, o_y);
+                    if constexpr (ACC) {
+                        // final layer: the emitted (rounded) delta goes straight into the dense output
+                        Raw o_O;
+#pragma unroll
+                        for (int i = 0; i < V; ++i) raw_set<T, V>(o_O, i, raw_get<T, V>(st.rr[h], i) + raw_get<T, V>(o_y, i));
+                        ws_store16<Raw>(rs_res, o_upd, o_O);
+                    } else {
+                        ws_store16<Raw>(rs_out, o_upd, o_y);
+                    }
                 } else {
                     ws_store16<Raw>(rs_out, o, d);
                 }

@@ -19,6 +19,7 @@ struct dcnn_layer {
     // pieces of the caller-provided state memory
     void* buf0; size_t buf0_bytes;      // x^A | stored input frame | dense output
     void* buf1; size_t buf1_bytes;      // x^T
+    void* buf2; size_t buf2_bytes;      // dense accumulated output of a layer with fuse_accum
     void* out_data;
     uint8_t* out_mask;
     int32_t* out_idx;

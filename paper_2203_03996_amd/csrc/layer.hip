@@ -75,6 +75,8 @@ static dcnn_status validate_desc(const dcnn_layer_desc& d) {
         if (d.proj_stride < 1 || d.proj_stride > 2 || d.proj_h < 1 || d.proj_w < 1) return DCNN_EINVAL;
         if ((d.proj_h - 1) / d.proj_stride + 1 != oh || (d.proj_w - 1) / d.proj_stride + 1 != ow) return DCNN_ESHAPE;
     }
+    if (d.fuse_accum != 0 && d.fuse_accum != 1) return DCNN_EINVAL;
+    if (d.fuse_accum && (d.kind != DCNN_CONV || d.act == DCNN_ACT_NONE || (d.n_in == 2 && !has_proj(d)))) return DCNN_EINVAL;
     return DCNN_OK;
 }
 
@@ -97,7 +99,7 @@ static void carve(dcnn_layer* L, void* state) {
     const size_t in_map = (size_t)L->in_pixels * d.c * es;
     const size_t out_map = (size_t)L->out_pixels * L->oc * es;
     const bool act = has_act(d), own = own_list(d);
-    L->buf0 = L->buf1 = nullptr; L->buf0_bytes = L->buf1_bytes = 0;
+    L->buf0 = L->buf1 = L->buf2 = nullptr; L->buf0_bytes = L->buf1_bytes = L->buf2_bytes = 0;
     L->out_data = nullptr; L->out_mask = nullptr; L->out_idx = nullptr; L->out_count = nullptr;
     L->list = nullptr; L->list_count = nullptr; L->taps = nullptr; L->wpacked = nullptr; L->bias = nullptr;
     L->wpacked2 = nullptr; L->wpacked2_dense = nullptr; L->bias2 = nullptr;
@@ -113,6 +115,7 @@ static void carve(dcnn_layer* L, void* state) {
                 L->buf0 = cv.take(out_map); L->buf0_bytes = out_map;
                 L->buf1 = cv.take(out_map); L->buf1_bytes = out_map;
             }
+            if (d.fuse_accum) { L->buf2 = cv.take(out_map); L->buf2_bytes = out_map; }
             break;
         case DCNN_MAXPOOL:
             L->buf0 = cv.take(in_map); L->buf0_bytes = in_map;
@@ -277,6 +280,12 @@ dcnn_status layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const void*
             if (st == DCNN_OK && proj_bias_dev) st = launch_copy(ctx, L->bias2, proj_bias_dev, (size_t)L->oc * es);
             L->has_bias2 = proj_bias_dev != nullptr;
         }
+        if (st == DCNN_OK && desc->fuse_accum &&
+            !conv_ws_supported(ctx, desc->dtype, desc->kh, desc->c, L->oc, L->in_pixels * desc->c, L->out_pixels * L->oc)) {
+            delete L;
+            return fail(ctx, DCNN_EUNSUPPORTED, "layer_create: conv %dx%d %d->%d with a fused final accumulation is not covered",
+                        desc->kh, desc->kh, desc->c, L->oc);
+        }
         if (st != DCNN_OK) { delete L; return st; }
         L->has_bias = bias_dev != nullptr;
     }
@@ -385,6 +394,7 @@ dcnn_status dcnn_layer_init(dcnn_layer* L, const void* const* dense_in, int32_t 
             e.res_data = d.n_in == 2 ? (has_proj(d) ? dense_out : dense_in[1]) : nullptr; e.res_mask = nullptr;
             e.xA = L->buf0; e.xT = L->buf1; e.out_data = dense_out; e.out_mask = nullptr; e.surv = nullptr;
             st = launch_conv(ctx, d.dtype, true, full_list(L->out_pixels), c, e);
+            if (st == DCNN_OK && d.fuse_accum) st = launch_copy(ctx, L->buf2, dense_out, L->buf2_bytes);
             break;
         }
         case DCNN_ACT: {
@@ -449,7 +459,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
     // the output view (aliases are refreshed every step)
     dcnn_delta& v = L->view;
     v.n = d.n; v.h = L->oh; v.w = L->ow; v.c = L->oc; v.dtype = d.dtype;
-    v.data = L->out_data;
+    v.data = d.fuse_accum ? L->buf2 : L->out_data;
     v.mask = L->alias_mask ? in[0]->mask : L->out_mask;
     v.idx = L->alias_mask ? in[0]->idx : L->out_idx;
     v.count = L->alias_mask ? in[0]->count : L->out_count;
@@ -521,6 +531,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
                 e.res_data = nullptr; e.res_mask = nullptr;
             }
             e.xA = L->buf0; e.xT = L->buf1; e.out_data = L->out_data;
+            e.accum_O = d.fuse_accum ? L->buf2 : nullptr;
             e.out_mask = act ? L->out_mask : nullptr;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;
             e.out_count = (act && !d.want_idx) ? L->out_count : nullptr;
@@ -581,7 +592,7 @@ dcnn_status dcnn_layer_output(const dcnn_layer* L, dcnn_delta* out_view) {
         // before the first step: an empty update
         dcnn_delta v{};
         v.n = L->d.n; v.h = L->oh; v.w = L->ow; v.c = L->oc; v.dtype = L->d.dtype;
-        v.data = L->d.kind == DCNN_ACCUM ? L->buf0 : L->out_data;
+        v.data = L->d.kind == DCNN_ACCUM ? L->buf0 : (L->d.fuse_accum ? L->buf2 : L->out_data);
         v.mask = L->out_mask; v.idx = L->out_idx; v.count = L->out_count;
         *out_view = v;
         return DCNN_OK;
@@ -594,6 +605,7 @@ dcnn_status dcnn_layer_state(const dcnn_layer* L, int32_t which, void** ptr_dev,
     if (!L || !ptr_dev || !bytes) return DCNN_EINVAL;
     if (which == 0 && L->buf0) { *ptr_dev = L->buf0; *bytes = L->buf0_bytes; return DCNN_OK; }
     if (which == 1 && L->buf1) { *ptr_dev = L->buf1; *bytes = L->buf1_bytes; return DCNN_OK; }
+    if (which == 2 && L->buf2) { *ptr_dev = L->buf2; *bytes = L->buf2_bytes; return DCNN_OK; }
     return fail(L->ctx, DCNN_EINVAL, "layer_state: the layer has no buffer %d", which);
 }
 
@@ -620,7 +632,7 @@ dcnn_status dcnn_layer_stats(dcnn_layer* L, dcnn_stats* s) {
     s->kind = L->d.kind; s->act = L->d.act; s->n_in = L->d.n_in;
     s->c_in = L->d.c; s->c_out = L->oc;
     const bool window = L->d.kind == DCNN_CONV || L->d.kind == DCNN_DWCONV || L->d.kind == DCNN_MAXPOOL;
-    s->k = window ? L->d.kh : 1; s->stride = window ? L->d.stride : 1; s->proj_c = L->d.proj_c;
+    s->k = window ? L->d.kh : 1; s->stride = window ? L->d.stride : 1; s->proj_c = L->d.proj_c; s->fuse_accum = L->d.fuse_accum; s->reserved = 0;
     return st;
 }
 

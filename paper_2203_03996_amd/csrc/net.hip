@@ -195,7 +195,24 @@ dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t fuse, size_t* arena_bytes) 
     // run layers in the order of the node whose output they produce (inputs always come earlier)
     for (size_t a = 1; a < net->plan.size(); ++a)
         for (size_t b = a; b > 0 && net->plan[b].out_node < net->plan[b - 1].out_node; --b) std::swap(net->plan[b], net->plan[b - 1]);
+    int folded_accum = -1;
+    // The output layer behind a convolution + activation that nothing else reads is folded into it: the
+    // emitted deltas go straight into the dense output instead of through memory.
+    if ((fuse & 1) && net->plan.size() >= 2 && net->plan.back().d.kind == DCNN_ACCUM) {
+        Planned& last = net->plan[net->plan.size() - 2];
+        const Planned& acc = net->plan.back();
+        const dcnn_layer_desc& d = last.d;
+        const Node& on = net->nodes[last.out_node];
+        if (acc.in_nodes.size() == 1 && acc.in_nodes[0] == last.out_node && on.consumers.size() == 1 &&
+            d.kind == DCNN_CONV && d.act != DCNN_ACT_NONE && (d.n_in == 1 || d.proj_c > 0) &&
+            conv_ws_supported(ctx, d.dtype, d.kh, d.c, on.oc, (int64_t)d.n * d.h * d.w * d.c, (int64_t)d.n * on.oh * on.ow * on.oc)) {
+            last.d.fuse_accum = 1;
+            folded_accum = acc.out_node;
+            net->plan.pop_back();
+        }
+    }
     for (size_t a = 0; a < net->plan.size(); ++a) net->layer_of_node[net->plan[a].out_node] = (int)a;
+    if (folded_accum >= 0) net->layer_of_node[folded_accum] = (int)net->plan.size() - 1;
     // every sparse input must be the output of a planned layer
     for (auto& p : net->plan)
         for (int in : p.in_nodes)
@@ -261,6 +278,7 @@ dcnn_status dcnn_net_init(dcnn_net* net, const void* frame_dev, void* out_dev) {
         }
         void* dense_out = p.d.kind == DCNN_ACCUM ? out_dev : p.layer->out_data;
         dcnn_status st = dcnn_layer_init(p.layer, ins, n_in, dense_out);
+        if (st == DCNN_OK && p.d.fuse_accum && out_dev) st = launch_copy(ctx, out_dev, p.layer->buf2, p.layer->buf2_bytes);
         if (st != DCNN_OK) return st;
     }
     net->inited = true;
@@ -295,6 +313,7 @@ dcnn_status dcnn_net_step(dcnn_net* net, const void* frame_dev, void* out_dev) {
     }
     if (out_dev) {
         dcnn_layer* last = net->plan.back().layer;
+        if (last->d.fuse_accum) return launch_copy(ctx, out_dev, last->buf2, last->buf2_bytes);
         return launch_copy(ctx, out_dev, last->buf0, last->buf0_bytes);
     }
     return DCNN_OK;

@@ -338,6 +338,69 @@ def test_conv_fused_projection(S, k, cin, cin2, cout, nhw, stride2):
     assert ties <= 3
 
 
+@pytest.mark.parametrize("S,k,cin,cout,nhw,proj", [
+    ("f16", 1, 64, 256, (2, 24, 40), True),
+    ("f16", 3, 32, 64, (1, 33, 35), False),
+    ("f32", 1, 16, 32, (1, 20, 21), False),
+    ("f32", 3, 16, 32, (1, 17, 21), True),
+])
+def test_conv_fused_accumulate(S, k, cin, cout, nhw, proj):
+    """The network's output layer folded into the last convolution + activation: the layer keeps the dense
+    accumulated output O and adds every emitted delta to it == oracle conv (, conv, add), act, accumulate."""
+    rng = np.random.default_rng(11 * k + cin + cout + int(proj))
+    n, h, w = nhw
+    cin2 = 16
+    eps = 0.3
+    wa = (rng.normal(0, 1, (k, k, cin, cout)) * np.sqrt(2.0 / (k * k * cin))).astype(NP_DTYPE[S])
+    wb = (rng.normal(0, 1, (1, 1, cin2, cout)) * np.sqrt(2.0 / cin2)).astype(NP_DTYPE[S])
+    ba = rng.normal(0, 0.1, cout).astype(NP_DTYPE[S])
+    bb = rng.normal(0, 0.1, cout).astype(NP_DTYPE[S])
+    ra, rb = orc.Conv(wa, ba, 1, k // 2, False, S), orc.Conv(wb, bb, 1, 0, False, S)
+    radd, ract, racc = orc.Add(S), orc.ActTrunc("relu", eps, S), orc.Accumulate(S)
+    ctx = pkg.Context(n * h * w)
+    desc = pkg.make_desc(pkg.CONV, DT[S], n, h, w, cin, k=k, stride=1, pad=k // 2, cout=cout, act=pkg.ACT_RELU, eps=eps,
+                         n_in=2 if proj else 1, proj=(cin2, h, w, 1) if proj else None, fuse_accum=1, want_idx=0)
+    wcat = np.concatenate([wa.ravel(), wb.ravel()]) if proj else wa
+    bcat = np.concatenate([ba, bb]) if proj else ba
+    layer = pkg.Layer(ctx, desc, torch.from_numpy(wcat).cuda(), torch.from_numpy(bcat).cuda())
+    x0 = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
+    z0 = rng.normal(0, 1, (n, h, w, cin2)).astype(NP_DTYPE[S])
+    y0 = ra.init(x0)
+    if proj:
+        y0 = radd.init(y0, rb.init(z0))
+    r0 = racc.init(ract.init(y0))
+    g0 = layer.init([torch.from_numpy(x0).cuda()] + ([torch.from_numpy(z0).cuda()] if proj else []))
+    ctx.sync()
+    assert rel_err(to_np(g0), r0) <= TOL[S]
+    assert np.array_equal(to_np(layer.state_tensor(2)), to_np(g0)), "O starts as the dense first output"
+    for t, dens in enumerate([0.05, 0.3, 1.0, 0.0, 0.1]):
+        layer.state_tensor(0).copy_(torch.from_numpy(ract.xA).cuda())
+        layer.state_tensor(1).copy_(torch.from_numpy(ract.xT).cuda())
+        layer.state_tensor(2).copy_(torch.from_numpy(racc.O).cuda())
+        d = _rand_delta(rng, (n, h, w, cin), dens, S, 0.5)
+        mid = ra.step(d).poisoned()
+        ins = [_upload(d)]
+        if proj:
+            z = _rand_delta(rng, (n, h, w, cin2), dens / 2, S, 0.5)
+            mid = radd.step(mid, rb.step(z).poisoned()).poisoned()
+            ins.append(_upload(z))
+        o_before = racc.O.copy()
+        want = ract.step(mid).poisoned()
+        o_ref = racc.step(want)
+        out = layer.step(ins)
+        ctx.sync()
+        gm = to_np(out.mask)
+        near = np.abs(np.nan_to_num(ract.last_u, nan=np.inf) - eps) <= TOL[S] * eps
+        assert np.all(near[gm != want.mask]), f"frame {t}: mask mismatch away from a threshold tie"
+        agree = gm == want.mask
+        got_o = to_np(layer.state_tensor(2)).reshape(o_ref.shape)
+        assert not np.isnan(got_o.astype(np.float64)).any()
+        assert rel_err(got_o[agree], o_ref[agree]) <= TOL[S], f"frame {t}: accumulated output"
+        untouched = want.mask == 0
+        assert np.array_equal(got_o[untouched & agree], o_before[untouched & agree]), "O changes only where a delta was emitted"
+        assert out.data.data_ptr() == layer.state_tensor(2).data_ptr(), "the layer's output data is O"
+
+
 @pytest.mark.parametrize("S", ["f32", "f16"])
 @pytest.mark.parametrize("stride,c", [(1, 32), (2, 192), (1, 960), (2, 20)])
 def test_depthwise(S, stride, c):
