@@ -202,3 +202,40 @@ def test_run_to_run_determinism():
         ctx.sync()
         outs.append(out.clone())
     assert torch.equal(outs[0], outs[1])
+
+
+def test_config2_bench_configuration_sampled_streams():
+    """The launch configuration bench.py times: 64 independent streams of BASELINE config 2 at full
+    size through the fused plan.  Streams do not interact, so sampled streams must match a
+    single-stream oracle run fed that stream's frames; masks, states and the dense output of every
+    stream must also equal what the same library computes for that stream alone."""
+    spec = wl.bottleneck_block(eps=0.0443)
+    S, seed, B, T = spec["dtype"], wl.CONFIG_SEEDS[2], 64, 4
+    wts = wl.make_weights(spec, seed)
+    vid = wl.make_batch(spec["video"], seed, B)[:T].astype(NP_DTYPE[S])        # [T, B, H, W, C]
+    ctx = pkg.Context(B * 128 * 128)
+    net = pkg.Net(ctx, spec, wts, B, 1)
+    out = torch.empty((B, 128, 128, 256), dtype=torch.float16, device="cuda")
+    sampled = [0, 37, 63]
+    oracles = {b: orc.OracleNet(spec, wts, S) for b in sampled}
+    solo_ctx = pkg.Context(128 * 128)
+    solo = {b: pkg.Net(solo_ctx, spec, wts, 1, 1) for b in (5, 63)}
+    solo_out = torch.empty((1, 128, 128, 256), dtype=torch.float16, device="cuda")
+    tol = TOL[S] * 1.0
+    for t in range(T):
+        frame = torch.from_numpy(vid[t]).cuda()
+        (net.init if t == 0 else net.step)(frame, out)
+        ctx.sync()
+        got = to_np(out)
+        assert not np.isnan(got.astype(np.float64)).any()
+        for b in sampled:
+            ref = oracles[b].frame(vid[t, b:b + 1])
+            assert rel_err(got[b:b + 1], ref) <= tol, f"frame {t} stream {b}: dense output vs oracle"
+        for b, sn in solo.items():
+            (sn.init if t == 0 else sn.step)(frame[b:b + 1].contiguous(), solo_out)
+            solo_ctx.sync()
+            assert np.array_equal(to_np(solo_out)[0], got[b]), f"frame {t} stream {b}: batched run differs from the stream alone"
+        if t > 0:
+            st = net.stats()
+            total = sum(s["pixels_work"] for s in st)
+            assert total > 0 and all(s["pixels_out"] <= s["pixels_work"] <= s["pixels_total"] for s in st if s["kind"] != pkg.DELTAGEN)
