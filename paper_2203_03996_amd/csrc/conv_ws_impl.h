@@ -76,7 +76,9 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
     typedef typename RawOf<T, V>::type Raw;
     constexpr bool RES = AUX == 1, ACC = AUX == 2;
     constexpr int COLS = NB * 32;
-    constexpr int GK = 4;                                      // K-steps whose gathers are in flight together
+    constexpr int GK = 4;                                      // K-steps gathered together (one register set)
+    constexpr int NSETS = 2;                                   // register sets: NSETS-1 groups in flight behind the current one
+                                                               // (finer groups and deeper rings were measured slower)
     constexpr int NP = kWsProducers;
     constexpr int ES = (int)sizeof(T);
     static_assert(sizeof(Vec) == 16 && sizeof(Raw) == 16, "16-byte channel vectors");
@@ -242,7 +244,8 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                         }
                     }
                     const int steps = proj ? c.kch2 : kch;
-                    const Vec* wtap = proj ? wbase2 : wbase + (size_t)(cu.t * kch) * 2 * COLS;
+                    const int tap = cu.t == kNoTap ? 0 : cu.t;     // past the end of the sequence: any valid row (it meets zeros)
+                    const Vec* wtap = proj ? wbase2 : wbase + (size_t)(tap * kch) * 2 * COLS;
                     Vec wv[2][NB];
                     auto request = [&](int u) {
                         const int kc = cu.kg * GK + u;
@@ -260,16 +263,20 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 };
-                Vec xa[GK], xb[GK];
-                Cursor cg{wave_taps, first_tap(wave_taps), 0};     // gathers run one group ahead of the matrix work
+                // Ring of NSETS register sets: the gathers of group s+NSETS-1 are issued right before group
+                // s is multiplied.  The loop body is straight-line code (groups past the end of the
+                // sequence multiply zeros), so every wait counts exactly the loads issued after it.
+                Vec x[NSETS][GK];
+                Cursor cg{wave_taps, first_tap(wave_taps), 0};     // gathers run ahead of the matrix work
                 Cursor cm = cg;
-                gather_group(cg, xa); advance(cg);
+#pragma unroll
+                for (int i = 0; i < NSETS - 1; ++i) { gather_group(cg, x[i]); advance(cg); }
                 while (cm.t != kNoTap) {
-                    gather_group(cg, xb); advance(cg);
-                    mma_group(cm, xa); advance(cm);
-                    if (cm.t == kNoTap) break;
-                    gather_group(cg, xa); advance(cg);
-                    mma_group(cm, xb); advance(cm);
+#pragma unroll
+                    for (int i = 0; i < NSETS; ++i) {
+                        gather_group(cg, x[(i + NSETS - 1) % NSETS]); advance(cg);
+                        mma_group(cm, x[i]); advance(cm);
+                    }
                 }
                 if (main_staged) stage_accumulators<T, NB, true>(acc, tile_row, g);
                 else stage_accumulators<T, NB, false>(acc, tile_row, g);
