@@ -56,6 +56,7 @@ struct Workspace {
     int32_t* chunk_counts;   // one per kChunk pixels
     uint32_t* surv;          // one survivor word per kTile list entries
     uint8_t* scratch_mask;   // mask of a pass whose caller only wants the list
+    uint8_t* scratch_mask2;  // second intermediate mask (separable dilation of the input mask)
     int64_t max_pixels;
 };
 size_t workspace_bytes(int64_t max_pixels);
@@ -75,6 +76,7 @@ struct MaskPassArgs {
     uint32_t* taps_out;          // optional [n*oh*ow]: per list entry, which window taps are flagged (k*k <= 25 bits);
                                  // bit 30: the entry's pixel is flagged in mask_b
     int b_stride, b_h, b_w;      // b_stride > 0: mask_b is [n,b_h,b_w] and output pixel (y,x) looks at (y,x)*b_stride
+    int kw, pad_w;               // kw > 0: the window is k rows x kw columns with padding pad / pad_w (stride 1)
 };
 dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& a);
 

@@ -23,7 +23,7 @@ dcnn_status check_hip(dcnn_ctx* ctx, hipError_t e, const char* what) {
 size_t workspace_bytes(int64_t max_pixels) {
     if (max_pixels < 1) max_pixels = 1;
     return align_up((size_t)cdiv(max_pixels, kChunk) * sizeof(int32_t)) +
-           align_up((size_t)cdiv(max_pixels, kTile) * sizeof(uint32_t)) + align_up((size_t)max_pixels) + kAlign;
+           align_up((size_t)cdiv(max_pixels, kTile) * sizeof(uint32_t)) + 2 * align_up((size_t)max_pixels) + kAlign;
 }
 
 dcnn_status workspace_view(dcnn_ctx* ctx, int64_t pixels, Workspace* out) {
@@ -37,6 +37,7 @@ dcnn_status workspace_view(dcnn_ctx* ctx, int64_t pixels, Workspace* out) {
     out->chunk_counts = reinterpret_cast<int32_t*>(p);
     out->surv = reinterpret_cast<uint32_t*>(p + a);
     out->scratch_mask = reinterpret_cast<uint8_t*>(p + a + b);
+    out->scratch_mask2 = out->scratch_mask + align_up((size_t)pixels);
     out->max_pixels = pixels;
     return DCNN_OK;
 }

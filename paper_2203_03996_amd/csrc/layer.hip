@@ -289,9 +289,9 @@ dcnn_status layer_create(dcnn_ctx* ctx, const dcnn_layer_desc* desc, const void*
         if (st != DCNN_OK) { delete L; return st; }
         L->has_bias = bias_dev != nullptr;
     }
-    if (desc->kind == DCNN_DELTAGEN && desc->dilate_r != 0) {
+    if (desc->kind == DCNN_DELTAGEN && (desc->dilate_r < 0 || desc->dilate_r > 15)) {
         delete L;
-        return fail(ctx, DCNN_EUNSUPPORTED, "layer_create: input-mask dilation is not implemented");
+        return fail(ctx, DCNN_EINVAL, "layer_create: input-mask dilation radius %d out of range (0..15)", desc->dilate_r);
     }
     st = clear_sparse_output(L);
     if (st == DCNN_OK) st = launch_fill_i32(ctx, L->counters, 0, kAlign / sizeof(int32_t));

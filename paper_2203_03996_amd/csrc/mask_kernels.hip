@@ -91,6 +91,7 @@ struct MaskKernelArgs {
     int64_t out_pixels;
     int n, h, w, oh, ow, k, stride, pad, up;
     int b_stride, b_h, b_w;       // > 0: mask_b is sampled at (y, x) * b_stride of an [n, b_h, b_w] map
+    int kw, pad_w;                // window columns and their padding (rows: k, pad)
 };
 
 __global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs a) {
@@ -100,10 +101,11 @@ __global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs 
     int cnt = 0;
     if (p0 < a.out_pixels) {
         const bool b_same = a.mask_b == nullptr || a.b_stride <= 0;
-        if (a.k == 1 && a.stride == 1 && a.up == 1 && b_same && p0 + kPxPerThread <= a.out_pixels) {
+        const bool square = a.kw == a.k && a.pad_w == a.pad;
+        if (square && a.k == 1 && a.stride == 1 && a.up == 1 && b_same && p0 + kPxPerThread <= a.out_pixels) {
             word = *reinterpret_cast<const uint64_t*>(a.mask_in + p0);
             if (a.mask_b) word |= *reinterpret_cast<const uint64_t*>(a.mask_b + p0);
-        } else if (b_same && window3_fast(a.k, a.stride, a.pad, a.up, a.h, a.w, a.oh, a.ow)) {
+        } else if (square && b_same && window3_fast(a.k, a.stride, a.pad, a.up, a.h, a.w, a.oh, a.ow)) {
             const int x0 = (int)(p0 % a.w);
             const int64_t t = p0 / a.w;
             const int y = (int)(t % a.h);
@@ -127,8 +129,8 @@ __global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs 
                         const int iy = oy * a.stride - a.pad + ky;
                         if (iy < 0 || iy >= a.h) continue;
                         const uint8_t* row = a.mask_in + (n * a.h + iy) * a.w;
-                        for (int kx = 0; kx < a.k; ++kx) {
-                            const int ix = ox * a.stride - a.pad + kx;
+                        for (int kx = 0; kx < a.kw; ++kx) {
+                            const int ix = ox * a.stride - a.pad_w + kx;
                             if (ix >= 0 && ix < a.w) f |= row[ix];
                         }
                     }
@@ -251,6 +253,7 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
         a.k = m.k; a.stride = m.stride; a.pad = m.pad;
         a.up = m.up > 1 ? m.up : 1;
         a.b_stride = m.b_stride; a.b_h = m.b_h; a.b_w = m.b_w;
+        a.kw = m.kw > 0 ? m.kw : m.k; a.pad_w = m.kw > 0 ? m.pad_w : m.pad;
         hipLaunchKernelGGL(mask_pass_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, a);
         st = check_hip(ctx, hipGetLastError(), "mask_pass_kernel launch");
         if (st != DCNN_OK) return st;
@@ -258,7 +261,7 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
     }
     if (m.idx_out == nullptr) return DCNN_OK;
     EmitArgs e{emit_mask, ws.chunk_counts, m.idx_out, m.count_out, out_pixels};
-    e.tap_mask = m.mask_in; e.taps_out = (m.emit_only || m.up > 1 || m.k * m.k > 25) ? nullptr : m.taps_out;
+    e.tap_mask = m.mask_in; e.taps_out = (m.emit_only || m.up > 1 || m.k * m.k > 25 || m.kw > 0) ? nullptr : m.taps_out;
     e.h = m.h; e.w = m.w; e.oh = m.oh; e.ow = m.ow; e.k = m.k; e.stride = m.stride; e.pad = m.pad;
     e.mask_b = m.mask_b; e.b_stride = m.b_stride; e.b_h = m.b_h; e.b_w = m.b_w;
     hipLaunchKernelGGL(emit_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, e);

@@ -162,6 +162,8 @@ dcnn_status launch_dwconv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l
 // ---- input delta generation (dense pass over the frame) ---------------------------------------
 // Per pixel: d = frame - P (P = value last propagated); flagged iff max_c |d_c| >= eps;
 // flagged: delta <- d, P <- frame.  Writes the whole mask and one count per chunk of pixels.
+// With out_data == nullptr only the mask is written (the flags are dilated before anything is
+// propagated, Section 4; deltagen_apply_kernel then serves the dilated list).
 constexpr int kDeltaGenThreads = 1024;                       // 16 waves per chunk of pixels: enough loads in flight per compute unit
 template <typename T, int V, int VPL>
 __global__ __launch_bounds__(kDeltaGenThreads) void deltagen_kernel(DeltaGenArgs a, int32_t* chunk_counts) {
@@ -217,7 +219,7 @@ __global__ __launch_bounds__(kDeltaGenThreads) void deltagen_kernel(DeltaGenArgs
             }
             for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
             const bool flag = valid && (u >= a.eps);
-            if (flag) {
+            if (flag && out != nullptr) {
 #pragma unroll
                 for (int v = 0; v < VPL; ++v) {
                     const int vi = sub + v * LP;
@@ -236,6 +238,30 @@ __global__ __launch_bounds__(kDeltaGenThreads) void deltagen_kernel(DeltaGenArgs
     if (mine) atomicAdd(&s_count, mine);
     __syncthreads();
     if (threadIdx.x == 0) chunk_counts[blockIdx.x] = s_count;
+}
+
+// Delta generation for a given list of pixels (the dilated input mask): delta <- frame - P, P <- frame.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void deltagen_apply_kernel(ListArgs l, DeltaGenArgs a) {
+    const int64_t count = list_count(l);
+    const int C = a.c;
+    const int nvec = (C + V - 1) / V;
+    const T* frame = static_cast<const T*>(a.frame);
+    T* P = static_cast<T*>(a.P);
+    T* out = static_cast<T*>(a.out_data);
+    const int64_t total = count * nvec;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t j = i / nvec;
+        const int vi = (int)(i - j * nvec);
+        const int64_t p = l.list ? (int64_t)l.list[j] : j;
+        float f[V], q[V], d[V];
+        load_vec<T, V>(frame + p * C + vi * V, f);
+        load_vec<T, V>(P + p * C + vi * V, q);
+#pragma unroll
+        for (int k = 0; k < V; ++k) d[k] = f[k] - q[k];
+        store_vec<T, V>(out + p * C + vi * V, d);
+        store_vec<T, V>(P + p * C + vi * V, f);
+    }
 }
 
 // ---- final accumulation, max pooling, upsampling ----------------------------------------------
@@ -402,11 +428,14 @@ dcnn_status launch_upsample(dcnn_ctx* ctx, int dtype, const ListArgs& l, const U
     return check_hip(ctx, hipGetLastError(), "upsample_kernel launch");
 }
 
-dcnn_status launch_deltagen(dcnn_ctx* ctx, int dtype, const DeltaGenArgs& a) {
-    if (a.dilate_r != 0) return fail(ctx, DCNN_EUNSUPPORTED, "input-mask dilation is not implemented");
+dcnn_status launch_deltagen(dcnn_ctx* ctx, int dtype, const DeltaGenArgs& a_in) {
+    if (a_in.dilate_r < 0 || a_in.dilate_r > 15) return fail(ctx, DCNN_EINVAL, "input-mask dilation radius %d out of range", a_in.dilate_r);
     Workspace ws;
-    dcnn_status st = workspace_view(ctx, a.pixels, &ws);
+    dcnn_status st = workspace_view(ctx, a_in.pixels, &ws);
     if (st != DCNN_OK) return st;
+    // With a dilation the first pass only flags (into scratch), nothing is propagated yet.
+    DeltaGenArgs a = a_in;
+    if (a.dilate_r > 0) { a.out_data = nullptr; a.out_mask = ws.scratch_mask; }
     const int nchunks = (int)cdiv(a.pixels, kChunk);
     dim3 g(nchunks), b(kDeltaGenThreads);
 #define DCNN_DG_LAUNCH(T, V, VPL) hipLaunchKernelGGL((deltagen_kernel<T, V, VPL>), g, b, 0, ctx->stream, a, ws.chunk_counts)
@@ -427,6 +456,26 @@ dcnn_status launch_deltagen(dcnn_ctx* ctx, int dtype, const DeltaGenArgs& a) {
 #undef DCNN_DG_LAUNCH
     st = check_hip(ctx, hipGetLastError(), "deltagen_kernel launch");
     if (st != DCNN_OK) return st;
+    if (a.dilate_r > 0) {
+        // square dilation as a row pass and a column pass (Section 4: the input mask is dilated so that
+        // small changes next to changed pixels are propagated with them), then the list-driven update
+        const int k = 2 * a.dilate_r + 1;
+        MaskPassArgs h{};
+        h.mask_in = ws.scratch_mask; h.mask_out = ws.scratch_mask2; h.idx_out = nullptr;
+        h.n = a.n; h.h = a.h; h.w = a.w; h.oh = a.h; h.ow = a.w; h.stride = 1; h.up = 1;
+        h.k = 1; h.pad = 0; h.kw = k; h.pad_w = a.dilate_r;
+        st = launch_mask_compact(ctx, h);
+        if (st != DCNN_OK) return st;
+        MaskPassArgs v = h;
+        v.mask_in = ws.scratch_mask2; v.mask_out = a_in.out_mask; v.idx_out = a_in.out_idx; v.count_out = a_in.out_count;
+        v.k = k; v.pad = a.dilate_r; v.kw = 1; v.pad_w = 0;
+        st = launch_mask_compact(ctx, v);
+        if (st != DCNN_OK) return st;
+        ListArgs l{};
+        l.list = a_in.out_idx; l.count = a_in.out_count; l.max_count = a_in.pixels;
+        DCNN_FLAT_DISPATCH(deltagen_apply_kernel, a_in.c, l.max_count, l, a_in);
+        return check_hip(ctx, hipGetLastError(), "deltagen_apply_kernel launch");
+    }
     // ordered emission of the flagged pixels from the mask just written and the chunk counts
     MaskPassArgs m{};
     m.mask_in = a.out_mask;

@@ -58,13 +58,16 @@ def test_mask_union():
 
 # ---- input delta generation (bit-exact) ---------------------------------------------------------
 @pytest.mark.parametrize("S", ["f32", "f16"])
-@pytest.mark.parametrize("shape", [(1, 64, 64, 32), (2, 45, 31, 64), (1, 40, 56, 3), (1, 9, 9, 17), (1, 16, 16, 1024)])
-def test_deltagen(S, shape):
-    rng = np.random.default_rng(sum(shape))
+@pytest.mark.parametrize("shape,r", [((1, 64, 64, 32), 0), ((2, 45, 31, 64), 0), ((1, 40, 56, 3), 0), ((1, 9, 9, 17), 0),
+                                     ((1, 16, 16, 1024), 0),
+                                     # input-mask dilation by the (2r+1)^2 square (Section 4)
+                                     ((2, 45, 31, 64), 1), ((1, 64, 72, 16), 7), ((1, 9, 9, 17), 3), ((3, 20, 20, 8), 15)])
+def test_deltagen(S, shape, r):
+    rng = np.random.default_rng(sum(shape) + r)
     n, h, w, c = shape
-    ref = orc.DeltaGen(0.3, 0, S)
+    ref = orc.DeltaGen(0.3, r, S)
     ctx = pkg.Context(n * h * w)
-    layer = pkg.Layer(ctx, pkg.make_desc(pkg.DELTAGEN, DT[S], n, h, w, c, eps=0.3))
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.DELTAGEN, DT[S], n, h, w, c, eps=0.3, dilate_r=r))
     f0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
     r0 = ref.init(f0)
     g0 = layer.init([torch.from_numpy(f0).cuda()])
@@ -72,7 +75,7 @@ def test_deltagen(S, shape):
     assert np.array_equal(to_np(g0), r0)
     frame = f0.astype(np.float64)
     for t in range(4):
-        frame = frame + (rng.random((n, h, w, 1)) < 0.2) * rng.normal(0, 0.4, shape)
+        frame = frame + (rng.random((n, h, w, 1)) < (0.2 if r == 0 else 0.02)) * rng.normal(0, 0.4, shape)
         fr = frame.astype(NP_DTYPE[S])
         want = ref.step(fr).poisoned()
         out = layer.step([pkg.Delta(torch.from_numpy(fr).cuda(), None, None, None)])

@@ -121,6 +121,11 @@ def test_config2_batched_streams():
     _run_net(wl.bottleneck_block(eps=0.1, h=64, w=48), wl.CONFIG_SEEDS[2], 3, frames=5)
 
 
+def test_input_mask_dilation_in_a_network():
+    """High input threshold with a dilated input mask (Section 4)."""
+    _run_net(wl.bottleneck_block(eps=0.1, eps0=0.3, h=64, w=48, dilate_r=3), wl.CONFIG_SEEDS[2], 2, frames=5)
+
+
 @pytest.mark.parametrize("S", ["f32", "f16"])
 @pytest.mark.parametrize("flags", [3, 2])
 def test_tiny_mixed_net_all_layer_kinds(S, flags):

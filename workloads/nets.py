@@ -76,12 +76,12 @@ def single_conv_relu(eps=0.05, eps0=None, h=64, w=64, c=32, frames=4, dtype="f32
 
 
 def bottleneck_block(eps=0.05, eps0=None, h=128, w=128, cin=64, mid=64, cout=256, frames=16, dtype="f16",
-                     n_objects=4):
+                     n_objects=4, dilate_r=0):
     """ResNet bottleneck with a projection shortcut: 1x1 cin->mid, 3x3 mid->mid,
     1x1 mid->cout, shortcut 1x1 cin->cout, add, ReLU."""
     eps0 = eps if eps0 is None else eps0
     b = _B()
-    x0 = b.deltagen(eps0)
+    x0 = b.deltagen(eps0, dilate_r)
     x = b.act(b.conv(x0, 1, 1, cin, mid), "relu", eps)
     x = b.act(b.conv(x, 3, 1, mid, mid), "relu", eps)
     x = b.conv(x, 1, 1, mid, cout)
