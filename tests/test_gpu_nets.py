@@ -244,3 +244,30 @@ def test_config2_bench_configuration_sampled_streams():
             st = net.stats()
             total = sum(s["pixels_work"] for s in st)
             assert total > 0 and all(s["pixels_out"] <= s["pixels_work"] <= s["pixels_total"] for s in st if s["kind"] != pkg.DELTAGEN)
+
+
+def test_tensors_beyond_2gib_take_the_plain_kernels():
+    """Buffer addressing limits the wave-specialised convolution to tensors below 2 GiB; a batch whose
+    256-channel maps exceed that must fall back (per layer) and still give, for every sampled stream,
+    exactly what the stream gives alone."""
+    spec = wl.bottleneck_block(eps=0.0443)
+    S, seed, B, T = spec["dtype"], wl.CONFIG_SEEDS[2], 260, 3          # 260 * 128*128*256 * 2 B = 2.18 GB
+    wts = wl.make_weights(spec, seed)
+    base = wl.make_batch(spec["video"], seed, 4)[:T].astype(NP_DTYPE[S])    # 4 distinct streams, tiled
+    ctx = pkg.Context(B * 128 * 128)
+    net = pkg.Net(ctx, spec, wts, B, 1)
+    solo_ctx = pkg.Context(128 * 128)
+    picks = {0: 0, 129: 1, 259: 3}                                    # stream index -> which base stream it shows
+    solo = {b: pkg.Net(solo_ctx, spec, wts, 1, 1) for b in picks}
+    solo_out = torch.empty((1, 128, 128, 256), dtype=torch.float16, device="cuda")
+    layout = np.array([picks.get(b, b % 4) for b in range(B)])
+    for t in range(T):
+        frame = torch.from_numpy(base[t]).cuda()[torch.from_numpy(layout).cuda()].contiguous()
+        (net.init if t == 0 else net.step)(frame)
+        ctx.sync()
+        view = net.output()
+        for b, src in picks.items():
+            sn = solo[b]
+            (sn.init if t == 0 else sn.step)(frame[b:b + 1].contiguous(), solo_out)
+            solo_ctx.sync()
+            assert torch.equal(view.data[b], solo_out[0]), f"frame {t} stream {b}: differs from the stream alone"
