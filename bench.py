@@ -271,6 +271,64 @@ def cpu_baseline(work: Workload, eps: float, budget_s: float = 12.0):
                       f"numpy fp16-storage oracle, {dt:.1f} s", "host_cpus": os.cpu_count()}
 
 
+def tile_ablation(streams: int, steps: int, warmup: int):
+    """Second workload (paper, supplementary tile-size table): ONE 3x3 convolution 128 -> 128 on 256x256
+    maps whose update mask is uniform random (no spatial structure: the case where skipping whole tiles
+    fails), at 0 / 50 / 90 / 99 % sparsity.  Times the layer's sparse step (mask dilation, list emission,
+    gather-GEMM on the flagged pixels) against a dense convolution of the same shape on the same GPU."""
+    import torch.nn.functional as F
+    import paper_2203_03996_amd as pkg
+    n, h, w, c = streams, 256, 256, 128
+    rng = np.random.default_rng(0xDE17A + 99)
+    wgt = (rng.normal(0, 1, (3, 3, c, c)) * np.sqrt(2.0 / (9 * c))).astype(np.float16)
+    ctx = pkg.Context(n * h * w)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.CONV, pkg.F16, n, h, w, c, k=3, stride=1, pad=1, cout=c, want_idx=0),
+                      torch.from_numpy(wgt).cuda(), None)
+    x0 = torch.zeros((n, h, w, c), dtype=torch.float16, device="cuda")
+    layer.init([x0])
+    data = torch.randn((n, h, w, c), dtype=torch.float16, device="cuda")
+    tw = torch.from_numpy(wgt).cuda().permute(3, 2, 0, 1).contiguous(memory_format=torch.channels_last)
+    xd = data.permute(0, 3, 1, 2)                                        # NCHW view of NHWC memory = channels-last
+    rows = []
+    dense_flops = 2.0 * n * h * w * 9 * c * c
+    for sparsity in (0.0, 0.5, 0.9, 0.99):
+        mask = (torch.rand((n, h, w), device="cuda") >= sparsity).to(torch.uint8)
+        flat = torch.nonzero(mask.reshape(-1)).reshape(-1).to(torch.int32)
+        idx = torch.zeros(mask.numel(), dtype=torch.int32, device="cuda")
+        idx[:flat.numel()] = flat
+        delta = pkg.Delta(data, mask, idx, torch.tensor([flat.numel()], dtype=torch.int32, device="cuda"))
+        for _ in range(warmup):
+            layer.step([delta])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            layer.step([delta])
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        st = layer.stats()
+        rows.append({"sparsity": sparsity, "flagged_in": st["pixels_in"] / st["pixels_in_total"],
+                     "flagged_out": st["pixels_work"] / st["pixels_total"], "ms_per_step": ms,
+                     "dense_equiv_gflops": dense_flops / ms / 1e6})
+        log(f"[bench] tile ablation sparsity {sparsity:.2f}: {ms:.3f} ms")
+    for _ in range(warmup):
+        F.conv2d(xd, tw, padding=1)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        F.conv2d(xd, tw, padding=1)
+    e1.record()
+    torch.cuda.synchronize()
+    md = e0.elapsed_time(e1) / steps
+    return {"metric": "ms per 3x3 128->128 convolution step vs uniform-random sparsity", "unit": "ms", "n_gpus": 1,
+            "steps": steps, "warmup": warmup, "higher_is_better": False, "dtype": "f16", "data": "synthetic",
+            "config": {"workload": "tile ablation: 3x3 conv 128->128, 256x256 NHWC fp16, uniform-random update mask",
+                       "streams": streams},
+            "rows": rows, "dense_baseline_ms": md, "dense_baseline_gflops": dense_flops / md / 1e6, "vs_baseline": None}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -281,6 +339,9 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the measurement run one plain 1 GiB device-to-device copy kernel (reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--workload", default="bottleneck", choices=["bottleneck", "tile_ablation"],
+                    help="bottleneck: BASELINE configs[1] (default, the headline); tile_ablation: one 3x3 128->128 "
+                         "convolution under uniform-random sparsity (second workload, 8 streams unless --streams is given)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (streams are independent; see DESIGN.md for how the "
@@ -292,6 +353,9 @@ def main():
     import paper_2203_03996_amd as pkg
     pkg.load_library()
     B, K, W = args.streams, args.steps, args.warmup
+    if args.workload == "tile_ablation":
+        print(json.dumps(tile_ablation(8 if B == 64 else B, min(K, 20), min(W, 5))))
+        return
     work = Workload(B)
     b = 2                                                    # bytes per element (fp16)
 
