@@ -430,6 +430,37 @@ def test_depthwise(S, stride, c):
     assert ties <= 3
 
 
+@pytest.mark.parametrize("S", ["f32", "f16"])
+@pytest.mark.parametrize("k,stride,pad,what", [(1, 1, 0, "batchnorm"), (2, 2, 0, "avgpool"), (3, 2, 1, "avgpool")])
+def test_depthwise_as_batchnorm_and_average_pooling(S, k, stride, pad, what):
+    """The remaining linear per-channel layers are depthwise convolutions: an unfused batch norm is a 1x1
+    depthwise layer (scale on the delta, shift only in the first frame -- Section 3.1: biases enter once),
+    average pooling a k x k depthwise layer with weights 1/k^2 (zero padding counted)."""
+    rng = np.random.default_rng(k * 10 + stride)
+    n, h, w, c = 2, 26, 22, 48
+    if what == "batchnorm":
+        wgt = rng.uniform(0.5, 1.5, (1, 1, c)).astype(NP_DTYPE[S])
+        bias = rng.normal(0, 0.5, c).astype(NP_DTYPE[S])
+    else:
+        wgt = np.full((k, k, c), 1.0 / (k * k)).astype(NP_DTYPE[S])
+        bias = np.zeros(c, NP_DTYPE[S])
+    ref = orc.Conv(wgt, bias, stride, pad, True, S)
+    ctx = pkg.Context(n * h * w)
+    desc = pkg.make_desc(pkg.DWCONV, DT[S], n, h, w, c, k=k, stride=stride, pad=pad, cout=c)
+    layer = pkg.Layer(ctx, desc, torch.from_numpy(wgt).cuda(), torch.from_numpy(bias).cuda())
+    x0 = rng.normal(0, 1, (n, h, w, c)).astype(NP_DTYPE[S])
+    r0 = ref.init(x0)
+    g0 = layer.init([torch.from_numpy(x0).cuda()])
+    ctx.sync()
+    assert rel_err(to_np(g0), r0) <= TOL[S]
+    for t, dens in enumerate([0.1, 0.6, 0.0]):
+        d = _rand_delta(rng, (n, h, w, c), dens, S)
+        want = ref.step(d).poisoned()
+        out = layer.step([_upload(d)])
+        ctx.sync()
+        check_delta(out, want, S, f"{what} frame {t}")
+
+
 # ---- pooling, upsampling, accumulation (bit-exact) -----------------------------------------------
 @pytest.mark.parametrize("S", ["f32", "f16"])
 def test_maxpool(S):

@@ -253,7 +253,9 @@ def test_relu_scalar_example(golden):
 
 # ---- P8: convolution / pooling / upsampling against brute force and a library -----------------
 CONV_CASES = [(3, 1, 1, False), (3, 2, 1, False), (1, 1, 0, False), (1, 2, 0, False), (7, 2, 3, False),
-              (3, 1, 1, True), (3, 2, 1, True), (3, 1, 0, False)]
+              (3, 1, 1, True), (3, 2, 1, True), (3, 1, 0, False),
+              # depthwise 1x1 (an unfused batch-norm scale) and even windows (average pooling as a depthwise layer)
+              (1, 1, 0, True), (2, 2, 0, True), (5, 1, 2, False)]
 
 
 @pytest.mark.parametrize("k,stride,pad,dw", CONV_CASES)
