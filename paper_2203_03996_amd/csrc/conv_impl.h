@@ -1,4 +1,8 @@
-// Sparse delta convolution with dense weights as a gather-GEMM on the matrix cores.
+// Sparse delta convolution with dense weights as a gather-GEMM on the matrix cores: the plain kernel
+// (every wave does gather, MFMA and tail of its tile in turn).  It serves the dense first frame, layers
+// whose weights are streamed, windows other than 1x1 / 3x3 and channel counts that do not fill 16-byte
+// vectors; the sparse steps of everything else run on the wave-specialised kernel (conv_ws_impl.h), which
+// launch_conv_nb below dispatches to.
 //
 // The work list holds the flagged OUTPUT pixels in ascending order.  A tile of 32 consecutive list
 // entries is owned by `cs` wavefronts, each computing nb*32 of the output channels:

@@ -6,7 +6,6 @@
 
 namespace dcnn {
 
-constexpr int kConvWavesMax = 12;                   // waves per workgroup (8 or 12); they share the weights in LDS
 constexpr int kStagePad = 16;                       // bytes added to a staging row against bank conflicts
 constexpr int kGroup = 4;                           // K-steps per streamed weight slice
 constexpr size_t kLdsBytes = 160 * 1024;            // LDS of one gfx950 compute unit; the context refuses less
@@ -108,19 +107,15 @@ inline ConvPlan conv_plan(int dtype, int k, int cin, int cout, bool need_full_ta
             p.kch = (int)cdiv(cin, 2 * kpack);
             p.w_bytes = (size_t)k * k * p.kch * 2 * p.cout_pad * 16;
             p.full_tail = npass == 1;
-            // narrow accumulators leave room for 12 waves per workgroup (168 registers each): more loads
-            // in flight per compute unit; otherwise 8 waves with up to 256 registers
+            // 8 waves per workgroup (up to 256 registers each) share the weights in LDS
             bool placed = false;
-            for (int waves : {8}) {
-                if (waves == 12 && nb > 2) continue;
+            {
+                const int waves = 8;
                 const size_t fixed = conv_stage_bytes(waves, nb, dtype) + conv_xchg_bytes(waves);
                 const size_t slice = (size_t)2 * cs * kGroup * 2 * nb * 32 * 16;   // double-buffered weight slice
-                if (p.w_bytes + fixed <= kLdsBytes) { p.stream = false; p.lds_bytes = p.w_bytes + fixed; }
-                else if (waves == 8 && slice + fixed <= kLdsBytes) { p.stream = true; p.lds_bytes = slice + fixed; }
-                else continue;
+                if (p.w_bytes + fixed <= kLdsBytes) { p.stream = false; p.lds_bytes = p.w_bytes + fixed; placed = true; }
+                else if (slice + fixed <= kLdsBytes) { p.stream = true; p.lds_bytes = slice + fixed; placed = true; }
                 p.waves = waves;
-                placed = true;
-                break;
             }
             if (!placed) continue;
             p.ok = true;
