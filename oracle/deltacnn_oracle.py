@@ -273,6 +273,25 @@ class Add:
         return Delta(s, m)
 
 
+class Concat:
+    """Channel concatenation of two delta streams (Section 3.4 lists it with the other
+    linear, stateless layers): mask is the OR; a stream that is not flagged at a pixel
+    contributes zeros there (its delta is zero by definition)."""
+
+    def __init__(self, S: str = "f32"):
+        self.S = S
+
+    def init(self, a: np.ndarray, b: np.ndarray) -> np.ndarray:
+        return np.concatenate([a, b], axis=-1).astype(_STORE[self.S])
+
+    def step(self, a: Delta, b: Delta) -> Delta:
+        st = _STORE[self.S]
+        m = (a.mask | b.mask).astype(np.uint8)
+        s = np.concatenate([a.zero_filled(), b.zero_filled()], axis=-1).astype(st)
+        s[m == 0] = np.nan
+        return Delta(s, m)
+
+
 class MaxPool:
     """Max pooling on deltas (Section 3.1, Eq. 3 with f = pooling): the layer keeps
     its accumulated dense input x^A; dy = pool(x^A + dx) - pool(x^A); no truncation."""
@@ -347,6 +366,8 @@ def build_layers(net: dict, weights: dict, S: str, use_xT: bool = True):
             layers.append(ActTrunc(nd["f"], nd["eps"], S, use_xT))
         elif k == "add":
             layers.append(Add(S))
+        elif k == "concat":
+            layers.append(Concat(S))
         elif k == "maxpool":
             layers.append(MaxPool(nd["k"], nd["stride"], nd["pad"], S))
         elif k == "upsample":
@@ -416,6 +437,8 @@ def dense_reference(net: dict, weights: dict, x: np.ndarray) -> np.ndarray:
             y = act_fn(nd["f"], ins[0])
         elif k == "add":
             y = ins[0] + ins[1]
+        elif k == "concat":
+            y = np.concatenate([ins[0], ins[1]], axis=-1)
         elif k == "maxpool":
             y = maxpool_dense(ins[0], nd["k"], nd["stride"], nd["pad"])
         elif k == "upsample":

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libdeltacnn.so")
 
 F32, F16 = 0, 1
-DELTAGEN, CONV, DWCONV, ACT, MAXPOOL, UPSAMPLE, ACCUM = range(7)
+DELTAGEN, CONV, DWCONV, ACT, MAXPOOL, UPSAMPLE, ACCUM, CONCAT = range(8)
 ACT_NONE, ACT_RELU, ACT_RELU6 = 0, 1, 2
 ACT_CODES = {"none": ACT_NONE, None: ACT_NONE, "relu": ACT_RELU, "relu6": ACT_RELU6}
 TORCH_DTYPE = {F32: torch.float32, F16: torch.float16}
@@ -331,6 +331,8 @@ class Net:
                 desc = make_desc(ACT, self.dtype, 0, 0, 0, 0, act=ACT_CODES[nd["f"]], eps=nd["eps"], n_in=1)
             elif kind == "add":
                 desc = make_desc(ACT, self.dtype, 0, 0, 0, 0, act=ACT_NONE, n_in=2)
+            elif kind == "concat":
+                desc = make_desc(CONCAT, self.dtype, 0, 0, 0, 0, n_in=2)
             elif kind == "maxpool":
                 desc = make_desc(MAXPOOL, self.dtype, 0, 0, 0, 0, k=nd["k"], stride=nd["stride"], pad=nd["pad"])
             elif kind == "upsample":

@@ -188,6 +188,16 @@ struct PoolArgs {
 dcnn_status launch_maxpool_out(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, const PoolArgs& a);
 dcnn_status launch_maxpool_commit(dcnn_ctx* ctx, int dtype, const ListArgs& l_in, const PoolArgs& a);
 
+struct ConcatArgs {
+    const void* a_data;          // [pixels, ca]
+    const void* b_data;          // [pixels, cb]
+    const uint8_t* a_mask;       // nullptr: dense (first frame)
+    const uint8_t* b_mask;
+    void* out_data;              // [pixels, ca + cb]
+    int ca, cb;
+};
+dcnn_status launch_concat(dcnn_ctx* ctx, int dtype, const ListArgs& l, const ConcatArgs& a);
+
 struct UpsampleArgs {
     const void* in_data;
     void* out_data;

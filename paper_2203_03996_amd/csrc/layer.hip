@@ -19,7 +19,8 @@ static bool own_list(const dcnn_layer_desc& d) {
         case DCNN_DWCONV: return !(d.kh == 1 && d.stride == 1 && d.n_in == 1);
         case DCNN_ACT: return d.n_in == 2;
         case DCNN_MAXPOOL:
-        case DCNN_UPSAMPLE: return true;
+        case DCNN_UPSAMPLE:
+        case DCNN_CONCAT: return true;
         default: return false;
     }
 }
@@ -41,6 +42,10 @@ static dcnn_status out_shape(const dcnn_layer_desc& d, int* oh, int* ow, int* oc
                 *oc = d.cout;
             }
             return DCNN_OK;
+        case DCNN_CONCAT:
+            if (d.cout <= d.c) return DCNN_EINVAL;
+            *oc = d.cout;
+            return DCNN_OK;
         case DCNN_UPSAMPLE:
             if (d.factor < 1 || d.factor > 16) return DCNN_EINVAL;
             *oh = d.h * d.factor; *ow = d.w * d.factor;
@@ -50,7 +55,7 @@ static dcnn_status out_shape(const dcnn_layer_desc& d, int* oh, int* ow, int* oc
 }
 
 static dcnn_status validate_desc(const dcnn_layer_desc& d) {
-    if (d.kind < DCNN_DELTAGEN || d.kind > DCNN_ACCUM) return DCNN_EINVAL;
+    if (d.kind < DCNN_DELTAGEN || d.kind > DCNN_CONCAT) return DCNN_EINVAL;
     if (d.dtype != DCNN_F32 && d.dtype != DCNN_F16) return DCNN_EDTYPE;
     if (d.n < 1 || d.h < 1 || d.w < 1 || d.c < 1) return DCNN_ESHAPE;
     if ((int64_t)d.n * d.h * d.w > INT32_MAX / 4) return DCNN_ESHAPE;
@@ -64,6 +69,7 @@ static dcnn_status validate_desc(const dcnn_layer_desc& d) {
             if (d.n_in != 1 && d.n_in != 2) return DCNN_EINVAL;
             if (d.n_in == 1 && d.act == DCNN_ACT_NONE) return DCNN_EINVAL;  // would be the identity
             break;
+        case DCNN_CONCAT: if (d.n_in != 2 || d.act != DCNN_ACT_NONE) return DCNN_EINVAL; break;
         default: if (d.n_in != 1) return DCNN_EINVAL;
     }
     int oh, ow, oc;
@@ -420,6 +426,11 @@ dcnn_status dcnn_layer_init(dcnn_layer* L, const void* const* dense_in, int32_t 
             st = launch_upsample(ctx, d.dtype, full_list(L->out_pixels), a);
             break;
         }
+        case DCNN_CONCAT: {
+            ConcatArgs a{dense_in[0], dense_in[1], nullptr, nullptr, dense_out, d.c, d.cout - d.c};
+            st = launch_concat(ctx, d.dtype, full_list(L->out_pixels), a);
+            break;
+        }
         case DCNN_ACCUM:
             st = launch_copy(ctx, L->buf0, dense_in[0], L->buf0_bytes);
             if (st == DCNN_OK && dense_out) st = launch_copy(ctx, dense_out, dense_in[0], L->buf0_bytes);
@@ -449,7 +460,8 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
     if (st != DCNN_OK) return st;
     if (n_in == 2) {
         st = has_proj(d) ? check_input(L, in[1], 1, d.proj_h, d.proj_w, d.proj_c, false)
-                         : check_input(L, in[1], 1, L->oh, L->ow, L->oc, false);
+             : d.kind == DCNN_CONCAT ? check_input(L, in[1], 1, L->oh, L->ow, d.cout - d.c, false)
+                                     : check_input(L, in[1], 1, L->oh, L->ow, L->oc, false);
         if (st != DCNN_OK) return st;
     }
     Workspace ws;
@@ -564,6 +576,11 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         case DCNN_UPSAMPLE: {
             UpsampleArgs a{in[0]->data, L->out_data, d.n, d.h, d.w, d.c, d.factor};
             st = launch_upsample(ctx, d.dtype, l, a);
+            break;
+        }
+        case DCNN_CONCAT: {
+            ConcatArgs a{in[0]->data, in[1]->data, in[0]->mask, in[1]->mask, L->out_data, d.c, d.cout - d.c};
+            st = launch_concat(ctx, d.dtype, l, a);
             break;
         }
         case DCNN_ACCUM: {

@@ -84,7 +84,7 @@ dcnn_status dcnn_net_add(dcnn_net* net, const dcnn_layer_desc* desc, const int32
         nd.d.n = net->n; nd.d.h = net->h; nd.d.w = net->w; nd.d.c = net->c; nd.d.n_in = 1;
     } else {
         if (id == 0) return fail(ctx, DCNN_EINVAL, "net_add: node 0 must be the input layer (DCNN_DELTAGEN)");
-        const int want = (desc->kind == DCNN_ACT) ? desc->n_in : 1;
+        const int want = (desc->kind == DCNN_ACT) ? desc->n_in : (desc->kind == DCNN_CONCAT ? 2 : 1);
         if (n_inputs != want || !inputs) return fail(ctx, DCNN_EINVAL, "net_add: node %d expects %d inputs, got %d", id, want, n_inputs);
         if (is_conv(*desc) && (desc->act != DCNN_ACT_NONE || desc->n_in != 1))
             return fail(ctx, DCNN_EINVAL, "net_add: add convolutions unfused (act NONE, one input); finalize fuses");
@@ -97,8 +97,9 @@ dcnn_status dcnn_net_add(dcnn_net* net, const dcnn_layer_desc* desc, const int32
         nd.d.n = net->n; nd.d.h = p0.oh; nd.d.w = p0.ow; nd.d.c = p0.oc;
         if (n_inputs == 2) {
             const Node& p1 = net->nodes[inputs[1]];
-            if (p1.oh != p0.oh || p1.ow != p0.ow || p1.oc != p0.oc)
-                return fail(ctx, DCNN_ESHAPE, "net_add: node %d adds [%d,%d,%d] and [%d,%d,%d]", id, p0.oh, p0.ow, p0.oc, p1.oh, p1.ow, p1.oc);
+            if (p1.oh != p0.oh || p1.ow != p0.ow || (desc->kind != DCNN_CONCAT && p1.oc != p0.oc))
+                return fail(ctx, DCNN_ESHAPE, "net_add: node %d joins [%d,%d,%d] and [%d,%d,%d]", id, p0.oh, p0.ow, p0.oc, p1.oh, p1.ow, p1.oc);
+            if (desc->kind == DCNN_CONCAT) { nd.d.n_in = 2; nd.d.cout = p0.oc + p1.oc; }
         }
         if (desc->kind == DCNN_DWCONV) nd.d.cout = nd.d.c;
     }

@@ -381,6 +381,31 @@ __global__ __launch_bounds__(256) void upsample_kernel(ListArgs l, UpsampleArgs 
     }
 }
 
+// Channel concatenation over the listed pixels: out[p] = [a[p] or zeros, b[p] or zeros] (a stream that is
+// not flagged at p contributes zeros; its memory there is not read).  One element per thread: the channel
+// counts of the two inputs need not be multiples of the vector width.
+template <typename T>
+__global__ __launch_bounds__(256) void concat_kernel(ListArgs l, ConcatArgs a) {
+    const int64_t count = list_count(l);
+    const int C = a.ca + a.cb;
+    const T* xa = static_cast<const T*>(a.a_data);
+    const T* xb = static_cast<const T*>(a.b_data);
+    T* out = static_cast<T*>(a.out_data);
+    const int64_t total = count * C;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t j = i / C;
+        const int ch = (int)(i - j * C);
+        const int64_t p = l.list ? (int64_t)l.list[j] : j;
+        T v = (T)0.0f;
+        if (ch < a.ca) {
+            if (a.a_mask == nullptr || a.a_mask[p]) v = xa[p * a.ca + ch];
+        } else {
+            if (a.b_mask == nullptr || a.b_mask[p]) v = xb[p * a.cb + (ch - a.ca)];
+        }
+        out[p * C + ch] = v;
+    }
+}
+
 static int flat_grid(const dcnn_ctx* ctx, int64_t max_count, int c, int vec) {
     int64_t total = (max_count > 0 ? max_count : 1) * cdiv(c, vec);
     int64_t want = cdiv(total, 256);
@@ -426,6 +451,13 @@ dcnn_status launch_maxpool_commit(dcnn_ctx* ctx, int dtype, const ListArgs& l, c
 dcnn_status launch_upsample(dcnn_ctx* ctx, int dtype, const ListArgs& l, const UpsampleArgs& a) {
     DCNN_FLAT_DISPATCH(upsample_kernel, a.c, l.max_count, l, a);
     return check_hip(ctx, hipGetLastError(), "upsample_kernel launch");
+}
+
+dcnn_status launch_concat(dcnn_ctx* ctx, int dtype, const ListArgs& l, const ConcatArgs& a) {
+    const int grid = flat_grid(ctx, l.max_count, a.ca + a.cb, 1);
+    if (dtype == DCNN_F16) hipLaunchKernelGGL((concat_kernel<f16>), dim3(grid), dim3(256), 0, ctx->stream, l, a);
+    else hipLaunchKernelGGL((concat_kernel<float>), dim3(grid), dim3(256), 0, ctx->stream, l, a);
+    return check_hip(ctx, hipGetLastError(), "concat_kernel launch");
 }
 
 dcnn_status launch_deltagen(dcnn_ctx* ctx, int dtype, const DeltaGenArgs& a_in) {

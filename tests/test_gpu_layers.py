@@ -506,6 +506,30 @@ def test_upsample(S, factor):
 
 
 @pytest.mark.parametrize("S", ["f32", "f16"])
+@pytest.mark.parametrize("ca,cb", [(32, 64), (16, 3), (5, 7)])
+def test_concat(S, ca, cb):
+    """Channel concatenation: values are copies (bit-exact); an unflagged stream contributes zeros."""
+    rng = np.random.default_rng(ca * 100 + cb)
+    n, h, w = 2, 23, 19
+    ref = orc.Concat(S)
+    ctx = pkg.Context(n * h * w)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.CONCAT, DT[S], n, h, w, ca, cout=ca + cb, n_in=2))
+    assert layer.out_shape == (n, h, w, ca + cb)
+    a0 = rng.normal(0, 1, (n, h, w, ca)).astype(NP_DTYPE[S])
+    b0 = rng.normal(0, 1, (n, h, w, cb)).astype(NP_DTYPE[S])
+    g0 = layer.init([torch.from_numpy(a0).cuda(), torch.from_numpy(b0).cuda()])
+    ctx.sync()
+    assert np.array_equal(to_np(g0), ref.init(a0, b0))
+    for t, (da_, db_) in enumerate([(0.2, 0.1), (1.0, 0.0), (0.0, 0.3), (0.0, 0.0)]):
+        da = _rand_delta(rng, (n, h, w, ca), da_, S)
+        db = _rand_delta(rng, (n, h, w, cb), db_, S)
+        want = ref.step(da, db).poisoned()
+        out = layer.step([_upload(da), _upload(db)])
+        ctx.sync()
+        check_delta(out, want, S, f"concat frame {t}", exact_values=True)
+
+
+@pytest.mark.parametrize("S", ["f32", "f16"])
 def test_accumulate(S):
     rng = np.random.default_rng(8)
     shape = (2, 21, 19, 256)

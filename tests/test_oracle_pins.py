@@ -31,6 +31,7 @@ NETS_DENSE_MODE = {
     "conv3x3": lambda e: wl.single_conv_relu(eps=e, h=16, w=12, c=4, frames=4),
     "bottleneck": lambda e: wl.bottleneck_block(eps=e, h=12, w=12, cin=8, mid=8, cout=16, frames=4, n_objects=1),
     "mixed": lambda e: wl.tiny_mixed_net(eps=e, frames=4),
+    "concat": lambda e: wl.tiny_concat_net(eps=e, frames=4),
 }
 
 
@@ -464,3 +465,17 @@ def test_truncation_error_is_bounded_not_accumulating():
     assert errs[0] < 1e-12
     assert max(errs[20:]) < 2.0 * max(errs[1:20]) + 1e-9
     assert max(errs) < 1.0
+
+
+def test_concat_by_hand():
+    """Channel concatenation of two updates: mask = OR, a stream that is not flagged at a pixel contributes
+    zeros (its delta there is zero by definition), nothing is defined where neither is flagged."""
+    a = orc.Delta(np.array([[[[1.0, 2.0]], [[3.0, 4.0]], [[5.0, 6.0]]]]), np.array([[[1], [0], [0]]], np.uint8)).poisoned()
+    b = orc.Delta(np.array([[[[7.0]], [[8.0]], [[9.0]]]]), np.array([[[1], [1], [0]]], np.uint8)).poisoned()
+    out = orc.Concat("f64").step(a, b)
+    assert out.mask.tolist() == [[[1], [1], [0]]]
+    assert out.data[0, 0, 0].tolist() == [1.0, 2.0, 7.0]
+    assert out.data[0, 1, 0].tolist() == [0.0, 0.0, 8.0]
+    assert np.isnan(out.data[0, 2, 0]).all()
+    dense = orc.Concat("f64").init(np.ones((1, 2, 2, 3)), np.zeros((1, 2, 2, 1)))
+    assert dense.shape == (1, 2, 2, 4) and dense[0, 1, 1].tolist() == [1.0, 1.0, 1.0, 0.0]

@@ -49,6 +49,9 @@ class _B:
     def add(self, a, b):
         return self._add(kind="add", **{"in": [a, b]})
 
+    def concat(self, a, b):
+        return self._add(kind="concat", **{"in": [a, b]})
+
     def maxpool(self, src, k=3, stride=2, pad=1):
         return self._add(kind="maxpool", **{"in": [src]}, k=k, stride=stride, pad=pad)
 
@@ -218,6 +221,8 @@ def node_shapes(net):
             shapes.append((ho, wo, c))
         elif k == "upsample":
             shapes.append((h * nd["factor"], w * nd["factor"], c))
+        elif k == "concat":
+            shapes.append((h, w, c + shapes[nd["in"][1]][2]))
         else:
             shapes.append((h, w, c))
     return shapes
@@ -250,6 +255,22 @@ def dense_flops(net) -> int:
         per_out = nd["k"] * nd["k"] * (1 if nd["depthwise"] else nd["cin"])
         total += 2 * ho * wo * co * per_out
     return total
+
+
+def tiny_concat_net(eps=0.05, eps0=None, h=20, w=24, c=8, frames=6, dtype="f32"):
+    """Two branches of different widths joined by a channel concatenation (tests only)."""
+    eps0 = eps if eps0 is None else eps0
+    b = _B()
+    x0 = b.deltagen(eps0)
+    a = b.act(b.conv(x0, 3, 1, c, 16), "relu", eps)
+    z = b.act(b.conv(x0, 1, 1, c, 8), "relu6", eps)
+    q = b.concat(a, z)                                          # 24 channels
+    q = b.act(b.conv(q, 3, 1, 24, 16), "relu", eps)
+    q = b.concat(q, x0)                                         # joins the raw input delta as well
+    q = b.conv(q, 1, 1, 16 + c, 8)
+    b.accum(q)
+    video = VideoSpec(h=h, w=w, c=c, frames=frames, n_objects=2, obj_kind="rect", obj_size=5, noise_sigma=0.01)
+    return _net("tiny_concat", dtype, h, w, c, video, b)
 
 
 def tiny_mixed_net(eps=0.05, eps0=None, h=24, w=20, c=8, frames=6, dtype="f32"):
