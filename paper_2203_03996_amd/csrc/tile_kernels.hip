@@ -16,9 +16,28 @@ static int list_grid(const dcnn_ctx* ctx, int64_t max_count, int entries_per_wg,
     return (int)(cdiv(g, kXcd) * kXcd);
 }
 
+// A wave serves the pixels of its tile one iteration after the other; when one pixel's channels fill the whole
+// wave (or half of it) that is 32 (16) dependent round trips to memory.  Such tiles are shared by 4 (2) waves:
+// each keeps a run of 8 (16) consecutive entries (the others look empty to it) and stores its byte (half) of
+// the tile's survivor word.
+constexpr int kSplitMaxVpl = 4;
+static int tile_parts(int nvec, int vpl) {
+    int lp = 1;
+    while (lp < (int)cdiv(nvec, vpl)) lp <<= 1;
+    lp = lp < 2 ? 2 : (lp > kWave ? kWave : lp);
+    const int iters = kTile / (kWave / lp);
+    return iters >= 32 ? 4 : (iters >= 16 ? 2 : 1);
+}
+
+__device__ __forceinline__ void store_survivors(uint32_t* surv, int64_t tile, int part, int parts, uint32_t bits) {
+    if (parts == 1) surv[tile] = bits;
+    else if (parts == 2) reinterpret_cast<uint16_t*>(surv)[tile * 2 + part] = (uint16_t)(bits >> (16 * part));
+    else reinterpret_cast<uint8_t*>(surv)[tile * 4 + part] = (uint8_t)(bits >> (8 * part));
+}
+
 // ---- activation + truncation (+ add) ----------------------------------------------------------
-template <typename T, int V, int VPL>
-__global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a, EpilogueArgs e, int init) {
+template <typename T, int V, int VPL, bool SPLIT>
+__global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a, EpilogueArgs e, int init, int parts) {
     typedef typename RawOf<T, V>::type Raw;
     constexpr int UB = (V * VPL >= 16) ? 2 : 4;
     const int64_t count = list_count(l);
@@ -31,15 +50,33 @@ __global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a
         return raw_zero<T, V>();
     };
     int survivors = 0;
-    const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
-    for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
-        const int64_t tile = wt * kTileWaves + wave;
-        const int64_t base = tile * kTile;
-        if (base >= count) continue;
-        const int p_mine = list_pixel(l.list, base + lane % kTile, count);
-        const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
-        if (e.surv) { if (lane == 0) e.surv[tile] = bits; }
-        else survivors += __popc(bits);
+    if constexpr (SPLIT) {
+        const int64_t ntiles = (count + kTile - 1) / kTile;
+        const int run = kTile / parts;                          // tile entries per wave
+        const WgTileRange r = wg_tile_range((ntiles * parts + kTileWaves - 1) / kTileWaves);
+        for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
+            const int64_t unit = wt * kTileWaves + wave;
+            const int64_t tile = unit / parts;
+            const int part = (int)(unit - tile * parts);
+            const int64_t base = tile * kTile;
+            if (base >= count) continue;
+            const int j = lane % kTile;
+            const int p_mine = (j / run == part) ? list_pixel(l.list, base + j, count) : -1;
+            const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
+            if (e.surv) { if (lane == 0) store_survivors(e.surv, tile, part, parts, bits); }
+            else survivors += __popc(bits);
+        }
+    } else {
+        const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
+        for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
+            const int64_t tile = wt * kTileWaves + wave;
+            const int64_t base = tile * kTile;
+            if (base >= count) continue;
+            const int p_mine = list_pixel(l.list, base + lane % kTile, count);
+            const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
+            if (e.surv) { if (lane == 0) e.surv[tile] = bits; }
+            else survivors += __popc(bits);
+        }
     }
     // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
     if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
@@ -51,10 +88,17 @@ static dcnn_status launch_act_t(dcnn_ctx* ctx, bool init, const ListArgs& l, con
     const bool vec = (e.c % VEC) == 0;
     const int nvec = vec ? e.c / VEC : e.c;
     const int vpl = (int)cdiv(nvec, kWave);
-    const int grid = list_grid(ctx, l.max_count, kTileWaves * kTile, 8);
+    const int vpl_used = vpl <= 1 ? 1 : (vpl <= 2 ? 2 : (vpl <= 4 ? 4 : 8));
+    // pixels of 8 vectors per lane keep one wave per tile (that form holds its whole batch in registers)
+    const int parts = vpl_used <= kSplitMaxVpl ? tile_parts(nvec, vpl_used) : 1;
+    const int grid = list_grid(ctx, l.max_count, kTileWaves * kTile / parts, 8);
     dim3 g(grid), b(kTileThreads);
     const int ini = init ? 1 : 0;
-#define DCNN_ACT_LAUNCH(V, VPL) hipLaunchKernelGGL((act_kernel<T, V, VPL>), g, b, 0, ctx->stream, l, a, e, ini)
+#define DCNN_ACT_LAUNCH(V, VPL)                                                                                      \
+    do {                                                                                                             \
+        if (parts > 1) hipLaunchKernelGGL((act_kernel<T, V, VPL, (VPL <= kSplitMaxVpl)>), g, b, 0, ctx->stream, l, a, e, ini, parts); \
+        else hipLaunchKernelGGL((act_kernel<T, V, VPL, false>), g, b, 0, ctx->stream, l, a, e, ini, 1);              \
+    } while (0)
     if (vec) {
         if (vpl <= 1) DCNN_ACT_LAUNCH(VEC, 1);
         else if (vpl <= 2) DCNN_ACT_LAUNCH(VEC, 2);
@@ -77,9 +121,12 @@ dcnn_status launch_act(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, c
 
 // ---- depthwise convolution: the first delta stream is formed on the fly ------------------------
 // Work list = flagged OUTPUT pixels.  Every tap's update flag is checked before its values are
-// read (unflagged memory is invalid), load and multiply are fused per pixel.
-template <typename T, int V, int VPL>
-__global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init) {
+// read (unflagged memory is invalid).  KS = 1, 2, 3: the flags of the whole tile are fetched first (entry
+// lane%32 per lane, one round trip) and packed into a tap word; the taps of a pixel are then loaded
+// back to back, an unflagged or padded tap reading the zero page instead, so no load waits for a flag.
+// KS = 0: any window, flag and values per tap.
+template <typename T, int V, int VPL, int KS>
+__global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init, int parts) {
     typedef typename RawOf<T, V>::type Raw;
     constexpr int UB = 2;
     const int64_t count = list_count(l);
@@ -87,7 +134,12 @@ __global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvAr
     const int C = e.c;
     const T* in = static_cast<const T*>(c.in_data);
     const T* wgt = static_cast<const T*>(c.wpacked);           // [k][k][C], unpacked
-    auto dx = [&](int, int64_t p, int c0) -> Raw {
+    const T* zeros = static_cast<const T*>(c.zero_page);
+    // KS > 0: per tile entry the tap word and the input pixel under tap (0,0) (which may lie outside the map);
+    // handed from the lane that computed them to the lanes that serve the entry through LDS (a lane shuffle
+    // inside the divergent per-vector code would read disabled lanes)
+    __shared__ int2 s_taps[kTileWaves][kTile];
+    auto dx_any = [&](int, int64_t p, int c0) -> Raw {
         const int ox = (int)(p % c.ow);
         const int64_t t = p / c.ow;
         const int oy = (int)(t % c.oh);
@@ -114,15 +166,79 @@ __global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvAr
         for (int i = 0; i < V; ++i) raw_set<T, V>(o, i, acc[i]);
         return o;
     };
+    auto dx_taps = [&](int ent, int64_t, int c0) -> Raw {
+        constexpr int KK = KS > 0 ? KS * KS : 1;
+        const int2 tq = s_taps[wave][ent & (kTile - 1)];
+        const uint32_t word = (uint32_t)tq.x;
+        const int q0 = tq.y;
+        Raw xv[KK], wv[KK];
+#pragma unroll
+        for (int t = 0; t < KK; ++t) {
+            const int64_t q = (int64_t)q0 + (t / (KS > 0 ? KS : 1)) * c.w + (t % (KS > 0 ? KS : 1));
+            const T* src = ((word >> t) & 1u) ? in + q * C + c0 : zeros;
+            xv[t] = raw_load<T, V>(src);
+        }
+#pragma unroll
+        for (int t = 0; t < KK; ++t) wv[t] = raw_load<T, V>(wgt + (int64_t)t * C + c0);
+        float acc[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+#pragma unroll
+        for (int t = 0; t < KK; ++t)
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc[i] = fmaf(raw_get<T, V>(xv[t], i), raw_get<T, V>(wv[t], i), acc[i]);
+        Raw o;
+#pragma unroll
+        for (int i = 0; i < V; ++i) raw_set<T, V>(o, i, acc[i]);
+        return o;
+    };
     int survivors = 0;
-    const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
+    const int64_t ntiles = (count + kTile - 1) / kTile;
+    const WgTileRange r = wg_tile_range((ntiles * parts + kTileWaves - 1) / kTileWaves);
     for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
-        const int64_t tile = wt * kTileWaves + wave;
+        const int64_t unit = wt * kTileWaves + wave;
+        const int64_t tile = unit / parts;
+        const int part = (int)(unit - tile * parts);
         const int64_t base = tile * kTile;
         if (base >= count) continue;
-        const int p_mine = list_pixel(l.list, base + lane % kTile, count);
-        const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
-        if (e.surv) { if (lane == 0) e.surv[tile] = bits; }
+        const int j = lane % kTile;
+        const int p_mine = (j / (kTile / parts) == part) ? list_pixel(l.list, base + j, count) : -1;   // the others look empty
+        uint32_t bits;
+        if constexpr (KS > 0) {
+            uint32_t tap_word = 0;
+            int q_first = 0;
+            if (p_mine >= 0) {
+                const int ox = p_mine % c.ow;
+                const int t = p_mine / c.ow;
+                const int oy = t % c.oh, n = t / c.oh;
+                const int iy0 = oy * c.stride - c.pad, ix0 = ox * c.stride - c.pad;
+                q_first = (n * c.h + iy0) * c.w + ix0;
+                uint32_t inb = 0;
+                int qq[KS * KS];
+#pragma unroll
+                for (int t2 = 0; t2 < KS * KS; ++t2) {
+                    const int iy = iy0 + t2 / KS, ix = ix0 + t2 % KS;
+                    const bool ok = iy >= 0 && iy < c.h && ix >= 0 && ix < c.w;
+                    inb |= ok ? (1u << t2) : 0u;
+                    qq[t2] = ok ? q_first + (t2 / KS) * c.w + t2 % KS : 0;       // a tap outside the map re-reads flag 0 (ignored)
+                }
+                tap_word = inb;
+                if (c.in_mask) {
+                    uint32_t f[KS * KS];
+#pragma unroll
+                    for (int t2 = 0; t2 < KS * KS; ++t2) f[t2] = c.in_mask[qq[t2]];
+                    tap_word = 0;
+#pragma unroll
+                    for (int t2 = 0; t2 < KS * KS; ++t2) tap_word |= f[t2] ? (1u << t2) : 0u;
+                }
+                tap_word &= inb;
+            }
+            s_taps[wave][lane % kTile] = make_int2((int)tap_word, q_first);     // both wave halves store the same pair
+            bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx_taps, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
+        } else {
+            bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx_any, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
+        }
+        if (e.surv) { if (lane == 0) store_survivors(e.surv, tile, part, parts, bits); }
         else survivors += __popc(bits);
     }
     // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
@@ -135,21 +251,33 @@ static dcnn_status launch_dwconv_t(dcnn_ctx* ctx, bool init, const ListArgs& l, 
     const bool vec = (e.c % VEC) == 0;
     const int nvec = vec ? e.c / VEC : e.c;
     const int vpl = (int)cdiv(nvec, kWave);
-    const int grid = list_grid(ctx, l.max_count, kTileWaves * kTile, 8);
+    if (vpl > 4) return fail(ctx, DCNN_EUNSUPPORTED, "depthwise conv: %d channels not supported", e.c);
+    const int vpl_used = vpl <= 1 ? 1 : (vpl <= 2 ? 2 : 4);
+    const int parts = tile_parts(nvec, vpl_used);
+    const int grid = list_grid(ctx, l.max_count, kTileWaves * kTile / parts, 8);
     dim3 g(grid), b(kTileThreads);
     const int ini = init ? 1 : 0;
-#define DCNN_DW_LAUNCH(V, VPL) hipLaunchKernelGGL((dwconv_kernel<T, V, VPL>), g, b, 0, ctx->stream, l, c, e, ini)
+    // the tap-word forms address input pixels with 32-bit indices
+    const bool small = (int64_t)c.n * c.h * c.w < ((int64_t)1 << 31) - 4 * (int64_t)c.w;
+    const int ks = (small && c.k >= 1 && c.k <= 3) ? c.k : 0;
+#define DCNN_DW_LAUNCH(V, VPL, KS) hipLaunchKernelGGL((dwconv_kernel<T, V, VPL, KS>), g, b, 0, ctx->stream, l, c, e, ini, parts)
+#define DCNN_DW_KS(V, VPL)                                                                                         \
+    do {                                                                                                           \
+        if (ks == 3) DCNN_DW_LAUNCH(V, VPL, 3);                                                                    \
+        else if (ks == 2) DCNN_DW_LAUNCH(V, VPL, 2);                                                               \
+        else if (ks == 1) DCNN_DW_LAUNCH(V, VPL, 1);                                                               \
+        else DCNN_DW_LAUNCH(V, VPL, 0);                                                                            \
+    } while (0)
     if (vec) {
-        if (vpl <= 1) DCNN_DW_LAUNCH(VEC, 1);
-        else if (vpl <= 2) DCNN_DW_LAUNCH(VEC, 2);
-        else if (vpl <= 4) DCNN_DW_LAUNCH(VEC, 4);
-        else return fail(ctx, DCNN_EUNSUPPORTED, "depthwise conv: %d channels not supported", e.c);
+        if (vpl_used == 1) DCNN_DW_KS(VEC, 1);
+        else if (vpl_used == 2) DCNN_DW_KS(VEC, 2);
+        else DCNN_DW_KS(VEC, 4);
     } else {
-        if (vpl <= 1) DCNN_DW_LAUNCH(1, 1);
-        else if (vpl <= 2) DCNN_DW_LAUNCH(1, 2);
-        else if (vpl <= 4) DCNN_DW_LAUNCH(1, 4);
-        else return fail(ctx, DCNN_EUNSUPPORTED, "depthwise conv: %d channels not supported", e.c);
+        if (vpl_used == 1) DCNN_DW_KS(1, 1);
+        else if (vpl_used == 2) DCNN_DW_KS(1, 2);
+        else DCNN_DW_KS(1, 4);
     }
+#undef DCNN_DW_KS
 #undef DCNN_DW_LAUNCH
     return check_hip(ctx, hipGetLastError(), "dwconv_kernel launch");
 }
