@@ -30,7 +30,7 @@ namespace dcnn {
 #endif
 template <typename T, int NB, int V, bool ALIGNED, bool STREAM, int KS>
 __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init,
-                                                                 int npass, int cs) {
+                                                                 int npass, int cs, int pass_split) {
     typedef typename Mma<T>::Vec Vec;
     typedef typename RawOf<T, V>::type Raw;
     constexpr int KP = Mma<T>::KPACK;
@@ -167,7 +167,11 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
             }
         };
 
-        for (int pass = 0; pass < npass; ++pass) {
+        // passes are independent (each writes its own output channels): short work lists spread them over
+        // blockIdx.y so that more compute units stream weights
+        const int pass_first = blockIdx.y * pass_split;
+        const int pass_last = pass_first + pass_split < npass ? pass_first + pass_split : npass;
+        for (int pass = pass_first; pass < pass_last; ++pass) {
             const int cgroup = pass * cs + part;               // which group of COLS output channels
             const int ch0 = cgroup * COLS;
             int nch = e.c - ch0;
@@ -320,6 +324,15 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
     per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
     int64_t cap = (int64_t)ctx->num_cu * per_cu;
     const int grid = (int)(cdiv(want < cap ? want : cap, kXcd) * kXcd);
+    // several passes and fewer workgroups than the chip holds: spread the passes over grid.y
+    int ysplit = 1;
+    if (p.npass > 1 && grid < cap) {
+        const int64_t room = cap / grid;
+        ysplit = (int)(room < p.npass ? room : p.npass);
+        if (ysplit < 1) ysplit = 1;
+    }
+    const int pass_split = (int)cdiv(p.npass, ysplit);
+    const int grid_y = (int)cdiv(p.npass, pass_split);
     const int ini = init ? 1 : 0;
     hipError_t err = hipSuccess;
     bool launched = false;
@@ -333,7 +346,7 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
             attr_set = (err == hipSuccess);                                                                      \
         }                                                                                                        \
         if (err == hipSuccess)                                                                                   \
-            hipLaunchKernelGGL(kern, dim3(grid), dim3(p.waves * kWave), p.lds_bytes, ctx->stream, l, c, e, ini, p.npass, p.cs); \
+            hipLaunchKernelGGL(kern, dim3(grid, grid_y), dim3(p.waves * kWave), p.lds_bytes, ctx->stream, l, c, e, ini, p.npass, p.cs, pass_split); \
         launched = true;                                                                                         \
     } while (0)
     // resident weights, vector-aligned channels, one pass, sparse step: the wave-specialised kernel

@@ -37,13 +37,9 @@ namespace dcnn {
 
 constexpr int kWsProducers = 8;
 constexpr int kWsWaves = 16;
-constexpr uint32_t kOob = 0x80000000u;                         // byte offset no descriptor here reaches
-constexpr uint64_t kWsMaxBytes = 0x7fffffffull;
 constexpr int kTapProj = 30;                                   // bit of a tap word: the projection's input pixel is flagged
 
 constexpr int ws_pow2_ceil(int v) { int p = 1; while (p < v) p <<= 1; return p; }
-
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // LDS needed by the wave-specialised kernel; 0 when the shape is not covered by it.
 inline size_t conv_ws_lds_bytes(const ConvPlan& p, int dtype, int k, int cout, int cin2 = 0) {
@@ -56,16 +52,6 @@ inline size_t conv_ws_lds_bytes(const ConvPlan& p, int dtype, int k, int cout, i
     return bytes <= kLdsBytes ? bytes : 0;
 }
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t ws_rsrc(const void* p, uint64_t bytes) {
-    // raw buffer (stride 0), 32-bit data format; a null pointer gives an empty range
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, p ? (int)bytes : 0, 0x00020000);
-}
-template <typename Raw> __device__ __forceinline__ Raw ws_load16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
-    return __builtin_bit_cast(Raw, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0));
-}
-template <typename Raw> __device__ __forceinline__ void ws_store16(__amdgpu_buffer_rsrc_t r, uint32_t off, Raw v) {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)off, 0, 0);
-}
 
 // AUX: third per-pixel stream of the tail -- 0 none, 1 residual delta (added before the activation),
 // 2 dense accumulated output O of a final layer (O += emitted delta; the delta itself is not stored).

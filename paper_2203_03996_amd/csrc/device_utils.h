@@ -442,6 +442,25 @@ __device__ __forceinline__ uint32_t tail_finish(const EpilogueArgs& e, bool init
     return bits;
 }
 
+// ---- buffer addressing ---------------------------------------------------------------------------
+// A load through a buffer descriptor at a byte offset outside the descriptor's range returns zeros and a
+// store there is dropped, so "this lane has nothing to do" is an offset, not a branch: every load of a
+// phase can be issued back to back.  Offsets are 32 bit: tensors addressed this way stay below 2 GiB.
+constexpr uint32_t kOob = 0x80000000u;                         // byte offset no descriptor here reaches
+constexpr uint64_t kWsMaxBytes = 0x7fffffffull;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t ws_rsrc(const void* p, uint64_t bytes) {
+    // raw buffer (stride 0), 32-bit data format; a null pointer gives an empty range
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, p ? (int)bytes : 0, 0x00020000);
+}
+template <typename Raw> __device__ __forceinline__ Raw ws_load16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    return __builtin_bit_cast(Raw, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0));
+}
+template <typename Raw> __device__ __forceinline__ void ws_store16(__amdgpu_buffer_rsrc_t r, uint32_t off, Raw v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)off, 0, 0);
+}
+
 // Pixel of work-list entry `j` for the lane that owns it (-1 beyond the end of the list).
 __device__ __forceinline__ int list_pixel(const int32_t* list, int64_t j, int64_t count) {
     if (j >= count) return -1;

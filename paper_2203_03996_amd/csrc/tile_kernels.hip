@@ -16,17 +16,129 @@ static int list_grid(const dcnn_ctx* ctx, int64_t max_count, int entries_per_wg,
     return (int)(cdiv(g, kXcd) * kXcd);
 }
 
-// A wave serves the pixels of its tile one iteration after the other; when one pixel's channels fill the whole
-// wave (or half of it) that is 32 (16) dependent round trips to memory.  Such tiles are shared by 4 (2) waves:
-// each keeps a run of 8 (16) consecutive entries (the others look empty to it) and stores its byte (half) of
-// the tile's survivor word.
-constexpr int kSplitMaxVpl = 4;
-static int tile_parts(int nvec, int vpl) {
+// ---- sparse-step tail with buffer addressing ---------------------------------------------------
+// Activation + truncation (Eqs. 4-6) of one run of tile entries, for the sparse steps of layers whose channel
+// count is a multiple of the vector width and whose tensors stay below 2 GiB.  Same arithmetic, rounding and
+// decisions as act_trunc_tile; what differs is how memory is reached: every flag a load depends on has been
+// fetched for the whole tile beforehand (one round trip, entry lane%32 per lane), and every load and store
+// goes through a buffer descriptor with an out-of-range offset where a lane has nothing to do.  A batch of
+// UB iterations therefore issues all its loads back to back and costs one round trip to memory.
+//
+// `Src` delivers the first delta stream: select(ub, ent) runs in wave-uniform control flow and picks the
+// per-entry values of iteration ub (lane shuffles); issue(ub, v, c0, on, off) requests the values of the
+// lane's vector v; finish(ub, v, c0) returns them, rounded to the storage type.
+struct TailRsrc {
+    __amdgpu_buffer_rsrc_t res, xA, xT, out, omask;
+};
+
+template <typename T, int V, int VPL, int UB, class Src>
+__device__ __forceinline__ uint32_t sparse_tile_tail(const EpilogueArgs& e, const TailRsrc& rs, Src& src, int LP, int p_mine,
+                                                    int rflag_mine, int ent_first, int ent_end, int nbatch, int lane) {
+    typedef typename RawOf<T, V>::type Raw;
+    constexpr uint32_t ES = sizeof(T);
+    const int PPI = kWave / LP;
+    const int sub = lane % LP, grp = lane / LP;
+    const int nvec = e.c / V;
+    const uint32_t row_bytes = (uint32_t)e.c * ES;
+    const bool stateful = e.act != DCNN_ACT_NONE;
+    const bool has_res = e.res_data != nullptr;
+    const float hi = act_hi(e.act);
+    uint32_t bits = 0;
+    for (int b = 0; b < nbatch; ++b) {
+        int pix[UB];
+        uint32_t off[UB][VPL];
+        Raw rr[UB][VPL], ra[UB][VPL], rt[UB][VPL];
+        // ---- phase 1: every load of the batch ----------------------------------------------------
+#pragma unroll
+        for (int ub = 0; ub < UB; ++ub) {
+            const int ent = ent_first + (b * UB + ub) * PPI + grp;
+            const int p_any = __shfl(p_mine, ent & (kTile - 1), kWave);
+            const int rf = __shfl(rflag_mine, ent & (kTile - 1), kWave);
+            src.select(ub, ent & (kTile - 1));
+            const int p = ent < ent_end ? p_any : -1;
+            pix[ub] = p;
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) {
+                const int vi = sub + v * LP;
+                const bool on = p >= 0 && vi < nvec;
+                const int c0 = vi * V;
+                const uint32_t o = on ? (uint32_t)p * row_bytes + (uint32_t)c0 * ES : kOob;
+                off[ub][v] = o;
+                src.issue(ub, v, c0, on, o);
+                rr[ub][v] = ws_load16<Raw>(rs.res, rf ? o : kOob);          // empty descriptor without a second stream
+                ra[ub][v] = ws_load16<Raw>(rs.xA, o);                        // empty descriptors without an activation
+                rt[ub][v] = ws_load16<Raw>(rs.xT, o);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- phase 2: arithmetic, per-pixel maximum, decision, stores -----------------------------
+#pragma unroll
+        for (int ub = 0; ub < UB; ++ub) {
+            Raw o_a[VPL], o_t[VPL], o_y[VPL];
+            float u = 0.0f;
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) {
+                const Raw d0 = src.finish(ub, v, (sub + v * LP) * V);
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    float d = raw_get<T, V>(d0, i);
+                    if (has_res) d = round_store<T>(d + raw_get<T, V>(rr[ub][v], i));
+                    if (stateful) {
+                        const float a = raw_get<T, V>(ra[ub][v], i), t = raw_get<T, V>(rt[ub][v], i);
+                        const float sum = (a + t) + d;
+                        const float dy = act_clamp(sum, hi) - act_clamp(a, hi);
+                        u = fmaxf(u, fabsf(dy));
+                        raw_set<T, V>(o_a[v], i, sum);
+                        raw_set<T, V>(o_t[v], i, t + d);                       // x^T if the pixel is truncated
+                        raw_set<T, V>(o_y[v], i, dy);
+                    } else {
+                        raw_set<T, V>(o_y[v], i, d);
+                    }
+                }
+            }
+            bool upd = true;
+            if (stateful) {
+                for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
+                upd = u >= e.eps;
+            }
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) {
+                const uint32_t o = off[ub][v];
+                if (stateful) {
+                    const uint32_t o_upd = upd ? o : kOob;
+                    ws_store16<Raw>(rs.xA, o_upd, o_a[v]);
+                    ws_store16<Raw>(rs.xT, o, upd ? raw_zero<T, V>() : o_t[v]);
+                    ws_store16<Raw>(rs.out, o_upd, o_y[v]);
+                } else {
+                    ws_store16<Raw>(rs.out, o, o_y[v]);
+                }
+            }
+            const bool lead = pix[ub] >= 0 && sub == 0;
+            if (stateful) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)(upd ? 1 : 0), rs.omask, lead ? pix[ub] : (int)kOob, 0, 0);
+            const int ent = ent_first + (b * UB + ub) * PPI + grp;
+            if (lead && upd) bits |= 1u << (ent & (kTile - 1));
+        }
+    }
+#pragma unroll
+    for (int m = kWave >> 1; m >= 1; m >>= 1) bits |= __shfl_xor(bits, m, kWave);
+    return bits;
+}
+
+// How the entries of a tile are spread over waves and batches for a pixel of `nvec` vectors.
+struct TailShape {
+    int lp;        // lanes per pixel
+    int run;       // consecutive tile entries per wave (8, 16 or 32)
+    int nbatch;    // batches of UB iterations per wave
+};
+static TailShape tail_shape(int nvec, int vpl, int ub) {
+    TailShape s;
     int lp = 1;
     while (lp < (int)cdiv(nvec, vpl)) lp <<= 1;
-    lp = lp < 2 ? 2 : (lp > kWave ? kWave : lp);
-    const int iters = kTile / (kWave / lp);
-    return iters >= 32 ? 4 : (iters >= 16 ? 2 : 1);
+    s.lp = lp < 2 ? 2 : (lp > kWave ? kWave : lp);
+    const int per_batch = ub * (kWave / s.lp);                 // entries one batch covers
+    s.run = per_batch < 8 ? 8 : (per_batch > kTile ? kTile : per_batch);
+    s.nbatch = (int)cdiv(s.run, per_batch);
+    return s;
 }
 
 __device__ __forceinline__ void store_survivors(uint32_t* surv, int64_t tile, int part, int parts, uint32_t bits) {
@@ -35,9 +147,58 @@ __device__ __forceinline__ void store_survivors(uint32_t* surv, int64_t tile, in
     else reinterpret_cast<uint8_t*>(surv)[tile * 4 + part] = (uint8_t)(bits >> (8 * part));
 }
 
+// Activation + truncation (+ add) of a sparse step: the first stream is a stored delta map.
+template <typename T, int V, int VPL, int UB> struct ActSrc {
+    typedef typename RawOf<T, V>::type Raw;
+    __amdgpu_buffer_rsrc_t in;
+    int flag_mine;                       // update flag of the first stream at entry lane%32
+    int flag[UB];
+    Raw d[UB][VPL];
+    __device__ __forceinline__ void select(int ub, int ent) { flag[ub] = __shfl(flag_mine, ent, kWave); }
+    __device__ __forceinline__ void issue(int ub, int v, int, bool, uint32_t o) { d[ub][v] = ws_load16<Raw>(in, flag[ub] ? o : kOob); }
+    __device__ __forceinline__ Raw finish(int ub, int v, int) const { return d[ub][v]; }
+};
+
+template <typename T, int V, int VPL, int UB>
+__global__ __launch_bounds__(kTileThreads) void act_sparse_kernel(ListArgs l, ActArgs a, EpilogueArgs e, TailShape shape,
+                                                                   uint32_t map_bytes, uint32_t pixels) {
+    const int64_t count = list_count(l);
+    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    TailRsrc rs;
+    rs.res = ws_rsrc(e.res_data, map_bytes); rs.xA = ws_rsrc(e.xA, map_bytes); rs.xT = ws_rsrc(e.xT, map_bytes);
+    rs.out = ws_rsrc(e.out_data, map_bytes); rs.omask = ws_rsrc(e.out_mask, pixels);
+    const __amdgpu_buffer_rsrc_t rs_rmask = ws_rsrc(e.res_mask, pixels), rs_imask = ws_rsrc(a.in_mask, pixels);
+    ActSrc<T, V, VPL, UB> src;
+    src.in = ws_rsrc(a.in_data, map_bytes);
+    const int parts = kTile / shape.run;
+    int survivors = 0;
+    const int64_t ntiles = (count + kTile - 1) / kTile;
+    const WgTileRange r = wg_tile_range((ntiles * parts + kTileWaves - 1) / kTileWaves);
+    for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
+        const int64_t unit = wt * kTileWaves + wave;
+        const int64_t tile = unit / parts;
+        const int part = (int)(unit - tile * parts);
+        const int64_t base = tile * kTile;
+        if (base >= count) continue;
+        const int j = lane % kTile;
+        const int p_mine = (j / shape.run == part) ? list_pixel(l.list, base + j, count) : -1;
+        const int p_off = p_mine >= 0 ? p_mine : (int)kOob;
+        // a stream without a mask is flagged wherever the list points
+        const int rflag = e.res_mask ? __builtin_amdgcn_raw_buffer_load_b8(rs_rmask, p_off, 0, 0) : 1;
+        src.flag_mine = a.in_mask ? __builtin_amdgcn_raw_buffer_load_b8(rs_imask, p_off, 0, 0) : 1;
+        const uint32_t bits = sparse_tile_tail<T, V, VPL, UB>(e, rs, src, shape.lp, p_mine, rflag, part * shape.run,
+                                                              (part + 1) * shape.run, shape.nbatch, lane);
+        if (e.surv) { if (lane == 0) store_survivors(e.surv, tile, part, parts, bits); }
+        else survivors += __popc(bits);
+    }
+    // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
+    if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
+}
+
 // ---- activation + truncation (+ add) ----------------------------------------------------------
-template <typename T, int V, int VPL, bool SPLIT>
-__global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a, EpilogueArgs e, int init, int parts) {
+template <typename T, int V, int VPL>
+__global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a, EpilogueArgs e, int init) {
     typedef typename RawOf<T, V>::type Raw;
     constexpr int UB = (V * VPL >= 16) ? 2 : 4;
     const int64_t count = list_count(l);
@@ -50,33 +211,15 @@ __global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a
         return raw_zero<T, V>();
     };
     int survivors = 0;
-    if constexpr (SPLIT) {
-        const int64_t ntiles = (count + kTile - 1) / kTile;
-        const int run = kTile / parts;                          // tile entries per wave
-        const WgTileRange r = wg_tile_range((ntiles * parts + kTileWaves - 1) / kTileWaves);
-        for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
-            const int64_t unit = wt * kTileWaves + wave;
-            const int64_t tile = unit / parts;
-            const int part = (int)(unit - tile * parts);
-            const int64_t base = tile * kTile;
-            if (base >= count) continue;
-            const int j = lane % kTile;
-            const int p_mine = (j / run == part) ? list_pixel(l.list, base + j, count) : -1;
-            const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
-            if (e.surv) { if (lane == 0) store_survivors(e.surv, tile, part, parts, bits); }
-            else survivors += __popc(bits);
-        }
-    } else {
-        const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
-        for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
-            const int64_t tile = wt * kTileWaves + wave;
-            const int64_t base = tile * kTile;
-            if (base >= count) continue;
-            const int p_mine = list_pixel(l.list, base + lane % kTile, count);
-            const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
-            if (e.surv) { if (lane == 0) e.surv[tile] = bits; }
-            else survivors += __popc(bits);
-        }
+    const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
+    for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
+        const int64_t tile = wt * kTileWaves + wave;
+        const int64_t base = tile * kTile;
+        if (base >= count) continue;
+        const int p_mine = list_pixel(l.list, base + lane % kTile, count);
+        const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
+        if (e.surv) { if (lane == 0) e.surv[tile] = bits; }
+        else survivors += __popc(bits);
     }
     // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
     if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
@@ -88,17 +231,25 @@ static dcnn_status launch_act_t(dcnn_ctx* ctx, bool init, const ListArgs& l, con
     const bool vec = (e.c % VEC) == 0;
     const int nvec = vec ? e.c / VEC : e.c;
     const int vpl = (int)cdiv(nvec, kWave);
-    const int vpl_used = vpl <= 1 ? 1 : (vpl <= 2 ? 2 : (vpl <= 4 ? 4 : 8));
-    // pixels of 8 vectors per lane keep one wave per tile (that form holds its whole batch in registers)
-    const int parts = vpl_used <= kSplitMaxVpl ? tile_parts(nvec, vpl_used) : 1;
-    const int grid = list_grid(ctx, l.max_count, kTileWaves * kTile / parts, 8);
+    // sparse steps over vector channels, tensors below 2 GiB: the buffer-addressed kernel
+    const uint64_t map_bytes = (uint64_t)(l.max_count > 0 ? l.max_count : 0) * e.c * sizeof(T);
+    if (!init && vec && vpl <= 4 && map_bytes > 0 && map_bytes <= kWsMaxBytes) {
+        const int vpl_used = vpl <= 1 ? 1 : (vpl <= 2 ? 2 : 4);
+        const int ub = vpl_used == 4 ? 2 : 4;
+        const TailShape shape = tail_shape(nvec, vpl_used, ub);
+        const int sgrid = list_grid(ctx, l.max_count, kTileWaves * shape.run, 8);
+        const uint32_t mb = (uint32_t)map_bytes, px = (uint32_t)l.max_count;
+#define DCNN_ACT_SPARSE(VPL, UB) hipLaunchKernelGGL((act_sparse_kernel<T, VEC, VPL, UB>), dim3(sgrid), dim3(kTileThreads), 0, ctx->stream, l, a, e, shape, mb, px)
+        if (vpl_used == 1) DCNN_ACT_SPARSE(1, 4);
+        else if (vpl_used == 2) DCNN_ACT_SPARSE(2, 4);
+        else DCNN_ACT_SPARSE(4, 2);
+#undef DCNN_ACT_SPARSE
+        return check_hip(ctx, hipGetLastError(), "act_sparse_kernel launch");
+    }
+    const int grid = list_grid(ctx, l.max_count, kTileWaves * kTile, 8);
     dim3 g(grid), b(kTileThreads);
     const int ini = init ? 1 : 0;
-#define DCNN_ACT_LAUNCH(V, VPL)                                                                                      \
-    do {                                                                                                             \
-        if (parts > 1) hipLaunchKernelGGL((act_kernel<T, V, VPL, (VPL <= kSplitMaxVpl)>), g, b, 0, ctx->stream, l, a, e, ini, parts); \
-        else hipLaunchKernelGGL((act_kernel<T, V, VPL, false>), g, b, 0, ctx->stream, l, a, e, ini, 1);              \
-    } while (0)
+#define DCNN_ACT_LAUNCH(V, VPL) hipLaunchKernelGGL((act_kernel<T, V, VPL>), g, b, 0, ctx->stream, l, a, e, ini)
     if (vec) {
         if (vpl <= 1) DCNN_ACT_LAUNCH(VEC, 1);
         else if (vpl <= 2) DCNN_ACT_LAUNCH(VEC, 2);
@@ -119,14 +270,124 @@ dcnn_status launch_act(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, c
     return dtype == DCNN_F16 ? launch_act_t<f16>(ctx, init, l, a, e) : launch_act_t<float>(ctx, init, l, a, e);
 }
 
+// ---- depthwise convolution, sparse steps, 1x1 / 2x2 / 3x3 windows ------------------------------
+// The first delta stream is formed on the fly: per tile entry a tap word (bit t: window tap t is inside
+// the map and flagged) and the input pixel under tap (0,0) are computed by lane entry%32 up front; the taps
+// of a pixel are then requested back to back, an unflagged or padded tap with an out-of-range offset.
+// The [k][k][C] weights sit in LDS.
+template <typename T, int V, int VPL, int UB, int KS> struct DwSrc {
+    typedef typename RawOf<T, V>::type Raw;
+    static constexpr int KK = KS * KS;
+    __amdgpu_buffer_rsrc_t in;
+    const T* w_lds;
+    int C, w;                            // channels, input width
+    uint32_t row_bytes;
+    int word_mine, q_mine;               // of entry lane%32; q = input pixel under tap (0,0), possibly outside
+    int word[UB], q[UB];
+    Raw x[UB][VPL][KK];
+    __device__ __forceinline__ void select(int ub, int ent) {
+        word[ub] = __shfl(word_mine, ent, kWave);
+        q[ub] = __shfl(q_mine, ent, kWave);
+    }
+    __device__ __forceinline__ void issue(int ub, int v, int c0, bool on, uint32_t) {
+#pragma unroll
+        for (int t = 0; t < KK; ++t) {
+            const bool ok = on && ((word[ub] >> t) & 1);
+            const uint32_t o = ok ? (uint32_t)(q[ub] + (t / KS) * w + t % KS) * row_bytes + (uint32_t)c0 * (uint32_t)sizeof(T) : kOob;
+            x[ub][v][t] = ws_load16<Raw>(in, o);
+        }
+    }
+    __device__ __forceinline__ Raw finish(int ub, int v, int c0) const {
+        float acc[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+        const int cw = c0 < C ? c0 : 0;                          // lanes without channels read weights of channel 0 (result unused)
+#pragma unroll
+        for (int t = 0; t < KK; ++t) {
+            const Raw wv = raw_load<T, V>(w_lds + t * C + cw);
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc[i] = fmaf(raw_get<T, V>(x[ub][v][t], i), raw_get<T, V>(wv, i), acc[i]);
+        }
+        Raw o;
+#pragma unroll
+        for (int i = 0; i < V; ++i) raw_set<T, V>(o, i, acc[i]);
+        return o;
+    }
+};
+
+template <typename T, int V, int VPL, int UB, int KS>
+__global__ __launch_bounds__(kTileThreads) void dwconv_sparse_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, TailShape shape,
+                                                                      uint32_t in_bytes, uint32_t in_pixels, uint32_t map_bytes,
+                                                                      uint32_t pixels) {
+    typedef typename RawOf<T, V>::type Raw;
+    extern __shared__ __align__(16) unsigned char dw_smem[];
+    T* w_lds = reinterpret_cast<T*>(dw_smem);
+    {
+        const Raw* wsrc = static_cast<const Raw*>(c.wpacked);      // [k][k][C], unpacked
+        const int nv = KS * KS * e.c / V;
+        for (int i = threadIdx.x; i < nv; i += kTileThreads) reinterpret_cast<Raw*>(w_lds)[i] = wsrc[i];
+    }
+    __syncthreads();
+    const int64_t count = list_count(l);
+    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    TailRsrc rs;
+    rs.res = ws_rsrc(e.res_data, map_bytes); rs.xA = ws_rsrc(e.xA, map_bytes); rs.xT = ws_rsrc(e.xT, map_bytes);
+    rs.out = ws_rsrc(e.out_data, map_bytes); rs.omask = ws_rsrc(e.out_mask, pixels);
+    const __amdgpu_buffer_rsrc_t rs_rmask = ws_rsrc(e.res_mask, pixels), rs_imask = ws_rsrc(c.in_mask, in_pixels);
+    DwSrc<T, V, VPL, UB, KS> src;
+    src.in = ws_rsrc(c.in_data, in_bytes);
+    src.w_lds = w_lds; src.C = e.c; src.w = c.w; src.row_bytes = (uint32_t)e.c * (uint32_t)sizeof(T);
+    const int parts = kTile / shape.run;
+    int survivors = 0;
+    const int64_t ntiles = (count + kTile - 1) / kTile;
+    const WgTileRange r = wg_tile_range((ntiles * parts + kTileWaves - 1) / kTileWaves);
+    for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
+        const int64_t unit = wt * kTileWaves + wave;
+        const int64_t tile = unit / parts;
+        const int part = (int)(unit - tile * parts);
+        const int64_t base = tile * kTile;
+        if (base >= count) continue;
+        const int j = lane % kTile;
+        const int p_mine = (j / shape.run == part) ? list_pixel(l.list, base + j, count) : -1;
+        const int rflag = e.res_mask ? __builtin_amdgcn_raw_buffer_load_b8(rs_rmask, p_mine >= 0 ? p_mine : (int)kOob, 0, 0) : 1;
+        // tap word of this lane's entry: all flags of the window requested together
+        uint32_t word = 0;
+        int q_first = 0;
+        {
+            const int pp = p_mine >= 0 ? p_mine : 0;
+            const int ox = pp % c.ow;
+            const int t = pp / c.ow;
+            const int oy = t % c.oh, n = t / c.oh;
+            const int iy0 = oy * c.stride - c.pad, ix0 = ox * c.stride - c.pad;
+            q_first = (n * c.h + iy0) * c.w + ix0;
+            uint32_t f[KS * KS];
+#pragma unroll
+            for (int t2 = 0; t2 < KS * KS; ++t2) {
+                const int iy = iy0 + t2 / KS, ix = ix0 + t2 % KS;
+                const bool ok = p_mine >= 0 && iy >= 0 && iy < c.h && ix >= 0 && ix < c.w;
+                // without a mask (never in a sparse step of a network, possible through the layer interface) every
+                // pixel inside the map counts as flagged
+                f[t2] = ok ? (c.in_mask ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rs_imask, q_first + (t2 / KS) * c.w + t2 % KS, 0, 0) : 1u) : 0u;
+            }
+#pragma unroll
+            for (int t2 = 0; t2 < KS * KS; ++t2) word |= f[t2] ? (1u << t2) : 0u;
+        }
+        src.word_mine = (int)word; src.q_mine = q_first;
+        const uint32_t bits = sparse_tile_tail<T, V, VPL, UB>(e, rs, src, shape.lp, p_mine, rflag, part * shape.run,
+                                                              (part + 1) * shape.run, shape.nbatch, lane);
+        if (e.surv) { if (lane == 0) store_survivors(e.surv, tile, part, parts, bits); }
+        else survivors += __popc(bits);
+    }
+    // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
+    if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
+}
+
 // ---- depthwise convolution: the first delta stream is formed on the fly ------------------------
 // Work list = flagged OUTPUT pixels.  Every tap's update flag is checked before its values are
-// read (unflagged memory is invalid).  KS = 1, 2, 3: the flags of the whole tile are fetched first (entry
-// lane%32 per lane, one round trip) and packed into a tap word; the taps of a pixel are then loaded
-// back to back, an unflagged or padded tap reading the zero page instead, so no load waits for a flag.
-// KS = 0: any window, flag and values per tap.
-template <typename T, int V, int VPL, int KS>
-__global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init, int parts) {
+// read (unflagged memory is invalid), load and multiply are fused per pixel.
+template <typename T, int V, int VPL>
+__global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init) {
     typedef typename RawOf<T, V>::type Raw;
     constexpr int UB = 2;
     const int64_t count = list_count(l);
@@ -134,12 +395,7 @@ __global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvAr
     const int C = e.c;
     const T* in = static_cast<const T*>(c.in_data);
     const T* wgt = static_cast<const T*>(c.wpacked);           // [k][k][C], unpacked
-    const T* zeros = static_cast<const T*>(c.zero_page);
-    // KS > 0: per tile entry the tap word and the input pixel under tap (0,0) (which may lie outside the map);
-    // handed from the lane that computed them to the lanes that serve the entry through LDS (a lane shuffle
-    // inside the divergent per-vector code would read disabled lanes)
-    __shared__ int2 s_taps[kTileWaves][kTile];
-    auto dx_any = [&](int, int64_t p, int c0) -> Raw {
+    auto dx = [&](int, int64_t p, int c0) -> Raw {
         const int ox = (int)(p % c.ow);
         const int64_t t = p / c.ow;
         const int oy = (int)(t % c.oh);
@@ -166,79 +422,15 @@ __global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvAr
         for (int i = 0; i < V; ++i) raw_set<T, V>(o, i, acc[i]);
         return o;
     };
-    auto dx_taps = [&](int ent, int64_t, int c0) -> Raw {
-        constexpr int KK = KS > 0 ? KS * KS : 1;
-        const int2 tq = s_taps[wave][ent & (kTile - 1)];
-        const uint32_t word = (uint32_t)tq.x;
-        const int q0 = tq.y;
-        Raw xv[KK], wv[KK];
-#pragma unroll
-        for (int t = 0; t < KK; ++t) {
-            const int64_t q = (int64_t)q0 + (t / (KS > 0 ? KS : 1)) * c.w + (t % (KS > 0 ? KS : 1));
-            const T* src = ((word >> t) & 1u) ? in + q * C + c0 : zeros;
-            xv[t] = raw_load<T, V>(src);
-        }
-#pragma unroll
-        for (int t = 0; t < KK; ++t) wv[t] = raw_load<T, V>(wgt + (int64_t)t * C + c0);
-        float acc[V];
-#pragma unroll
-        for (int i = 0; i < V; ++i) acc[i] = 0.0f;
-#pragma unroll
-        for (int t = 0; t < KK; ++t)
-#pragma unroll
-            for (int i = 0; i < V; ++i) acc[i] = fmaf(raw_get<T, V>(xv[t], i), raw_get<T, V>(wv[t], i), acc[i]);
-        Raw o;
-#pragma unroll
-        for (int i = 0; i < V; ++i) raw_set<T, V>(o, i, acc[i]);
-        return o;
-    };
     int survivors = 0;
-    const int64_t ntiles = (count + kTile - 1) / kTile;
-    const WgTileRange r = wg_tile_range((ntiles * parts + kTileWaves - 1) / kTileWaves);
+    const WgTileRange r = wg_tile_range((count + kTileWaves * kTile - 1) / (kTileWaves * kTile));
     for (int64_t wt = r.begin; wt < r.end; wt += r.step) {
-        const int64_t unit = wt * kTileWaves + wave;
-        const int64_t tile = unit / parts;
-        const int part = (int)(unit - tile * parts);
+        const int64_t tile = wt * kTileWaves + wave;
         const int64_t base = tile * kTile;
         if (base >= count) continue;
-        const int j = lane % kTile;
-        const int p_mine = (j / (kTile / parts) == part) ? list_pixel(l.list, base + j, count) : -1;   // the others look empty
-        uint32_t bits;
-        if constexpr (KS > 0) {
-            uint32_t tap_word = 0;
-            int q_first = 0;
-            if (p_mine >= 0) {
-                const int ox = p_mine % c.ow;
-                const int t = p_mine / c.ow;
-                const int oy = t % c.oh, n = t / c.oh;
-                const int iy0 = oy * c.stride - c.pad, ix0 = ox * c.stride - c.pad;
-                q_first = (n * c.h + iy0) * c.w + ix0;
-                uint32_t inb = 0;
-                int qq[KS * KS];
-#pragma unroll
-                for (int t2 = 0; t2 < KS * KS; ++t2) {
-                    const int iy = iy0 + t2 / KS, ix = ix0 + t2 % KS;
-                    const bool ok = iy >= 0 && iy < c.h && ix >= 0 && ix < c.w;
-                    inb |= ok ? (1u << t2) : 0u;
-                    qq[t2] = ok ? q_first + (t2 / KS) * c.w + t2 % KS : 0;       // a tap outside the map re-reads flag 0 (ignored)
-                }
-                tap_word = inb;
-                if (c.in_mask) {
-                    uint32_t f[KS * KS];
-#pragma unroll
-                    for (int t2 = 0; t2 < KS * KS; ++t2) f[t2] = c.in_mask[qq[t2]];
-                    tap_word = 0;
-#pragma unroll
-                    for (int t2 = 0; t2 < KS * KS; ++t2) tap_word |= f[t2] ? (1u << t2) : 0u;
-                }
-                tap_word &= inb;
-            }
-            s_taps[wave][lane % kTile] = make_int2((int)tap_word, q_first);     // both wave halves store the same pair
-            bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx_taps, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
-        } else {
-            bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx_any, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
-        }
-        if (e.surv) { if (lane == 0) store_survivors(e.surv, tile, part, parts, bits); }
+        const int p_mine = list_pixel(l.list, base + lane % kTile, count);
+        const uint32_t bits = act_trunc_tile<T, V, VPL, UB, false>(e, init != 0, p_mine, lane, dx, 0, e.c, e.c, MaxExchange{nullptr, 1, 0});
+        if (e.surv) { if (lane == 0) e.surv[tile] = bits; }
         else survivors += __popc(bits);
     }
     // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
@@ -251,33 +443,46 @@ static dcnn_status launch_dwconv_t(dcnn_ctx* ctx, bool init, const ListArgs& l, 
     const bool vec = (e.c % VEC) == 0;
     const int nvec = vec ? e.c / VEC : e.c;
     const int vpl = (int)cdiv(nvec, kWave);
-    if (vpl > 4) return fail(ctx, DCNN_EUNSUPPORTED, "depthwise conv: %d channels not supported", e.c);
-    const int vpl_used = vpl <= 1 ? 1 : (vpl <= 2 ? 2 : 4);
-    const int parts = tile_parts(nvec, vpl_used);
-    const int grid = list_grid(ctx, l.max_count, kTileWaves * kTile / parts, 8);
+    // sparse steps, vector channels, windows up to 3x3, tensors below 2 GiB: the buffer-addressed kernel
+    const uint64_t map_bytes = (uint64_t)(l.max_count > 0 ? l.max_count : 0) * e.c * sizeof(T);
+    const uint64_t in_pixels = (uint64_t)c.n * c.h * c.w, in_bytes = in_pixels * e.c * sizeof(T);
+    const size_t w_bytes = (size_t)c.k * c.k * e.c * sizeof(T);
+    if (!init && vec && vpl <= 4 && c.k >= 1 && c.k <= 3 && map_bytes > 0 && map_bytes <= kWsMaxBytes && in_bytes <= kWsMaxBytes &&
+        w_bytes <= 64 * 1024) {
+        const int vpl_used = vpl <= 1 ? 1 : (vpl <= 2 ? 2 : 4);
+        const int ub = 4 / vpl_used;
+        const TailShape shape = tail_shape(nvec, vpl_used, ub);
+        const int sgrid = list_grid(ctx, l.max_count, kTileWaves * shape.run, 8);
+        const uint32_t ib = (uint32_t)in_bytes, ip = (uint32_t)in_pixels, mb = (uint32_t)map_bytes, px = (uint32_t)l.max_count;
+#define DCNN_DW_SPARSE(VPL, UB, KS) hipLaunchKernelGGL((dwconv_sparse_kernel<T, VEC, VPL, UB, KS>), dim3(sgrid), dim3(kTileThreads), w_bytes, ctx->stream, l, c, e, shape, ib, ip, mb, px)
+#define DCNN_DW_SPARSE_K(VPL, UB)                                                                                  \
+    do {                                                                                                           \
+        if (c.k == 3) DCNN_DW_SPARSE(VPL, UB, 3);                                                                  \
+        else if (c.k == 2) DCNN_DW_SPARSE(VPL, UB, 2);                                                             \
+        else DCNN_DW_SPARSE(VPL, UB, 1);                                                                           \
+    } while (0)
+        if (vpl_used == 1) DCNN_DW_SPARSE_K(1, 4);
+        else if (vpl_used == 2) DCNN_DW_SPARSE_K(2, 2);
+        else DCNN_DW_SPARSE_K(4, 1);
+#undef DCNN_DW_SPARSE_K
+#undef DCNN_DW_SPARSE
+        return check_hip(ctx, hipGetLastError(), "dwconv_sparse_kernel launch");
+    }
+    const int grid = list_grid(ctx, l.max_count, kTileWaves * kTile, 8);
     dim3 g(grid), b(kTileThreads);
     const int ini = init ? 1 : 0;
-    // the tap-word forms address input pixels with 32-bit indices
-    const bool small = (int64_t)c.n * c.h * c.w < ((int64_t)1 << 31) - 4 * (int64_t)c.w;
-    const int ks = (small && c.k >= 1 && c.k <= 3) ? c.k : 0;
-#define DCNN_DW_LAUNCH(V, VPL, KS) hipLaunchKernelGGL((dwconv_kernel<T, V, VPL, KS>), g, b, 0, ctx->stream, l, c, e, ini, parts)
-#define DCNN_DW_KS(V, VPL)                                                                                         \
-    do {                                                                                                           \
-        if (ks == 3) DCNN_DW_LAUNCH(V, VPL, 3);                                                                    \
-        else if (ks == 2) DCNN_DW_LAUNCH(V, VPL, 2);                                                               \
-        else if (ks == 1) DCNN_DW_LAUNCH(V, VPL, 1);                                                               \
-        else DCNN_DW_LAUNCH(V, VPL, 0);                                                                            \
-    } while (0)
+#define DCNN_DW_LAUNCH(V, VPL) hipLaunchKernelGGL((dwconv_kernel<T, V, VPL>), g, b, 0, ctx->stream, l, c, e, ini)
     if (vec) {
-        if (vpl_used == 1) DCNN_DW_KS(VEC, 1);
-        else if (vpl_used == 2) DCNN_DW_KS(VEC, 2);
-        else DCNN_DW_KS(VEC, 4);
+        if (vpl <= 1) DCNN_DW_LAUNCH(VEC, 1);
+        else if (vpl <= 2) DCNN_DW_LAUNCH(VEC, 2);
+        else if (vpl <= 4) DCNN_DW_LAUNCH(VEC, 4);
+        else return fail(ctx, DCNN_EUNSUPPORTED, "depthwise conv: %d channels not supported", e.c);
     } else {
-        if (vpl_used == 1) DCNN_DW_KS(1, 1);
-        else if (vpl_used == 2) DCNN_DW_KS(1, 2);
-        else DCNN_DW_KS(1, 4);
+        if (vpl <= 1) DCNN_DW_LAUNCH(1, 1);
+        else if (vpl <= 2) DCNN_DW_LAUNCH(1, 2);
+        else if (vpl <= 4) DCNN_DW_LAUNCH(1, 4);
+        else return fail(ctx, DCNN_EUNSUPPORTED, "depthwise conv: %d channels not supported", e.c);
     }
-#undef DCNN_DW_KS
 #undef DCNN_DW_LAUNCH
     return check_hip(ctx, hipGetLastError(), "dwconv_kernel launch");
 }
