@@ -140,7 +140,10 @@ typedef struct dcnn_net dcnn_net;
 /* ---- context ------------------------------------------------------------------------------- */
 /* hip_stream: a hipStream_t (may be NULL = default stream), borrowed.  workspace_dev: scratch
  * shared by all layers of the context (partial counts, survivor bits); dcnn_workspace_bytes(p)
- * is enough for any layer whose output has at most p = n*h*w pixels. */
+ * is enough for any layer whose output has at most p = n*h*w pixels.  dcnn_ctx_create clears the
+ * workspace (asynchronously, on the stream); the library keeps a few control words in its last 256
+ * bytes, so the memory must not be written by anything else while the context lives, and all work
+ * of one context is issued to its one stream. */
 size_t      dcnn_workspace_bytes(int64_t max_pixels);
 dcnn_status dcnn_ctx_create(void* hip_stream, void* workspace_dev, size_t workspace_bytes, dcnn_ctx** out);
 void        dcnn_ctx_destroy(dcnn_ctx* ctx);
@@ -179,6 +182,10 @@ dcnn_status dcnn_layer_step(dcnn_layer* layer, const dcnn_delta* const* in, int3
 dcnn_status dcnn_layer_output(const dcnn_layer* layer, dcnn_delta* out_view);
 /* Forget the buffers: the next call must be dcnn_layer_init (supplementary Section 1.4). */
 dcnn_status dcnn_layer_reset(dcnn_layer* layer);
+/* Replace the truncation threshold of a layer that has one (DCNN_DELTAGEN, or any layer with an
+ * activation): thresholds are per layer and tuned front to back (Section 4).  Takes effect at the next
+ * step; the buffers are kept.  DCNN_EINVAL for NaN or for a layer without a threshold. */
+dcnn_status dcnn_layer_set_eps(dcnn_layer* layer, float eps);
 /* which: 0 = x^A (ACT/CONV+act/MAXPOOL), stored frame (DELTAGEN), dense output (ACCUM); 1 = x^T;
  * 2 = dense output of a layer with fuse_accum.
  * Returns the device pointer and byte size of that buffer inside the state memory. */

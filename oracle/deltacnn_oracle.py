@@ -421,6 +421,37 @@ class OracleNet:
         return dens
 
 
+def tune_thresholds(onet: "OracleNet", video: np.ndarray, target: float, lo: float = 1e-4, hi: float = 16.0,
+                    iters: int = 10) -> dict:
+    """Density-budget analogue of the front-to-back threshold tuning of Section 4 (which needs a
+    dataset and a loss): for every node with a threshold (input layer, activations) in
+    topological order, earlier thresholds fixed, bisect on a geometric scale for the smallest
+    threshold at which the node flags at most `target` of its output pixels, averaged over the
+    sparse frames of `video` ([T, N, H, W, C]).  Returns {node: threshold} and leaves them set."""
+    found = {}
+    for v, (nd, ly) in enumerate(zip(onet.net["nodes"], onet.layers)):
+        if nd["kind"] not in ("deltagen", "act"):
+            continue
+        a, b = lo, hi
+        for _ in range(iters):
+            mid = float(np.sqrt(a * b))
+            ly.eps = mid
+            onet.reset()
+            onet.frame(video[0])
+            dens = []
+            for t in range(1, video.shape[0]):
+                onet.frame(video[t])
+                dens.append(float(onet.outs[v].mask.mean()))
+            if sum(dens) / len(dens) > target:
+                a = mid
+            else:
+                b = mid
+        ly.eps = b
+        found[v] = b
+    onet.reset()
+    return found
+
+
 def dense_reference(net: dict, weights: dict, x: np.ndarray) -> np.ndarray:
     """Ordinary per-frame inference in float64 (what the method must reproduce
     when nothing is truncated)."""

@@ -29,7 +29,7 @@ EXPORTS = [
     "dcnn_workspace_bytes", "dcnn_ctx_create", "dcnn_ctx_destroy", "dcnn_ctx_sync", "dcnn_status_str",
     "dcnn_last_error", "dcnn_mask_compact", "dcnn_layer_query", "dcnn_layer_create", "dcnn_layer_destroy",
     "dcnn_layer_init", "dcnn_layer_step", "dcnn_layer_output", "dcnn_layer_reset", "dcnn_layer_state",
-    "dcnn_layer_stats", "dcnn_layer_set_timing", "dcnn_layer_timing", "dcnn_net_create", "dcnn_net_destroy", "dcnn_net_add", "dcnn_net_finalize",
+    "dcnn_layer_stats", "dcnn_layer_set_eps", "dcnn_layer_set_timing", "dcnn_layer_timing", "dcnn_net_create", "dcnn_net_destroy", "dcnn_net_add", "dcnn_net_finalize",
     "dcnn_net_bind", "dcnn_net_init", "dcnn_net_step", "dcnn_net_reset", "dcnn_net_output",
     "dcnn_net_num_layers", "dcnn_net_layer", "dcnn_net_stats",
 ]
@@ -107,6 +107,7 @@ def load_library() -> C.CDLL:
     lib.dcnn_layer_reset.argtypes = [vp]
     lib.dcnn_layer_state.argtypes = [vp, i32, P(vp), P(sz)]
     lib.dcnn_layer_stats.argtypes = [vp, P(Stats)]
+    lib.dcnn_layer_set_eps.argtypes = [vp, C.c_float]
     lib.dcnn_layer_set_timing.argtypes = [vp, i32]
     lib.dcnn_layer_timing.argtypes = [vp, P(C.c_float), P(i32)]
     lib.dcnn_net_create.argtypes = [vp, i32, i32, i32, i32, i32, P(vp)]
@@ -276,6 +277,9 @@ class Layer:
     def reset(self):
         self.ctx.check(self.ctx.lib.dcnn_layer_reset(self.handle))
 
+    def set_eps(self, eps: float):
+        self.ctx.check(self.ctx.lib.dcnn_layer_set_eps(self.handle, float(eps)))
+
     def state_tensor(self, which: int) -> torch.Tensor:
         p, n = C.c_void_p(), C.c_size_t()
         self.ctx.check(self.ctx.lib.dcnn_layer_state(self.handle, which, C.byref(p), C.byref(n)))
@@ -390,6 +394,18 @@ class Net:
         arr = (Stats * self.num_layers)()
         self.ctx.check(self.ctx.lib.dcnn_net_stats(self.handle, arr))
         return [s.as_dict() for s in arr]
+
+    def layer_node(self, i: int) -> int:
+        """Node of the topology table whose output planned layer i produces."""
+        lh, nid = C.c_void_p(), C.c_int32()
+        self.ctx.check(self.ctx.lib.dcnn_net_layer(self.handle, i, C.byref(lh), C.byref(nid)))
+        return nid.value
+
+    def set_eps(self, i: int, eps: float):
+        """New truncation threshold for planned layer i (input layer or a layer with an activation)."""
+        lh, nid = C.c_void_p(), C.c_int32()
+        self.ctx.check(self.ctx.lib.dcnn_net_layer(self.handle, i, C.byref(lh), C.byref(nid)))
+        self.ctx.check(self.ctx.lib.dcnn_layer_set_eps(lh, float(eps)))
 
     def set_timing(self, i: int, max_steps: int):
         lh, nid = C.c_void_p(), C.c_int32()

@@ -322,6 +322,15 @@ void dcnn_layer_destroy(dcnn_layer* layer) {
     delete layer;
 }
 
+dcnn_status dcnn_layer_set_eps(dcnn_layer* L, float eps) {
+    if (!L) return DCNN_EINVAL;
+    if (eps != eps) return fail(L->ctx, DCNN_EINVAL, "set_eps: the threshold is NaN");
+    if (L->d.kind != DCNN_DELTAGEN && L->d.act == DCNN_ACT_NONE)
+        return fail(L->ctx, DCNN_EINVAL, "set_eps: the layer has no truncation threshold");
+    L->d.eps = eps;
+    return DCNN_OK;
+}
+
 dcnn_status dcnn_layer_set_timing(dcnn_layer* L, int32_t max_steps) {
     if (!L) return DCNN_EINVAL;
     if (max_steps < 0 || max_steps > 65536) return fail(L->ctx, DCNN_EINVAL, "set_timing: max_steps out of range");

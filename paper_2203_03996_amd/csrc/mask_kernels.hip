@@ -94,11 +94,9 @@ struct MaskKernelArgs {
     int kw, pad_w;                // window columns and their padding (rows: k, pad)
 };
 
-__global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs a) {
-    __shared__ int s_red[kMaskThreads / kWave];
-    const int64_t p0 = (int64_t)blockIdx.x * kChunk + (int64_t)threadIdx.x * kPxPerThread;
+// Output flags of the 8 pixels from p0 on (byte i of the word: pixel p0+i), also stored to the output mask.
+__device__ __forceinline__ uint64_t mask_word(const MaskKernelArgs& a, int64_t p0) {
     uint64_t word = 0;
-    int cnt = 0;
     if (p0 < a.out_pixels) {
         const bool b_same = a.mask_b == nullptr || a.b_stride <= 0;
         const bool square = a.kw == a.k && a.pad_w == a.pad;
@@ -140,14 +138,20 @@ __global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs 
                 if (++ox == a.ow) { ox = 0; if (++oy == a.oh) { oy = 0; ++n; } }
             }
         }
-        cnt = __popcll(word);
         if (p0 + kPxPerThread <= a.out_pixels) {
             *reinterpret_cast<uint64_t*>(a.mask_out + p0) = word;
         } else {
             for (int i = 0; p0 + i < a.out_pixels; ++i) a.mask_out[p0 + i] = (uint8_t)((word >> (8 * i)) & 1);
         }
     }
-    const int total = block_sum(cnt, s_red);
+    return word;
+}
+
+__global__ __launch_bounds__(kMaskThreads) void mask_pass_kernel(MaskKernelArgs a) {
+    __shared__ int s_red[kMaskThreads / kWave];
+    const int64_t p0 = (int64_t)blockIdx.x * kChunk + (int64_t)threadIdx.x * kPxPerThread;
+    const uint64_t word = mask_word(a, p0);
+    const int total = block_sum(__popcll(word), s_red);
     if (threadIdx.x == 0) {
         a.chunk_counts[blockIdx.x] = total;
         if (blockIdx.x == 0 && a.zero_count) *a.zero_count = 0;
@@ -167,26 +171,8 @@ struct EmitArgs {
     int b_stride, b_h, b_w;
 };
 
-__global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
-    __shared__ int s_red[kMaskThreads / kWave];
-    const int chunk = blockIdx.x;
-    const bool last = chunk == (int)gridDim.x - 1;
-    const int mine = a.chunk_counts[chunk];
-    if (mine == 0 && !last) return;                           // uniform for the block
-    int part = 0;
-    for (int i = threadIdx.x; i < chunk; i += kMaskThreads) part += a.chunk_counts[i];
-    const int prefix = block_sum(part, s_red);
-    if (last && threadIdx.x == 0) *a.count_out = prefix + mine;
-    if (mine == 0) return;
-    const int64_t p0 = (int64_t)chunk * kChunk + (int64_t)threadIdx.x * kPxPerThread;
-    uint64_t word = 0;
-    if (p0 + kPxPerThread <= a.pixels) {
-        word = *reinterpret_cast<const uint64_t*>(a.mask + p0);
-    } else {
-        for (int i = 0; p0 + i < a.pixels; ++i) word |= (uint64_t)(a.mask[p0 + i] ? 1 : 0) << (8 * i);
-    }
-    int total;
-    int pos = prefix + block_exclusive_scan(__popcll(word), s_red, &total);
+// List entries (and tap words) of the flagged pixels among p0 .. p0+7, written from position `pos` on.
+__device__ __forceinline__ void emit_entries(const EmitArgs& a, int64_t p0, uint64_t word, int pos) {
     if (a.taps_out == nullptr) {
         for (int i = 0; i < kPxPerThread; ++i)
             if ((word >> (8 * i)) & 1) a.idx_out[pos++] = (int32_t)(p0 + i);
@@ -234,6 +220,84 @@ __global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
     }
 }
 
+
+__global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
+    __shared__ int s_red[kMaskThreads / kWave];
+    const int chunk = blockIdx.x;
+    const bool last = chunk == (int)gridDim.x - 1;
+    const int mine = a.chunk_counts[chunk];
+    if (mine == 0 && !last) return;                           // uniform for the block
+    int part = 0;
+    for (int i = threadIdx.x; i < chunk; i += kMaskThreads) part += a.chunk_counts[i];
+    const int prefix = block_sum(part, s_red);
+    if (last && threadIdx.x == 0) *a.count_out = prefix + mine;
+    if (mine == 0) return;
+    const int64_t p0 = (int64_t)chunk * kChunk + (int64_t)threadIdx.x * kPxPerThread;
+    uint64_t word = 0;
+    if (p0 + kPxPerThread <= a.pixels) {
+        word = *reinterpret_cast<const uint64_t*>(a.mask + p0);
+    } else {
+        for (int i = 0; p0 + i < a.pixels; ++i) word |= (uint64_t)(a.mask[p0 + i] ? 1 : 0) << (8 * i);
+    }
+    int total;
+    const int pos = prefix + block_exclusive_scan(__popcll(word), s_red, &total);
+    emit_entries(a, p0, word, pos);
+}
+
+// ---- mask pass and list emission in one launch -------------------------------------------------------
+// Chunks are handed out by a ticket counter, so the workgroups of all earlier chunks have started when a
+// workgroup looks for their counts: it publishes its own count first (bit 31 = published), then waits for the
+// earlier ones, which never wait for it.  The waits are bounded: a count that does not arrive sets the error
+// word and the kernel still ends.  The last workgroup to finish puts the counter and the published words back
+// to zero, so the next launch (or a replay of a captured one) starts from the same state.
+constexpr uint32_t kPublished = 0x80000000u;
+constexpr int kSpinLimit = 1 << 20;
+constexpr int kFusedMaxChunks = 32;
+
+__global__ __launch_bounds__(kMaskThreads) void mask_emit_kernel(MaskKernelArgs a, EmitArgs e, int32_t* ctl, int nchunks) {
+    __shared__ int s_red[kMaskThreads / kWave];
+    __shared__ int s_word;
+    if (threadIdx.x == 0) s_word = atomicAdd(&ctl[0], 1);
+    __syncthreads();
+    const int chunk = s_word;
+    const bool last = chunk == nchunks - 1;
+    uint32_t* status = reinterpret_cast<uint32_t*>(a.chunk_counts);
+    if (chunk < nchunks) {                                     // always true: one workgroup per chunk
+        const int64_t p0 = (int64_t)chunk * kChunk + (int64_t)threadIdx.x * kPxPerThread;
+        const uint64_t word = mask_word(a, p0);
+        int total;
+        const int loc = block_exclusive_scan(__popcll(word), s_red, &total);
+        if (threadIdx.x == 0) {
+            __hip_atomic_store(&status[chunk], kPublished | (uint32_t)total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (chunk == 0 && a.zero_count) *a.zero_count = 0;
+        }
+        if (total != 0 || last) {                              // uniform for the block
+            int part = 0;
+            bool arrived = true;
+            for (int i = threadIdx.x; i < chunk; i += kMaskThreads) {
+                uint32_t v = __hip_atomic_load(&status[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int spins = 0; !(v & kPublished) && spins < kSpinLimit; ++spins) {
+                    __builtin_amdgcn_s_sleep(2);
+                    v = __hip_atomic_load(&status[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (!(v & kPublished)) arrived = false;
+                part += (int)(v & ~kPublished);
+            }
+            if (!arrived) __hip_atomic_store(&ctl[2], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int prefix = block_sum(part, s_red);
+            if (last && threadIdx.x == 0) *e.count_out = prefix + total;
+            if (total != 0) emit_entries(e, p0, word, prefix + loc);
+        }
+    }
+    __syncthreads();                                           // every wait of this workgroup is over
+    if (threadIdx.x == 0) s_word = atomicAdd(&ctl[1], 1);
+    __syncthreads();
+    if (s_word == (int)gridDim.x - 1) {                        // every other workgroup has finished waiting as well
+        for (int i = threadIdx.x; i < nchunks; i += kMaskThreads) status[i] = 0;
+        if (threadIdx.x == 0) { ctl[0] = 0; ctl[1] = 0; }
+    }
+}
+
 dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
     const int64_t out_pixels = (int64_t)m.n * m.oh * m.ow;
     if (out_pixels <= 0 || out_pixels > INT32_MAX) return fail(ctx, DCNN_ESHAPE, "mask pass: bad pixel count");
@@ -242,8 +306,11 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
     if (st != DCNN_OK) return st;
     const int nchunks = (int)cdiv(out_pixels, kChunk);
     const uint8_t* emit_mask = m.mask_in;
+    // one launch for small maps (the waits for earlier chunks are short); large maps keep the two passes, whose
+    // chunks never wait for each other
+    const bool fused = !m.emit_only && m.idx_out != nullptr && nchunks <= kFusedMaxChunks;
+    MaskKernelArgs a{};
     if (!m.emit_only) {
-        MaskKernelArgs a{};
         a.mask_in = m.mask_in; a.mask_b = m.mask_b;
         a.mask_out = m.mask_out ? m.mask_out : ws.scratch_mask;
         a.chunk_counts = ws.chunk_counts;
@@ -254,9 +321,11 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
         a.up = m.up > 1 ? m.up : 1;
         a.b_stride = m.b_stride; a.b_h = m.b_h; a.b_w = m.b_w;
         a.kw = m.kw > 0 ? m.kw : m.k; a.pad_w = m.kw > 0 ? m.pad_w : m.pad;
-        hipLaunchKernelGGL(mask_pass_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, a);
-        st = check_hip(ctx, hipGetLastError(), "mask_pass_kernel launch");
-        if (st != DCNN_OK) return st;
+        if (!fused) {
+            hipLaunchKernelGGL(mask_pass_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, a);
+            st = check_hip(ctx, hipGetLastError(), "mask_pass_kernel launch");
+            if (st != DCNN_OK) return st;
+        }
         emit_mask = a.mask_out;
     }
     if (m.idx_out == nullptr) return DCNN_OK;
@@ -264,6 +333,10 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
     e.tap_mask = m.mask_in; e.taps_out = (m.emit_only || m.up > 1 || m.k * m.k > 25 || m.kw > 0) ? nullptr : m.taps_out;
     e.h = m.h; e.w = m.w; e.oh = m.oh; e.ow = m.ow; e.k = m.k; e.stride = m.stride; e.pad = m.pad;
     e.mask_b = m.mask_b; e.b_stride = m.b_stride; e.b_h = m.b_h; e.b_w = m.b_w;
+    if (fused) {
+        hipLaunchKernelGGL(mask_emit_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, a, e, scan_control(ctx), nchunks);
+        return check_hip(ctx, hipGetLastError(), "mask_emit_kernel launch");
+    }
     hipLaunchKernelGGL(emit_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, e);
     return check_hip(ctx, hipGetLastError(), "emit_kernel launch");
 }

@@ -278,3 +278,39 @@ def test_tensors_beyond_2gib_take_the_plain_kernels():
             (sn.init if t == 0 else sn.step)(frame[b:b + 1].contiguous(), solo_out)
             solo_ctx.sync()
             assert torch.equal(view.data[b], solo_out[0]), f"frame {t} stream {b}: differs from the stream alone"
+
+
+def test_density_budget_tuner_matches_the_oracle():
+    """Thresholds found front to back on a density budget: the library's tuner (every frame through the HIP
+    kernels) and the oracle's arrive at the same threshold for every layer, and the densities they were
+    decided on are equal."""
+    from paper_2203_03996_amd import tuner
+    spec = wl.tiny_mixed_net(eps=0.05, frames=5)
+    seed, n_streams = 3, 2
+    wts = wl.make_weights(spec, seed)
+    vid = wl.make_batch(spec["video"], seed, n_streams).astype(np.float32)
+    target, lo, hi, iters = 0.3, 1e-4, 16.0, 8
+    onet = orc.OracleNet(spec, wts, "f32")
+    want = orc.tune_thresholds(onet, vid, target, lo, hi, iters)
+
+    shapes = wl.node_shapes(spec)
+    ctx = pkg.Context(n_streams * max(h * w for h, w, _ in shapes))
+    net = pkg.Net(ctx, spec, wts, n_streams, 3)
+    frames = [torch.from_numpy(vid[t]).cuda() for t in range(vid.shape[0])]
+    # stats need one step to exist
+    net.init(frames[0]); net.step(frames[1])
+    layers = tuner.tunable_layers(net)
+    assert [net.layer_node(i) for i in layers] == sorted(want)
+    got = tuner.tune_thresholds(net, frames, target, lo, hi, iters)
+    for i in layers:
+        assert got[i] == pytest.approx(want[net.layer_node(i)], rel=1e-12), f"layer {i} (node {net.layer_node(i)})"
+    # with the tuned thresholds both sides flag the same number of pixels in every tuned layer
+    net.reset(); onet.reset()
+    net.init(frames[0]); onet.frame(vid[0])
+    for t in range(1, vid.shape[0]):
+        net.step(frames[t]); onet.frame(vid[t])
+        st = net.stats()
+        for i in layers:
+            assert st[i]["pixels_out"] == int(onet.outs[net.layer_node(i)].mask.sum()), f"frame {t} layer {i}"
+    with pytest.raises(pkg.DcnnError):
+        net.set_eps(1, float("nan"))

@@ -479,3 +479,40 @@ def test_concat_by_hand():
     assert np.isnan(out.data[0, 2, 0]).all()
     dense = orc.Concat("f64").init(np.ones((1, 2, 2, 3)), np.zeros((1, 2, 2, 1)))
     assert dense.shape == (1, 2, 2, 4) and dense[0, 1, 1].tolist() == [1.0, 1.0, 1.0, 0.0]
+
+
+def test_density_budget_tuner_meets_the_budget_with_the_smallest_probed_threshold():
+    """Front-to-back tuning on a density budget (dataset-free analogue of Section 4): after tuning, every
+    node with a threshold emits at most `target` of its pixels on the clip, and one bisection step below the
+    threshold found (earlier thresholds unchanged) the budget is exceeded -- unless the search ended at its
+    lower bound."""
+    spec = wl.tiny_mixed_net(eps=0.05, frames=5)
+    wts = wl.make_weights(spec, 3)
+    vid = wl.make_batch(spec["video"], 3, 1).astype(np.float32)
+    net = orc.OracleNet(spec, wts, "f32")
+    target, lo, hi, iters = 0.3, 1e-4, 16.0, 8
+    found = orc.tune_thresholds(net, vid, target, lo, hi, iters)
+    assert sorted(found) == [i for i, nd in enumerate(spec["nodes"]) if nd["kind"] in ("deltagen", "act")]
+
+    def density(v):
+        net.reset()
+        net.frame(vid[0])
+        d = []
+        for t in range(1, vid.shape[0]):
+            net.frame(vid[t])
+            d.append(float(net.outs[v].mask.mean()))
+        return sum(d) / len(d)
+
+    step = (hi / lo) ** (2.0 ** -iters)                          # ratio between the last two probes of a bisection
+    for v in sorted(found):
+        for u, e in found.items():
+            net.layers[u].eps = e
+        assert density(v) <= target
+        if found[v] / step > lo * step:
+            net.layers[v].eps = found[v] / step
+            # later thresholds do not influence node v; earlier ones are as they were during the search
+            assert density(v) > target, f"node {v}: a smaller threshold also meets the budget"
+    # a looser budget never needs larger thresholds at the input layer
+    net2 = orc.OracleNet(spec, wts, "f32")
+    found2 = orc.tune_thresholds(net2, vid, 0.6, lo, hi, iters)
+    assert found2[0] <= found[0]
