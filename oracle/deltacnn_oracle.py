@@ -332,6 +332,77 @@ class Upsample:
         return Delta(self.init(d.data), np.repeat(np.repeat(d.mask, self.r, axis=1), self.r, axis=2))
 
 
+def bilinear_taps(o: int, r: int, size: int):
+    """Source indices and weights of output coordinate `o` of a bilinear upsampling by the
+    integer factor r with half-pixel centres: the sample position is (o + 0.5) / r - 0.5 =
+    (2o + 1 - r) / 2r, clamped to the map.  Integer arithmetic decides which sources carry
+    weight, so "weight is zero" is exact."""
+    num, den = 2 * o + 1 - r, 2 * r
+    if num <= 0:
+        return [(0, 1.0)]
+    i0, rem = divmod(num, den)
+    if i0 >= size - 1:
+        return [(size - 1, 1.0)]
+    if rem == 0:
+        return [(i0, 1.0)]
+    w1 = rem / den
+    return [(i0, 1.0 - w1), (i0 + 1, w1)]
+
+
+class UpsampleBilinear:
+    """Bilinear upsampling by an integer factor (half-pixel centres): linear, stateless
+    (Section 3.4 lists bilinear upsampling with the supported layers).  An output pixel is
+    flagged iff a source pixel that carries weight is flagged; unflagged sources contribute
+    zeros."""
+
+    def __init__(self, factor: int, S: str = "f32"):
+        self.r, self.S = int(factor), S
+
+    def _apply(self, x: np.ndarray, mask):
+        n, h, w, c = x.shape
+        r = self.r
+        out = np.zeros((n, h * r, w * r, c), np.float64)
+        m = np.zeros((n, h * r, w * r), np.uint8)
+        for oy in range(h * r):
+            ty = bilinear_taps(oy, r, h)
+            for ox in range(w * r):
+                tx = bilinear_taps(ox, r, w)
+                for iy, wy in ty:
+                    for ix, wx in tx:
+                        out[:, oy, ox, :] += wy * wx * x[:, iy, ix, :]
+                        if mask is not None:
+                            m[:, oy, ox] |= mask[:, iy, ix]
+        return out, m
+
+    def init(self, x: np.ndarray) -> np.ndarray:
+        return self._apply(x.astype(np.float64), None)[0].astype(_STORE[self.S])
+
+    def step(self, d: Delta) -> Delta:
+        out, m = self._apply(d.zero_filled().astype(np.float64), d.mask)
+        o = out.astype(_STORE[self.S])
+        o[m == 0] = np.nan
+        return Delta(o, m)
+
+
+class GlobalAvgPool:
+    """Global average pooling to a 1x1 map (linear, stateless; Section 3.4 lists average pooling
+    with the supported layers): the output pixel of a stream is flagged iff any of its input
+    pixels is; unflagged inputs contribute zeros."""
+
+    def __init__(self, S: str = "f32"):
+        self.S = S
+
+    def init(self, x: np.ndarray) -> np.ndarray:
+        return x.astype(np.float64).mean(axis=(1, 2), keepdims=True).astype(_STORE[self.S])
+
+    def step(self, d: Delta) -> Delta:
+        n, h, w, c = d.data.shape
+        m = d.mask.reshape(n, -1).any(axis=1).astype(np.uint8).reshape(n, 1, 1)
+        o = (d.zero_filled().astype(np.float64).sum(axis=(1, 2), keepdims=True) / (h * w)).astype(_STORE[self.S])
+        o[m == 0] = np.nan
+        return Delta(o, m)
+
+
 class Accumulate:
     """Output layer (Fig. 2: deltas are accumulated onto the previous dense output)."""
 
@@ -372,6 +443,10 @@ def build_layers(net: dict, weights: dict, S: str, use_xT: bool = True):
             layers.append(MaxPool(nd["k"], nd["stride"], nd["pad"], S))
         elif k == "upsample":
             layers.append(Upsample(nd["factor"], S))
+        elif k == "upsample_bilinear":
+            layers.append(UpsampleBilinear(nd["factor"], S))
+        elif k == "gavgpool":
+            layers.append(GlobalAvgPool(S))
         elif k == "accum":
             layers.append(Accumulate(S))
         else:
@@ -474,6 +549,10 @@ def dense_reference(net: dict, weights: dict, x: np.ndarray) -> np.ndarray:
             y = maxpool_dense(ins[0], nd["k"], nd["stride"], nd["pad"])
         elif k == "upsample":
             y = np.repeat(np.repeat(ins[0], nd["factor"], axis=1), nd["factor"], axis=2)
+        elif k == "upsample_bilinear":
+            y = UpsampleBilinear(nd["factor"], "f64").init(ins[0])
+        elif k == "gavgpool":
+            y = ins[0].mean(axis=(1, 2), keepdims=True)
         elif k == "accum":
             y = ins[0]
         else:

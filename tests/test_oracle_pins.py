@@ -32,6 +32,7 @@ NETS_DENSE_MODE = {
     "bottleneck": lambda e: wl.bottleneck_block(eps=e, h=12, w=12, cin=8, mid=8, cout=16, frames=4, n_objects=1),
     "mixed": lambda e: wl.tiny_mixed_net(eps=e, frames=4),
     "concat": lambda e: wl.tiny_concat_net(eps=e, frames=4),
+    "pool": lambda e: wl.tiny_pool_net(eps=e, frames=4),
 }
 
 
@@ -516,3 +517,48 @@ def test_density_budget_tuner_meets_the_budget_with_the_smallest_probed_threshol
     net2 = orc.OracleNet(spec, wts, "f32")
     found2 = orc.tune_thresholds(net2, vid, 0.6, lo, hi, iters)
     assert found2[0] <= found[0]
+
+
+@pytest.mark.parametrize("r", [2, 3, 4])
+def test_bilinear_upsampling_against_torch(r):
+    """Half-pixel-centre bilinear upsampling: dense values equal torch's (align_corners=False); a sparse step
+    is the same operator on the zero-filled delta, and the output mask is exactly the support of the
+    interpolated 0/1 mask (a source flags an output pixel iff it carries weight there)."""
+    rng = np.random.default_rng(r)
+    x = rng.normal(size=(2, 5, 7, 3))
+    up = orc.UpsampleBilinear(r, "f64")
+    tx = torch.from_numpy(x).permute(0, 3, 1, 2)
+    ref = F.interpolate(tx, scale_factor=r, mode="bilinear", align_corners=False).permute(0, 2, 3, 1).numpy()
+    assert np.abs(up.init(x) - ref).max() < 1e-13
+    mask = (rng.random((2, 5, 7)) < 0.2).astype(np.uint8)
+    d = Delta(np.where(mask[..., None] > 0, x, np.nan), mask)
+    out = up.step(d)
+    zf = torch.from_numpy(np.where(mask[..., None] > 0, x, 0.0)).permute(0, 3, 1, 2)
+    ref_d = F.interpolate(zf, scale_factor=r, mode="bilinear", align_corners=False).permute(0, 2, 3, 1).numpy()
+    ref_m = F.interpolate(torch.from_numpy(mask.astype(np.float64))[:, None], scale_factor=r, mode="bilinear",
+                          align_corners=False)[:, 0].numpy() > 0
+    assert np.array_equal(out.mask.astype(bool), ref_m)
+    assert np.abs(out.zero_filled() - np.where(ref_m[..., None], ref_d, 0.0)).max() < 1e-13
+    assert np.isnan(out.data[out.mask == 0]).all()
+    # the tap rule by hand: factor 2, output 0 sits on source 0; output 1 = 3/4 * s0 + 1/4 * s1
+    assert orc.bilinear_taps(0, 2, 5) == [(0, 1.0)]
+    assert orc.bilinear_taps(1, 2, 5) == [(0, 0.75), (1, 0.25)]
+    assert orc.bilinear_taps(9, 2, 5) == [(4, 1.0)]
+    assert orc.bilinear_taps(1, 3, 5) == [(0, 1.0)]             # sample position exactly on source 0: source 1 carries no weight
+
+
+def test_global_average_pooling_against_torch_and_by_hand():
+    rng = np.random.default_rng(4)
+    x = rng.normal(size=(3, 4, 6, 5))
+    gap = orc.GlobalAvgPool("f64")
+    ref = F.adaptive_avg_pool2d(torch.from_numpy(x).permute(0, 3, 1, 2), 1).permute(0, 2, 3, 1).numpy()
+    assert np.abs(gap.init(x) - ref).max() < 1e-14
+    mask = np.zeros((3, 4, 6), np.uint8)
+    mask[0, 1, 2] = mask[0, 3, 5] = 1                           # stream 0: two updates; stream 1: none; stream 2: one
+    mask[2, 0, 0] = 1
+    d = Delta(np.where(mask[..., None] > 0, x, np.nan), mask)
+    out = gap.step(d)
+    assert out.mask.reshape(-1).tolist() == [1, 0, 1]
+    assert np.allclose(out.data[0, 0, 0], (x[0, 1, 2] + x[0, 3, 5]) / 24.0, rtol=0, atol=1e-15)
+    assert np.allclose(out.data[2, 0, 0], x[2, 0, 0] / 24.0, rtol=0, atol=1e-15)
+    assert np.isnan(out.data[1]).all()

@@ -8,5 +8,5 @@ consume what it produces; neither is imported here.
 from .video import VideoSpec, make_video, make_batch          # noqa: F401
 from .nets import (                                            # noqa: F401
     single_conv_relu, bottleneck_block, mobilenet_stack, resnet50_backbone,
-    hrnet_like, tiny_mixed_net, tiny_concat_net, make_weights, dense_flops, node_shapes, CONFIG_SEEDS,
+    hrnet_like, tiny_mixed_net, tiny_concat_net, tiny_pool_net, make_weights, dense_flops, node_shapes, CONFIG_SEEDS,
 )

@@ -58,6 +58,12 @@ class _B:
     def upsample(self, src, factor):
         return self._add(kind="upsample", **{"in": [src]}, factor=int(factor))
 
+    def upsample_bilinear(self, src, factor):
+        return self._add(kind="upsample_bilinear", **{"in": [src]}, factor=int(factor))
+
+    def gavgpool(self, src):
+        return self._add(kind="gavgpool", **{"in": [src]})
+
     def accum(self, src):
         return self._add(kind="accum", **{"in": [src]})
 
@@ -219,8 +225,10 @@ def node_shapes(net):
             ho = (h + 2 * nd["pad"] - nd["k"]) // nd["stride"] + 1
             wo = (w + 2 * nd["pad"] - nd["k"]) // nd["stride"] + 1
             shapes.append((ho, wo, c))
-        elif k == "upsample":
+        elif k in ("upsample", "upsample_bilinear"):
             shapes.append((h * nd["factor"], w * nd["factor"], c))
+        elif k == "gavgpool":
+            shapes.append((1, 1, c))
         elif k == "concat":
             shapes.append((h, w, c + shapes[nd["in"][1]][2]))
         else:
@@ -271,6 +279,20 @@ def tiny_concat_net(eps=0.05, eps0=None, h=20, w=24, c=8, frames=6, dtype="f32")
     b.accum(q)
     video = VideoSpec(h=h, w=w, c=c, frames=frames, n_objects=2, obj_kind="rect", obj_size=5, noise_sigma=0.01)
     return _net("tiny_concat", dtype, h, w, c, video, b)
+
+
+def tiny_pool_net(eps=0.05, eps0=None, h=18, w=22, c=8, frames=6, dtype="f32"):
+    """Bilinear upsampling of a coarser branch and a global-average-pooled head (tests only)."""
+    eps0 = eps if eps0 is None else eps0
+    b = _B()
+    x0 = b.deltagen(eps0)
+    x = b.act(b.conv(x0, 3, 2, c, 16), "relu", eps)             # h/2
+    u = b.upsample_bilinear(b.conv(x, 1, 1, 16, 8), 2)          # back to h
+    q = b.act(b.conv(b.add(u, x0), 3, 1, 8, 16), "relu", eps)
+    g = b.gavgpool(q)                                           # [1, 1, 16]
+    b.accum(b.conv(g, 1, 1, 16, 10))                            # a fully connected head
+    video = VideoSpec(h=h, w=w, c=c, frames=frames, n_objects=2, obj_kind="rect", obj_size=5, noise_sigma=0.01)
+    return _net("tiny_pool", dtype, h, w, c, video, b)
 
 
 def tiny_mixed_net(eps=0.05, eps0=None, h=24, w=20, c=8, frames=6, dtype="f32"):
