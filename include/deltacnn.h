@@ -55,7 +55,9 @@ typedef enum {
     DCNN_MAXPOOL = 4,       /* max pooling with accumulated-input buffer             Section 3.1, Eq. 3  */
     DCNN_UPSAMPLE = 5,      /* nearest-neighbour upsampling                          Section 3.4         */
     DCNN_ACCUM = 6,         /* output layer: deltas accumulated into a dense map     Fig. 2              */
-    DCNN_CONCAT = 7         /* channel concatenation of two updates (linear)         Section 3.4         */
+    DCNN_CONCAT = 7,        /* channel concatenation of two updates (linear)         Section 3.4         */
+    DCNN_UPSAMPLE_BILINEAR = 8, /* bilinear upsampling, half-pixel centres (linear)  Section 3.4         */
+    DCNN_GAVGPOOL = 9       /* global average pooling to a 1x1 map (linear)          Section 3.4         */
 } dcnn_kind;
 
 typedef enum { DCNN_ACT_NONE = 0, DCNN_ACT_RELU = 1, DCNN_ACT_RELU6 = 2 } dcnn_act;
@@ -82,6 +84,8 @@ typedef struct {
  *                  act == NONE with n_in == 2 is a plain, stateless add.
  *  DELTAGEN      : eps is the input threshold, dilate_r the radius of the square mask dilation.
  *  MAXPOOL       : kh, stride, pad.     UPSAMPLE : factor.     ACCUM : nothing else.
+ *  UPSAMPLE_BILINEAR : factor (2..16); an output pixel is flagged iff a source pixel that carries
+ *                  weight is flagged.   GAVGPOOL : nothing else; output [n, 1, 1, c].
  *  CONCAT        : n_in == 2; c = channels of input 0, cout = c + channels of input 1.  The output
  *                  mask is the OR of both; a stream that is not flagged at a pixel contributes zeros.
  * The update rule is "update iff max_c |dy_c| >= eps": eps < 0 updates every visited pixel,

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libdeltacnn.so")
 
 F32, F16 = 0, 1
-DELTAGEN, CONV, DWCONV, ACT, MAXPOOL, UPSAMPLE, ACCUM, CONCAT = range(8)
+DELTAGEN, CONV, DWCONV, ACT, MAXPOOL, UPSAMPLE, ACCUM, CONCAT, UPSAMPLE_BILINEAR, GAVGPOOL = range(10)
 ACT_NONE, ACT_RELU, ACT_RELU6 = 0, 1, 2
 ACT_CODES = {"none": ACT_NONE, None: ACT_NONE, "relu": ACT_RELU, "relu6": ACT_RELU6}
 TORCH_DTYPE = {F32: torch.float32, F16: torch.float16}
@@ -341,6 +341,10 @@ class Net:
                 desc = make_desc(MAXPOOL, self.dtype, 0, 0, 0, 0, k=nd["k"], stride=nd["stride"], pad=nd["pad"])
             elif kind == "upsample":
                 desc = make_desc(UPSAMPLE, self.dtype, 0, 0, 0, 0, factor=nd["factor"])
+            elif kind == "upsample_bilinear":
+                desc = make_desc(UPSAMPLE_BILINEAR, self.dtype, 0, 0, 0, 0, factor=nd["factor"])
+            elif kind == "gavgpool":
+                desc = make_desc(GAVGPOOL, self.dtype, 0, 0, 0, 0)
             elif kind == "accum":
                 desc = make_desc(ACCUM, self.dtype, 0, 0, 0, 0)
             else:

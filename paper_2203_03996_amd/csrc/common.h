@@ -76,6 +76,7 @@ struct MaskPassArgs {
     int32_t* count_out;
     int n, h, w, oh, ow, k, stride, pad;
     int up;                      // > 1: nearest upsampling of the input mask by this factor (k = 1)
+    int bilinear;                // with up > 1: bilinear upsampling instead (sources that carry weight)
     int32_t* zero_count;         // optional counter the pass resets to 0 (survivor count of the layer)
     int emit_only;               // 1: mask_in is final and its chunk counts are in the workspace already
     uint32_t* taps_out;          // optional [n*oh*ow]: per list entry, which window taps are flagged (k*k <= 25 bits);
@@ -207,7 +208,19 @@ struct UpsampleArgs {
     const void* in_data;
     void* out_data;
     int n, h, w, c, factor;
+    int bilinear;                // 0: nearest neighbour; 1: bilinear, half-pixel centres
+    const uint8_t* in_mask;      // bilinear: unflagged sources count as zero (nullptr: all flagged)
 };
+
+// Global average pooling: one list entry per stream with an update; out[n, c] = sum over the stream's flagged
+// pixels / (h * w).
+struct GapArgs {
+    const void* in_data;         // [n, h*w, c]
+    const uint8_t* in_mask;      // nullptr: every pixel counts (first frame)
+    void* out_data;              // [n, c]
+    int hw, c;
+};
+dcnn_status launch_gavgpool(dcnn_ctx* ctx, int dtype, const ListArgs& l_out, const GapArgs& a);
 dcnn_status launch_upsample(dcnn_ctx* ctx, int dtype, const ListArgs& l_out, const UpsampleArgs& a);
 
 }  // namespace dcnn

@@ -442,6 +442,21 @@ __device__ __forceinline__ uint32_t tail_finish(const EpilogueArgs& e, bool init
     return bits;
 }
 
+// Sources of output coordinate o of a bilinear upsampling by the integer factor r (half-pixel centres): the
+// sample position (o + 0.5) / r - 0.5 = (2o + 1 - r) / 2r, clamped to the map.  Source i0 always carries weight;
+// i1 == i0 when it alone does (w1 = 0), else i1 = i0 + 1 with weight w1.  Integer arithmetic decides, so "no
+// weight" is exact.
+struct BilinTaps { int i0, i1; float w1; };
+__device__ __forceinline__ BilinTaps bilin_taps(int o, int r, int size) {
+    BilinTaps t;
+    const int num = 2 * o + 1 - r, den = 2 * r;
+    if (num <= 0) { t.i0 = t.i1 = 0; t.w1 = 0.0f; return t; }
+    const int i0 = num / den, rem = num - i0 * den;
+    if (i0 >= size - 1) { t.i0 = t.i1 = size - 1; t.w1 = 0.0f; return t; }
+    t.i0 = i0; t.i1 = rem ? i0 + 1 : i0; t.w1 = (float)rem / (float)den;
+    return t;
+}
+
 // ---- buffer addressing ---------------------------------------------------------------------------
 // A load through a buffer descriptor at a byte offset outside the descriptor's range returns zeros and a
 // store there is dropped, so "this lane has nothing to do" is an offset, not a branch: every load of a

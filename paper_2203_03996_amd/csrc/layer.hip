@@ -20,6 +20,8 @@ static bool own_list(const dcnn_layer_desc& d) {
         case DCNN_ACT: return d.n_in == 2;
         case DCNN_MAXPOOL:
         case DCNN_UPSAMPLE:
+        case DCNN_UPSAMPLE_BILINEAR:
+        case DCNN_GAVGPOOL:
         case DCNN_CONCAT: return true;
         default: return false;
     }
@@ -47,15 +49,20 @@ static dcnn_status out_shape(const dcnn_layer_desc& d, int* oh, int* ow, int* oc
             *oc = d.cout;
             return DCNN_OK;
         case DCNN_UPSAMPLE:
-            if (d.factor < 1 || d.factor > 16) return DCNN_EINVAL;
+        case DCNN_UPSAMPLE_BILINEAR:
+            if (d.factor < (d.kind == DCNN_UPSAMPLE ? 1 : 2) || d.factor > 16) return DCNN_EINVAL;
             *oh = d.h * d.factor; *ow = d.w * d.factor;
+            return DCNN_OK;
+        case DCNN_GAVGPOOL:
+            if (d.n > 65535) return DCNN_ESHAPE;
+            *oh = 1; *ow = 1;
             return DCNN_OK;
         default: return DCNN_OK;
     }
 }
 
 static dcnn_status validate_desc(const dcnn_layer_desc& d) {
-    if (d.kind < DCNN_DELTAGEN || d.kind > DCNN_CONCAT) return DCNN_EINVAL;
+    if (d.kind < DCNN_DELTAGEN || d.kind > DCNN_GAVGPOOL) return DCNN_EINVAL;
     if (d.dtype != DCNN_F32 && d.dtype != DCNN_F16) return DCNN_EDTYPE;
     if (d.n < 1 || d.h < 1 || d.w < 1 || d.c < 1) return DCNN_ESHAPE;
     if ((int64_t)d.n * d.h * d.w > INT32_MAX / 4) return DCNN_ESHAPE;
@@ -430,9 +437,15 @@ dcnn_status dcnn_layer_init(dcnn_layer* L, const void* const* dense_in, int32_t 
             st = launch_maxpool_out(ctx, d.dtype, true, full_list(L->out_pixels), a);
             break;
         }
-        case DCNN_UPSAMPLE: {
-            UpsampleArgs a{dense_in[0], dense_out, d.n, d.h, d.w, d.c, d.factor};
+        case DCNN_UPSAMPLE:
+        case DCNN_UPSAMPLE_BILINEAR: {
+            UpsampleArgs a{dense_in[0], dense_out, d.n, d.h, d.w, d.c, d.factor, d.kind == DCNN_UPSAMPLE_BILINEAR ? 1 : 0, nullptr};
             st = launch_upsample(ctx, d.dtype, full_list(L->out_pixels), a);
+            break;
+        }
+        case DCNN_GAVGPOOL: {
+            GapArgs a{dense_in[0], nullptr, dense_out, d.h * d.w, d.c};
+            st = launch_gavgpool(ctx, d.dtype, full_list(L->out_pixels), a);
             break;
         }
         case DCNN_CONCAT: {
@@ -508,7 +521,8 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         m.k = 1; m.stride = 1; m.pad = 0; m.up = 1; m.emit_only = 0;
         m.zero_count = (act && !d.want_idx) ? L->out_count : nullptr;
         if (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV || d.kind == DCNN_MAXPOOL) { m.k = d.kh; m.stride = d.stride; m.pad = d.pad; }
-        if (d.kind == DCNN_UPSAMPLE) m.up = d.factor;
+        if (d.kind == DCNN_UPSAMPLE || d.kind == DCNN_UPSAMPLE_BILINEAR) { m.up = d.factor; m.bilinear = d.kind == DCNN_UPSAMPLE_BILINEAR; }
+        if (d.kind == DCNN_GAVGPOOL) { m.k = d.h; m.kw = d.w; m.pad_w = 0; }   // one window over the whole map
         m.taps_out = L->taps;
         if (has_proj(d) && !(d.proj_stride == 1 && d.proj_h == L->oh && d.proj_w == L->ow)) {
             m.b_stride = d.proj_stride; m.b_h = d.proj_h; m.b_w = d.proj_w;
@@ -582,9 +596,15 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             st = launch_maxpool_commit(ctx, d.dtype, li, a);
             break;
         }
-        case DCNN_UPSAMPLE: {
-            UpsampleArgs a{in[0]->data, L->out_data, d.n, d.h, d.w, d.c, d.factor};
+        case DCNN_UPSAMPLE:
+        case DCNN_UPSAMPLE_BILINEAR: {
+            UpsampleArgs a{in[0]->data, L->out_data, d.n, d.h, d.w, d.c, d.factor, d.kind == DCNN_UPSAMPLE_BILINEAR ? 1 : 0, in[0]->mask};
             st = launch_upsample(ctx, d.dtype, l, a);
+            break;
+        }
+        case DCNN_GAVGPOOL: {
+            GapArgs a{in[0]->data, in[0]->mask, L->out_data, d.h * d.w, d.c};
+            st = launch_gavgpool(ctx, d.dtype, l, a);
             break;
         }
         case DCNN_CONCAT: {

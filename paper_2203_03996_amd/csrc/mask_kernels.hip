@@ -90,6 +90,7 @@ struct MaskKernelArgs {
     int32_t* zero_count;
     int64_t out_pixels;
     int n, h, w, oh, ow, k, stride, pad, up;
+    int bilinear;                 // with up > 1: sources of a bilinear upsampling instead of the nearest pixel
     int b_stride, b_h, b_w;       // > 0: mask_b is sampled at (y, x) * b_stride of an [n, b_h, b_w] map
     int kw, pad_w;                // window columns and their padding (rows: k, pad)
 };
@@ -120,7 +121,12 @@ __device__ __forceinline__ uint64_t mask_word(const MaskKernelArgs& a, int64_t p
             int64_t n = t / a.oh;
             for (int i = 0; i < kPxPerThread && p0 + i < a.out_pixels; ++i) {
                 uint8_t f = 0;
-                if (a.up > 1) {
+                if (a.up > 1 && a.bilinear) {
+                    const BilinTaps ty = bilin_taps(oy, a.up, a.h), tx = bilin_taps(ox, a.up, a.w);
+                    const uint8_t* r0 = a.mask_in + (n * a.h + ty.i0) * a.w;
+                    const uint8_t* r1 = a.mask_in + (n * a.h + ty.i1) * a.w;
+                    f = r0[tx.i0] | r0[tx.i1] | r1[tx.i0] | r1[tx.i1];
+                } else if (a.up > 1) {
                     f = a.mask_in[(n * a.h + oy / a.up) * a.w + ox / a.up];
                 } else {
                     for (int ky = 0; ky < a.k; ++ky) {
@@ -319,6 +325,7 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
         a.n = m.n; a.h = m.h; a.w = m.w; a.oh = m.oh; a.ow = m.ow;
         a.k = m.k; a.stride = m.stride; a.pad = m.pad;
         a.up = m.up > 1 ? m.up : 1;
+        a.bilinear = m.bilinear;
         a.b_stride = m.b_stride; a.b_h = m.b_h; a.b_w = m.b_w;
         a.kw = m.kw > 0 ? m.kw : m.k; a.pad_w = m.kw > 0 ? m.pad_w : m.pad;
         if (!fused) {

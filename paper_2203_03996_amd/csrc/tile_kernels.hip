@@ -707,10 +707,71 @@ __global__ __launch_bounds__(256) void upsample_kernel(ListArgs l, UpsampleArgs 
         const int64_t t = p / ow;
         const int oy = (int)(t % oh);
         const int64_t n = t / oh;
-        const int64_t q = (n * a.h + oy / a.factor) * a.w + ox / a.factor;
         float x[V];
-        load_vec<T, V>(in + q * C + vi * V, x);
+        if (a.bilinear) {
+            // up to four sources; an unflagged one counts as zero and is not read
+            const BilinTaps ty = bilin_taps(oy, a.factor, a.h), tx = bilin_taps(ox, a.factor, a.w);
+#pragma unroll
+            for (int i = 0; i < V; ++i) x[i] = 0.0f;
+            for (int sy = 0; sy < 2; ++sy) {
+                if (sy == 1 && ty.i1 == ty.i0) break;
+                const float wy = sy ? ty.w1 : 1.0f - ty.w1;
+                const int iy = sy ? ty.i1 : ty.i0;
+                for (int sx = 0; sx < 2; ++sx) {
+                    if (sx == 1 && tx.i1 == tx.i0) break;
+                    const float wgt = wy * (sx ? tx.w1 : 1.0f - tx.w1);
+                    const int64_t q = (n * a.h + iy) * a.w + (sx ? tx.i1 : tx.i0);
+                    if (a.in_mask && a.in_mask[q] == 0) continue;
+                    float s[V];
+                    load_vec<T, V>(in + q * C + vi * V, s);
+#pragma unroll
+                    for (int i = 0; i < V; ++i) x[i] = fmaf(wgt, s[i], x[i]);
+                }
+            }
+        } else {
+            const int64_t q = (n * a.h + oy / a.factor) * a.w + ox / a.factor;
+            load_vec<T, V>(in + q * C + vi * V, x);
+        }
         store_vec<T, V>(out + p * C + vi * V, x);
+    }
+}
+
+// Global average pooling: workgroup (j, cb) serves list entry j (a stream) and 64 * V channels; wave w sums the
+// stream's flagged pixels p = w, w + 4, ... in ascending order, the four partial sums are added in a fixed order:
+// the result does not depend on scheduling.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void gavgpool_kernel(ListArgs l, GapArgs a) {
+    __shared__ float s_part[3][kWave][V];
+    const int64_t count = list_count(l);
+    if ((int64_t)blockIdx.x >= count) return;                  // uniform for the block
+    const int64_t n = l.list ? (int64_t)l.list[blockIdx.x] : (int64_t)blockIdx.x;
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int c0 = (blockIdx.y * kWave + lane) * V;
+    const bool on = c0 < a.c;
+    const T* in = static_cast<const T*>(a.in_data) + n * (int64_t)a.hw * a.c;
+    const uint8_t* mask = a.in_mask ? a.in_mask + n * (int64_t)a.hw : nullptr;
+    float acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+    for (int p = wave; p < a.hw; p += 4) {
+        if (mask && mask[p] == 0) continue;                    // uniform for the wave
+        if (on) {
+            float s[V];
+            load_vec<T, V>(in + (int64_t)p * a.c + c0, s);
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc[i] += s[i];
+        }
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) s_part[wave - 1][lane][i] = acc[i];
+    }
+    __syncthreads();
+    if (wave == 0 && on) {
+        const float inv = 1.0f / (float)a.hw;
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = ((acc[i] + s_part[0][lane][i]) + (s_part[1][lane][i] + s_part[2][lane][i])) * inv;
+        store_vec<T, V>(static_cast<T*>(a.out_data) + n * (int64_t)a.c + c0, acc);
     }
 }
 
@@ -784,6 +845,18 @@ dcnn_status launch_maxpool_commit(dcnn_ctx* ctx, int dtype, const ListArgs& l, c
 dcnn_status launch_upsample(dcnn_ctx* ctx, int dtype, const ListArgs& l, const UpsampleArgs& a) {
     DCNN_FLAT_DISPATCH(upsample_kernel, a.c, l.max_count, l, a);
     return check_hip(ctx, hipGetLastError(), "upsample_kernel launch");
+}
+
+dcnn_status launch_gavgpool(dcnn_ctx* ctx, int dtype, const ListArgs& l, const GapArgs& a) {
+    if (l.max_count < 1 || l.max_count > 65535) return fail(ctx, DCNN_ESHAPE, "global average pooling: %lld streams", (long long)l.max_count);
+    const bool f16v = dtype == DCNN_F16 && a.c % 8 == 0, f32v = dtype == DCNN_F32 && a.c % 4 == 0;
+    const int v = f16v ? 8 : (f32v ? 4 : 1);
+    const dim3 g((unsigned)l.max_count, (unsigned)cdiv(a.c, kWave * v)), b(256);
+    if (f16v) hipLaunchKernelGGL((gavgpool_kernel<f16, 8>), g, b, 0, ctx->stream, l, a);
+    else if (f32v) hipLaunchKernelGGL((gavgpool_kernel<float, 4>), g, b, 0, ctx->stream, l, a);
+    else if (dtype == DCNN_F16) hipLaunchKernelGGL((gavgpool_kernel<f16, 1>), g, b, 0, ctx->stream, l, a);
+    else hipLaunchKernelGGL((gavgpool_kernel<float, 1>), g, b, 0, ctx->stream, l, a);
+    return check_hip(ctx, hipGetLastError(), "gavgpool_kernel launch");
 }
 
 dcnn_status launch_concat(dcnn_ctx* ctx, int dtype, const ListArgs& l, const ConcatArgs& a) {

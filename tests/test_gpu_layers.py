@@ -506,6 +506,53 @@ def test_upsample(S, factor):
 
 
 @pytest.mark.parametrize("S", ["f32", "f16"])
+@pytest.mark.parametrize("factor,c", [(2, 32), (3, 5), (4, 16)])
+def test_upsample_bilinear(S, factor, c):
+    """Masks and lists bit-exact (integer tap rule); values within tolerance (fp32 weights vs float64)."""
+    rng = np.random.default_rng(factor * 10 + c)
+    shape = (2, 7, 9, c)
+    n, h, w, _ = shape
+    ref = orc.UpsampleBilinear(factor, S)
+    ctx = pkg.Context(n * h * w * factor * factor)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.UPSAMPLE_BILINEAR, DT[S], n, h, w, c, factor=factor))
+    assert layer.out_shape == (n, h * factor, w * factor, c)
+    x0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
+    g0 = layer.init([torch.from_numpy(x0).cuda()])
+    ctx.sync()
+    assert rel_err(to_np(g0), ref.init(x0)) <= TOL[S]
+    for t, dens in enumerate([0.1, 1.0, 0.02, 0.0]):
+        d = _rand_delta(rng, shape, dens, S)
+        want = ref.step(d).poisoned()
+        out = layer.step([_upload(d)])
+        ctx.sync()
+        check_delta(out, want, S, f"bilinear x{factor} frame {t}")
+
+
+@pytest.mark.parametrize("S", ["f32", "f16"])
+@pytest.mark.parametrize("shape", [(3, 7, 7, 64), (2, 13, 10, 20), (5, 4, 6, 3), (1, 1, 1, 8), (2, 24, 24, 1280)])
+def test_global_average_pooling(S, shape):
+    rng = np.random.default_rng(sum(shape))
+    n, h, w, c = shape
+    ref = orc.GlobalAvgPool(S)
+    ctx = pkg.Context(n * h * w)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.GAVGPOOL, DT[S], n, h, w, c))
+    assert layer.out_shape == (n, 1, 1, c)
+    x0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
+    g0 = layer.init([torch.from_numpy(x0).cuda()])
+    ctx.sync()
+    assert rel_err(to_np(g0), ref.init(x0)) <= TOL[S]
+    for t, dens in enumerate([0.1, 1.0, 0.0]):
+        d = _rand_delta(rng, shape, dens, S)
+        if t == 0 and n > 1:
+            d.mask[1] = 0                                       # one stream without any update
+            d.data[1] = np.nan
+        want = ref.step(d).poisoned()
+        out = layer.step([_upload(d)])
+        ctx.sync()
+        check_delta(out, want, S, f"global average pool frame {t}")
+
+
+@pytest.mark.parametrize("S", ["f32", "f16"])
 @pytest.mark.parametrize("ca,cb", [(32, 64), (16, 3), (5, 7)])
 def test_concat(S, ca, cb):
     """Channel concatenation: values are copies (bit-exact); an unflagged stream contributes zeros."""

@@ -139,8 +139,14 @@ def test_tiny_concat_net(S, flags):
     _run_net(wl.tiny_concat_net(eps=0.05, dtype=S), 13, 2, flags=flags)
 
 
+@pytest.mark.parametrize("S", ["f32", "f16"])
+def test_tiny_pool_net(S):
+    """Bilinear upsampling of a coarser branch and a global-average-pooled, fully connected head."""
+    _run_net(wl.tiny_pool_net(eps=0.05, dtype=S), 17, 2)
+
+
 @pytest.mark.parametrize("spec_fn", [lambda: wl.single_conv_relu(eps=-1.0), lambda: wl.bottleneck_block(eps=-1.0, h=32, w=32, frames=4),
-                                     lambda: wl.tiny_mixed_net(eps=-1.0, dtype="f16"), lambda: wl.tiny_concat_net(eps=-1.0)])
+                                     lambda: wl.tiny_mixed_net(eps=-1.0, dtype="f16"), lambda: wl.tiny_concat_net(eps=-1.0), lambda: wl.tiny_pool_net(eps=-1.0)])
 def test_dense_mode_matches_dense_inference(spec_fn):
     """Negative thresholds: every pixel is reprocessed and the output is plain dense inference."""
     spec = spec_fn()
