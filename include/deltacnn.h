@@ -111,6 +111,10 @@ typedef struct {
      * (state buffer 2, dcnn_layer_output's data) and adds every delta it emits to it instead of storing
      * the delta.  CONV with activation and without a residual input only. */
     int32_t fuse_accum;
+    /* 1: a layer with an activation keeps no buffer of truncated values x^T (Section 6: the buffer can be
+     * left out to save memory): a truncated update is dropped, an update is x^A <- x^A + dx.  Small changes
+     * below the threshold are then lost instead of accumulated (Eq. 6 does not hold). */
+    int32_t no_xT;
 } dcnn_layer_desc;
 
 typedef struct {

@@ -434,7 +434,7 @@ def build_layers(net: dict, weights: dict, S: str, use_xT: bool = True):
             wgt, bias = weights[i]
             layers.append(Conv(wgt, bias, nd["stride"], nd["pad"], nd["depthwise"], S))
         elif k == "act":
-            layers.append(ActTrunc(nd["f"], nd["eps"], S, use_xT))
+            layers.append(ActTrunc(nd["f"], nd["eps"], S, use_xT and not nd.get("no_xT", False)))
         elif k == "add":
             layers.append(Add(S))
         elif k == "concat":

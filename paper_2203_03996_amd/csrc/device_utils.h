@@ -207,7 +207,7 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
                 if (res_ok) rr[ub][v] = raw_load<T, V>(res + p * C + c0);
                 if (stateful && !init) {
                     ra[ub][v] = raw_load<T, V>(xA + p * C + c0);
-                    rt[ub][v] = raw_load<T, V>(xT + p * C + c0);
+                    if (xT) rt[ub][v] = raw_load<T, V>(xT + p * C + c0);           // no buffer: truncated values are not kept
                 }
                 if (init && bias) ra[ub][v] = raw_load<T, V>(bias + c0);      // slot reused for the bias
             }
@@ -284,9 +284,9 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
                     raw_store<T, V>(out + off, o_y[ub][v]);
                 } else if (upd) {
                     raw_store<T, V>(xA + off, o_a[ub][v]);
-                    raw_store<T, V>(xT + off, raw_zero<T, V>());
+                    if (xT) raw_store<T, V>(xT + off, raw_zero<T, V>());
                     raw_store<T, V>(out + off, o_y[ub][v]);
-                } else {
+                } else if (xT) {
                     raw_store<T, V>(xT + off, o_t[ub][v]);
                 }
             }
@@ -340,7 +340,7 @@ __device__ __forceinline__ void tail_prefetch(const EpilogueArgs& e, bool init, 
         if (res && (init || e.res_mask == nullptr || e.res_mask[p] != 0)) r.rr[it] = raw_load<T, V>(res + p * C + c0);
         if (stateful && !init) {
             r.ra[it] = raw_load<T, V>(xA + p * C + c0);
-            r.rt[it] = raw_load<T, V>(xT + p * C + c0);
+            if (xT) r.rt[it] = raw_load<T, V>(xT + p * C + c0);
         }
         if (init && bias) r.ra[it] = raw_load<T, V>(bias + c0);               // slot reused for the bias
     }
@@ -425,9 +425,9 @@ __device__ __forceinline__ uint32_t tail_finish(const EpilogueArgs& e, bool init
                 raw_store<T, V>(out + off, o_y[it]);
             } else if (upd) {
                 raw_store<T, V>(xA + off, o_a[it]);
-                raw_store<T, V>(xT + off, raw_zero<T, V>());
+                if (xT) raw_store<T, V>(xT + off, raw_zero<T, V>());
                 raw_store<T, V>(out + off, o_y[it]);
-            } else {
+            } else if (xT) {
                 raw_store<T, V>(xT + off, o_t[it]);
             }
         }

@@ -89,6 +89,8 @@ static dcnn_status validate_desc(const dcnn_layer_desc& d) {
         if ((d.proj_h - 1) / d.proj_stride + 1 != oh || (d.proj_w - 1) / d.proj_stride + 1 != ow) return DCNN_ESHAPE;
     }
     if (d.fuse_accum != 0 && d.fuse_accum != 1) return DCNN_EINVAL;
+    if (d.no_xT != 0 && d.no_xT != 1) return DCNN_EINVAL;
+    if (d.no_xT && (d.act == DCNN_ACT_NONE || d.kind == DCNN_DELTAGEN)) return DCNN_EINVAL;
     if (d.fuse_accum && (d.kind != DCNN_CONV || d.act == DCNN_ACT_NONE || (d.n_in == 2 && !has_proj(d)))) return DCNN_EINVAL;
     return DCNN_OK;
 }
@@ -126,7 +128,7 @@ static void carve(dcnn_layer* L, void* state) {
         case DCNN_ACT:
             if (act) {
                 L->buf0 = cv.take(out_map); L->buf0_bytes = out_map;
-                L->buf1 = cv.take(out_map); L->buf1_bytes = out_map;
+                if (!d.no_xT) { L->buf1 = cv.take(out_map); L->buf1_bytes = out_map; }
             }
             if (d.fuse_accum) { L->buf2 = cv.take(out_map); L->buf2_bytes = out_map; }
             break;

@@ -163,6 +163,7 @@ dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t fuse, size_t* arena_bytes) 
             if (k >= 0 && !absorbed[k] && is_plain_act(net->nodes[k].d)) {
                 d.act = net->nodes[k].d.act;
                 d.eps = net->nodes[k].d.eps;
+                d.no_xT = net->nodes[k].d.no_xT;
                 taken.push_back(k);
                 cur = k;
             }
@@ -187,6 +188,7 @@ dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t fuse, size_t* arena_bytes) 
             if (k >= 0 && !absorbed[k] && is_plain_act(net->nodes[k].d)) {
                 p.d.act = net->nodes[k].d.act;
                 p.d.eps = net->nodes[k].d.eps;
+                p.d.no_xT = net->nodes[k].d.no_xT;
                 p.out_node = k;
                 absorbed[k] = 1;
             }

@@ -283,6 +283,71 @@ def test_conv_fused_act(S, k, stride, cin, cout, nhw, res):
     assert ties <= 3
 
 
+@pytest.mark.parametrize("S,k,cin,cout,nhw,res", [
+    ("f16", 1, 64, 64, (2, 30, 30), False),       # wave-specialised kernel
+    ("f16", 3, 32, 96, (1, 21, 24), True),        # three column blocks, residual
+    ("f16", 3, 256, 256, (1, 12, 12), False),     # streamed weights: plain kernel tail
+    ("f32", 3, 16, 32, (1, 20, 22), False),
+    ("f16", 0, 0, 576, (2, 9, 11), False),        # k = 0: a stand-alone activation layer (wide pixels)
+    ("f32", 0, 0, 2048, (1, 6, 6), False),        # eight vectors per lane: the pointer-addressed kernel
+])
+def test_layers_without_truncated_value_buffer(S, k, cin, cout, nhw, res):
+    """no_xT = 1 (Section 6, memory remark): a truncated update is dropped, an update is x^A <- x^A + dx;
+    teacher-forced against the oracle's ActTrunc(use_xT=False).  Buffer 1 does not exist."""
+    rng = np.random.default_rng(k * 7 + cout)
+    n, h, w = nhw
+    eps = 1.6 if k else 0.3                                     # of the order of a pixel's largest change: both branches occur
+    ract = orc.ActTrunc("relu", eps, S, use_xT=False)
+    if k:
+        wgt = (rng.normal(0, 1, (k, k, cin, cout)) * np.sqrt(2.0 / (k * k * cin))).astype(NP_DTYPE[S])
+        bias = rng.normal(0, 0.1, cout).astype(NP_DTYPE[S])
+        rconv, radd = orc.Conv(wgt, bias, 1, k // 2, False, S), orc.Add(S)
+        ctx = pkg.Context(n * h * w)
+        desc = pkg.make_desc(pkg.CONV, DT[S], n, h, w, cin, k=k, stride=1, pad=k // 2, cout=cout, act=pkg.ACT_RELU, eps=eps,
+                             n_in=2 if res else 1, no_xT=1)
+        layer = pkg.Layer(ctx, desc, torch.from_numpy(wgt).cuda(), torch.from_numpy(bias).cuda())
+    else:
+        cin = cout
+        ctx = pkg.Context(n * h * w)
+        layer = pkg.Layer(ctx, pkg.make_desc(pkg.ACT, DT[S], n, h, w, cout, act=pkg.ACT_RELU, eps=eps, no_xT=1))
+    with pytest.raises(pkg.DcnnError):
+        layer.state_tensor(1)
+    x0 = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
+    y0 = rconv.init(x0) if k else x0
+    ins0 = [torch.from_numpy(x0).cuda()]
+    if res:
+        s0 = rng.normal(0, 1, (n, h, w, cout)).astype(NP_DTYPE[S])
+        y0 = radd.init(y0, s0)
+        ins0.append(torch.from_numpy(s0).cuda())
+    r0 = ract.init(y0)
+    g0 = layer.init(ins0)
+    ctx.sync()
+    assert rel_err(to_np(g0), r0) <= TOL[S]
+    ties = 0
+    saw_trunc = False
+    for t, dens in enumerate([0.1, 0.5, 1.0, 0.0, 0.2]):
+        layer.state_tensor(0).copy_(torch.from_numpy(ract.xA).cuda())
+        d = _rand_delta(rng, (n, h, w, cin), dens, S, 0.05 if not k else 0.5)
+        mid = rconv.step(d).poisoned() if k else d
+        ins = [_upload(d)]
+        if res:
+            ds = _rand_delta(rng, (n, h, w, cout), dens / 2, S, 0.5)
+            mid = radd.step(mid, ds).poisoned()
+            ins.append(_upload(ds))
+        xa_before = ract.xA.copy()
+        want = ract.step(mid).poisoned()
+        out = layer.step(ins)
+        ctx.sync()
+        near = np.abs(np.nan_to_num(ract.last_u, nan=np.inf) - eps) <= TOL[S] * eps
+        ties += check_delta(out, want, S, f"no-xT frame {t}", allow_mask_diff=near, exact_values=not k)
+        agree = to_np(out.mask) == want.mask
+        assert rel_err(to_np(layer.state_tensor(0))[agree], ract.xA[agree]) <= TOL[S]
+        trunc = (mid.mask == 1) & (want.mask == 0)
+        saw_trunc |= bool(trunc.any())
+        assert np.array_equal(ract.xA[trunc], xa_before[trunc])       # the oracle really dropped those updates
+    assert ties <= 3 and (saw_trunc or cout > 96)
+
+
 @pytest.mark.parametrize("S,k,cin,cin2,cout,nhw,stride2", [
     ("f16", 1, 64, 64, 256, (2, 24, 40), 1),
     ("f16", 1, 64, 32, 128, (1, 19, 23), 2),

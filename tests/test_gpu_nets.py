@@ -84,8 +84,9 @@ def _run_net(spec, seed, n_streams, flags=3, frames=None, check_dense=True):
                     # non-linear layer, x^A + x^T (deltas are compared teacher-forced in test_gpu_layers)
                     ly = oracle.layers[nid]
                     xa, xt = net.layer_state(li, 0), net.layer_state(li, 1)
-                    if xa is not None and xt is not None and getattr(ly, "xT", None) is not None:
-                        got_acc = to_np(xa).astype(np.float64) + to_np(xt).astype(np.float64)
+                    if xa is not None and getattr(ly, "xT", None) is not None:
+                        # (a layer without a buffer of truncated values has x^T = 0 on both sides)
+                        got_acc = to_np(xa).astype(np.float64) + (to_np(xt).astype(np.float64) if xt is not None else 0.0)
                         ref_acc = ly.xA.astype(np.float64).reshape(-1) + ly.xT.astype(np.float64).reshape(-1)
                         e = rel_err(got_acc, ref_acc, floor=0.1)
                         assert e <= tol, f"frame {t} node {nid}: accumulated input off by {e:.2e}"
@@ -320,3 +321,20 @@ def test_density_budget_tuner_matches_the_oracle():
             assert st[i]["pixels_out"] == int(onet.outs[net.layer_node(i)].mask.sum()), f"frame {t} layer {i}"
     with pytest.raises(pkg.DcnnError):
         net.set_eps(1, float("nan"))
+
+
+@pytest.mark.parametrize("spec_fn", [lambda: wl.bottleneck_block(eps=0.08, h=48, w=40, frames=6, no_xT=True),
+                                     lambda: wl.tiny_mixed_net(eps=0.05, dtype="f32", no_xT=True),
+                                     lambda: wl.tiny_mixed_net(eps=0.05, dtype="f16", no_xT=True)])
+def test_networks_without_truncated_value_buffers(spec_fn):
+    """Memory-lean variant (Section 6): activations keep no x^T; a truncated update is dropped.  Same
+    frame-by-frame comparison as every other network, against the oracle run in the same mode; the layers
+    report no buffer 1 and need less state memory."""
+    spec = spec_fn()
+    r = _run_net(spec, 23, 2, check_dense=False)
+    net = r["net"]
+    acts = [li for li in range(net.num_layers) if net.stats()[li]["act"] != pkg.ACT_NONE]
+    assert acts and all(net.layer_state(li, 1) is None and net.layer_state(li, 0) is not None for li in acts)
+    with_xt = pkg.Net(r["ctx"], dict(spec, nodes=[{k: v for k, v in nd.items() if k != "no_xT"} for nd in spec["nodes"]]),
+                      wl.make_weights(spec, 23), 2, 3)
+    assert net.arena.numel() < with_xt.arena.numel()
