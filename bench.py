@@ -329,6 +329,85 @@ def tile_ablation(streams: int, steps: int, warmup: int):
             "rows": rows, "dense_baseline_ms": md, "dense_baseline_gflops": dense_flops / md / 1e6, "vs_baseline": None}
 
 
+def drift_study(streams: int, frames: int):
+    """Long-run behaviour (supplementary Section 1.4: errors of the accumulated values grow slowly, a periodic
+    dense frame resets them): the bottleneck block runs `frames` frames of a looped clip to which a slow global
+    brightness drift is added, with and without the buffer of truncated values x^T and with periodic resets;
+    every 50 frames the dense output is compared with ordinary dense inference of the same frame (PyTorch,
+    fp32 accumulation over the fp16 weights: comparison only).  Reports max |out - dense| / max |dense|."""
+    import torch.nn.functional as F
+    import paper_2203_03996_amd as pkg
+    import workloads as wl
+    seed = wl.CONFIG_SEEDS[2]
+    T = 16
+    base = wl.bottleneck_block(frames=T)
+    weights = wl.make_weights(base, seed)
+    clip = torch.from_numpy(wl.make_batch(base["video"], seed, streams).astype(np.float32)).cuda()   # [T,B,H,W,C]
+    order = list(range(1, T)) + list(range(T - 2, -1, -1))
+    drift = 0.0005                                          # per frame, all pixels: far below any threshold here
+
+    def frame(t):
+        return (clip[order[t % len(order)] if t else 0] + drift * t).half()
+
+    tw = {}
+    for i, (w, b) in weights.items():
+        wt = torch.from_numpy(np.ascontiguousarray(w)).permute(3, 2, 0, 1).contiguous().half().float().cuda()
+        tw[i] = (wt, torch.from_numpy(b).half().float().cuda())
+    nodes = base["nodes"]
+
+    def dense(x):                                           # x: [B,H,W,C] fp16 -> [B,H,W,C'] fp32
+        outs = []
+        for i, nd in enumerate(nodes):
+            k = nd["kind"]
+            a = outs[nd["in"][0]] if nd["in"] else None
+            if k == "deltagen":
+                y = x.float().permute(0, 3, 1, 2)
+            elif k == "conv":
+                y = F.conv2d(a, tw[i][0], tw[i][1], stride=nd["stride"], padding=nd["pad"])
+            elif k == "act":
+                y = F.relu(a)
+            elif k == "add":
+                y = a + outs[nd["in"][1]]
+            else:
+                y = a
+            outs.append(y)
+        return outs[-1].permute(0, 2, 3, 1)
+
+    rows = []
+    checkpoints = [c for c in (100, 500, 1000, 2000, 5000) if c <= frames]
+    for eps in (0.02, 0.05):
+        for no_xT in (False, True):
+            for period in (0, 500, 100):
+                spec = wl.bottleneck_block(eps=eps, frames=T, no_xT=no_xT)
+                ctx = pkg.Context(streams * 128 * 128)
+                net = pkg.Net(ctx, spec, weights, streams, 1)
+                out = torch.empty((streams, 128, 128, 256), dtype=torch.float16, device="cuda")
+                errs, worst = {}, 0.0
+                for t in range(frames + 1):
+                    f = frame(t)
+                    if t == 0 or (period and t % period == 0):
+                        if t:
+                            net.reset()
+                        net.init(f, out)
+                    else:
+                        net.step(f, out)
+                    if t and t % 50 == 0:
+                        ref = dense(f)
+                        e = float((out.float() - ref).abs().max() / ref.abs().max())
+                        worst = max(worst, e)
+                        if t in checkpoints:
+                            errs[t] = worst
+                            worst = 0.0
+                rows.append({"eps": eps, "x_T": not no_xT, "reset_every": period,
+                             "max_rel_err_up_to_frame": {str(k): v for k, v in errs.items()}})
+                log(f"[bench] drift eps {eps} x_T {not no_xT} reset {period}: " + " ".join(f"{k}:{v:.3g}" for k, v in errs.items()))
+    return {"metric": "max relative error of the dense output vs dense inference over a long run", "unit": "max|out-dense|/max|dense|",
+            "n_gpus": 1, "higher_is_better": False, "dtype": "f16", "data": "synthetic",
+            "config": {"workload": "drift study: bottleneck block 128x128 fp16, looped 16-frame clip + 0.0005/frame brightness drift",
+                       "streams": streams, "frames": frames},
+            "rows": rows, "vs_baseline": None}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -339,9 +418,11 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the measurement run one plain 1 GiB device-to-device copy kernel (reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--workload", default="bottleneck", choices=["bottleneck", "tile_ablation"],
+    ap.add_argument("--workload", default="bottleneck", choices=["bottleneck", "tile_ablation", "drift"],
                     help="bottleneck: BASELINE configs[1] (default, the headline); tile_ablation: one 3x3 128->128 "
-                         "convolution under uniform-random sparsity (second workload, 8 streams unless --streams is given)")
+                         "convolution under uniform-random sparsity (second workload, 8 streams unless --streams is given); "
+                         "drift: error against dense inference over --frames frames, with / without x^T and resets")
+    ap.add_argument("--frames", type=int, default=2000, help="drift workload: frames per run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (streams are independent; see DESIGN.md for how the "
@@ -355,6 +436,9 @@ def main():
     B, K, W = args.streams, args.steps, args.warmup
     if args.workload == "tile_ablation":
         print(json.dumps(tile_ablation(8 if B == 64 else B, min(K, 20), min(W, 5))))
+        return
+    if args.workload == "drift":
+        print(json.dumps(drift_study(4 if B == 64 else B, args.frames)))
         return
     work = Workload(B)
     b = 2                                                    # bytes per element (fp16)
