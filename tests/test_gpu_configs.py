@@ -1,7 +1,8 @@
-"""GPU parity on the remaining BASELINE configurations (reduced spatial sizes / frame counts so the
-CPU oracle finishes in seconds; channel counts, strides, kernel sizes and topology are the real
-ones).  These exercise depthwise and strided convolutions, ReLU6, max pooling, weight streaming,
-multi-branch adds and nearest upsampling through dcnn_net_*."""
+"""GPU parity on the remaining BASELINE configurations: first at reduced spatial sizes / depths with
+objects that fill more of the map (channel counts, strides, kernel sizes and topology are the real
+ones), then at the full sizes the benchmark spec names, one stream, the first frames of the clip.  These
+exercise depthwise and strided convolutions, ReLU6, max pooling, weight streaming, multi-branch adds
+and nearest upsampling through dcnn_net_*."""
 import pytest
 
 import workloads as wl
@@ -33,3 +34,22 @@ def test_config5_hrnet_like():
     spec["video"] = wl.VideoSpec(h=96, w=64, c=3, frames=3, n_objects=1, obj_kind="stick", obj_size=40, noise_sigma=0.01)
     r = _run_net(spec, wl.CONFIG_SEEDS[5], 1)
     assert r["ties"] <= 40
+
+
+# ---- the same three configurations at the benchmark's full sizes (one stream, the first frames of the clip) ----
+def test_config3_full_size():
+    """224x224x3 input, 7 blocks, channels 32 -> 160, fp16; video: static camera, ~10 % moving pixels."""
+    r = _run_net(wl.mobilenet_stack(eps=0.05, frames=5), wl.CONFIG_SEEDS[3], 1)
+    assert r["ties"] <= 200
+
+
+def test_config4_full_size():
+    """256x256x3 input, conv1 7x7 s2, max-pool, stages [3,4,6,3], fp16; 6 blobs, brightness drift, noise 0.02."""
+    r = _run_net(wl.resnet50_backbone(eps=0.05, frames=4), wl.CONFIG_SEEDS[4], 1)
+    assert r["ties"] <= 200
+
+
+def test_config5_full_size():
+    """384x288x3 input, four resolutions, fp16; articulated stick figure over a textured background."""
+    r = _run_net(wl.hrnet_like(eps=0.05, frames=4), wl.CONFIG_SEEDS[5], 1)
+    assert r["ties"] <= 200
