@@ -126,6 +126,7 @@ struct ConvArgs {
     const void* zero_page;       // >= 16 bytes of zeros: what lanes read instead of an unflagged / padded input
     int n, h, w, cin, oh, ow, cout, cout_pad, k, stride, pad, kch;
     int depthwise;
+    int flat;                    // filled by launch_conv: kch counts K-steps over the flat (tap, channel) dimension
     FastDiv div_ow, div_oh;      // filled by launch_conv
     // optional projection: a 1x1 convolution (stride2, no padding) of a second input [n,h2,w2,cin2] whose
     // result is added to this one's before the epilogue; its update flag is bit 30 of the list's tap words

@@ -28,14 +28,18 @@ namespace dcnn {
 #ifndef DCNN_CONV_BOUNDS
 #define DCNN_CONV_BOUNDS 512
 #endif
-template <typename T, int NB, int V, bool ALIGNED, bool STREAM, int KS>
-__global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init,
+// WMODE: where the weight operands come from -- 0 resident in LDS, 1 streamed through LDS in slices (8 waves in
+// lockstep), 2 loaded straight from global memory / L2 by each wave together with its gathers, several K-steps in
+// flight (short work lists on layers whose weights do not fit LDS; 4 waves of up to 512 registers).
+template <typename T, int NB, int V, bool ALIGNED, int WMODE, int KS>
+__global__ __launch_bounds__(WMODE == 2 ? 256 : DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int init,
                                                                  int npass, int cs, int pass_split) {
     typedef typename Mma<T>::Vec Vec;
     typedef typename RawOf<T, V>::type Raw;
     constexpr int KP = Mma<T>::KPACK;
     constexpr int COLS = NB * 32;
     constexpr int GK = 4;                                      // K-steps whose gathers are in flight together
+    constexpr bool STREAM = WMODE == 1;
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int nwaves = blockDim.x / kWave, nthreads = blockDim.x;
@@ -49,10 +53,14 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
     const int slot = wave / cs, part = wave % cs;              // which tile of the iteration, which channel slice
     const int ksz = KS ? KS : c.k;
     const int taps = ksz * ksz, kch = c.kch;
-    const int ksteps = taps * kch;
+    // flat K (stems with very few channels, unaligned kernels only): the K loop sees ONE tap of kch K-steps whose
+    // elements are (tap, channel) pairs; which window tap an element belongs to is looked up per element
+    const bool flat = !ALIGNED && c.flat != 0;
+    const int ktaps = flat ? 1 : taps;
+    const int ksteps = ktaps * kch;
     const bool full_tail = npass == 1;
     const int slice_vecs = cs * kGroup * 2 * COLS;             // one streamed slice (all channel slices)
-    const int w_vecs = STREAM ? 2 * slice_vecs : npass * cs * ksteps * 2 * COLS;
+    const int w_vecs = WMODE == 2 ? 0 : (STREAM ? 2 * slice_vecs : npass * cs * ksteps * 2 * COLS);
     Vec* w_lds = reinterpret_cast<Vec*>(smem);
     constexpr int stage_stride = COLS * (int)sizeof(T) + kStagePad;
     unsigned char* stage = smem + (size_t)w_vecs * 16 + (size_t)wave * kTile * stage_stride;
@@ -62,8 +70,20 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
     const T* in = static_cast<const T*>(c.in_data);
     const T* zeros = static_cast<const T*>(c.zero_page);
 
-    if constexpr (!STREAM) {
+    // flat K: element j of the K dimension -> (offset of its value from the window's first input element, tap)
+    int2* flat_lut = reinterpret_cast<int2*>(smem + (size_t)w_vecs * 16 + (size_t)nwaves * kTile * stage_stride +
+                                             (size_t)2 * nwaves * kTile * sizeof(float));
+    if constexpr (WMODE == 0) {
         for (int i = threadIdx.x; i < w_vecs; i += nthreads) w_lds[i] = wglob[i];
+        if constexpr (!ALIGNED) {
+            if (flat) {
+                for (int j = threadIdx.x; j < taps * c.cin; j += nthreads) {
+                    const int tap = j / c.cin, ch = j - tap * c.cin;
+                    const int dy = tap / ksz, dx = tap - dy * ksz;
+                    flat_lut[j] = make_int2((dy * c.w + dx) * c.cin + ch, tap);
+                }
+            }
+        }
         lds_block_sync();
     }
 
@@ -71,7 +91,7 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
     // tail loads are prefetched when a tile takes at most 4 lane-iterations (narrow channel slices)
     constexpr int TAIL_LP = (COLS / V) <= 2 ? 2 : ((COLS / V) <= 4 ? 4 : ((COLS / V) <= 8 ? 8 : ((COLS / V) <= 16 ? 16 : ((COLS / V) <= 32 ? 32 : 64))));
     constexpr int NIT = kTile / (kWave / TAIL_LP);
-    constexpr bool PREFETCH_TAIL = NIT <= 4 && !STREAM;
+    constexpr bool PREFETCH_TAIL = NIT <= 4 && WMODE == 0;
     // Software pipeline over tiles: the list entry of tile n+2 and the update flags of tile n+1 are
     // requested while tile n is processed, so neither round trip sits on a tile's critical path.
     struct TileGeom { int p32; bool valid; int iy0, ix0, q00; };
@@ -145,10 +165,31 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
                 cu.kc0 = 0; ++cu.t;
                 if (++cu.dx == ksz) { cu.dx = 0; ++cu.dy; }
             }
+            // (flat K: t counts to ktaps = 1, dy / dx are not used)
         };
         // 16 bytes of input channels per K-step for this lane's pixel; lanes that do not need the tap
         // (or whose channels are padding) read the zero page instead: no branches, no invalid reads
         auto gather_group = [&](const Cursor& cu, Vec (&x)[GK]) {
+            if constexpr (!ALIGNED) {
+                if (flat) {
+                    const T* first = in + (int64_t)q00 * c.cin;   // element of tap (0,0), channel 0; only used with a flagged tap
+                    const int nflat = taps * c.cin;
+#pragma unroll
+                    for (int u = 0; u < GK; ++u) {
+                        Vec v;
+#pragma unroll
+                        for (int i = 0; i < KP; ++i) {
+                            const int j = (2 * (cu.kc0 + u) + g) * KP + i;
+                            const bool inside = cu.t < ktaps && cu.kc0 + u < kch && j < nflat;
+                            const int2 lt = flat_lut[inside ? j : 0];
+                            const bool ok = inside && ((tapbits >> lt.y) & 1);
+                            v[i] = ok ? first[lt.x] : (T)0.0f;
+                        }
+                        x[u] = v;
+                    }
+                    return;
+                }
+            }
             const bool tap_ok = cu.t < taps && ((tapbits >> cu.t) & 1);
             const T* src = in + (int64_t)(q00 + cu.dy * c.w + cu.dx) * c.cin;
 #pragma unroll
@@ -184,7 +225,48 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
 
-            if constexpr (!STREAM) {
+            if constexpr (WMODE == 2) {
+                // weights from global memory: every K-step's operands (one gathered input vector, NB weight vectors)
+                // are requested RH K-steps at a time, two such sets in flight; no LDS, no barrier in the loop.
+                // K-steps are walked linearly over (tap, channel group); past the end a step gathers zeros.
+                constexpr int RH = 8;
+                const Vec* wbase = wglob + ((size_t)cgroup * ksteps * 2 + g) * COLS + col;
+                struct Lin { int ks, t, kc, dy, dx; };
+                auto issue = [&](Lin& li, Vec (&x)[RH], Vec (&wv)[RH][NB]) {
+#pragma unroll
+                    for (int u = 0; u < RH; ++u) {
+                        const bool live = li.ks < ksteps;
+                        const bool tap_ok = live && ((tapbits >> (li.t & 63)) & 1);
+                        const int ch = (2 * li.kc + g) * KP;
+                        const bool ok = tap_ok && ch < c.cin;
+                        const T* ptr = ok ? in + (int64_t)(q00 + li.dy * c.w + li.dx) * c.cin + ch : zeros;
+                        x[u] = *reinterpret_cast<const Vec*>(ptr);
+                        const Vec* wrow = wbase + (size_t)(live ? li.ks : 0) * 2 * COLS;
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) wv[u][b] = wrow[b * 32];
+                        ++li.ks;
+                        if (++li.kc == kch) {
+                            li.kc = 0; ++li.t;
+                            if (++li.dx == ksz) { li.dx = 0; ++li.dy; }
+                        }
+                    }
+                };
+                auto mma = [&](const Vec (&x)[RH], const Vec (&wv)[RH][NB]) {
+#pragma unroll
+                    for (int u = 0; u < RH; ++u)
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wv[u][b], x[u]);
+                };
+                Vec xa[RH], xb[RH], wa[RH][NB], wb[RH][NB];
+                Lin li{0, 0, 0, 0, 0};
+                issue(li, xa, wa);
+                for (int ks0 = 0; ks0 < ksteps; ks0 += 2 * RH) {
+                    issue(li, xb, wb);
+                    mma(xa, wa);
+                    issue(li, xa, wa);
+                    mma(xb, wb);
+                }
+            } else if constexpr (!STREAM) {
                 // weights resident: waves run independently; the gathers of the next group of K-steps
                 // are in flight while the matrix cores work on the current group (two register sets)
                 const Vec* wbase = w_lds + ((size_t)cgroup * ksteps * 2 + g) * COLS + col;
@@ -210,13 +292,13 @@ __global__ __launch_bounds__(DCNN_CONV_BOUNDS) void conv_mfma_kernel(ListArgs l,
                 Vec xa[GK], xb[GK];
                 Cursor ca{0, 0, 0, 0}, cb;
                 gather_group(ca, xa);
-                while (ca.t < taps) {
+                while (ca.t < ktaps) {
                     cb = ca; advance(cb);
-                    if (cb.t < taps) gather_group(cb, xb);
+                    if (cb.t < ktaps) gather_group(cb, xb);
                     mma_group(ca, xa);
-                    if (cb.t >= taps) break;
+                    if (cb.t >= ktaps) break;
                     ca = cb; advance(ca);
-                    if (ca.t < taps) gather_group(ca, xa);
+                    if (ca.t < ktaps) gather_group(ca, xa);
                     mma_group(cb, xb);
                 }
             } else {
@@ -318,10 +400,20 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
     constexpr int VEC = Elem<T>::VEC;
     const bool vec_out = (e.c % VEC) == 0;
     const bool aligned = ((size_t)c.cin * sizeof(T)) % 16 == 0;
-    const int tiles_per_iter = p.waves / p.cs;
+    // Weights that do not fit LDS and a short work list (at most two 4-wave workgroups per compute unit cover it):
+    // every wave loads its weight operands itself, several K-steps ahead, instead of one streamed slice per round
+    // trip to memory.  Sparse steps with 16-byte aligned channels only.
+    constexpr int kDirectWaves = 4;
+    const int64_t max_tiles = cdiv(l.max_count > 0 ? l.max_count : 1, kTile);
+    const bool direct = p.stream && !init && vec_out && aligned && cdiv(max_tiles * p.cs, kDirectWaves) <= 2 * (int64_t)ctx->num_cu;
+    const int waves = direct ? kDirectWaves : p.waves;
+    const size_t lds_bytes = direct ? conv_stage_bytes(kDirectWaves, NB, sizeof(T) == 2 ? DCNN_F16 : DCNN_F32) + conv_xchg_bytes(kDirectWaves)
+                                    : p.lds_bytes;
+    const int tiles_per_iter = waves / p.cs;
     int64_t want = cdiv(l.max_count > 0 ? l.max_count : 1, tiles_per_iter * kTile);
-    int64_t per_cu = (int64_t)(kLdsBytes / p.lds_bytes);
+    int64_t per_cu = (int64_t)(kLdsBytes / lds_bytes);
     per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
+    if (direct) per_cu = 2;
     int64_t cap = (int64_t)ctx->num_cu * per_cu;
     const int grid = (int)(cdiv(want < cap ? want : cap, kXcd) * kXcd);
     // several passes and fewer workgroups than the chip holds: spread the passes over grid.y
@@ -336,9 +428,9 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
     const int ini = init ? 1 : 0;
     hipError_t err = hipSuccess;
     bool launched = false;
-#define DCNN_CONV_LAUNCH(V, AL, ST, KS)                                                                          \
+#define DCNN_CONV_LAUNCH(V, AL, WM, KS)                                                                          \
     do {                                                                                                         \
-        auto kern = conv_mfma_kernel<T, NB, V, AL, ST, KS>;                                                      \
+        auto kern = conv_mfma_kernel<T, NB, V, AL, WM, KS>;                                                      \
         static bool attr_set = false;                                                                            \
         if (!attr_set) {                                                                                         \
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -346,7 +438,7 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
             attr_set = (err == hipSuccess);                                                                      \
         }                                                                                                        \
         if (err == hipSuccess)                                                                                   \
-            hipLaunchKernelGGL(kern, dim3(grid, grid_y), dim3(p.waves * kWave), p.lds_bytes, ctx->stream, l, c, e, ini, p.npass, p.cs, pass_split); \
+            hipLaunchKernelGGL(kern, dim3(grid, grid_y), dim3(waves * kWave), lds_bytes, ctx->stream, l, c, e, ini, p.npass, p.cs, pass_split); \
         launched = true;                                                                                         \
     } while (0)
     // resident weights, vector-aligned channels, one pass, sparse step: the wave-specialised kernel
@@ -398,15 +490,20 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
     // instantiated combinations: the common case (16-byte aligned input pixels, vector-width output
     // channels) is specialised on the window size; odd shapes take the generic-window kernels
     if (vec_out && aligned) {
-        if (p.stream) DCNN_CONV_LAUNCH(VEC, true, true, 0);
-        else if (c.k == 1) DCNN_CONV_LAUNCH(VEC, true, false, 1);
-        else if (c.k == 3) DCNN_CONV_LAUNCH(VEC, true, false, 3);
-        else DCNN_CONV_LAUNCH(VEC, true, false, 0);
+        if (direct) {
+            if (c.k == 1) DCNN_CONV_LAUNCH(VEC, true, 2, 1);
+            else if (c.k == 3) DCNN_CONV_LAUNCH(VEC, true, 2, 3);
+            else DCNN_CONV_LAUNCH(VEC, true, 2, 0);
+        }
+        else if (p.stream) DCNN_CONV_LAUNCH(VEC, true, 1, 0);
+        else if (c.k == 1) DCNN_CONV_LAUNCH(VEC, true, 0, 1);
+        else if (c.k == 3) DCNN_CONV_LAUNCH(VEC, true, 0, 3);
+        else DCNN_CONV_LAUNCH(VEC, true, 0, 0);
     } else if (vec_out && !p.stream) {
-        DCNN_CONV_LAUNCH(VEC, false, false, 0);
+        DCNN_CONV_LAUNCH(VEC, false, 0, 0);
     } else if (!vec_out && !p.stream) {
         if constexpr (NB <= 2) {
-            if (aligned) DCNN_CONV_LAUNCH(1, true, false, 0); else DCNN_CONV_LAUNCH(1, false, false, 0);
+            if (aligned) DCNN_CONV_LAUNCH(1, true, 0, 0); else DCNN_CONV_LAUNCH(1, false, 0, 0);
         }
     }
 #undef DCNN_CONV_LAUNCH

@@ -54,6 +54,7 @@ dcnn_status launch_pack_weights(dcnn_ctx* ctx, int dtype, const void* w, void* w
     if (!p.ok) return fail(ctx, DCNN_EUNSUPPORTED, "pack_weights: unsupported convolution shape");
     const int64_t total = (int64_t)p.w_bytes / (int64_t)dtype_size(dtype);
     const int grid = (int)(cdiv(total, 256) < 4096 ? cdiv(total, 256) : 4096);
+    if (p.flat) { cin = k * k * cin; k = 1; }                 // [k][k][cin][cout] read as [k*k*cin][cout]
     if (dtype == DCNN_F16)
         hipLaunchKernelGGL((pack_weights_kernel<f16>), dim3(grid), dim3(256), 0, ctx->stream, static_cast<const f16*>(w),
                            static_cast<f16*>(wpacked), k, cin, cout, p.nb, p.npass * p.cs, p.kch);
@@ -123,6 +124,7 @@ dcnn_status launch_conv(dcnn_ctx* ctx, int dtype, bool init, const ListArgs& l, 
     const ConvPlan p = conv_plan(dtype, c.k, c.cin, c.cout, fused);
     c.cout_pad = p.cout_pad;
     c.kch = p.kch;
+    c.flat = p.flat ? 1 : 0;
     c.kch2 = c.in2_data ? (int)cdiv(c.cin2, dtype == DCNN_F16 ? 16 : 8) : 0;
     c.div_ow = make_fastdiv((uint32_t)c.ow);
     c.div_oh = make_fastdiv((uint32_t)c.oh);

@@ -72,6 +72,7 @@ struct ConvPlan {
     int kch;           // K-steps per tap, each covering 2 * KPACK input channels
     size_t w_bytes;    // packed weights
     bool stream;       // weights do not fit LDS: stream them in slices
+    bool flat;         // the window's (tap, channel) pairs form one flat K dimension (stems with very few channels)
     bool full_tail;    // one pass: the activation tail sees the whole pixel
     size_t lds_bytes;
     bool ok;
@@ -80,8 +81,31 @@ struct ConvPlan {
 inline size_t conv_stage_bytes(int waves, int nb, int dtype) { return (size_t)waves * kTile * (nb * 32 * dtype_size(dtype) + kStagePad); }
 inline size_t conv_xchg_bytes(int waves) { return (size_t)2 * waves * kTile * sizeof(float); }
 
+// A k x k window over fewer channels than one 16-byte vector holds (network stems: 3 channels) would spend one
+// K-step per tap on mostly padding.  Its k*k*cin values are one flat K dimension instead: the weights
+// [k][k][cin][cout] already are [k*k*cin][cout], and the gather decodes (tap, channel) per element.
+constexpr int kFlatMaxK = 256;                       // flat K values (the decode table sits in LDS)
+inline bool conv_flat_k(int dtype, int k, int cin) {
+    return k > 1 && (size_t)cin * dtype_size(dtype) < 16 && k * k * cin <= kFlatMaxK;
+}
+inline size_t conv_flat_lut_bytes() { return (size_t)kFlatMaxK * 8; }
+
+inline ConvPlan conv_plan_window(int dtype, int k, int cin, int cout, bool need_full_tail);
+
 // The plan depends only on the layer's description, so packing, sizing and launching agree on it.
 inline ConvPlan conv_plan(int dtype, int k, int cin, int cout, bool need_full_tail) {
+    if (conv_flat_k(dtype, k, cin)) {
+        ConvPlan p = conv_plan_window(dtype, 1, k * k * cin, cout, need_full_tail);
+        if (p.ok && !p.stream && p.lds_bytes + conv_flat_lut_bytes() <= kLdsBytes) {
+            p.flat = true;
+            p.lds_bytes += conv_flat_lut_bytes();
+            return p;
+        }
+    }
+    return conv_plan_window(dtype, k, cin, cout, need_full_tail);
+}
+
+inline ConvPlan conv_plan_window(int dtype, int k, int cin, int cout, bool need_full_tail) {
     const int kpack = dtype == DCNN_F16 ? 8 : 4;
     const int vec = dtype == DCNN_F16 ? 8 : 4;
     const bool vec_out = cout % vec == 0;
