@@ -148,10 +148,8 @@ typedef struct dcnn_net dcnn_net;
 /* ---- context ------------------------------------------------------------------------------- */
 /* hip_stream: a hipStream_t (may be NULL = default stream), borrowed.  workspace_dev: scratch
  * shared by all layers of the context (partial counts, survivor bits); dcnn_workspace_bytes(p)
- * is enough for any layer whose output has at most p = n*h*w pixels.  dcnn_ctx_create clears the
- * workspace (asynchronously, on the stream); the library keeps a few control words in its last 256
- * bytes, so the memory must not be written by anything else while the context lives, and all work
- * of one context is issued to its one stream. */
+ * is enough for any layer whose output has at most p = n*h*w pixels.  All work of one context is
+ * issued to its one stream; the workspace must not be used by anything else meanwhile. */
 size_t      dcnn_workspace_bytes(int64_t max_pixels);
 dcnn_status dcnn_ctx_create(void* hip_stream, void* workspace_dev, size_t workspace_bytes, dcnn_ctx** out);
 void        dcnn_ctx_destroy(dcnn_ctx* ctx);

@@ -60,11 +60,6 @@ struct Workspace {
     int64_t max_pixels;
 };
 size_t workspace_bytes(int64_t max_pixels);
-// Three control words (ticket counter, finished counter, error) of the single-launch compaction: the last 256
-// bytes of the workspace, zero between launches.
-inline int32_t* scan_control(const dcnn_ctx* ctx) {
-    return reinterpret_cast<int32_t*>(ctx->ws + ((ctx->ws_bytes - kAlign) & ~(size_t)(kAlign - 1)));
-}
 dcnn_status workspace_view(dcnn_ctx* ctx, int64_t pixels, Workspace* out);
 
 // ---- kernel launchers (defined in the *.hip files) -------------------------------------------

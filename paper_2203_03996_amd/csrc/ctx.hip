@@ -68,11 +68,6 @@ dcnn_status dcnn_ctx_create(void* hip_stream, void* workspace_dev, size_t worksp
     c->num_cu = prop.multiProcessorCount;
     c->max_lds = prop.sharedMemPerBlock;                // 160 KB on gfx950; the conv plans rely on it
     c->err[0] = 0;
-    // the compaction kernels expect their control words and count words to start at zero
-    if (c->ws && c->ws_bytes >= kAlign) {
-        const hipError_t e = hipMemsetAsync(c->ws, 0, c->ws_bytes, c->stream);
-        if (e != hipSuccess) { delete c; return DCNN_EHIP; }
-    }
     *out = c;
     return DCNN_OK;
 }
