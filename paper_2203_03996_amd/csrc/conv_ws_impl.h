@@ -319,6 +319,11 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 }
             }
         };
+        // x^A, x^T and the dense output O are touched once per frame: they stream past the caches (non-temporal), which
+        // leaves L2 to the deltas and tap rows that producers and the next kernels re-read.  Measured over the whole
+        // step, all three non-temporal is best (4 % against plain accesses).
+        auto state_load = [&](__amdgpu_buffer_rsrc_t r, uint32_t o) -> Raw { return ws_load16_nt<Raw>(r, o); };
+        auto state_store = [&](__amdgpu_buffer_rsrc_t r, uint32_t o, Raw v) { ws_store16_nt<Raw>(r, o, v); };
         struct Set { Raw ra[H], rt[H], rr[AUX ? H : 1]; };
         // loads that do not depend on the convolution result, for the H iterations of set s
         auto load_set = [&](auto sf, const Tile& t, int s, Set& st) {
@@ -326,10 +331,10 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
             for (int h = 0; h < H; ++h) {
                 const uint32_t o = t.off[s * H + h];
                 if constexpr (RES) st.rr[h] = ws_load16<Raw>(rs_res, t.rflag[s * H + h] ? o : kOob);
-                if constexpr (ACC) st.rr[h] = ws_load16<Raw>(rs_res, o);   // O, read before the decision is known
+                if constexpr (ACC) st.rr[h] = state_load(rs_res, o);      // O, read before the decision is known
                 if constexpr (decltype(sf)::value) {
-                    st.ra[h] = ws_load16<Raw>(rs_xA, o);
-                    st.rt[h] = ws_load16<Raw>(rs_xT, o);
+                    st.ra[h] = state_load(rs_xA, o);
+                    st.rt[h] = state_load(rs_xT, o);
                 }
             }
         };
@@ -369,14 +374,14 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
                     upd = u >= e.eps;
                     const uint32_t o_upd = upd ? o : kOob;
-                    ws_store16<Raw>(rs_xA, o_upd, o_a);
-                    ws_store16<Raw>(rs_xT, o, upd ? raw_zero<T, V>() : o_t);
+                    state_store(rs_xA, o_upd, o_a);
+                    state_store(rs_xT, o, upd ? raw_zero<T, V>() : o_t);
                     if constexpr (ACC) {
                         // final layer: the emitted (rounded) delta goes straight into the dense output
                         Raw o_O;
 #pragma unroll
                         for (int i = 0; i < V; ++i) raw_set<T, V>(o_O, i, raw_get<T, V>(st.rr[h], i) + raw_get<T, V>(o_y, i));
-                        ws_store16<Raw>(rs_res, o_upd, o_O);
+                        state_store(rs_res, o_upd, o_O);
                     } else {
                         ws_store16<Raw>(rs_out, o_upd, o_y);
                     }

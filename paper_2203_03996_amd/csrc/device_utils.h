@@ -475,6 +475,16 @@ template <typename Raw> __device__ __forceinline__ Raw ws_load16(__amdgpu_buffer
 template <typename Raw> __device__ __forceinline__ void ws_store16(__amdgpu_buffer_rsrc_t r, uint32_t off, Raw v) {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)off, 0, 0);
 }
+// The same with the non-temporal hint, for data that is touched once per frame (accumulated values, truncated
+// values, the stored frame, the dense output): it streams past the caches instead of displacing the deltas and
+// weights that the next kernels re-read.
+constexpr int kAuxNonTemporal = 2;
+template <typename Raw> __device__ __forceinline__ Raw ws_load16_nt(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    return __builtin_bit_cast(Raw, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, kAuxNonTemporal));
+}
+template <typename Raw> __device__ __forceinline__ void ws_store16_nt(__amdgpu_buffer_rsrc_t r, uint32_t off, Raw v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)off, 0, kAuxNonTemporal);
+}
 
 // Pixel of work-list entry `j` for the lane that owns it (-1 beyond the end of the list).
 __device__ __forceinline__ int list_pixel(const int32_t* list, int64_t j, int64_t count) {

@@ -66,8 +66,8 @@ __device__ __forceinline__ uint32_t sparse_tile_tail(const EpilogueArgs& e, cons
                 off[ub][v] = o;
                 src.issue(ub, v, c0, on, o);
                 rr[ub][v] = ws_load16<Raw>(rs.res, rf ? o : kOob);          // empty descriptor without a second stream
-                ra[ub][v] = ws_load16<Raw>(rs.xA, o);                        // empty descriptors without an activation
-                rt[ub][v] = ws_load16<Raw>(rs.xT, o);
+                ra[ub][v] = ws_load16_nt<Raw>(rs.xA, o);                     // empty descriptors without an activation
+                rt[ub][v] = ws_load16_nt<Raw>(rs.xT, o);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -106,8 +106,8 @@ __device__ __forceinline__ uint32_t sparse_tile_tail(const EpilogueArgs& e, cons
                 const uint32_t o = off[ub][v];
                 if (stateful) {
                     const uint32_t o_upd = upd ? o : kOob;
-                    ws_store16<Raw>(rs.xA, o_upd, o_a[v]);
-                    ws_store16<Raw>(rs.xT, o, upd ? raw_zero<T, V>() : o_t[v]);
+                    ws_store16_nt<Raw>(rs.xA, o_upd, o_a[v]);
+                    ws_store16_nt<Raw>(rs.xT, o, upd ? raw_zero<T, V>() : o_t[v]);
                     ws_store16<Raw>(rs.out, o_upd, o_y[v]);
                 } else {
                     ws_store16<Raw>(rs.out, o, o_y[v]);
@@ -530,8 +530,8 @@ __global__ __launch_bounds__(kDeltaGenThreads) void deltagen_kernel(DeltaGenArgs
                 const int vi = sub + v * LP;
                 rf[ub][v] = raw_zero<T, V>(); rq[ub][v] = raw_zero<T, V>();
                 if (p < chunk_end && vi < nvec) {
-                    rf[ub][v] = raw_load<T, V>(frame + p * C + vi * V);
-                    rq[ub][v] = raw_load<T, V>(P + p * C + vi * V);
+                    rf[ub][v] = __builtin_nontemporal_load(reinterpret_cast<const Raw*>(frame + p * C + vi * V));
+                    rq[ub][v] = __builtin_nontemporal_load(reinterpret_cast<const Raw*>(P + p * C + vi * V));
                 }
             }
         }
@@ -558,7 +558,7 @@ __global__ __launch_bounds__(kDeltaGenThreads) void deltagen_kernel(DeltaGenArgs
                     const int vi = sub + v * LP;
                     if (vi < nvec) {
                         raw_store<T, V>(out + p * C + vi * V, rd[v]);
-                        raw_store<T, V>(P + p * C + vi * V, rf[ub][v]);
+                        __builtin_nontemporal_store(rf[ub][v], reinterpret_cast<Raw*>(P + p * C + vi * V));
                     }
                 }
             }
