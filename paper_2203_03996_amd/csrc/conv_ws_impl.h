@@ -375,7 +375,9 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     upd = u >= e.eps;
                     const uint32_t o_upd = upd ? o : kOob;
                     state_store(rs_xA, o_upd, o_a);
-                    state_store(rs_xT, o, upd ? raw_zero<T, V>() : o_t);
+                    // an update resets x^T to zero: where this lane's x^T already is all zero bits nothing needs to be
+                    // written (most pixels that update every frame never accumulate anything)
+                    state_store(rs_xT, (upd && all_bits_zero(st.rt[h])) ? kOob : o, upd ? raw_zero<T, V>() : o_t);
                     if constexpr (ACC) {
                         // final layer: the emitted (rounded) delta goes straight into the dense output
                         Raw o_O;

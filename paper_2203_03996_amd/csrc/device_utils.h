@@ -475,6 +475,11 @@ template <typename Raw> __device__ __forceinline__ Raw ws_load16(__amdgpu_buffer
 template <typename Raw> __device__ __forceinline__ void ws_store16(__amdgpu_buffer_rsrc_t r, uint32_t off, Raw v) {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)off, 0, 0);
 }
+// True iff every bit of the 16-byte vector is zero (+0.0 in every element).
+template <typename Raw> __device__ __forceinline__ bool all_bits_zero(Raw v) {
+    const u32x4 w = __builtin_bit_cast(u32x4, v);
+    return (w[0] | w[1] | w[2] | w[3]) == 0u;
+}
 // The same with the non-temporal hint, for data that is touched once per frame (accumulated values, truncated
 // values, the stored frame, the dense output): it streams past the caches instead of displacing the deltas and
 // weights that the next kernels re-read.

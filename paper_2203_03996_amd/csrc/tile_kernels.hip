@@ -107,7 +107,8 @@ __device__ __forceinline__ uint32_t sparse_tile_tail(const EpilogueArgs& e, cons
                 if (stateful) {
                     const uint32_t o_upd = upd ? o : kOob;
                     ws_store16_nt<Raw>(rs.xA, o_upd, o_a[v]);
-                    ws_store16_nt<Raw>(rs.xT, o, upd ? raw_zero<T, V>() : o_t[v]);
+                    // (an x^T that already is all zero bits is not rewritten on an update)
+                    ws_store16_nt<Raw>(rs.xT, (upd && all_bits_zero(rt[ub][v])) ? kOob : o, upd ? raw_zero<T, V>() : o_t[v]);
                     ws_store16<Raw>(rs.out, o_upd, o_y[v]);
                 } else {
                     ws_store16<Raw>(rs.out, o, o_y[v]);
