@@ -489,7 +489,11 @@ def main():
                      "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": layer_names[dominant], "kernel_ms": kern_ms, "algorithmic_bytes_per_launch": dom_bytes,
                      "needed_gflop_per_launch": dom_need / 1e9, "issued_gflop_per_launch": dom_issued / 1e9,
-                     "mfma_frac_of_fp16_peak": dom_issued / (kern_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS},
+                     "mfma_frac_of_fp16_peak": dom_issued / (kern_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
+                     # measured HBM bytes over the same time (below the algorithmic figure: an x^T that is already
+                     # zero is not rewritten when its pixel updates)
+                     "traffic_gbs": (traffic / (kern_ms * 1e-3) / 1e9) if traffic else None,
+                     "traffic_frac_of_peak": (traffic / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS) if traffic else None},
         "whole_step": {"algorithmic_bytes": step_bytes, "achieved_gbs": step_bytes / (ms * 1e-3) / 1e9,
                        "frac_of_hbm_peak": step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "layer_kernel_ms": dict(zip(layer_names, [round(x, 5) for x in prof]))},
