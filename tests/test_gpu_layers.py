@@ -164,6 +164,11 @@ CONV_CASES = [
     ("f16", 1, 1, 0, 64, 256, (1, 48, 48)),
     ("f16", 3, 2, 1, 3, 32, (1, 50, 50)),
     ("f16", 7, 2, 3, 3, 64, (1, 40, 40)),
+    # few input channels: the window's (tap, channel) pairs are one flat K dimension
+    ("f16", 5, 1, 2, 6, 32, (1, 18, 20)),
+    ("f32", 5, 2, 2, 3, 16, (2, 17, 19)),
+    ("f16", 3, 1, 1, 1, 8, (1, 12, 16)),
+    ("f16", 7, 1, 3, 5, 40, (1, 15, 15)),
     ("f16", 1, 1, 0, 48, 96, (1, 25, 25)),
     ("f16", 3, 1, 1, 32, 160, (1, 21, 20)),
     ("f16", 1, 2, 0, 64, 128, (1, 30, 30)),
