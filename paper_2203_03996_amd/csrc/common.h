@@ -85,6 +85,8 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& a);
 dcnn_status launch_emit_sublist(dcnn_ctx* ctx, const int32_t* list, const int32_t* count, int64_t max_count,
                                 const uint32_t* surv, int32_t* idx_out, int32_t* count_out);
 dcnn_status launch_fill_i32(dcnn_ctx* ctx, int32_t* p, int32_t v, int64_t n);
+// flags[p] = 1 iff row p of `data` ([pixels, c] elements) has a non-zero bit.
+dcnn_status launch_row_flags(dcnn_ctx* ctx, int dtype, const void* data, uint8_t* flags, int64_t pixels, int c);
 dcnn_status launch_fill_u8(dcnn_ctx* ctx, uint8_t* p, uint8_t v, int64_t n);
 
 // Element-wise tail shared by CONV / ACT: (+bias) (+residual) activation, truncation, state.
@@ -101,6 +103,8 @@ struct EpilogueArgs {
     uint8_t* out_mask;           // written at every visited pixel (0 or 1); nullptr: not written
     uint32_t* surv;              // survivor word per tile; nullptr: not written
     int32_t* out_count;          // when surv is null: survivors are added here (zeroed by the mask pass)
+    uint8_t* xt_flags;           // optional, per output pixel: 0 = the pixel's x^T row is all zero bits in memory and is
+                                 // not read; 1 = it may hold values.  Kept up to date by the wave-specialised kernel only.
     void* accum_O;               // fused final accumulation: dense output O (output shape); the emitted delta is
                                  // added to it and not stored (sparse steps of layers with an activation only)
 };

@@ -458,6 +458,9 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
     if (accum && (!ws_ok || e.res_data != nullptr || e.act == DCNN_ACT_NONE))
         return fail(ctx, DCNN_EUNSUPPORTED, "conv %dx%d %d->%d with a fused final accumulation: shape not covered", c.k, c.k,
                     c.cin, c.cout);
+    if (e.xt_flags != nullptr && !ws_ok && !init)
+        return fail(ctx, DCNN_EUNSUPPORTED, "conv %dx%d %d->%d: x^T row flags are kept by the wave-specialised kernel only", c.k, c.k,
+                    c.cin, c.cout);
     if (ws_ok) {
         const int64_t ws_want = cdiv(l.max_count > 0 ? l.max_count : 1, (kWsProducers / p.cs) * kTile);
         const int64_t ws_cap = ctx->num_cu;                    // 16 waves of up to 128 registers fill a compute unit

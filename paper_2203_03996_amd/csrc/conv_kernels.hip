@@ -66,7 +66,8 @@ dcnn_status launch_pack_weights(dcnn_ctx* ctx, int dtype, const void* w, void* w
 
 bool conv_ws_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cout, int64_t in_elems, int64_t out_elems) {
     const size_t es = dtype_size(dtype);
-    if (ctx->max_lds < kLdsBytes || (k != 1 && k != 3) || ((size_t)cin * es) % 16 != 0) return false;
+    // (ctx may be null: every context that exists has the LDS the plans assume)
+    if ((ctx && ctx->max_lds < kLdsBytes) || (k != 1 && k != 3) || ((size_t)cin * es) % 16 != 0) return false;
     const ConvPlan p = conv_plan(dtype, k, cin, cout, true);
     if (!p.ok || conv_ws_lds_bytes(p, dtype, k, cout, 0) == 0) return false;
     const uint64_t lim = kWsMaxBytes / es;
@@ -76,7 +77,7 @@ bool conv_ws_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cout,
 bool conv_proj_supported(const dcnn_ctx* ctx, int dtype, int k, int cin, int cin2, int cout, int64_t in_elems,
                          int64_t in2_elems, int64_t out_elems) {
     const size_t es = dtype_size(dtype);
-    if (ctx->max_lds < kLdsBytes || (k != 1 && k != 3)) return false;
+    if ((ctx && ctx->max_lds < kLdsBytes) || (k != 1 && k != 3)) return false;
     if (((size_t)cin * es) % 16 != 0 || ((size_t)cin2 * es) % 16 != 0) return false;
     const ConvPlan p = conv_plan(dtype, k, cin, cout, true);
     if (!p.ok || conv_ws_lds_bytes(p, dtype, k, cout, cin2) == 0) return false;

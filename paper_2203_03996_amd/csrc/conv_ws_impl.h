@@ -296,6 +296,8 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         const __amdgpu_buffer_rsrc_t rs_rmask = ws_rsrc(e.res_mask, out_pixels);
         const __amdgpu_buffer_rsrc_t rs_omask = ws_rsrc(e.out_mask, out_pixels);
         const bool has_rmask = e.res_mask != nullptr;
+        const __amdgpu_buffer_rsrc_t rs_tflag = ws_rsrc(e.xt_flags, out_pixels);
+        const bool has_tflag = e.xt_flags != nullptr;
         const float hi = act_hi(e.act);
         // this lane's 16 bytes in row 0 of the producer slice that holds its channels (lanes without
         // channels read slot 0 and discard it; their stores go nowhere)
@@ -306,6 +308,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
             int pix[NIT];          // pixel of iteration it (-1 beyond the list)
             uint32_t off[NIT];     // byte offset of this lane's channels (out of range: nothing to do)
             uint8_t rflag[NIT];    // update flag of the residual stream
+            uint8_t tflag[NIT];    // 0: the pixel's x^T row is known to be all zero and is not read
         };
         // derived values of a tile whose list entries have arrived; requests its residual flags
         auto prepare = [&](Tile& t) {
@@ -317,6 +320,8 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 if constexpr (RES) {
                     if (has_rmask) t.rflag[it] = __builtin_amdgcn_raw_buffer_load_b8(rs_rmask, p >= 0 ? p : (int)kOob, 0, 0);
                 }
+                t.tflag[it] = 1;
+                if (has_tflag) t.tflag[it] = __builtin_amdgcn_raw_buffer_load_b8(rs_tflag, p >= 0 ? p : (int)kOob, 0, 0);
             }
         };
         // x^A, x^T and the dense output O are touched once per frame: they stream past the caches (non-temporal), which
@@ -334,7 +339,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 if constexpr (ACC) st.rr[h] = state_load(rs_res, o);      // O, read before the decision is known
                 if constexpr (decltype(sf)::value) {
                     st.ra[h] = state_load(rs_xA, o);
-                    st.rt[h] = state_load(rs_xT, o);
+                    st.rt[h] = state_load(rs_xT, t.tflag[s * H + h] ? o : kOob);
                 }
             }
         };
@@ -392,6 +397,11 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 }
                 const bool lead = t.pix[it] >= 0 && sub == 0;
                 __builtin_amdgcn_raw_buffer_store_b8((uint8_t)(upd ? 1 : 0), rs_omask, lead ? t.pix[it] : (int)kOob, 0, 0);
+                if constexpr (decltype(sf)::value) {
+                    // after an update the row is zero again; after a truncation it holds values (empty descriptor: no flags)
+                    const uint8_t keep = upd ? 0 : 1;
+                    __builtin_amdgcn_raw_buffer_store_b8(keep, rs_tflag, (lead && keep != t.tflag[it]) ? t.pix[it] : (int)kOob, 0, 0);
+                }
                 if (lead && upd) bits |= 1u << (ent0 + it * PPI);
             }
             return bits;

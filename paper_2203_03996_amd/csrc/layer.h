@@ -27,6 +27,9 @@ struct dcnn_layer {
     int32_t* list;                      // work list when the layer builds its own
     int32_t* list_count;
     uint32_t* taps;                     // per work-list entry: flagged window taps (dense convolutions, 1x1 / 3x3)
+    uint8_t* xt_flags;                  // per output pixel: 0 = its x^T row is all zero and need not be read (layers whose
+                                        // sparse steps run on the wave-specialised kernel); nullptr: none
+    mutable bool xt_flags_stale = false;  // the state memory was handed out: the flags are rebuilt from x^T before the next step
     void* wpacked;
     void* bias;
     void* wpacked2;                     // fused projection: weights in the main plan's column grouping (sparse steps)

@@ -107,6 +107,15 @@ struct Carver {
     }
 };
 
+// Do the sparse steps of this convolution run on the wave-specialised kernel?  (The same conditions the launcher
+// tests; they depend on the description only.)
+static bool ws_steps(const dcnn_layer_desc& d, int64_t in_pixels, int64_t out_pixels, int oc) {
+    if (has_proj(d))
+        return conv_proj_supported(nullptr, d.dtype, d.kh, d.c, d.proj_c, oc, in_pixels * d.c,
+                                   (int64_t)d.n * d.proj_h * d.proj_w * d.proj_c, out_pixels * oc);
+    return conv_ws_supported(nullptr, d.dtype, d.kh, d.c, oc, in_pixels * d.c, out_pixels * oc);
+}
+
 static void carve(dcnn_layer* L, void* state) {
     const dcnn_layer_desc& d = L->d;
     const size_t es = dtype_size(d.dtype);
@@ -117,7 +126,7 @@ static void carve(dcnn_layer* L, void* state) {
     L->buf0 = L->buf1 = L->buf2 = nullptr; L->buf0_bytes = L->buf1_bytes = L->buf2_bytes = 0;
     L->out_data = nullptr; L->out_mask = nullptr; L->out_idx = nullptr; L->out_count = nullptr;
     L->list = nullptr; L->list_count = nullptr; L->taps = nullptr; L->wpacked = nullptr; L->bias = nullptr;
-    L->wpacked2 = nullptr; L->wpacked2_dense = nullptr; L->bias2 = nullptr;
+    L->wpacked2 = nullptr; L->wpacked2_dense = nullptr; L->bias2 = nullptr; L->xt_flags = nullptr;
     L->counters = static_cast<int32_t*>(cv.take(kAlign));      // stays all zero: doubles as the zero page of the gathers
     switch (d.kind) {
         case DCNN_DELTAGEN:
@@ -131,6 +140,8 @@ static void carve(dcnn_layer* L, void* state) {
                 if (!d.no_xT) { L->buf1 = cv.take(out_map); L->buf1_bytes = out_map; }
             }
             if (d.fuse_accum) { L->buf2 = cv.take(out_map); L->buf2_bytes = out_map; }
+            if (act && !d.no_xT && d.kind == DCNN_CONV && ws_steps(d, L->in_pixels, L->out_pixels, L->oc))
+                L->xt_flags = static_cast<uint8_t*>(cv.take((size_t)L->out_pixels));
             break;
         case DCNN_MAXPOOL:
             L->buf0 = cv.take(in_map); L->buf0_bytes = in_map;
@@ -464,6 +475,11 @@ dcnn_status dcnn_layer_init(dcnn_layer* L, const void* const* dense_in, int32_t 
     if (st != DCNN_OK) return st;
     st = clear_sparse_output(L);
     if (st != DCNN_OK) return st;
+    if (L->xt_flags) {                                        // the first frame leaves x^T all zero
+        st = launch_fill_u8(ctx, L->xt_flags, 0, L->out_pixels);
+        if (st != DCNN_OK) return st;
+        L->xt_flags_stale = false;
+    }
     L->inited = true;
     L->last_in_count = nullptr;
     L->last_in2_count = nullptr;
@@ -569,6 +585,14 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             }
             e.xA = L->buf0; e.xT = L->buf1; e.out_data = L->out_data;
             e.accum_O = d.fuse_accum ? L->buf2 : nullptr;
+            if (L->xt_flags) {
+                if (L->xt_flags_stale) {                          // the caller may have written x^T: look at it once
+                    st = launch_row_flags(ctx, d.dtype, L->buf1, L->xt_flags, L->out_pixels, L->oc);
+                    if (st != DCNN_OK) return st;
+                    L->xt_flags_stale = false;
+                }
+                e.xt_flags = L->xt_flags;
+            }
             e.out_mask = act ? L->out_mask : nullptr;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;
             e.out_count = (act && !d.want_idx) ? L->out_count : nullptr;
@@ -652,7 +676,7 @@ dcnn_status dcnn_layer_output(const dcnn_layer* L, dcnn_delta* out_view) {
 dcnn_status dcnn_layer_state(const dcnn_layer* L, int32_t which, void** ptr_dev, size_t* bytes) {
     if (!L || !ptr_dev || !bytes) return DCNN_EINVAL;
     if (which == 0 && L->buf0) { *ptr_dev = L->buf0; *bytes = L->buf0_bytes; return DCNN_OK; }
-    if (which == 1 && L->buf1) { *ptr_dev = L->buf1; *bytes = L->buf1_bytes; return DCNN_OK; }
+    if (which == 1 && L->buf1) { L->xt_flags_stale = true; *ptr_dev = L->buf1; *bytes = L->buf1_bytes; return DCNN_OK; }
     if (which == 2 && L->buf2) { *ptr_dev = L->buf2; *bytes = L->buf2_bytes; return DCNN_OK; }
     return fail(L->ctx, DCNN_EINVAL, "layer_state: the layer has no buffer %d", which);
 }

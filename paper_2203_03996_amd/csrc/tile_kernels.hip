@@ -931,6 +931,29 @@ template <typename T> __global__ void fill_kernel(T* p, T v, int64_t n) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
+// One wave per row: any non-zero bit among the row's bytes (rows are multiples of 4 bytes for the layers that use it).
+__global__ __launch_bounds__(256) void row_flags_kernel(const uint32_t* data, uint8_t* flags, int64_t pixels, int words) {
+    const int lane = threadIdx.x % kWave;
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    const int64_t nwaves = (int64_t)gridDim.x * blockDim.x / kWave;
+    for (int64_t p = wave; p < pixels; p += nwaves) {
+        uint32_t acc = 0;
+        for (int i = lane; i < words; i += kWave) acc |= data[p * words + i];
+        for (int m = kWave >> 1; m >= 1; m >>= 1) acc |= (uint32_t)__shfl_xor((int)acc, m, kWave);
+        if (lane == 0) flags[p] = acc ? 1 : 0;
+    }
+}
+
+dcnn_status launch_row_flags(dcnn_ctx* ctx, int dtype, const void* data, uint8_t* flags, int64_t pixels, int c) {
+    const int64_t row_bytes = (int64_t)c * (int64_t)dtype_size(dtype);
+    if (row_bytes % 4 != 0) return fail(ctx, DCNN_EINVAL, "row flags: rows of %lld bytes", (long long)row_bytes);
+    const int64_t want = cdiv(pixels, 4);
+    const int grid = (int)(want < (int64_t)ctx->num_cu * 8 ? (want > 0 ? want : 1) : (int64_t)ctx->num_cu * 8);
+    hipLaunchKernelGGL(row_flags_kernel, dim3(grid), dim3(256), 0, ctx->stream, static_cast<const uint32_t*>(data), flags,
+                       pixels, (int)(row_bytes / 4));
+    return check_hip(ctx, hipGetLastError(), "row_flags_kernel launch");
+}
+
 dcnn_status launch_fill_i32(dcnn_ctx* ctx, int32_t* p, int32_t v, int64_t n) {
     int grid = (int)(cdiv(n, 256) < 2048 ? cdiv(n, 256) : 2048);
     hipLaunchKernelGGL((fill_kernel<int32_t>), dim3(grid > 0 ? grid : 1), dim3(256), 0, ctx->stream, p, v, n);

@@ -338,3 +338,44 @@ def test_networks_without_truncated_value_buffers(spec_fn):
     with_xt = pkg.Net(r["ctx"], dict(spec, nodes=[{k: v for k, v in nd.items() if k != "no_xT"} for nd in spec["nodes"]]),
                       wl.make_weights(spec, 23), 2, 3)
     assert net.arena.numel() < with_xt.arena.numel()
+
+
+@pytest.mark.parametrize("eps", [0.05, 0.3])
+def test_free_running_without_touching_the_state(eps):
+    """The library keeps, per pixel, whether a layer's x^T row is all zero (such rows are not read).  Reading
+    the state through the ABI makes it rebuild those flags, so this run never does until the end: dense
+    outputs are compared every frame, the accumulated buffers after the last one."""
+    spec = wl.bottleneck_block(eps=eps, h=40, w=48, frames=8)
+    seed, n_streams = 29, 2
+    wts = wl.make_weights(spec, seed)
+    vid = wl.make_batch(spec["video"], seed, n_streams)
+    oracle = orc.OracleNet(spec, wts, "f16")
+    shapes = wl.node_shapes(spec)
+    ctx = pkg.Context(n_streams * max(h * w for h, w, _ in shapes))
+    net = pkg.Net(ctx, spec, wts, n_streams, 1)
+    oh, ow, oc = shapes[-1]
+    out = torch.empty((n_streams, oh, ow, oc), dtype=torch.float16, device="cuda")
+    tol = TOL["f16"]
+    for t in range(vid.shape[0]):
+        fr = vid[t].astype(np.float16)
+        (net.init if t == 0 else net.step)(torch.from_numpy(fr).cuda(), out)
+        ctx.sync()
+        ref = oracle.frame(fr)
+        assert rel_err(to_np(out), ref) <= 2 * tol, f"frame {t}"
+    checked = 0
+    for li in range(net.num_layers):
+        nid = net.layer_node(li)
+        ly = oracle.layers[nid]
+        xa, xt = net.layer_state(li, 0), net.layer_state(li, 1)
+        if xa is None or xt is None or getattr(ly, "xT", None) is None:
+            continue
+        got = to_np(xa).astype(np.float64) + to_np(xt).astype(np.float64)
+        want = ly.xA.astype(np.float64).reshape(-1) + ly.xT.astype(np.float64).reshape(-1)
+        assert rel_err(got, want, floor=0.1) <= 2 * tol, f"layer {li}"
+        checked += 1
+    assert checked >= 3
+    # one more frame after the state was handed out (flags rebuilt from x^T)
+    fr = vid[-2].astype(np.float16)
+    net.step(torch.from_numpy(fr).cuda(), out)
+    ctx.sync()
+    assert rel_err(to_np(out), oracle.frame(fr)) <= 2 * tol
