@@ -8,7 +8,7 @@ one frame of every stream through the whole path (delta generation -> ... -> acc
 output); inputs are resident in HBM before the timed region.  Update density is set by a single
 global threshold found by bisection.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -425,8 +425,8 @@ def main():
     ap.add_argument("--frames", type=int, default=2000, help="drift workload: frames per run")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (streams are independent; see DESIGN.md for how the "
-              "path would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (streams are independent: more GPUs would each take a share "
+              "of the streams, without any exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
