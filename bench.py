@@ -122,6 +122,7 @@ def conv_density(stats) -> float:
 
 
 def measure_density(work: Workload, eps: float, streams: int = 2) -> float:
+    streams = min(streams, work.streams)                      # the clip holds work.streams streams
     ctx, net = make_net(work, eps, streams)
     frames = [f[:streams].contiguous() for f in work.video]
     net.init(frames[0])

@@ -363,10 +363,22 @@ class Net:
         ctx.sync()                      # weights have been packed into the arena
         self.num_layers = lib.dcnn_net_num_layers(self.handle)
 
+    def _check_frame(self, frame: torch.Tensor, out: torch.Tensor | None):
+        # the ABI takes bare pointers: a tensor of the wrong size would be read or written out of bounds
+        want = (self.n, self.spec["h"], self.spec["w"], self.spec["c"])
+        if tuple(frame.shape) != want or frame.dtype != TORCH_DTYPE[self.dtype] or not frame.is_contiguous() or not frame.is_cuda:
+            raise ValueError(f"frame must be a contiguous device tensor {want} of {TORCH_DTYPE[self.dtype]}, got "
+                             f"{tuple(frame.shape)} {frame.dtype}")
+        if out is not None and (out.dtype != TORCH_DTYPE[self.dtype] or not out.is_contiguous() or not out.is_cuda or
+                                out.shape[0] != self.n):
+            raise ValueError("out must be a contiguous device tensor [n, h, w, c] of the network's type")
+
     def init(self, frame: torch.Tensor, out: torch.Tensor | None = None):
+        self._check_frame(frame, out)
         self.ctx.check(self.ctx.lib.dcnn_net_init(self.handle, _ptr(frame), _ptr(out)))
 
     def step(self, frame: torch.Tensor, out: torch.Tensor | None = None):
+        self._check_frame(frame, out)
         self.ctx.check(self.ctx.lib.dcnn_net_step(self.handle, _ptr(frame), _ptr(out)))
 
     def reset(self):

@@ -379,3 +379,18 @@ def test_free_running_without_touching_the_state(eps):
     net.step(torch.from_numpy(fr).cuda(), out)
     ctx.sync()
     assert rel_err(to_np(out), oracle.frame(fr)) <= 2 * tol
+
+
+def test_frames_of_the_wrong_shape_are_refused_before_any_launch():
+    """The ABI takes bare pointers; the binding refuses a frame whose shape or type does not match the network."""
+    spec = wl.single_conv_relu(h=16, w=16, c=8, frames=2)
+    wts = wl.make_weights(spec, 1)
+    ctx = pkg.Context(2 * 16 * 16)
+    net = pkg.Net(ctx, spec, wts, 2, 1)
+    good = torch.zeros((2, 16, 16, 8), dtype=torch.float32, device="cuda")
+    net.init(good)
+    for bad in (good[:1], good.half(), good.permute(0, 2, 1, 3), good.cpu()):
+        with pytest.raises(ValueError):
+            net.step(bad)
+    net.step(good)
+    ctx.sync()
