@@ -255,6 +255,12 @@ class Layer:
         self._keep = (weights, bias)
 
     def init(self, dense_in, dense_out=None):
+        d = self.desc
+        if not dense_in or tuple(dense_in[0].shape) != (d.n, d.h, d.w, d.c):
+            raise ValueError(f"dense input 0 must have shape {(d.n, d.h, d.w, d.c)}")
+        for t in dense_in:
+            if t.dtype != TORCH_DTYPE[d.dtype] or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError("dense inputs must be contiguous device tensors of the layer's type")
         arr = (C.c_void_p * len(dense_in))(*[t.data_ptr() for t in dense_in])
         if dense_out is None and self.desc.kind != ACCUM:
             dense_out = torch.empty(self.out_shape, dtype=TORCH_DTYPE[self.desc.dtype], device=self.ctx.device)
