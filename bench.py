@@ -63,8 +63,7 @@ def layer_bytes(s: dict, b: int) -> float:
         total += work * 2 * cout * b                                      # read x^A, x^T
         total += out * 3 * cout * b + (work - out) * cout * b             # write x^A, x^T, delta | x^T
         total += 2 * work                                                 # mask bytes
-        if s.get("fuse_accum", 0):
-            total += out * cout * b                                       # read O where updated (its write replaces the delta's)
+        # (a folded output layer writes O = f(new x^A) where updated, in place of the delta: nothing to add)
     else:
         total += work * cout * b
     return total
@@ -474,7 +473,8 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(f"streams{B}_density{HEADLINE_DENSITY}", {}).get("bytes_per_launch")
+            per_kernel = json.load(open(tpath)).get(f"streams{B}_density{HEADLINE_DENSITY}", {}).get("bytes_per_launch", {})
+            traffic = per_kernel.get(layer_names[dominant])
         except Exception:
             traffic = None
     result = {

@@ -329,14 +329,13 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         // step, all three non-temporal is best (4 % against plain accesses).
         auto state_load = [&](__amdgpu_buffer_rsrc_t r, uint32_t o) -> Raw { return ws_load16_nt<Raw>(r, o); };
         auto state_store = [&](__amdgpu_buffer_rsrc_t r, uint32_t o, Raw v) { ws_store16_nt<Raw>(r, o, v); };
-        struct Set { Raw ra[H], rt[H], rr[AUX ? H : 1]; };
+        struct Set { Raw ra[H], rt[H], rr[RES ? H : 1]; };
         // loads that do not depend on the convolution result, for the H iterations of set s
         auto load_set = [&](auto sf, const Tile& t, int s, Set& st) {
 #pragma unroll
             for (int h = 0; h < H; ++h) {
                 const uint32_t o = t.off[s * H + h];
                 if constexpr (RES) st.rr[h] = ws_load16<Raw>(rs_res, t.rflag[s * H + h] ? o : kOob);
-                if constexpr (ACC) st.rr[h] = state_load(rs_res, o);      // O, read before the decision is known
                 if constexpr (decltype(sf)::value) {
                     st.ra[h] = state_load(rs_xA, o);
                     st.rt[h] = state_load(rs_xT, t.tflag[s * H + h] ? o : kOob);
@@ -384,10 +383,12 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     // written (most pixels that update every frame never accumulate anything)
                     state_store(rs_xT, (upd && all_bits_zero(st.rt[h])) ? kOob : o, upd ? raw_zero<T, V>() : o_t);
                     if constexpr (ACC) {
-                        // final layer: the emitted (rounded) delta goes straight into the dense output
+                        // final layer: O + dy with O = f(x^A_old) (true after the first frame and kept by every update:
+                        // f(x^A_old) + f(s) - f(x^A_old)) is f of the new x^A, so O is written without being read -- and
+                        // without the rounding an accumulation in the storage type would add frame after frame
                         Raw o_O;
 #pragma unroll
-                        for (int i = 0; i < V; ++i) raw_set<T, V>(o_O, i, raw_get<T, V>(st.rr[h], i) + raw_get<T, V>(o_y, i));
+                        for (int i = 0; i < V; ++i) raw_set<T, V>(o_O, i, act_clamp(raw_get<T, V>(o_a, i), hi));
                         state_store(rs_res, o_upd, o_O);
                     } else {
                         ws_store16<Raw>(rs_out, o_upd, o_y);
