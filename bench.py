@@ -515,7 +515,7 @@ def main():
             sweep.append({"density_target": name, "eps": eps if np.isfinite(eps) else "inf", "ms_per_step": ms_d,
                           "frames_per_s": B * 1e3 / ms_d, "dense_equiv_gflops": B * 1e3 / ms_d * work.dense_flops / 1e9})
             log(f"[bench] {name}: {ms_d:.3f} ms/step")
-        ms1, _, _, _ = run_timed(work, eps_h, K, W, 1)
+        ms1, _, _, _ = run_timed(work, eps_h, max(K, 200), max(W, 20), 1)    # launch-bound: needs more steps to settle
         result["single_stream"] = {"streams": 1, "ms_per_step": ms1, "frames_per_s": 1e3 / ms1}
         md = dense_baseline(work, K, W, B)
         md1 = dense_baseline(work, K, W, 1)
