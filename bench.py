@@ -408,6 +408,106 @@ def drift_study(streams: int, frames: int):
             "rows": rows, "vs_baseline": None}
 
 
+def networks(streams: int, steps: int, warmup: int, target: float = 0.10):
+    """The other BASELINE configurations at full size (MobileNetV2-style stack, ResNet-50-shaped backbone, HRNet-shaped
+    network; random He weights): thresholds tuned front to back to a density budget per layer, then ms per frame
+    of all streams for the sparse path, for eps < 0 (everything propagated) and for the same network through
+    PyTorch-ROCm dense (fp16, channels-last; comparison only)."""
+    import torch.nn.functional as F
+    import paper_2203_03996_amd as pkg
+    from paper_2203_03996_amd import tuner
+    import workloads as wl
+    T = 6
+    order = list(range(1, T)) + list(range(T - 2, -1, -1))
+    rows = []
+    for name, fn, cfg in (("configs[2] mobilenetv2_stack 224x224", wl.mobilenet_stack, 3),
+                          ("configs[3] resnet50_backbone 256x256", wl.resnet50_backbone, 4),
+                          ("configs[4] hrnet_like 384x288", wl.hrnet_like, 5)):
+        spec = fn(eps=0.05, frames=T)
+        seed = wl.CONFIG_SEEDS[cfg]
+        weights = wl.make_weights(spec, seed)
+        vid = wl.make_batch(spec["video"], seed, streams).astype(np.float16)
+        frames = [torch.from_numpy(vid[t]).cuda() for t in range(T)]
+        maxpix = max(streams * h * w for h, w, _ in wl.node_shapes(spec))
+
+        def timed(eps, tune):
+            ctx = pkg.Context(maxpix)
+            net = pkg.Net(ctx, fn(eps=eps, frames=T), weights, streams, 1)
+            net.init(frames[0])
+            net.step(frames[1])
+            if tune:
+                tuner.tune_thresholds(net, frames, target, iters=8)
+                net.init(frames[0])
+            for k in range(warmup):
+                net.step(frames[order[k % len(order)]])
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for k in range(warmup, warmup + steps):
+                net.step(frames[order[k % len(order)]])
+            e1.record()
+            torch.cuda.synchronize()
+            st = [s for s in net.stats() if s["kind"] in (pkg.CONV, pkg.DWCONV)]
+            dens = float(np.mean([s["pixels_in"] / s["pixels_in_total"] for s in st]))
+            return e0.elapsed_time(e1) / steps, dens, net.num_layers
+
+        ms_sparse, dens, nlayers = timed(0.05, True)
+        ms_all, _, _ = timed(-1.0, False)
+        nodes = spec["nodes"]
+        tw = {}
+        for i, (w, b) in weights.items():
+            if nodes[i]["depthwise"]:
+                wt = torch.from_numpy(np.ascontiguousarray(w)).permute(2, 0, 1).unsqueeze(1).contiguous().half().cuda()
+            else:
+                wt = torch.from_numpy(np.ascontiguousarray(w)).permute(3, 2, 0, 1).contiguous().half().cuda()
+                wt = wt.contiguous(memory_format=torch.channels_last)
+            tw[i] = (wt, torch.from_numpy(b).half().cuda())
+        tf = [f.permute(0, 3, 1, 2) for f in frames]
+
+        def forward(x):
+            outs = []
+            for i, nd in enumerate(nodes):
+                k = nd["kind"]
+                a = outs[nd["in"][0]] if nd["in"] else None
+                if k == "deltagen":
+                    y = x
+                elif k == "conv":
+                    y = F.conv2d(a, tw[i][0], tw[i][1], stride=nd["stride"], padding=nd["pad"],
+                                 groups=(nd["cin"] if nd["depthwise"] else 1))
+                elif k == "act":
+                    y = F.relu(a) if nd["f"] == "relu" else F.relu6(a)
+                elif k == "add":
+                    y = a + outs[nd["in"][1]]
+                elif k == "maxpool":
+                    y = F.max_pool2d(a, nd["k"], nd["stride"], nd["pad"])
+                elif k == "upsample":
+                    y = F.interpolate(a, scale_factor=nd["factor"], mode="nearest")
+                else:
+                    y = a
+                outs.append(y)
+            return outs[-1]
+
+        with torch.no_grad():
+            for k in range(warmup):
+                forward(tf[order[k % len(order)]])
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for k in range(steps):
+                forward(tf[order[k % len(order)]])
+            e1.record()
+            torch.cuda.synchronize()
+        ms_dense = e0.elapsed_time(e1) / steps
+        rows.append({"network": name, "layers": nlayers, "conv_input_density": dens, "ms_sparse": ms_sparse,
+                     "ms_all_propagated": ms_all, "ms_dense_library": ms_dense, "speedup_vs_dense_library": ms_dense / ms_sparse})
+        log(f"[bench] {name}: sparse {ms_sparse:.3f} ms (density {dens:.3f}), eps<0 {ms_all:.3f} ms, dense library {ms_dense:.3f} ms")
+    return {"metric": "ms per frame of all streams, full-size networks at a tuned density budget", "unit": "ms", "n_gpus": 1,
+            "steps": steps, "warmup": warmup, "higher_is_better": False, "dtype": "f16", "data": "synthetic",
+            "config": {"workload": "BASELINE configs[2..4] at full size, random weights, per-layer thresholds tuned to "
+                                   f"{target:.0%} output density", "streams": streams},
+            "rows": rows, "vs_baseline": None}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -418,10 +518,11 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the measurement run one plain 1 GiB device-to-device copy kernel (reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--workload", default="bottleneck", choices=["bottleneck", "tile_ablation", "drift"],
+    ap.add_argument("--workload", default="bottleneck", choices=["bottleneck", "tile_ablation", "drift", "networks"],
                     help="bottleneck: BASELINE configs[1] (default, the headline); tile_ablation: one 3x3 128->128 "
                          "convolution under uniform-random sparsity (second workload, 8 streams unless --streams is given); "
-                         "drift: error against dense inference over --frames frames, with / without x^T and resets")
+                         "drift: error against dense inference over --frames frames, with / without x^T and resets; "
+                         "networks: the other BASELINE configurations at full size (8 streams unless --streams is given)")
     ap.add_argument("--frames", type=int, default=2000, help="drift workload: frames per run")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -436,6 +537,9 @@ def main():
     B, K, W = args.streams, args.steps, args.warmup
     if args.workload == "tile_ablation":
         print(json.dumps(tile_ablation(8 if B == 64 else B, min(K, 20), min(W, 5))))
+        return
+    if args.workload == "networks":
+        print(json.dumps(networks(8 if B == 64 else B, min(K, 20), min(W, 5))))
         return
     if args.workload == "drift":
         print(json.dumps(drift_study(4 if B == 64 else B, args.frames)))
