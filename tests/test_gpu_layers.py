@@ -180,6 +180,8 @@ CONV_CASES = [
     ("f16", 1, 1, 0, 512, 2048, (1, 9, 8)),
     ("f32", 3, 1, 1, 128, 128, (1, 16, 16)),
     ("f32", 1, 1, 0, 64, 1024, (1, 12, 12)),
+    # a long work list on streamed weights: the sparse steps, too, walk the weight slices through LDS
+    ("f16", 3, 1, 1, 128, 128, (6, 128, 128)),
 ]
 
 
@@ -219,6 +221,7 @@ def test_conv_linear(S, k, stride, pad, cin, cout, nhw):
 
 
 @pytest.mark.parametrize("S,k,stride,cin,cout,nhw,res", [
+    ("f16", 3, 1, 128, 128, (5, 128, 136), True),      # streamed weights, long list, fused tail with residual
     ("f32", 3, 1, 32, 32, (1, 64, 64), False),
     ("f16", 1, 1, 64, 64, (2, 32, 32), False),
     ("f16", 3, 1, 64, 64, (2, 33, 35), False),
