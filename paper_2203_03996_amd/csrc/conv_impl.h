@@ -1,7 +1,8 @@
 // Sparse delta convolution with dense weights as a gather-GEMM on the matrix cores: the plain kernel
 // (every wave does gather, MFMA and tail of its tile in turn).  It serves the dense first frame, layers
 // whose weights are streamed, windows other than 1x1 / 3x3 and channel counts that do not fill 16-byte
-// vectors; the sparse steps of everything else run on the wave-specialised kernel (conv_ws_impl.h), which
+// vectors; the sparse steps of everything else run on the wave-specialised kernel (conv_ws_impl.h) or, with
+// weights too large for LDS and a long list, on the register-blocked kernel (conv_direct_impl.h), which
 // launch_conv_nb below dispatches to.
 //
 // The work list holds the flagged OUTPUT pixels in ascending order.  A tile of 32 consecutive list
@@ -22,6 +23,7 @@
 
 #include "conv_plan.h"
 #include "conv_ws_impl.h"
+#include "conv_direct_impl.h"
 
 namespace dcnn {
 
@@ -403,7 +405,6 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
     // Weights that do not fit LDS and a short work list (at most two 4-wave workgroups per compute unit cover it):
     // every wave loads its weight operands itself, several K-steps ahead, instead of one streamed slice per round
     // trip to memory.  Sparse steps with 16-byte aligned channels only.
-    constexpr int kDirectWaves = 4;
     const int64_t max_tiles = cdiv(l.max_count > 0 ? l.max_count : 1, kTile);
     const bool direct = p.stream && !init && vec_out && aligned && cdiv(max_tiles * p.cs, kDirectWaves) <= 2 * (int64_t)ctx->num_cu;
     const int waves = direct ? kDirectWaves : p.waves;
@@ -489,6 +490,36 @@ static dcnn_status launch_conv_nb(dcnn_ctx* ctx, bool init, const ListArgs& l, c
 #undef DCNN_WS_LAUNCH
         if (err != hipSuccess) return check_hip(ctx, err, "hipFuncSetAttribute(conv_ws_kernel)");
         return check_hip(ctx, hipGetLastError(), "conv_ws_kernel launch");
+    }
+    // Streamed weights and a list too long for the above: two pixel tiles per wave share every weight operand
+    // (1x1 / 3x3 windows whose tap words are known, tensors within 32-bit byte offsets).
+    const bool blocked = p.stream && !init && !direct && vec_out && aligned && (c.k == 1 || c.k == 3) && ws_taps &&
+                         in_bytes <= kWsMaxBytes && p.w_bytes <= kWsMaxBytes;
+    if (blocked) {
+        constexpr int TI = NB <= 2 ? 4 : 2;               // pixel tiles per wave: a register block of 128 accumulators
+        const size_t b_lds = conv_stage_bytes(kDirectWaves, NB, sizeof(T) == 2 ? DCNN_F16 : DCNN_F32) + conv_xchg_bytes(kDirectWaves);
+        const int64_t b_want = cdiv(max_tiles, kDirectWaves / p.cs);
+        // TI tiles per wave once that still gives every SIMD of the chip a wave (the list's length is read on the device)
+        const int blocked_min_tiles = (int)((int64_t)ctx->num_cu * 4 * TI / p.cs);
+        const int64_t b_cap = (int64_t)ctx->num_cu * 2;        // 4 waves of up to 256 registers: two workgroups per compute unit
+        const int b_grid = (int)(cdiv(b_want < b_cap ? b_want : b_cap, kXcd) * kXcd);
+#define DCNN_BLOCKED_LAUNCH(KS)                                                                                  \
+    do {                                                                                                         \
+        auto kern = conv_direct_kernel<T, NB, KS, TI>;                                                           \
+        static bool attr_set = false;                                                                            \
+        if (!attr_set) {                                                                                         \
+            err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                      (int)kLdsBytes);                                                           \
+            attr_set = (err == hipSuccess);                                                                      \
+        }                                                                                                        \
+        if (err == hipSuccess)                                                                                   \
+            hipLaunchKernelGGL(kern, dim3(b_grid), dim3(kDirectWaves* kWave), b_lds, ctx->stream, l, c, e, p.npass, p.cs, \
+                               blocked_min_tiles);                                                       \
+    } while (0)
+        if (c.k == 1) DCNN_BLOCKED_LAUNCH(1); else DCNN_BLOCKED_LAUNCH(3);
+#undef DCNN_BLOCKED_LAUNCH
+        if (err != hipSuccess) return check_hip(ctx, err, "hipFuncSetAttribute(conv_direct_kernel)");
+        return check_hip(ctx, hipGetLastError(), "conv_direct_kernel launch");
     }
     // instantiated combinations: the common case (16-byte aligned input pixels, vector-width output
     // channels) is specialised on the window size; odd shapes take the generic-window kernels

@@ -180,8 +180,13 @@ CONV_CASES = [
     ("f16", 1, 1, 0, 512, 2048, (1, 9, 8)),
     ("f32", 3, 1, 1, 128, 128, (1, 16, 16)),
     ("f32", 1, 1, 0, 64, 1024, (1, 12, 12)),
-    # a long work list on streamed weights: the sparse steps, too, walk the weight slices through LDS
+    # long work lists on streamed weights (sparse steps: several pixel tiles per wave share the weight operands):
+    # two / four waves per tile, an input's own list, a strided window, fp32, and two passes over the channels
     ("f16", 3, 1, 1, 128, 128, (6, 128, 128)),
+    ("f16", 1, 1, 0, 256, 512, (4, 96, 96)),
+    ("f16", 3, 2, 1, 128, 256, (8, 128, 128)),
+    ("f32", 3, 1, 1, 64, 128, (6, 96, 96)),
+    ("f16", 1, 1, 0, 256, 1024, (4, 80, 80)),
 ]
 
 
@@ -221,7 +226,11 @@ def test_conv_linear(S, k, stride, pad, cin, cout, nhw):
 
 
 @pytest.mark.parametrize("S,k,stride,cin,cout,nhw,res", [
-    ("f16", 3, 1, 128, 128, (5, 128, 136), True),      # streamed weights, long list, fused tail with residual
+    # streamed weights, long lists, fused tail: two waves per tile with a residual, four waves per tile, three
+    # column blocks per wave in fp32
+    ("f16", 3, 1, 128, 128, (5, 128, 136), True),
+    ("f16", 1, 1, 256, 256, (4, 96, 96), True),
+    ("f32", 3, 1, 64, 96, (6, 96, 96), True),
     ("f32", 3, 1, 32, 32, (1, 64, 64), False),
     ("f16", 1, 1, 64, 64, (2, 32, 32), False),
     ("f16", 3, 1, 64, 64, (2, 33, 35), False),
