@@ -258,7 +258,9 @@ __global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
 // number of chunks -- the workgroup of chunk c recomputes the flags of the earlier chunks instead of waiting for
 // their counts -- but measured slower than two launches from the second chunk on, as was a variant in which
 // workgroups published their counts and waited for the earlier ones with device-scope atomics: 20 us against 12
-// on 1 M pixels, 22 against 11 on 55 K.)
+// on 1 M pixels, 22 against 11 on 55 K.  So was a single workgroup of 1024 threads that owns a whole map of up
+// to 16 K pixels, two words of 8 pixels per thread: its chain of dependent memory round trips is longer than two
+// short launches back to back -- an 84-layer network on small maps went from 2.10 to 2.48 ms per step.)
 constexpr int kFusedMaxChunks = 1;
 
 __global__ __launch_bounds__(kMaskThreads) void mask_emit_kernel(MaskKernelArgs a, EmitArgs e) {
