@@ -180,25 +180,40 @@ struct EmitArgs {
     int b_stride, b_h, b_w;
 };
 
+// The three rows of input flags that the tap words of pixels p0 .. p0+7 are cut from (3x3 windows on rows a
+// multiple of 8 wide).  They depend on p0 alone, so they are requested before the scan that fixes the list
+// positions instead of after it: one round trip to memory less on the kernel's critical path.
+struct EmitRows {
+    bool fast;
+    uint32_t rows[3];
+};
+__device__ __forceinline__ EmitRows emit_rows(const EmitArgs& a, int64_t p0) {
+    EmitRows r;
+    r.fast = a.taps_out != nullptr && window3_fast(a.k, a.stride, a.pad, 1, a.h, a.w, a.oh, a.ow) && p0 + kPxPerThread <= a.pixels;
+    r.rows[0] = r.rows[1] = r.rows[2] = 0;
+    if (r.fast) {
+        const int x0 = (int)(p0 % a.w);
+        const int64_t t = p0 / a.w;
+        const int y = (int)(t % a.h);
+        const int64_t n = t / a.h;
+        for (int i = 0; i < 3; ++i) r.rows[i] = row_flags10(a.tap_mask, n, y + i - 1, x0, a.h, a.w);
+    }
+    return r;
+}
+
 // List entries (and tap words) of the flagged pixels among p0 .. p0+7, written from position `pos` on.
-__device__ __forceinline__ void emit_entries(const EmitArgs& a, int64_t p0, uint64_t word, int pos) {
+__device__ __forceinline__ void emit_entries(const EmitArgs& a, int64_t p0, uint64_t word, int pos, const EmitRows& er) {
     if (a.taps_out == nullptr) {
         for (int i = 0; i < kPxPerThread; ++i)
             if ((word >> (8 * i)) & 1) a.idx_out[pos++] = (int32_t)(p0 + i);
         return;
     }
     if (word == 0) return;
-    if (window3_fast(a.k, a.stride, a.pad, 1, a.h, a.w, a.oh, a.ow) && p0 + kPxPerThread <= a.pixels) {
-        const int x0 = (int)(p0 % a.w);
-        const int64_t t = p0 / a.w;
-        const int y = (int)(t % a.h);
-        const int64_t n = t / a.h;
-        uint32_t rows[3];
-        for (int r = 0; r < 3; ++r) rows[r] = row_flags10(a.tap_mask, n, y + r - 1, x0, a.h, a.w);
+    if (er.fast) {
         for (int i = 0; i < kPxPerThread; ++i) {
             if ((word >> (8 * i)) & 1) {
                 a.idx_out[pos] = (int32_t)(p0 + i);
-                uint32_t taps = ((rows[0] >> i) & 7u) | (((rows[1] >> i) & 7u) << 3) | (((rows[2] >> i) & 7u) << 6);
+                uint32_t taps = ((er.rows[0] >> i) & 7u) | (((er.rows[1] >> i) & 7u) << 3) | (((er.rows[2] >> i) & 7u) << 6);
                 if (a.mask_b && mask_b_flag(a.mask_b, p0 + i, a.b_stride, a.b_h, a.b_w, a.oh, a.ow)) taps |= 1u << 30;
                 a.taps_out[pos] = taps;
                 ++pos;
@@ -234,13 +249,10 @@ __global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
     __shared__ int s_red[kMaskThreads / kWave];
     const int chunk = blockIdx.x;
     const bool last = chunk == (int)gridDim.x - 1;
-    const int mine = a.chunk_counts[chunk];
-    if (mine == 0 && !last) return;                           // uniform for the block
+    // every load the block needs is requested up front: the counts of the chunks before it, its own flags and
+    // the rows its tap words come from
     int part = 0;
     for (int i = threadIdx.x; i < chunk; i += kMaskThreads) part += a.chunk_counts[i];
-    const int prefix = block_sum(part, s_red);
-    if (last && threadIdx.x == 0) *a.count_out = prefix + mine;
-    if (mine == 0) return;
     const int64_t p0 = (int64_t)chunk * kChunk + (int64_t)threadIdx.x * kPxPerThread;
     uint64_t word = 0;
     if (p0 + kPxPerThread <= a.pixels) {
@@ -248,9 +260,12 @@ __global__ __launch_bounds__(kMaskThreads) void emit_kernel(EmitArgs a) {
     } else {
         for (int i = 0; p0 + i < a.pixels; ++i) word |= (uint64_t)(a.mask[p0 + i] ? 1 : 0) << (8 * i);
     }
+    const EmitRows er = emit_rows(a, p0);
+    const int prefix = block_sum(part, s_red);
     int total;
     const int pos = prefix + block_exclusive_scan(__popcll(word), s_red, &total);
-    emit_entries(a, p0, word, pos);
+    if (last && threadIdx.x == 0) *a.count_out = prefix + total;
+    emit_entries(a, p0, word, pos, er);
 }
 
 // ---- mask pass and list emission in one launch (maps of one chunk) -----------------------------------
@@ -272,6 +287,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_emit_kernel(MaskKernelArgs 
         part += __popcll(mask_word<false>(a, (int64_t)cc * kChunk + (int64_t)threadIdx.x * kPxPerThread));
     const int64_t p0 = (int64_t)chunk * kChunk + (int64_t)threadIdx.x * kPxPerThread;
     const uint64_t word = mask_word<true>(a, p0);
+    const EmitRows er = emit_rows(e, p0);
     const int prefix = block_sum(part, s_red);
     int total;
     const int loc = block_exclusive_scan(__popcll(word), s_red, &total);
@@ -279,7 +295,7 @@ __global__ __launch_bounds__(kMaskThreads) void mask_emit_kernel(MaskKernelArgs 
         if (chunk == 0 && a.zero_count) *a.zero_count = 0;
         if (last) *e.count_out = prefix + total;
     }
-    if (total != 0) emit_entries(e, p0, word, prefix + loc);
+    if (total != 0) emit_entries(e, p0, word, prefix + loc, er);
 }
 
 dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
