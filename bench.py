@@ -191,15 +191,12 @@ def profile_layers(work: Workload, eps: float, steps: int, warmup: int, streams:
     net.init(frames[0])
     for k in range(warmup):
         net.step(frames[work.order[k % len(work.order)]])
-    for i in range(1, net.num_layers):
+    for i in range(net.num_layers):
         net.set_timing(i, steps)
     for k in range(warmup, warmup + steps):
         net.step(frames[work.order[k % len(work.order)]])
     out = []
     for i in range(net.num_layers):
-        if i == 0:
-            out.append(0.0)
-            continue
         ms, n = net.timing(i)
         out.append(ms / max(n, 1))
     return out

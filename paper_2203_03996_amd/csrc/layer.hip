@@ -525,7 +525,18 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         a.n = d.n; a.h = d.h; a.w = d.w; a.c = d.c; a.eps = d.eps; a.dilate_r = d.dilate_r;
         L->last_in_count = nullptr;
         L->last_work_count = L->out_count;
-        return launch_deltagen(ctx, d.dtype, a);
+        // optional timing: the generation pass together with the list emission that belongs to it
+        const bool timed_gen = L->events_used < L->events.size();
+        if (timed_gen) {
+            st = check_hip(ctx, hipEventRecord(L->events[L->events_used].first, ctx->stream), "hipEventRecord");
+            if (st != DCNN_OK) return st;
+        }
+        st = launch_deltagen(ctx, d.dtype, a);
+        if (st == DCNN_OK && timed_gen) {
+            st = check_hip(ctx, hipEventRecord(L->events[L->events_used].second, ctx->stream), "hipEventRecord");
+            if (st == DCNN_OK) ++L->events_used;
+        }
+        return st;
     }
 
     // ---- work list -----------------------------------------------------------------------------
