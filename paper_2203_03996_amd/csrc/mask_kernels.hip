@@ -72,6 +72,46 @@ __device__ __forceinline__ bool window3_fast(int k, int stride, int pad, int up,
     return k == 3 && stride == 1 && pad == 1 && up == 1 && (w % 8) == 0 && oh == h && ow == w;
 }
 
+// The same window on rows of any width.  The 8 pixels of a thread may then straddle rows, so the flags are taken
+// from three spans of 10 consecutive bytes in FLAT pixel order (rows above / at / below, one pixel of margin on
+// either side) and each tap is masked by its own bounds test.  All 30 byte loads are independent of each other:
+// one round trip to memory instead of one per tap.
+__device__ __forceinline__ bool window3_any(int k, int stride, int pad, int up, int h, int w, int oh, int ow) {
+    return k == 3 && stride == 1 && pad == 1 && up == 1 && oh == h && ow == w;
+}
+// bit j: the pixel with flat index first + j exists and is flagged
+__device__ __forceinline__ uint32_t span_flags10(const uint8_t* mask, int64_t first, int64_t total) {
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < 10; ++j) {
+        const int64_t q = first + j;
+        const bool in = q >= 0 && q < total;
+        const uint8_t f = mask[in ? q : 0];
+        if (in && f) bits |= 1u << j;
+    }
+    return bits;
+}
+struct Spans3 { uint32_t row[3]; };
+__device__ __forceinline__ Spans3 window3_spans(const uint8_t* mask, int64_t p0, int w, int64_t total) {
+    Spans3 s;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) s.row[r] = span_flags10(mask, p0 - 1 + (int64_t)(r - 1) * w, total);
+    return s;
+}
+// taps of pixel p0 + i at (x, y): bit dy*3+dx set iff the tap is inside the map and flagged
+__device__ __forceinline__ uint32_t window3_taps(const Spans3& s, int i, int x, int y, int h, int w) {
+    uint32_t taps = 0;
+#pragma unroll
+    for (int dy = 0; dy < 3; ++dy) {
+        if ((unsigned)(y + dy - 1) >= (unsigned)h) continue;
+        uint32_t three = (s.row[dy] >> i) & 7u;
+        if (x == 0) three &= ~1u;
+        if (x == w - 1) three &= ~4u;
+        taps |= three << (3 * dy);
+    }
+    return taps;
+}
+
 // Flag of the second mask for output pixel p (same shape as the output, or sampled with a stride).
 __device__ __forceinline__ bool mask_b_flag(const uint8_t* mask_b, int64_t p, int b_stride, int b_h, int b_w, int oh, int ow) {
     if (b_stride <= 0) return mask_b[p] != 0;
@@ -115,6 +155,18 @@ __device__ __forceinline__ uint64_t mask_word(const MaskKernelArgs& a, int64_t p
             const uint32_t hit = (any | (any >> 1) | (any >> 2)) & 0xffu;   // bit i: window of pixel x0+i has a flag
             for (int i = 0; i < kPxPerThread; ++i) word |= (uint64_t)((hit >> i) & 1u) << (8 * i);
             if (a.mask_b) word |= bytes01(*reinterpret_cast<const uint64_t*>(a.mask_b + p0));
+        } else if (square && b_same && window3_any(a.k, a.stride, a.pad, a.up, a.h, a.w, a.oh, a.ow)) {
+            const Spans3 sp = window3_spans(a.mask_in, p0, a.w, a.out_pixels);
+            int x = (int)(p0 % a.w);
+            int y = (int)((p0 / a.w) % a.h);
+            for (int i = 0; i < kPxPerThread && p0 + i < a.out_pixels; ++i) {
+                if (window3_taps(sp, i, x, y, a.h, a.w)) word |= (uint64_t)1 << (8 * i);
+                if (++x == a.w) { x = 0; if (++y == a.h) y = 0; }
+            }
+            if (a.mask_b) {
+                if (p0 + kPxPerThread <= a.out_pixels) word |= bytes01(*reinterpret_cast<const uint64_t*>(a.mask_b + p0));
+                else for (int i = 0; p0 + i < a.out_pixels; ++i) word |= (uint64_t)(a.mask_b[p0 + i] ? 1 : 0) << (8 * i);
+            }
         } else {
             int ox = (int)(p0 % a.ow);
             int64_t t = p0 / a.ow;
@@ -184,19 +236,25 @@ struct EmitArgs {
 // multiple of 8 wide).  They depend on p0 alone, so they are requested before the scan that fixes the list
 // positions instead of after it: one round trip to memory less on the kernel's critical path.
 struct EmitRows {
-    bool fast;
+    int mode;                     // 0: none (taps are tested one by one), 1: rows a multiple of 8 wide, 2: any width
     uint32_t rows[3];
 };
 __device__ __forceinline__ EmitRows emit_rows(const EmitArgs& a, int64_t p0) {
     EmitRows r;
-    r.fast = a.taps_out != nullptr && window3_fast(a.k, a.stride, a.pad, 1, a.h, a.w, a.oh, a.ow) && p0 + kPxPerThread <= a.pixels;
+    r.mode = 0;
     r.rows[0] = r.rows[1] = r.rows[2] = 0;
-    if (r.fast) {
+    if (a.taps_out == nullptr || p0 >= a.pixels) return r;
+    if (window3_fast(a.k, a.stride, a.pad, 1, a.h, a.w, a.oh, a.ow) && p0 + kPxPerThread <= a.pixels) {
+        r.mode = 1;
         const int x0 = (int)(p0 % a.w);
         const int64_t t = p0 / a.w;
         const int y = (int)(t % a.h);
         const int64_t n = t / a.h;
         for (int i = 0; i < 3; ++i) r.rows[i] = row_flags10(a.tap_mask, n, y + i - 1, x0, a.h, a.w);
+    } else if (window3_any(a.k, a.stride, a.pad, 1, a.h, a.w, a.oh, a.ow)) {
+        r.mode = 2;
+        const Spans3 sp = window3_spans(a.tap_mask, p0, a.w, a.pixels);
+        for (int i = 0; i < 3; ++i) r.rows[i] = sp.row[i];
     }
     return r;
 }
@@ -209,7 +267,23 @@ __device__ __forceinline__ void emit_entries(const EmitArgs& a, int64_t p0, uint
         return;
     }
     if (word == 0) return;
-    if (er.fast) {
+    if (er.mode == 2) {
+        const Spans3 sp{{er.rows[0], er.rows[1], er.rows[2]}};
+        int x = (int)(p0 % a.w);
+        int y = (int)((p0 / a.w) % a.h);
+        for (int i = 0; i < kPxPerThread; ++i) {
+            if ((word >> (8 * i)) & 1) {
+                a.idx_out[pos] = (int32_t)(p0 + i);
+                uint32_t taps = window3_taps(sp, i, x, y, a.h, a.w);
+                if (a.mask_b && mask_b_flag(a.mask_b, p0 + i, a.b_stride, a.b_h, a.b_w, a.oh, a.ow)) taps |= 1u << 30;
+                a.taps_out[pos] = taps;
+                ++pos;
+            }
+            if (++x == a.w) { x = 0; if (++y == a.h) y = 0; }
+        }
+        return;
+    }
+    if (er.mode == 1) {
         for (int i = 0; i < kPxPerThread; ++i) {
             if ((word >> (8 * i)) & 1) {
                 a.idx_out[pos] = (int32_t)(p0 + i);
