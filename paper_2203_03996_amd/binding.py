@@ -299,6 +299,16 @@ class Layer:
         self.ctx.check(self.ctx.lib.dcnn_layer_stats(self.handle, C.byref(s)))
         return s.as_dict()
 
+    def set_timing(self, max_steps: int):
+        """Record HIP events around the layer's main kernel for the next `max_steps` steps (0: off)."""
+        self.ctx.check(self.ctx.lib.dcnn_layer_set_timing(self.handle, max_steps))
+
+    def timing(self):
+        """(summed kernel milliseconds, launches) since the last call."""
+        ms, n = C.c_float(), C.c_int32()
+        self.ctx.check(self.ctx.lib.dcnn_layer_timing(self.handle, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
     def __del__(self):
         try:
             if getattr(self, "handle", None):
