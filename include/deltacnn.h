@@ -199,8 +199,9 @@ dcnn_status dcnn_layer_state(const dcnn_layer* layer, int32_t which, void** ptr_
 /* Counters of the last step; synchronises the stream. */
 dcnn_status dcnn_layer_stats(dcnn_layer* layer, dcnn_stats* stats_host);
 /* Kernel timing for measurements: with max_steps > 0 the layer brackets its main compute kernel
- * (not its mask passes) with HIP events on the context's stream for up to max_steps steps;
- * 0 switches it off.  dcnn_layer_timing synchronises, reports the summed kernel time and the
+ * (not its mask passes; for the delta generation layer: the generation pass together with the
+ * list emission that belongs to it) with HIP events on the context's stream for up to max_steps
+ * steps; 0 switches it off.  dcnn_layer_timing synchronises, reports the summed kernel time and the
  * number of timed launches since the last call, and starts over. */
 dcnn_status dcnn_layer_set_timing(dcnn_layer* layer, int32_t max_steps);
 dcnn_status dcnn_layer_timing(dcnn_layer* layer, float* total_ms_host, int32_t* launches_host);
