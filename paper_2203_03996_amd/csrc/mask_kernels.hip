@@ -112,6 +112,46 @@ __device__ __forceinline__ uint32_t window3_taps(const Spans3& s, int i, int x, 
     return taps;
 }
 
+// Window taps of the 8 output pixels from p0 on, for a K x K window of any stride and padding: bit ky*K+kx of
+// taps[i] is set iff that tap of pixel p0+i lies inside the map and is flagged.  Every load is issued
+// unconditionally (a tap outside the map or a pixel beyond the end reads byte 0 of the mask and is masked out),
+// so the 8*K*K loads are independent and cost one round trip instead of one each.
+template <int K>
+__device__ __forceinline__ void window_taps8(const uint8_t* mask, int64_t p0, int64_t out_pixels, int h, int w, int oh, int ow,
+                                             int stride, int pad, uint32_t (&taps)[kPxPerThread]) {
+    int ox = (int)(p0 % ow);
+    const int64_t t = p0 / ow;
+    int oy = (int)(t % oh);
+    int64_t n = t / oh;
+    uint8_t f[kPxPerThread][K * K];
+    uint32_t ok[kPxPerThread];
+#pragma unroll
+    for (int i = 0; i < kPxPerThread; ++i) {
+        const bool live = p0 + i < out_pixels;
+        const int iy0 = oy * stride - pad, ix0 = ox * stride - pad;
+        const int64_t base = (n * h + iy0) * (int64_t)w + ix0;
+        uint32_t okm = 0;
+#pragma unroll
+        for (int ky = 0; ky < K; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < K; ++kx) {
+                const bool in = live && (unsigned)(iy0 + ky) < (unsigned)h && (unsigned)(ix0 + kx) < (unsigned)w;
+                f[i][ky * K + kx] = mask[in ? base + (int64_t)ky * w + kx : 0];
+                if (in) okm |= 1u << (ky * K + kx);
+            }
+        ok[i] = okm;
+        if (++ox == ow) { ox = 0; if (++oy == oh) { oy = 0; ++n; } }
+    }
+#pragma unroll
+    for (int i = 0; i < kPxPerThread; ++i) {
+        uint32_t tp = 0;
+#pragma unroll
+        for (int j = 0; j < K * K; ++j)
+            if (f[i][j]) tp |= 1u << j;
+        taps[i] = tp & ok[i];
+    }
+}
+
 // Flag of the second mask for output pixel p (same shape as the output, or sampled with a stride).
 __device__ __forceinline__ bool mask_b_flag(const uint8_t* mask_b, int64_t p, int b_stride, int b_h, int b_w, int oh, int ow) {
     if (b_stride <= 0) return mask_b[p] != 0;
@@ -167,6 +207,37 @@ __device__ __forceinline__ uint64_t mask_word(const MaskKernelArgs& a, int64_t p
                 if (p0 + kPxPerThread <= a.out_pixels) word |= bytes01(*reinterpret_cast<const uint64_t*>(a.mask_b + p0));
                 else for (int i = 0; p0 + i < a.out_pixels; ++i) word |= (uint64_t)(a.mask_b[p0 + i] ? 1 : 0) << (8 * i);
             }
+        } else if (square && a.up == 1 && (a.k == 3 || a.k == 1)) {
+            // strided / unpadded 3x3 and 1x1 windows: all taps of the 8 pixels in one batch of loads
+            uint32_t taps[kPxPerThread];
+            if (a.k == 3) window_taps8<3>(a.mask_in, p0, a.out_pixels, a.h, a.w, a.oh, a.ow, a.stride, a.pad, taps);
+            else window_taps8<1>(a.mask_in, p0, a.out_pixels, a.h, a.w, a.oh, a.ow, a.stride, a.pad, taps);
+            uint8_t fb[kPxPerThread];
+#pragma unroll
+            for (int i = 0; i < kPxPerThread; ++i) {
+                const int64_t q = p0 + i < a.out_pixels ? p0 + i : p0;
+                fb[i] = (a.mask_b && mask_b_flag(a.mask_b, q, a.b_stride, a.b_h, a.b_w, a.oh, a.ow)) ? 1 : 0;
+            }
+#pragma unroll
+            for (int i = 0; i < kPxPerThread; ++i)
+                if (p0 + i < a.out_pixels && (taps[i] || fb[i])) word |= (uint64_t)1 << (8 * i);
+        } else if (a.up > 1 && !a.bilinear && a.mask_b == nullptr) {
+            // nearest upsampling: one source flag per pixel, the 8 loads in one batch
+            int ox = (int)(p0 % a.ow);
+            const int64_t t = p0 / a.ow;
+            int oy = (int)(t % a.oh);
+            int64_t n = t / a.oh;
+            uint8_t f[kPxPerThread];
+#pragma unroll
+            for (int i = 0; i < kPxPerThread; ++i) {
+                const bool live = p0 + i < a.out_pixels;
+                f[i] = a.mask_in[live ? (n * a.h + oy / a.up) * a.w + ox / a.up : 0];
+                if (!live) f[i] = 0;
+                if (++ox == a.ow) { ox = 0; if (++oy == a.oh) { oy = 0; ++n; } }
+            }
+#pragma unroll
+            for (int i = 0; i < kPxPerThread; ++i)
+                if (f[i]) word |= (uint64_t)1 << (8 * i);
         } else {
             int ox = (int)(p0 % a.ow);
             int64_t t = p0 / a.ow;
@@ -236,7 +307,8 @@ struct EmitArgs {
 // multiple of 8 wide).  They depend on p0 alone, so they are requested before the scan that fixes the list
 // positions instead of after it: one round trip to memory less on the kernel's critical path.
 struct EmitRows {
-    int mode;                     // 0: none (taps are tested one by one), 1: rows a multiple of 8 wide, 2: any width
+    int mode;                     // 0: none (taps are tested one by one), 1: 3x3/1/1 on rows a multiple of 8 wide,
+                                  // 2: 3x3/1/1 on any width, 3: tap words of the 8 pixels (3x3 or 1x1, any stride)
     uint32_t rows[3];
 };
 __device__ __forceinline__ EmitRows emit_rows(const EmitArgs& a, int64_t p0) {
@@ -255,6 +327,14 @@ __device__ __forceinline__ EmitRows emit_rows(const EmitArgs& a, int64_t p0) {
         r.mode = 2;
         const Spans3 sp = window3_spans(a.tap_mask, p0, a.w, a.pixels);
         for (int i = 0; i < 3; ++i) r.rows[i] = sp.row[i];
+    } else if (a.k == 3 || a.k == 1) {
+        // any stride / padding: the tap words of all 8 pixels, 9 bits each, three to a word
+        r.mode = 3;
+        uint32_t taps[kPxPerThread];
+        if (a.k == 3) window_taps8<3>(a.tap_mask, p0, a.pixels, a.h, a.w, a.oh, a.ow, a.stride, a.pad, taps);
+        else window_taps8<1>(a.tap_mask, p0, a.pixels, a.h, a.w, a.oh, a.ow, a.stride, a.pad, taps);
+#pragma unroll
+        for (int i = 0; i < kPxPerThread; ++i) r.rows[i / 3] |= taps[i] << (9 * (i % 3));
     }
     return r;
 }
@@ -280,6 +360,18 @@ __device__ __forceinline__ void emit_entries(const EmitArgs& a, int64_t p0, uint
                 ++pos;
             }
             if (++x == a.w) { x = 0; if (++y == a.h) y = 0; }
+        }
+        return;
+    }
+    if (er.mode == 3) {
+        for (int i = 0; i < kPxPerThread; ++i) {
+            if ((word >> (8 * i)) & 1) {
+                a.idx_out[pos] = (int32_t)(p0 + i);
+                uint32_t taps = (er.rows[i / 3] >> (9 * (i % 3))) & 0x1ffu;
+                if (a.mask_b && mask_b_flag(a.mask_b, p0 + i, a.b_stride, a.b_h, a.b_w, a.oh, a.ow)) taps |= 1u << 30;
+                a.taps_out[pos] = taps;
+                ++pos;
+            }
         }
         return;
     }
