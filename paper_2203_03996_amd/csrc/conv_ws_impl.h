@@ -93,17 +93,19 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
     auto tile_of = [&](int rd) { return (r.begin + (int64_t)rd * r.step) * tiles_per_iter + slot; };
     auto list_entry = [&](int rd, int j) { return rd < rounds ? list_pixel(l.list, tile_of(rd) * kTile + j, count) : -1; };
 
-    {
+    // The weights travel global -> LDS once per workgroup.  Every wave calls this exactly once, right after it
+    // has requested the list entries of its first tiles, so that round trip hides behind the copy.
+    auto load_weights = [&]() {
         const Vec* wglob = static_cast<const Vec*>(c.wpacked);
         for (int i = threadIdx.x; i < w1_vecs; i += kWsWaves * kWave) w_lds[i] = wglob[i];
         if constexpr (DUAL) {
             const Vec* wglob2 = static_cast<const Vec*>(c.wpacked2);
             for (int i = threadIdx.x; i < w2_vecs; i += kWsWaves * kWave) w_lds[w1_vecs + i] = wglob2[i];
         }
-    }
-    lds_block_sync();
+        lds_block_sync();
+    };
 
-    // Both roles pass the same number of workgroup barriers: one per round 0..rounds.
+    // Both roles pass the same number of workgroup barriers: the weight copy, then one per round 0..rounds.
     if (producer) {
         // =====================================================================================
         // producer: tile -> gathered taps x weights -> rounded result tile in LDS
@@ -148,6 +150,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         };
         int p32_next = list_entry(0, col), p32_next2 = list_entry(1, col);
         uint32_t taps_next = tap_word(0, p32_next), taps_next2 = tap_word(1, p32_next2);
+        load_weights();
         const Vec* wbase = w_lds + ((size_t)part * ksteps * 2 + g) * COLS + col;
         const Vec* wbase2 = w_lds + w1_vecs + ((size_t)part * (DUAL ? c.kch2 : 0) * 2 + g) * COLS + col;
 
@@ -420,6 +423,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 nxt.pix[it] = list_entry(1, ent0 + it * PPI);
                 pix_nn[it] = list_entry(2, ent0 + it * PPI);
             }
+            load_weights();
             prepare(cur);
             prepare(nxt);
             Set set0, set1;
