@@ -378,7 +378,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                         raw_set<T, V>(o_t, i, tt + dd);             // x^T if the pixel is truncated
                         raw_set<T, V>(o_y, i, dy);
                     }
-                    for (int m = LP >> 1; m >= 1; m >>= 1) u = fmaxf(u, __shfl_xor(u, m, kWave));
+                    u = group_max(u, LP);
                     upd = u >= e.eps;
                     const uint32_t o_upd = upd ? o : kOob;
                     state_store(rs_xA, o_upd, o_a);

@@ -118,6 +118,26 @@ template <typename T, int V> __device__ __forceinline__ void raw_set(typename Ra
     else v[i] = (T)x;
 }
 
+// Maximum of a non-negative value over aligned groups of LP lanes (LP a power of two, 2 .. 64), delivered to every
+// lane of the group.  Steps within a row of 16 lanes use DPP lane permutations (register to register, a few
+// clocks each: two quad swaps, then the half-row and the row mirrored -- after the quad steps every quad holds
+// one value, so a mirror serves as well as an exchange); only the steps across rows go through the LDS
+// crossbar.  All lanes of the wave must be active.
+template <int CTRL> __device__ __forceinline__ float dpp_max_step(float u) {
+    const int v = __builtin_bit_cast(int, u);
+    const int o = __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, true);
+    return fmaxf(u, __builtin_bit_cast(float, o));
+}
+__device__ __forceinline__ float group_max(float u, int LP) {
+    if (LP >= 2) u = dpp_max_step<0xB1>(u);       // quad_perm [1,0,3,2]
+    if (LP >= 4) u = dpp_max_step<0x4E>(u);       // quad_perm [2,3,0,1]
+    if (LP >= 8) u = dpp_max_step<0x141>(u);      // row_half_mirror
+    if (LP >= 16) u = dpp_max_step<0x140>(u);     // row_mirror
+    if (LP >= 32) u = fmaxf(u, __shfl_xor(u, 16, kWave));
+    if (LP >= 64) u = fmaxf(u, __shfl_xor(u, 32, kWave));
+    return u;
+}
+
 // LDS-only synchronisation: orders shared-memory traffic without waiting for outstanding global
 // loads and stores (a generic fence would drain them and stall the memory pipeline).
 __device__ __forceinline__ void lds_wave_sync() {
