@@ -365,6 +365,11 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 }
                 bool upd = true;
                 if constexpr (decltype(sf)::value) {
+                    // o_y: the emitted delta -- or, in a final layer, the new dense output.  There O + dy with
+                    // O = f(x^A_old) (true after the first frame and kept by every update: f(x^A_old) + f(s) - f(x^A_old))
+                    // is f of the new x^A, so O is written without being read, and without the rounding an accumulation
+                    // in the storage type would add frame after frame.  f(s) rounded to the storage type IS f of the
+                    // rounded s: rounding is monotone and keeps 0 and the upper bound, which are representable.
                     Raw o_a, o_t, o_y;
                     float u = 0.0f;
 #pragma unroll
@@ -372,11 +377,12 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                         const float dd = raw_get<T, V>(d, i);
                         const float a = raw_get<T, V>(st.ra[h], i), tt = raw_get<T, V>(st.rt[h], i);
                         const float sum = (a + tt) + dd;
-                        const float dy = act_clamp(sum, hi) - act_clamp(a, hi);
+                        const float fs = act_clamp(sum, hi);
+                        const float dy = fs - act_clamp(a, hi);
                         u = fmaxf(u, fabsf(dy));
                         raw_set<T, V>(o_a, i, sum);
                         raw_set<T, V>(o_t, i, tt + dd);             // x^T if the pixel is truncated
-                        raw_set<T, V>(o_y, i, dy);
+                        raw_set<T, V>(o_y, i, ACC ? fs : dy);
                     }
                     u = group_max(u, LP);
                     upd = u >= e.eps;
@@ -385,17 +391,8 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     // an update resets x^T to zero: where this lane's x^T already is all zero bits nothing needs to be
                     // written (most pixels that update every frame never accumulate anything)
                     state_store(rs_xT, (upd && all_bits_zero(st.rt[h])) ? kOob : o, upd ? raw_zero<T, V>() : o_t);
-                    if constexpr (ACC) {
-                        // final layer: O + dy with O = f(x^A_old) (true after the first frame and kept by every update:
-                        // f(x^A_old) + f(s) - f(x^A_old)) is f of the new x^A, so O is written without being read -- and
-                        // without the rounding an accumulation in the storage type would add frame after frame
-                        Raw o_O;
-#pragma unroll
-                        for (int i = 0; i < V; ++i) raw_set<T, V>(o_O, i, act_clamp(raw_get<T, V>(o_a, i), hi));
-                        state_store(rs_res, o_upd, o_O);
-                    } else {
-                        ws_store16<Raw>(rs_out, o_upd, o_y);
-                    }
+                    if constexpr (ACC) state_store(rs_res, o_upd, o_y);
+                    else ws_store16<Raw>(rs_out, o_upd, o_y);
                 } else {
                     ws_store16<Raw>(rs_out, o, d);
                 }
