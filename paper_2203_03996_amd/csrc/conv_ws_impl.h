@@ -63,8 +63,10 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
     constexpr bool RES = AUX == 1, ACC = AUX == 2;
     constexpr int COLS = NB * 32;
     constexpr int GK = 4;                                      // K-steps gathered together (one register set)
-    constexpr int NSETS = 2;                                   // register sets: NSETS-1 groups in flight behind the current one
-                                                               // (finer groups and deeper rings were measured slower)
+    // register sets of the gather ring: NSETS-1 groups in flight behind the one being multiplied.  The 3x3 kernel
+    // is bound by its producers (nine dependent gather round trips per tile) and takes a third set where the
+    // registers allow it; everywhere else two are best (finer groups and deeper rings were measured slower).
+    constexpr int NSETS = (KS == 3 && NB <= 2 && AUX == 0 && !DUAL) ? 3 : 2;
     constexpr int NP = kWsProducers;
     constexpr int ES = (int)sizeof(T);
     static_assert(sizeof(Vec) == 16 && sizeof(Raw) == 16, "16-byte channel vectors");
