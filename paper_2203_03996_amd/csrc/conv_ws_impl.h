@@ -118,6 +118,12 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         const int cin_bytes = c.cin * ES;
         const int kgroups = (kch + GK - 1) / GK;               // groups of GK K-steps per tap
         const bool k_exact = kgroups * GK * 32 == cin_bytes;   // no K-step of a group reaches past the pixel's channels
+        const bool k_exact2 = kch * 32 == cin_bytes;           // no K-step at all does
+        // (one gather per window row pays when most of the map is listed -- the dense mode and high update densities:
+        // 4.6 % of the step with everything listed, 1 % at 50 % density; on short lists the tap-by-tap ring with its
+        // third set in flight is 1 % ahead)
+        const bool row_shift = KS == 3 && !DUAL && c.stride == 1 && c.pad == 1 && count * 4 >= (int64_t)c.n * c.oh * c.ow * 3;
+        (void)k_exact2; (void)row_shift;
         constexpr int kNoTap = 31;                             // cursor sentinel: no tap has this number
         // Which window taps of a list entry are in bounds and flagged comes with the work list (one
         // word per entry); a 1x1 layer that walks its input's own list has exactly its one tap.
@@ -257,6 +263,98 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 // Ring of NSETS register sets: the gathers of group s+NSETS-1 are issued right before group
                 // s is multiplied.  The loop body is straight-line code (groups past the end of the
                 // sequence multiply zeros), so every wait counts exactly the loads issued after it.
+                bool rows_done = false;
+                if constexpr (KS == 3 && !DUAL) {
+                    if (row_shift) {
+                        // ---- 3x3, stride 1, padding 1: one gather per window ROW instead of one per tap ---------------
+                        // The list is ascending and holds every pixel with a flagged tap, so if this lane's left tap
+                        // (dy, 0) is flagged, the pixel to its left is listed too and is the entry just before it: the
+                        // lane below holds that very input pixel as ITS centre tap (dy, 1).  The left and right taps of
+                        // a row are therefore the centre column moved by one lane; only the first and the last column
+                        // of the tile (whose neighbours sit in other tiles) fetch theirs.  A third of the gathers, and
+                        // of the cache lines the vector memory pipeline has to look up -- which is what bounds this
+                        // kernel.  A lane whose tap is not flagged (or out of bounds) takes zeros, whatever its
+                        // neighbour holds.
+                        constexpr int RG = 2;                          // K-steps per row group
+                        const int rgroups = (kch + RG - 1) / RG;
+                        uint32_t rows = 0;
+#pragma unroll
+                        for (int dy = 0; dy < 3; ++dy)
+                            if ((wave_taps >> (3 * dy)) & 7u) rows |= 1u << dy;
+                        struct RCur { uint32_t rest; int dy, kg; };
+                        auto rfirst = [](uint32_t m) { return m ? __builtin_ctz(m) : 3; };
+                        auto radvance = [&](RCur& cu) {
+                            if (++cu.kg >= rgroups) { cu.kg = 0; cu.rest &= cu.rest - 1; cu.dy = rfirst(cu.rest); }
+                        };
+                        const bool first_col = col == 0, last_col = col == kTile - 1;
+                        struct RSet { Vec xc[RG], xl[RG], xr[RG]; };
+                        auto gather_row = [&](const RCur& cu, RSet& st) {
+                            const bool live = cu.dy < 3;
+                            const int dy = live ? cu.dy : 0;
+                            const uint32_t three = live ? (tapbits >> (3 * dy)) & 7u : 0u;
+                            const uint32_t row0 = base00 + (uint32_t)(dy * c.w * cin_bytes + cu.kg * (RG * 32));
+                            const uint32_t offc = (three & 2u) ? row0 + (uint32_t)cin_bytes : kOob;
+                            const uint32_t offl = (first_col && (three & 1u)) ? row0 : kOob;
+                            const uint32_t offr = (last_col && (three & 4u)) ? row0 + 2u * (uint32_t)cin_bytes : kOob;
+#pragma unroll
+                            for (int u = 0; u < RG; ++u) {
+                                const bool pad = !k_exact2 && (2 * (cu.kg * RG + u) + g) * 16 >= cin_bytes;
+                                st.xc[u] = ws_load16<Vec>(rs_in, pad ? kOob : offc + (uint32_t)u * 32u);
+                                st.xl[u] = ws_load16<Vec>(rs_in, pad ? kOob : offl + (uint32_t)u * 32u);
+                                st.xr[u] = ws_load16<Vec>(rs_in, pad ? kOob : offr + (uint32_t)u * 32u);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        };
+                        // the centre column moved by one lane: lane l takes lane l-1 (from_below) or l+1
+                        auto shifted = [&](const Vec& v, bool from_below, bool take, const Vec& other) -> Vec {
+                            const u32x4 w = __builtin_bit_cast(u32x4, v), o = __builtin_bit_cast(u32x4, other);
+                            u32x4 r;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int sft = from_below ? __builtin_amdgcn_update_dpp(0, (int)w[i], 0x138, 0xf, 0xf, true)    // wave_shr:1
+                                                           : __builtin_amdgcn_update_dpp(0, (int)w[i], 0x130, 0xf, 0xf, true);   // wave_shl:1
+                                r[i] = take ? (uint32_t)sft : o[i];
+                            }
+                            return __builtin_bit_cast(Vec, r);
+                        };
+                        auto mma_row = [&](const RCur& cu, const RSet& st) {
+                            const int dy = cu.dy < 3 ? cu.dy : 0;
+                            const uint32_t three = cu.dy < 3 ? (tapbits >> (3 * dy)) & 7u : 0u;
+                            const bool take_l = !first_col && (three & 1u), take_r = !last_col && (three & 4u);
+                            const uint32_t wave_three = cu.dy < 3 ? (wave_taps >> (3 * dy)) & 7u : 0u;
+#pragma unroll
+                            for (int u = 0; u < RG; ++u) {
+                                const int kc = cu.kg * RG + u;
+                                if (kc >= kch) continue;
+                                const Vec xl = shifted(st.xc[u], true, take_l, st.xl[u]);
+                                const Vec xr = shifted(st.xc[u], false, take_r, st.xr[u]);
+#pragma unroll
+                                for (int dx = 0; dx < 3; ++dx) {
+                                    if (!((wave_three >> dx) & 1u)) continue;
+                                    const Vec* wrow = wbase + (size_t)((3 * dy + dx) * kch + kc) * 2 * COLS;
+                                    Vec wv[NB];
+#pragma unroll
+                                    for (int b = 0; b < NB; ++b) wv[b] = wrow[b * 32];
+#pragma unroll
+                                    for (int b = 0; b < NB; ++b) Mma<T>::run(acc[b], wv[b], dx == 0 ? xl : (dx == 1 ? st.xc[u] : xr));
+                                }
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        };
+                        RSet ra, rb;
+                        RCur rg{rows, rfirst(rows), 0};
+                        RCur rm = rg;
+                        gather_row(rg, ra); radvance(rg);
+                        while (rm.dy < 3) {
+                            gather_row(rg, rb); radvance(rg);
+                            mma_row(rm, ra); radvance(rm);
+                            gather_row(rg, ra); radvance(rg);
+                            mma_row(rm, rb); radvance(rm);
+                        }
+                        rows_done = true;
+                    }
+                }
+                if (!rows_done) {
                 Vec x[NSETS][GK];
                 Cursor cg{wave_taps, first_tap(wave_taps), 0};     // gathers run ahead of the matrix work
                 Cursor cm = cg;
@@ -268,6 +366,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                         gather_group(cg, x[(i + NSETS - 1) % NSETS]); advance(cg);
                         mma_group(cm, x[i]); advance(cm);
                     }
+                }
                 }
                 if (main_staged) stage_accumulators<T, NB, true>(acc, tile_row, g);
                 else stage_accumulators<T, NB, false>(acc, tile_row, g);
