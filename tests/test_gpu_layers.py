@@ -225,6 +225,33 @@ def test_conv_linear(S, k, stride, pad, cin, cout, nhw):
         assert st["pixels_in"] == d.count and st["pixels_out"] == want.count
 
 
+@pytest.mark.parametrize("pattern", ["columns3", "rows3", "diagonal", "holes", "border"])
+@pytest.mark.parametrize("nhw", [(2, 40, 37), (1, 33, 64)])
+def test_conv3x3_row_gathers_on_structured_masks(pattern, nhw):
+    """3x3 / stride 1 / padding 1 on a resident-weight layer with masks that list (nearly) the whole map while
+    every pixel has only some taps flagged: the kernel then fetches one centre column per window row and takes the
+    left / right taps from neighbouring lanes -- across tile boundaries, row ends and images."""
+    S, cin, cout = "f16", 64, 64
+    rng = np.random.default_rng(len(pattern) * 7 + nhw[1])
+    n, h, w = nhw
+    ctx, layer, ref = _conv_layers(S, 3, 1, 1, cin, cout, nhw, rng)
+    x0 = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
+    ref.init(x0)
+    layer.init([torch.from_numpy(x0).cuda()])
+    yy, xx = np.meshgrid(np.arange(h), np.arange(w), indexing="ij")
+    mask2d = {"columns3": xx % 3 == 0, "rows3": yy % 3 == 1, "diagonal": (xx + yy) % 3 == 0,
+              "holes": (xx * 7 + yy * 13) % 11 != 0, "border": (xx == 0) | (xx == w - 1) | (yy % 2 == 0)}[pattern]
+    mask = np.broadcast_to(mask2d, (n, h, w)).astype(np.uint8).copy()
+    mask[-1, h // 2:, : w // 3] = 0                      # a corner of the last image without any flag
+    data = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
+    d = ODelta(data, mask).poisoned()
+    want = ref.step(d).poisoned()
+    out = layer.step([_upload(d)])
+    ctx.sync()
+    assert want.count * 4 >= n * h * w * 3, "the pattern must list at least three quarters of the map"
+    check_delta(out, want, S, f"row gathers, {pattern}")
+
+
 @pytest.mark.parametrize("S,k,stride,cin,cout,nhw,res", [
     # streamed weights, long lists, fused tail: two waves per tile with a residual, four waves per tile, three
     # column blocks per wave in fp32
