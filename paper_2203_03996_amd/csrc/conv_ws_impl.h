@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         // (one gather per window row pays when most of the map is listed -- the dense mode and high update densities:
         // 4.6 % of the step with everything listed, 1 % at 50 % density; on short lists the tap-by-tap ring with its
         // third set in flight is 1 % ahead)
-        const bool row_shift = KS == 3 && !DUAL && c.stride == 1 && c.pad == 1 && count * 4 >= (int64_t)c.n * c.oh * c.ow * 3;
+        const bool row_shift = KS == 3 && !DUAL && NB <= 2 && c.stride == 1 && c.pad == 1 && count * 4 >= (int64_t)c.n * c.oh * c.ow * 3;
         (void)k_exact2; (void)row_shift;
         constexpr int kNoTap = 31;                             // cursor sentinel: no tap has this number
         // Which window taps of a list entry are in bounds and flagged comes with the work list (one
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 // s is multiplied.  The loop body is straight-line code (groups past the end of the
                 // sequence multiply zeros), so every wait counts exactly the loads issued after it.
                 bool rows_done = false;
-                if constexpr (KS == 3 && !DUAL) {
+                if constexpr (KS == 3 && !DUAL && NB <= 2) {
                     if (row_shift) {
                         // ---- 3x3, stride 1, padding 1: one gather per window ROW instead of one per tap ---------------
                         // The list is ascending and holds every pixel with a flagged tap, so if this lane's left tap
@@ -379,7 +379,9 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         // =====================================================================================
         constexpr int LPB = ws_pow2_ceil(COLS / V);            // lanes per pixel and producer slice
         constexpr int NIT = LPB / 2;                           // lane-iterations over this wave's 32/cs pixels
-        constexpr int H = NIT >= 4 ? 2 : 1;                    // iterations per register set
+        constexpr int H = (NIT >= 4 && !RES) ? 2 : 1;          // iterations per register set (a residual stream adds a
+                                                               // third vector per iteration: single-iteration sets keep
+                                                               // that variant within its 128 registers)
         constexpr int NS = NIT / H;                            // sets per tile; two register sets alternate
         static_assert(NIT >= 2 && NS * H == NIT && NS % 2 == 0, "tile iterations split into an even number of sets");
         const int LP = cs * LPB;                               // lanes per pixel (all channels), <= 64
