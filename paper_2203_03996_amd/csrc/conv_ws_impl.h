@@ -404,6 +404,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         const bool has_rmask = e.res_mask != nullptr;
         const __amdgpu_buffer_rsrc_t rs_tflag = ws_rsrc(e.xt_flags, out_pixels);
         const bool has_tflag = e.xt_flags != nullptr;
+        const bool has_omask = e.out_mask != nullptr;
         const float hi = act_hi(e.act);
         // this lane's 16 bytes in row 0 of the producer slice that holds its channels (lanes without
         // channels read slot 0 and discard it; their stores go nowhere)
@@ -500,11 +501,18 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     ws_store16<Raw>(rs_out, o, d);
                 }
                 const bool lead = t.pix[it] >= 0 && sub == 0;
-                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)(upd ? 1 : 0), rs_omask, lead ? t.pix[it] : (int)kOob, 0, 0);
+                // The output mask arrives holding 1 at every listed pixel (the dilated flags, or a copy of the input's
+                // mask), so only truncated pixels are written; and a store instruction that no lane needs is not
+                // issued at all -- the vector memory pipeline is what this kernel queues on.
+                const bool clear = lead && !upd;
+                if (has_omask && __builtin_amdgcn_ballot_w64(clear))
+                    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)0, rs_omask, clear ? t.pix[it] : (int)kOob, 0, 0);
                 if constexpr (decltype(sf)::value) {
-                    // after an update the row is zero again; after a truncation it holds values (empty descriptor: no flags)
+                    // after an update the row is zero again; after a truncation it holds values
                     const uint8_t keep = upd ? 0 : 1;
-                    __builtin_amdgcn_raw_buffer_store_b8(keep, rs_tflag, (lead && keep != t.tflag[it]) ? t.pix[it] : (int)kOob, 0, 0);
+                    const bool change = lead && keep != t.tflag[it];
+                    if (has_tflag && __builtin_amdgcn_ballot_w64(change))
+                        __builtin_amdgcn_raw_buffer_store_b8(keep, rs_tflag, change ? t.pix[it] : (int)kOob, 0, 0);
                 }
                 if (lead && upd) bits |= 1u << (ent0 + it * PPI);
             }
