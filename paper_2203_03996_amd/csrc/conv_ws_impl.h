@@ -445,7 +445,10 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 if constexpr (RES) st.rr[h] = ws_load16<Raw>(rs_res, t.rflag[s * H + h] ? o : kOob);
                 if constexpr (decltype(sf)::value) {
                     st.ra[h] = state_load(rs_xA, o);
-                    st.rt[h] = state_load(rs_xT, t.tflag[s * H + h] ? o : kOob);
+                    // (not even issued when the flags say that no lane of the wave has anything to read)
+                    st.rt[h] = raw_zero<T, V>();
+                    if (__builtin_amdgcn_ballot_w64(t.tflag[s * H + h] != 0 && o != kOob))
+                        st.rt[h] = state_load(rs_xT, t.tflag[s * H + h] ? o : kOob);
                 }
             }
         };
@@ -494,7 +497,10 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     state_store(rs_xA, o_upd, o_a);
                     // an update resets x^T to zero: where this lane's x^T already is all zero bits nothing needs to be
                     // written (most pixels that update every frame never accumulate anything)
-                    state_store(rs_xT, (upd && all_bits_zero(st.rt[h])) ? kOob : o, upd ? raw_zero<T, V>() : o_t);
+                    {
+                        const uint32_t o_t_off = (upd && all_bits_zero(st.rt[h])) ? kOob : o;
+                        if (__builtin_amdgcn_ballot_w64(o_t_off != kOob)) state_store(rs_xT, o_t_off, upd ? raw_zero<T, V>() : o_t);
+                    }
                     if constexpr (ACC) state_store(rs_res, o_upd, o_y);
                     else ws_store16<Raw>(rs_out, o_upd, o_y);
                 } else {
