@@ -145,18 +145,6 @@ class Delta:
         code = F16 if self.data.dtype == torch.float16 else F32
         return DeltaStruct(_ptr(self.data), _ptr(self.mask), _ptr(self.idx), _ptr(self.count), n, h, w, c, code)
 
-    @staticmethod
-    def from_numpy(data: np.ndarray, mask: np.ndarray, device="cuda") -> "Delta":
-        """Upload a delta; idx / count are the ascending flagged pixel indices (host-side
-        marshalling of a test input, not part of the method)."""
-        flat = np.flatnonzero(mask.reshape(-1)).astype(np.int32)
-        idx = np.zeros(mask.size, np.int32)
-        idx[:flat.size] = flat
-        return Delta(torch.from_numpy(np.ascontiguousarray(data)).to(device),
-                     torch.from_numpy(np.ascontiguousarray(mask.astype(np.uint8))).to(device),
-                     torch.from_numpy(idx).to(device),
-                     torch.tensor([flat.size], dtype=torch.int32, device=device))
-
 
 class Context:
     """dcnn_ctx on torch's current stream, with a torch-allocated workspace."""
@@ -340,8 +328,11 @@ class Net:
             wdev = bdev = None
             if kind == "conv":
                 wgt, bias = weights[i]
-                wdev = torch.from_numpy(np.ascontiguousarray(wgt)).to(tdt).to(ctx.device)
-                bdev = torch.from_numpy(np.ascontiguousarray(bias)).to(tdt).to(ctx.device)
+                # one direct round-to-nearest-even to the storage type (numpy's conversion; going through
+                # float32 first, as torch's float64 -> float16 does, rounds twice)
+                ndt = np.float16 if self.dtype == F16 else np.float32
+                wdev = torch.from_numpy(np.ascontiguousarray(np.asarray(wgt).astype(ndt))).to(ctx.device)
+                bdev = torch.from_numpy(np.ascontiguousarray(np.asarray(bias).astype(ndt))).to(ctx.device)
                 self._weights[i] = (wdev, bdev)
                 desc = make_desc(DWCONV if nd["depthwise"] else CONV, self.dtype, 0, 0, 0, 0, k=nd["k"],
                                  stride=nd["stride"], pad=nd["pad"], cout=nd["cout"])

@@ -89,6 +89,9 @@ __global__ __launch_bounds__(WMODE == 2 ? 256 : DCNN_CONV_BOUNDS) void conv_mfma
         lds_block_sync();
     }
 
+    // First frame: the bias joins the fp32 sum BEFORE its one rounding to the storage type (a convolution with
+    // bias is one operation); the tail sees a finished result.
+    const T* bias_f = (init != 0) ? static_cast<const T*>(e.bias) : nullptr;
     int survivors = 0;                                         // per-wave count, added to the layer's counter once
     // tail loads are prefetched when a tile takes at most 4 lane-iterations (narrow channel slices)
     constexpr int TAIL_LP = (COLS / V) <= 2 ? 2 : ((COLS / V) <= 4 ? 4 : ((COLS / V) <= 8 ? 8 : ((COLS / V) <= 16 ? 16 : ((COLS / V) <= 32 ? 32 : 64))));
@@ -370,6 +373,18 @@ __global__ __launch_bounds__(WMODE == 2 ? 256 : DCNN_CONV_BOUNDS) void conv_mfma
             }
 
             // ---- tail: this wave's channel slice of the tile ------------------------------------
+            if (bias_f) {
+                // accumulator i of block b, quad q belongs to output channel b*32 + 8*q + 4*g + i
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int ch = ch0 + b * 32 + 8 * q + 4 * g + i;
+                            if (ch < e.c) acc[b][4 * q + i] += (float)bias_f[ch];
+                        }
+            }
             stage_accumulators<T, NB>(acc, stage + (size_t)col * stage_stride, g);
             lds_wave_sync();
             auto dx = [&](int ent, int64_t, int c0) -> Raw {

@@ -166,7 +166,8 @@ struct MaxExchange {
 // Per pixel (Section 3.1, Eqs. 4-6):  s = (x^A + x^T) + dx;  dy = f(s) - f(x^A);
 //   max_c |dy_c| >= eps : x^A <- s, x^T <- 0, emit dy, flag the pixel
 //   otherwise           : x^T <- x^T + dx, pixel stays unflagged.
-// First frame (init): v = dx (+ bias) (+ dense residual); x^A <- v, x^T <- 0, emit f(v).
+// First frame (init): v = dx (+ dense residual); x^A <- v, x^T <- 0, emit f(v).  (A convolution's bias is part
+// of dx: the producer adds it to the fp32 sum before that is rounded to the storage type.)
 // act == NONE: the (summed) delta is passed through, no state.
 //
 // The call handles the channel window [ch0, ch0+nch) of every pixel.  LP consecutive lanes share
@@ -193,7 +194,6 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
     const int PPI = kWave / LP;                       // pixels per iteration (<= 32)
     const int sub = lane % LP, grp = lane / LP;
     const int iters = kTile / PPI;
-    const T* bias = static_cast<const T*>(e.bias);
     const T* res = static_cast<const T*>(e.res_data);
     T* xA = static_cast<T*>(e.xA);
     T* xT = static_cast<T*>(e.xT);
@@ -229,7 +229,6 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
                     ra[ub][v] = raw_load<T, V>(xA + p * C + c0);
                     if (xT) rt[ub][v] = raw_load<T, V>(xT + p * C + c0);           // no buffer: truncated values are not kept
                 }
-                if (init && bias) ra[ub][v] = raw_load<T, V>(bias + c0);      // slot reused for the bias
             }
         }
         // ---- phase 2: arithmetic and the per-pixel maximum ---------------------------------------
@@ -244,7 +243,6 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
                 for (int i = 0; i < V; ++i) {
                     float d = raw_get<T, V>(rd[ub][v], i);
                     if (init) {
-                        if (bias) d = round_store<T>(d + raw_get<T, V>(ra[ub][v], i));
                         if (res) d = round_store<T>(d + raw_get<T, V>(rr[ub][v], i));
                         raw_set<T, V>(o_a[ub][v], i, d);
                         raw_set<T, V>(o_t[ub][v], i, 0.0f);
@@ -342,7 +340,6 @@ __device__ __forceinline__ void tail_prefetch(const EpilogueArgs& e, bool init, 
     const int C = e.c;
     const int nvec = (nch + V - 1) / V;
     const int sub = lane % LP, grp = lane / LP;
-    const T* bias = static_cast<const T*>(e.bias);
     const T* res = static_cast<const T*>(e.res_data);
     const T* xA = static_cast<const T*>(e.xA);
     const T* xT = static_cast<const T*>(e.xT);
@@ -362,7 +359,6 @@ __device__ __forceinline__ void tail_prefetch(const EpilogueArgs& e, bool init, 
             r.ra[it] = raw_load<T, V>(xA + p * C + c0);
             if (xT) r.rt[it] = raw_load<T, V>(xT + p * C + c0);
         }
-        if (init && bias) r.ra[it] = raw_load<T, V>(bias + c0);               // slot reused for the bias
     }
 }
 
@@ -374,7 +370,7 @@ __device__ __forceinline__ uint32_t tail_finish(const EpilogueArgs& e, bool init
     const int C = e.c;
     const int nvec = (nch + V - 1) / V;
     const int sub = lane % LP, grp = lane / LP;
-    const bool has_bias = e.bias != nullptr, has_res = e.res_data != nullptr;
+    const bool has_res = e.res_data != nullptr;
     T* xA = static_cast<T*>(e.xA);
     T* xT = static_cast<T*>(e.xT);
     T* out = static_cast<T*>(e.out_data);
@@ -394,7 +390,6 @@ __device__ __forceinline__ uint32_t tail_finish(const EpilogueArgs& e, bool init
         for (int i = 0; i < V; ++i) {
             float d = raw_get<T, V>(rd, i);
             if (init) {
-                if (has_bias) d = round_store<T>(d + raw_get<T, V>(r.ra[it], i));
                 if (has_res) d = round_store<T>(d + raw_get<T, V>(r.rr[it], i));
                 raw_set<T, V>(o_a[it], i, d);
                 raw_set<T, V>(o_t[it], i, 0.0f);

@@ -396,6 +396,8 @@ __global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvAr
     const int C = e.c;
     const T* in = static_cast<const T*>(c.in_data);
     const T* wgt = static_cast<const T*>(c.wpacked);           // [k][k][C], unpacked
+    // first frame: the bias joins the fp32 sum before its one rounding to the storage type
+    const T* bias_f = init ? static_cast<const T*>(e.bias) : nullptr;
     auto dx = [&](int, int64_t p, int c0) -> Raw {
         const int ox = (int)(p % c.ow);
         const int64_t t = p / c.ow;
@@ -417,6 +419,11 @@ __global__ __launch_bounds__(kTileThreads) void dwconv_kernel(ListArgs l, ConvAr
 #pragma unroll
                 for (int i = 0; i < V; ++i) acc[i] = fmaf(raw_get<T, V>(xv, i), raw_get<T, V>(wv, i), acc[i]);
             }
+        }
+        if (bias_f) {
+            const Raw bv = raw_load<T, V>(bias_f + c0);
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc[i] += raw_get<T, V>(bv, i);
         }
         Raw o;
 #pragma unroll

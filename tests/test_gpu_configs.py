@@ -1,6 +1,9 @@
 """GPU parity on the remaining BASELINE configurations: first at reduced spatial sizes / depths with
 objects that fill more of the map (channel counts, strides, kernel sizes and topology are the real
-ones), then at the full sizes the benchmark spec names, one stream, the first frames of the clip.  These
+ones), then at the full sizes the benchmark spec names, one stream, the first 12 frames of the clip: every
+planned layer of every frame is replayed against the oracle at single-operation tolerance, and the
+free-running run is compared with an independent oracle run outside the dependence cone of the
+threshold ties (tests/test_gpu_nets.py).  These
 exercise depthwise and strided convolutions, ReLU6, max pooling, weight streaming, multi-branch adds
 and nearest upsampling through dcnn_net_*."""
 import pytest
@@ -9,6 +12,15 @@ import workloads as wl
 from tests.test_gpu_nets import _run_net
 
 pytestmark = pytest.mark.gpu
+FULL_FRAMES = 12
+
+
+def _bounded(r, per_frame=40, replay_per_frame=3):
+    """Threshold ties stay rare: a few pixels per frame among ~10^5-10^6 decisions free-running, and (nearly)
+    none when every layer is replayed from the library's own inputs."""
+    msg = f"free-running ties per frame {r['ties_per_frame']} (first at frame {r['first_tie_frame']}), in replay {r['replay_ties']}"
+    assert max(r["ties_per_frame"]) <= per_frame, msg
+    assert max(r["replay_ties"], default=0) <= replay_per_frame, msg
 
 
 def test_config3_mobilenet_stack():
@@ -16,7 +28,7 @@ def test_config3_mobilenet_stack():
     spec = wl.mobilenet_stack(eps=0.05, h=96, w=96, frames=4)
     spec["video"] = wl.VideoSpec(h=96, w=96, c=3, frames=4, n_objects=3, obj_kind="rect", obj_size=20, noise_sigma=0.01)
     r = _run_net(spec, wl.CONFIG_SEEDS[3], 1)
-    assert r["ties"] <= 40
+    _bounded(r)
 
 
 def test_config4_resnet50_backbone():
@@ -25,7 +37,7 @@ def test_config4_resnet50_backbone():
     spec["video"] = wl.VideoSpec(h=64, w=64, c=3, frames=3, n_objects=2, obj_kind="blob", obj_size=12, noise_sigma=0.02,
                                  drift=0.002)
     r = _run_net(spec, wl.CONFIG_SEEDS[4], 1)
-    assert r["ties"] <= 40
+    _bounded(r)
 
 
 def test_config5_hrnet_like():
@@ -33,23 +45,23 @@ def test_config5_hrnet_like():
     spec = wl.hrnet_like(eps=0.05, h=96, w=64, frames=3)
     spec["video"] = wl.VideoSpec(h=96, w=64, c=3, frames=3, n_objects=1, obj_kind="stick", obj_size=40, noise_sigma=0.01)
     r = _run_net(spec, wl.CONFIG_SEEDS[5], 1)
-    assert r["ties"] <= 40
+    _bounded(r)
 
 
 # ---- the same three configurations at the benchmark's full sizes (one stream, the first frames of the clip) ----
 def test_config3_full_size():
     """224x224x3 input, 7 blocks, channels 32 -> 160, fp16; video: static camera, ~10 % moving pixels."""
-    r = _run_net(wl.mobilenet_stack(eps=0.05, frames=5), wl.CONFIG_SEEDS[3], 1)
-    assert r["ties"] <= 200
+    r = _run_net(wl.mobilenet_stack(eps=0.05, frames=FULL_FRAMES), wl.CONFIG_SEEDS[3], 1)
+    _bounded(r)
 
 
 def test_config4_full_size():
     """256x256x3 input, conv1 7x7 s2, max-pool, stages [3,4,6,3], fp16; 6 blobs, brightness drift, noise 0.02."""
-    r = _run_net(wl.resnet50_backbone(eps=0.05, frames=4), wl.CONFIG_SEEDS[4], 1)
-    assert r["ties"] <= 200
+    r = _run_net(wl.resnet50_backbone(eps=0.05, frames=FULL_FRAMES), wl.CONFIG_SEEDS[4], 1)
+    _bounded(r)
 
 
 def test_config5_full_size():
     """384x288x3 input, four resolutions, fp16; articulated stick figure over a textured background."""
-    r = _run_net(wl.hrnet_like(eps=0.05, frames=4), wl.CONFIG_SEEDS[5], 1)
-    assert r["ties"] <= 200
+    r = _run_net(wl.hrnet_like(eps=0.05, frames=FULL_FRAMES), wl.CONFIG_SEEDS[5], 1)
+    _bounded(r)

@@ -9,7 +9,7 @@ import torch
 import paper_2203_03996_amd as pkg
 from oracle import deltacnn_oracle as orc
 from oracle.deltacnn_oracle import Delta as ODelta
-from tests.helpers import NP_DTYPE, TOL, check_delta, rel_err, to_np
+from tests.helpers import NP_DTYPE, TOL, U32, check_delta, rel_err, sum_slack, to_np, ulp, upload_delta
 
 pytestmark = pytest.mark.gpu
 DT = {"f32": pkg.F32, "f16": pkg.F16}
@@ -25,7 +25,7 @@ def _rand_delta(rng, shape, density, S, scale=1.0):
 
 
 def _upload(d: ODelta):
-    return pkg.Delta.from_numpy(d.data, d.mask)
+    return upload_delta(d.data, d.mask)
 
 
 # ---- mask propagation + compaction (bit-exact) --------------------------------------------------
@@ -190,6 +190,13 @@ CONV_CASES = [
 ]
 
 
+def _near_tie(ract, eps, slack):
+    """Pixels whose decision the arithmetic leaves open: the oracle's max-norm lies within the value
+    tolerance of the threshold, or within what the pixel's own intermediates may differ by."""
+    u = np.nan_to_num(ract.last_u, nan=np.inf)
+    return np.abs(u - eps) <= TOL[ract.S] * abs(eps) + np.asarray(slack).max(axis=-1)
+
+
 def _conv_layers(S, k, stride, pad, cin, cout, nhw, rng, act=pkg.ACT_NONE, eps=0.0, n_in=1, depthwise=False):
     n, h, w = nhw
     if depthwise:
@@ -214,13 +221,13 @@ def test_conv_linear(S, k, stride, pad, cin, cout, nhw):
     r0 = ref.init(x0)
     g0 = layer.init([torch.from_numpy(x0).cuda()])
     ctx.sync()
-    assert rel_err(to_np(g0), r0) <= TOL[S], "dense first frame"
+    assert rel_err(to_np(g0), r0, slack=sum_slack(ref, x0, bias=True)) <= TOL[S], "dense first frame"
     for t, dens in enumerate([0.05, 0.4, 1.0, 0.0]):
         d = _rand_delta(rng, (n, h, w, cin), dens, S)
         want = ref.step(d).poisoned()
         out = layer.step([_upload(d)])
         ctx.sync()
-        check_delta(out, want, S, f"conv frame {t} density {dens}")
+        check_delta(out, want, S, f"conv frame {t} density {dens}", slack=sum_slack(ref, d.zero_filled()))
         st = layer.stats()
         assert st["pixels_in"] == d.count and st["pixels_out"] == want.count
 
@@ -249,7 +256,7 @@ def test_conv3x3_row_gathers_on_structured_masks(pattern, nhw):
     out = layer.step([_upload(d)])
     ctx.sync()
     assert want.count * 4 >= n * h * w * 3, "the pattern must list at least three quarters of the map"
-    check_delta(out, want, S, f"row gathers, {pattern}")
+    check_delta(out, want, S, f"row gathers, {pattern}", slack=sum_slack(ref, d.zero_filled()))
 
 
 @pytest.mark.parametrize("S,k,stride,cin,cout,nhw,res", [
@@ -292,16 +299,20 @@ def test_conv_fused_act(S, k, stride, cin, cout, nhw, res):
     oh, ow = layer.out_shape[1:3]
     x0 = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
     y0 = rconv.init(x0)
+    # what the arithmetic leaves open, per element: the fp32 sum, and one unit in the last place of every
+    # intermediate the two sides round independently (convolution sum; sum with the residual)
+    sl0 = sum_slack(rconv, x0, bias=True) + ulp(y0, S)
     ins0 = [torch.from_numpy(x0).cuda()]
     if res:
         s0 = rng.normal(0, 1, (n, oh, ow, cout)).astype(NP_DTYPE[S])
         y0 = radd.init(y0, s0)
+        sl0 = sl0 + ulp(y0, S)
         ins0.append(torch.from_numpy(s0).cuda())
     r0 = ract.init(y0)
     g0 = layer.init(ins0)
     ctx.sync()
-    assert rel_err(to_np(g0), r0) <= TOL[S]
-    assert rel_err(to_np(layer.state_tensor(0)), ract.xA) <= TOL[S]
+    assert rel_err(to_np(g0), r0, slack=sl0) <= TOL[S]
+    assert rel_err(to_np(layer.state_tensor(0)), ract.xA, slack=sl0) <= TOL[S]
     ties = 0
     for t, dens in enumerate([0.05, 0.3, 1.0, 0.0, 0.1]):
         # teacher forcing: the layer starts every frame from the oracle's state
@@ -309,21 +320,22 @@ def test_conv_fused_act(S, k, stride, cin, cout, nhw, res):
         layer.state_tensor(1).copy_(torch.from_numpy(ract.xT).cuda())
         d = _rand_delta(rng, (n, h, w, cin), dens, S, 0.5)
         mid = rconv.step(d).poisoned()
+        sl = sum_slack(rconv, d.zero_filled()) + ulp(mid.data, S)
         ins = [_upload(d)]
         if res:
             ds = _rand_delta(rng, (n, oh, ow, cout), dens / 2, S, 0.5)
             mid = radd.step(mid, ds).poisoned()
+            sl = sl + ulp(mid.data, S)
             ins.append(_upload(ds))
         want = ract.step(mid).poisoned()
         out = layer.step(ins)
         ctx.sync()
-        near = np.abs(np.nan_to_num(ract.last_u, nan=np.inf) - eps) <= TOL[S] * eps
-        ties += check_delta(out, want, S, f"fused frame {t}", allow_mask_diff=near)
+        near = _near_tie(ract, eps, sl)
+        ties += check_delta(out, want, S, f"fused frame {t}", allow_mask_diff=near, slack=sl)
         # state: equal to the oracle's where the decision agreed
         agree = to_np(out.mask) == want.mask
-        assert rel_err(to_np(layer.state_tensor(0))[agree], ract.xA[agree]) <= TOL[S]
-        xt_g, xt_r = to_np(layer.state_tensor(1))[agree], ract.xT[agree]
-        assert np.abs(xt_g.astype(np.float64) - xt_r).max(initial=0) <= TOL[S] * max(1.0, np.abs(xt_r).max(initial=0))
+        assert rel_err(to_np(layer.state_tensor(0))[agree], ract.xA[agree], slack=sl[agree]) <= TOL[S]
+        assert rel_err(to_np(layer.state_tensor(1))[agree], ract.xT[agree], slack=sl[agree]) <= TOL[S]
     assert ties <= 3
 
 
@@ -366,26 +378,29 @@ def test_layers_without_truncated_value_buffer(S, k, cin, cout, nhw, res):
     r0 = ract.init(y0)
     g0 = layer.init(ins0)
     ctx.sync()
-    assert rel_err(to_np(g0), r0) <= TOL[S]
+    sl0 = (sum_slack(rconv, x0, bias=True) + ulp(rconv.init(x0), S) + (ulp(y0, S) if res else 0.0)) if k else 0.0
+    assert rel_err(to_np(g0), r0, slack=sl0) <= TOL[S]
     ties = 0
     saw_trunc = False
     for t, dens in enumerate([0.1, 0.5, 1.0, 0.0, 0.2]):
         layer.state_tensor(0).copy_(torch.from_numpy(ract.xA).cuda())
         d = _rand_delta(rng, (n, h, w, cin), dens, S, 0.05 if not k else 0.5)
         mid = rconv.step(d).poisoned() if k else d
+        sl = (sum_slack(rconv, d.zero_filled()) + ulp(mid.data, S)) if k else np.zeros(mid.data.shape)
         ins = [_upload(d)]
         if res:
             ds = _rand_delta(rng, (n, h, w, cout), dens / 2, S, 0.5)
             mid = radd.step(mid, ds).poisoned()
+            sl = sl + ulp(mid.data, S)
             ins.append(_upload(ds))
         xa_before = ract.xA.copy()
         want = ract.step(mid).poisoned()
         out = layer.step(ins)
         ctx.sync()
-        near = np.abs(np.nan_to_num(ract.last_u, nan=np.inf) - eps) <= TOL[S] * eps
-        ties += check_delta(out, want, S, f"no-xT frame {t}", allow_mask_diff=near, exact_values=not k)
+        near = _near_tie(ract, eps, sl)
+        ties += check_delta(out, want, S, f"no-xT frame {t}", allow_mask_diff=near, exact_values=not k, slack=sl)
         agree = to_np(out.mask) == want.mask
-        assert rel_err(to_np(layer.state_tensor(0))[agree], ract.xA[agree]) <= TOL[S]
+        assert rel_err(to_np(layer.state_tensor(0))[agree], ract.xA[agree], slack=sl[agree]) <= TOL[S]
         trunc = (mid.mask == 1) & (want.mask == 0)
         saw_trunc |= bool(trunc.any())
         assert np.array_equal(ract.xA[trunc], xa_before[trunc])       # the oracle really dropped those updates
@@ -424,27 +439,33 @@ def test_conv_fused_projection(S, k, cin, cin2, cout, nhw, stride2):
     assert layer.out_shape == (n, oh, ow, cout)
     x0 = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
     z0 = rng.normal(0, 1, (n, h2, w2, cin2)).astype(NP_DTYPE[S])
-    r0 = ract.init(radd.init(ra.init(x0), rb.init(z0)))
+    ya0, yb0 = ra.init(x0), rb.init(z0)
+    y0 = radd.init(ya0, yb0)
+    r0 = ract.init(y0)
     g0 = layer.init([torch.from_numpy(x0).cuda(), torch.from_numpy(z0).cuda()])
     ctx.sync()
-    assert rel_err(to_np(g0), r0) <= TOL[S], "dense first frame"
-    assert rel_err(to_np(layer.state_tensor(0)), ract.xA) <= TOL[S]
+    # both convolution sums and their sum are intermediates each side rounds on its own
+    sl0 = sum_slack(ra, x0, bias=True) + sum_slack(rb, z0, bias=True) + ulp(ya0, S) + ulp(yb0, S) + ulp(y0, S)
+    assert rel_err(to_np(g0), r0, slack=sl0) <= TOL[S], "dense first frame"
+    assert rel_err(to_np(layer.state_tensor(0)), ract.xA, slack=sl0) <= TOL[S]
     ties = 0
     for t, (dx, dz) in enumerate([(0.05, 0.1), (0.3, 0.0), (0.0, 0.2), (1.0, 1.0), (0.0, 0.0), (0.1, 0.02)]):
         layer.state_tensor(0).copy_(torch.from_numpy(ract.xA).cuda())
         layer.state_tensor(1).copy_(torch.from_numpy(ract.xT).cuda())
         d = _rand_delta(rng, (n, h, w, cin), dx, S, 0.5)
         z = _rand_delta(rng, (n, h2, w2, cin2), dz, S, 0.5)
-        mid = radd.step(ra.step(d).poisoned(), rb.step(z).poisoned()).poisoned()
+        ma, mb = ra.step(d).poisoned(), rb.step(z).poisoned()
+        mid = radd.step(ma, mb).poisoned()
+        sl = (sum_slack(ra, d.zero_filled()) + sum_slack(rb, z.zero_filled()) + ulp(ma.data, S) + ulp(mb.data, S)
+              + ulp(mid.data, S))
         want = ract.step(mid).poisoned()
         out = layer.step([_upload(d), _upload(z)])
         ctx.sync()
-        near = np.abs(np.nan_to_num(ract.last_u, nan=np.inf) - eps) <= TOL[S] * eps
-        ties += check_delta(out, want, S, f"projection frame {t}", allow_mask_diff=near)
+        near = _near_tie(ract, eps, sl)
+        ties += check_delta(out, want, S, f"projection frame {t}", allow_mask_diff=near, slack=sl)
         agree = to_np(out.mask) == want.mask
-        assert rel_err(to_np(layer.state_tensor(0))[agree], ract.xA[agree]) <= TOL[S]
-        xt_g, xt_r = to_np(layer.state_tensor(1))[agree], ract.xT[agree]
-        assert np.abs(xt_g.astype(np.float64) - xt_r).max(initial=0) <= TOL[S] * max(1.0, np.abs(xt_r).max(initial=0))
+        assert rel_err(to_np(layer.state_tensor(0))[agree], ract.xA[agree], slack=sl[agree]) <= TOL[S]
+        assert rel_err(to_np(layer.state_tensor(1))[agree], ract.xT[agree], slack=sl[agree]) <= TOL[S]
         st = layer.stats()
         assert st["pixels_in"] == d.count and st["pixels_in2"] == z.count and st["pixels_work"] == mid.count
     assert ties <= 3
@@ -478,12 +499,15 @@ def test_conv_fused_accumulate(S, k, cin, cout, nhw, proj):
     x0 = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
     z0 = rng.normal(0, 1, (n, h, w, cin2)).astype(NP_DTYPE[S])
     y0 = ra.init(x0)
+    sl0 = sum_slack(ra, x0, bias=True) + ulp(y0, S)
     if proj:
-        y0 = radd.init(y0, rb.init(z0))
+        yb0 = rb.init(z0)
+        y0 = radd.init(y0, yb0)
+        sl0 = sl0 + sum_slack(rb, z0, bias=True) + ulp(yb0, S) + ulp(y0, S)
     r0 = racc.init(ract.init(y0))
     g0 = layer.init([torch.from_numpy(x0).cuda()] + ([torch.from_numpy(z0).cuda()] if proj else []))
     ctx.sync()
-    assert rel_err(to_np(g0), r0) <= TOL[S]
+    assert rel_err(to_np(g0), r0, slack=sl0) <= TOL[S]
     assert np.array_equal(to_np(layer.state_tensor(2)), to_np(g0)), "O starts as the dense first output"
     for t, dens in enumerate([0.05, 0.3, 1.0, 0.0, 0.1]):
         layer.state_tensor(0).copy_(torch.from_numpy(ract.xA).cuda())
@@ -491,10 +515,13 @@ def test_conv_fused_accumulate(S, k, cin, cout, nhw, proj):
         layer.state_tensor(2).copy_(torch.from_numpy(racc.O).cuda())
         d = _rand_delta(rng, (n, h, w, cin), dens, S, 0.5)
         mid = ra.step(d).poisoned()
+        sl = sum_slack(ra, d.zero_filled()) + ulp(mid.data, S)
         ins = [_upload(d)]
         if proj:
             z = _rand_delta(rng, (n, h, w, cin2), dens / 2, S, 0.5)
-            mid = radd.step(mid, rb.step(z).poisoned()).poisoned()
+            mb = rb.step(z).poisoned()
+            mid = radd.step(mid, mb).poisoned()
+            sl = sl + sum_slack(rb, z.zero_filled()) + ulp(mb.data, S) + ulp(mid.data, S)
             ins.append(_upload(z))
         o_before = racc.O.copy()
         want = ract.step(mid).poisoned()
@@ -502,12 +529,15 @@ def test_conv_fused_accumulate(S, k, cin, cout, nhw, proj):
         out = layer.step(ins)
         ctx.sync()
         gm = to_np(out.mask)
-        near = np.abs(np.nan_to_num(ract.last_u, nan=np.inf) - eps) <= TOL[S] * eps
+        near = _near_tie(ract, eps, sl)
         assert np.all(near[gm != want.mask]), f"frame {t}: mask mismatch away from a threshold tie"
         agree = gm == want.mask
         got_o = to_np(layer.state_tensor(2)).reshape(o_ref.shape)
         assert not np.isnan(got_o.astype(np.float64)).any()
-        assert rel_err(got_o[agree], o_ref[agree]) <= TOL[S], f"frame {t}: accumulated output"
+        # the folded layer writes O = f(new x^A), the oracle's output layer adds the rounded delta onto O:
+        # one more independent rounding, of the delta
+        sl_o = sl + ulp(want.data, S)
+        assert rel_err(got_o[agree], o_ref[agree], slack=sl_o[agree]) <= TOL[S], f"frame {t}: accumulated output"
         untouched = want.mask == 0
         assert np.array_equal(got_o[untouched & agree], o_before[untouched & agree]), "O changes only where a delta was emitted"
         assert out.data.data_ptr() == layer.state_tensor(2).data_ptr(), "the layer's output data is O"
@@ -522,20 +552,23 @@ def test_depthwise(S, stride, c):
     ctx, layer, rconv = _conv_layers(S, 3, stride, 1, c, c, nhw, rng, act=pkg.ACT_RELU6, eps=eps, depthwise=True)
     ract = orc.ActTrunc("relu6", eps, S)
     x0 = rng.normal(0, 1, nhw + (c,)).astype(NP_DTYPE[S])
-    r0 = ract.init(rconv.init(x0))
+    y0 = rconv.init(x0)
+    r0 = ract.init(y0)
     g0 = layer.init([torch.from_numpy(x0).cuda()])
     ctx.sync()
-    assert rel_err(to_np(g0), r0) <= TOL[S]
+    assert rel_err(to_np(g0), r0, slack=sum_slack(rconv, x0, bias=True) + ulp(y0, S)) <= TOL[S]
     ties = 0
     for t, dens in enumerate([0.1, 0.5, 0.0]):
         layer.state_tensor(0).copy_(torch.from_numpy(ract.xA).cuda())
         layer.state_tensor(1).copy_(torch.from_numpy(ract.xT).cuda())
         d = _rand_delta(rng, nhw + (c,), dens, S, 0.5)
-        want = ract.step(rconv.step(d).poisoned()).poisoned()
+        mid = rconv.step(d).poisoned()
+        sl = sum_slack(rconv, d.zero_filled()) + ulp(mid.data, S)
+        want = ract.step(mid).poisoned()
         out = layer.step([_upload(d)])
         ctx.sync()
-        near = np.abs(np.nan_to_num(ract.last_u, nan=np.inf) - eps) <= TOL[S] * eps
-        ties += check_delta(out, want, S, f"depthwise frame {t}", allow_mask_diff=near)
+        near = _near_tie(ract, eps, sl)
+        ties += check_delta(out, want, S, f"depthwise frame {t}", allow_mask_diff=near, slack=sl)
     assert ties <= 3
 
 
@@ -561,13 +594,13 @@ def test_depthwise_as_batchnorm_and_average_pooling(S, k, stride, pad, what):
     r0 = ref.init(x0)
     g0 = layer.init([torch.from_numpy(x0).cuda()])
     ctx.sync()
-    assert rel_err(to_np(g0), r0) <= TOL[S]
+    assert rel_err(to_np(g0), r0, slack=sum_slack(ref, x0, bias=True)) <= TOL[S]
     for t, dens in enumerate([0.1, 0.6, 0.0]):
         d = _rand_delta(rng, (n, h, w, c), dens, S)
         want = ref.step(d).poisoned()
         out = layer.step([_upload(d)])
         ctx.sync()
-        check_delta(out, want, S, f"{what} frame {t}")
+        check_delta(out, want, S, f"{what} frame {t}", slack=sum_slack(ref, d.zero_filled()))
 
 
 # ---- pooling, upsampling, accumulation (bit-exact) -----------------------------------------------
@@ -628,13 +661,15 @@ def test_upsample_bilinear(S, factor, c):
     x0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
     g0 = layer.init([torch.from_numpy(x0).cuda()])
     ctx.sync()
-    assert rel_err(to_np(g0), ref.init(x0)) <= TOL[S]
+    # a weighted sum of up to four sources in fp32 against the oracle's float64: same allowance as a convolution sum
+    mag = orc.UpsampleBilinear(factor, "f64")
+    assert rel_err(to_np(g0), ref.init(x0), slack=8 * U32 * mag.init(np.abs(x0))) <= TOL[S]
     for t, dens in enumerate([0.1, 1.0, 0.02, 0.0]):
         d = _rand_delta(rng, shape, dens, S)
         want = ref.step(d).poisoned()
         out = layer.step([_upload(d)])
         ctx.sync()
-        check_delta(out, want, S, f"bilinear x{factor} frame {t}")
+        check_delta(out, want, S, f"bilinear x{factor} frame {t}", slack=8 * U32 * mag.init(np.abs(d.zero_filled())))
 
 
 @pytest.mark.parametrize("S", ["f32", "f16"])
@@ -649,7 +684,8 @@ def test_global_average_pooling(S, shape):
     x0 = rng.normal(0, 1, shape).astype(NP_DTYPE[S])
     g0 = layer.init([torch.from_numpy(x0).cuda()])
     ctx.sync()
-    assert rel_err(to_np(g0), ref.init(x0)) <= TOL[S]
+    mag = orc.GlobalAvgPool("f64")
+    assert rel_err(to_np(g0), ref.init(x0), slack=8 * U32 * mag.init(np.abs(x0))) <= TOL[S]
     for t, dens in enumerate([0.1, 1.0, 0.0]):
         d = _rand_delta(rng, shape, dens, S)
         if t == 0 and n > 1:
@@ -658,7 +694,8 @@ def test_global_average_pooling(S, shape):
         want = ref.step(d).poisoned()
         out = layer.step([_upload(d)])
         ctx.sync()
-        check_delta(out, want, S, f"global average pool frame {t}")
+        check_delta(out, want, S, f"global average pool frame {t}",
+                    slack=8 * U32 * mag.init(np.abs(d.zero_filled().astype(np.float64))))
 
 
 @pytest.mark.parametrize("S", ["f32", "f16"])

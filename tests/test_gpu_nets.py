@@ -1,15 +1,18 @@
 """GPU parity of whole networks run free (no teacher forcing) through dcnn_net_*.
 
 The library's convolution sums differ from the oracle's in rounding order, so a pixel whose
-max |dy| lands within rounding of the threshold may be decided differently ("threshold tie");
-from then on the two delta streams legitimately differ while both keep tracking dense
-inference.  The checks are therefore:
-  * until the first tie: every mask identical, every index list the oracle's, the dense
-    output within the value tolerance;
-  * a mask difference is only accepted at pixels whose oracle max-norm is within the value
-    tolerance of the threshold;
-  * always: the dense output stays as close to plain dense inference as the oracle's does
-    (truncation error does not accumulate), and with negative thresholds it equals it.
+max |dy| lands within rounding of the threshold may be decided differently ("threshold tie").
+From then on the two sides legitimately differ, but only inside the tie's dependence cone: the
+pixels of later layers (and later frames) whose windows reach a tied pixel.  The checks are:
+  * outside the cone, every frame: every mask identical, every index list the ordered
+    compaction (and the oracle's list when the whole mask agrees), every accumulated input
+    x^A + x^T, every pooling buffer, the stored input frame and the dense output equal to the
+    oracle's within the value tolerance;
+  * a mask difference outside the cone is only accepted at a layer with a threshold, at pixels
+    whose oracle max-norm is within rounding of the threshold; these ties are counted per frame
+    and reported, and their cone is excluded from then on;
+  * everywhere, cone included: the dense output stays as close to plain dense inference as the
+    oracle's does (truncation error does not accumulate), and with negative thresholds it equals it.
 """
 import numpy as np
 import pytest
@@ -19,12 +22,195 @@ import paper_2203_03996_amd as pkg
 import workloads as wl
 from oracle import deltacnn_oracle as orc
 from oracle.deltacnn_oracle import Delta as ODelta
-from tests.helpers import NP_DTYPE, TOL, rel_err, to_np
+from tests.helpers import NP_DTYPE, TOL, U32, rel_err, sum_slack, to_np, ulp, worst
 
 pytestmark = pytest.mark.gpu
 
+# Free-running, both sides round every stored intermediate on their own (fp32 against float64
+# convolution sums): a layer's accumulated input differs between two correct implementations by a few
+# units in the last place of the tensor's largest magnitude -- not of the element: a small element is a
+# sum of large rounded ones -- and these differences random-walk through the layers.  The free-running
+# comparison with the independent oracle run therefore allows, per tensor, QUANTA * sqrt(depth) units in
+# the last place of its scale on top of the relative tolerance (depth = rounding stages on the longest
+# path from the input; measured need on the five configurations: below 2).  The TIGHT per-layer gate at
+# network scale is the replay below, which has no such term.
+QUANTA = 4.0
 
-def _run_net(spec, seed, n_streams, flags=3, frames=None, check_dense=True):
+
+def _spread(nd, taints):
+    """Which output pixels of node `nd` depend on the given pixels of its inputs (structural)."""
+    k = nd["kind"]
+    ins = [taints[j] for j in nd["in"]]
+    if k in ("conv", "maxpool"):
+        return orc.window_mask(ins[0], nd["k"], nd["stride"], nd["pad"]).astype(bool)
+    if k in ("add", "concat"):
+        return ins[0] | ins[1]
+    if k == "upsample":
+        return np.repeat(np.repeat(ins[0], nd["factor"], axis=1), nd["factor"], axis=2)
+    if k == "upsample_bilinear":
+        # a dependence is a tap with weight: the oracle's own mask rule gives it
+        n, h, w = ins[0].shape
+        return orc.UpsampleBilinear(nd["factor"], "f64")._apply(np.zeros((n, h, w, 1)), ins[0].astype(np.uint8))[1].astype(bool)
+    if k == "gavgpool":
+        return ins[0].reshape(ins[0].shape[0], -1).any(axis=1).reshape(-1, 1, 1)
+    return ins[0]                                                    # act, accum: pixel-local
+
+
+_ROUNDS = ("conv", "add", "upsample_bilinear", "gavgpool")           # kinds whose result each side rounds on its own
+
+
+def _depths(nodes):
+    d = []
+    for nd in nodes:
+        d.append(max([d[j] for j in nd["in"]], default=0) + (1 if nd["kind"] in _ROUNDS else 0))
+    return d
+
+
+def free_running_slack(spec, ref, S):
+    """Absolute allowance of a network's dense output in a free-running comparison (see QUANTA)."""
+    return QUANTA * max(1.0, _depths(spec["nodes"])[-1]) ** 0.5 * float(ulp(float(np.abs(ref).max(initial=0)), S))
+
+
+# ---- replay: every planned layer of the running network against the oracle's definition of that layer ----
+def _snapshot(net):
+    """Host copies of every layer's buffers (x^A / stored frame / pooling buffer / O, x^T, folded O)."""
+    snap = {}
+    for li in range(net.num_layers):
+        snap[li] = tuple(None if (b := net.layer_state(li, which)) is None else to_np(b).copy() for which in (0, 1, 2))
+    return snap
+
+
+def _replay_layers(net, spec, oracle, layer_of, pre, S, t):
+    """Teacher forcing by the library's own stream: for every planned layer, the oracle's layers of the nodes
+    it covers are run on the inputs the library's producer layers left in memory this frame and on the
+    library's buffers from before the step; the library's output and buffers after the step must equal the
+    result to single-operation tolerance.  No compounding over depth or frames, no dependence cone: a
+    threshold tie is a property of one pixel of one layer in one frame.  Returns the ties it saw."""
+    nodes = spec["nodes"]
+    tol = TOL[S]
+    st = NP_DTYPE[S]
+    stats = net.stats()
+    cache = {}
+
+    def produced(j):                                               # output of a planned layer, as the library left it
+        if j not in cache:
+            _, view, _ = net.layer_output(layer_of[j])
+            cache[j] = ODelta(to_np(view.data).copy(), to_np(view.mask)).poisoned()
+        return cache[j]
+
+    ties = 0
+    for li in range(net.num_layers):
+        nid = net.layer_node(li)
+        group = []
+
+        def walk(j):
+            for a in nodes[j]["in"]:
+                if a not in layer_of and a not in group:
+                    walk(a)
+            group.append(j)
+        walk(nid)
+        folded = bool(stats[li]["fuse_accum"])
+        vals, slk = {}, {}
+
+        def val(j):
+            return vals[j] if j in vals else produced(j)
+
+        def slack(j):
+            return slk.get(j, 0.0)
+
+        xa0, xt0, o0 = pre[li]
+        what = f"frame {t} layer {li} (nodes {group})"
+        act_ly = None
+        for j in group:
+            nd = nodes[j]
+            k = nd["kind"]
+            ly = oracle.layers[j]
+            if k == "deltagen":
+                continue
+            ins = [val(a) for a in nd["in"]]
+            if k == "conv":
+                vals[j] = ly.step(ins[0]).poisoned()                # stateless: the oracle's own object serves
+                slk[j] = sum_slack(ly, ins[0].zero_filled()) + ulp(vals[j].data, S)
+            elif k == "add":
+                vals[j] = ly.step(*ins).poisoned()
+                sa, sb = slack(nd["in"][0]), slack(nd["in"][1])
+                # the sum of two stored streams is one exact fp32 addition and one rounding on both sides
+                slk[j] = (sa + sb + ulp(vals[j].data, S)) if (np.any(sa) or np.any(sb)) else 0.0
+            elif k == "act":
+                act_ly = orc.ActTrunc(ly.f, ly.eps, S, ly.use_xT)
+                act_ly.xA = xa0.reshape(ins[0].data.shape).copy()
+                act_ly.xT = np.zeros_like(act_ly.xA) if xt0 is None else xt0.reshape(ins[0].data.shape).copy()
+                vals[j] = act_ly.step(ins[0]).poisoned()
+                slk[j] = slack(nd["in"][0])
+            elif k == "maxpool":
+                sh = orc.MaxPool(ly.k, ly.stride, ly.pad, S)
+                sh.xA = xa0.reshape(ins[0].data.shape).copy()
+                vals[j] = sh.step(ins[0]).poisoned()
+                act_ly = sh
+            elif k == "accum":
+                sh = orc.Accumulate(S)
+                sh.O = xa0.reshape(ins[0].data.shape).copy()
+                vals[j] = sh.step(ins[0])
+            elif k in ("upsample", "concat"):
+                vals[j] = ly.step(*ins).poisoned()
+            elif k == "upsample_bilinear":
+                vals[j] = ly.step(ins[0]).poisoned()
+                slk[j] = 8 * U32 * orc.UpsampleBilinear(nd["factor"], "f64").init(np.abs(ins[0].zero_filled().astype(np.float64)))
+            elif k == "gavgpool":
+                vals[j] = ly.step(ins[0]).poisoned()
+                slk[j] = 8 * U32 * orc.GlobalAvgPool("f64").init(np.abs(ins[0].zero_filled().astype(np.float64)))
+            else:
+                raise ValueError(k)
+        kind = nodes[nid]["kind"]
+        _, view, _ = net.layer_output(li)
+        xa1, xt1, o1 = (None if (b := net.layer_state(li, w)) is None else to_np(b) for w in (0, 1, 2))
+        if kind == "deltagen":
+            # the input layer is replayed from the frame itself by the free-running comparison (bit-exact there)
+            continue
+        if kind == "accum":
+            assert np.array_equal(xa1.reshape(vals[nid].shape), vals[nid]), f"{what}: accumulated output"
+            continue
+        want = vals[nid]
+        sl = np.broadcast_to(np.asarray(slack(nid), np.float64), want.data.shape)
+        gm = to_np(view.mask)
+        diff = gm != want.mask
+        if diff.any():
+            assert isinstance(act_ly, orc.ActTrunc), f"{what}: {int(diff.sum())} mask differences in a layer without a threshold"
+            gap = np.abs(np.nan_to_num(act_ly.last_u, nan=np.inf) - act_ly.eps)
+            room = tol * abs(act_ly.eps) + sl.max(axis=-1)
+            assert np.all(gap[diff] <= room[diff]), f"{what}: mask differs away from a threshold tie (gap {gap[diff].max():.3e})"
+            ties += int(diff.sum())
+        agree = ~diff
+        exact = not np.any(sl)
+        both = (gm == 1) & (want.mask == 1)
+        if not folded:
+            g, r = to_np(view.data)[both], want.data[both]
+            assert not np.isnan(g.astype(np.float64)).any(), f"{what}: NaN in a flagged output"
+            if exact:
+                assert np.array_equal(g, r), f"{what}: values differ"
+            else:
+                e = rel_err(g, r, slack=sl[both])
+                assert e <= tol, f"{what}: output off by {e:.2e}; {worst(g, r, slack=sl[both])}"
+        if isinstance(act_ly, (orc.ActTrunc, orc.MaxPool)):
+            shape = act_ly.xA.shape
+            sl_state = sl if isinstance(act_ly, orc.ActTrunc) else 0.0 * act_ly.xA.astype(np.float64)
+            ag = agree if isinstance(act_ly, orc.ActTrunc) else np.ones(shape[:3], bool)
+            e = rel_err(xa1.reshape(shape)[ag], act_ly.xA[ag], slack=sl_state[ag])
+            assert e <= (0.0 if exact else tol), f"{what}: x^A off by {e:.2e}; {worst(xa1.reshape(shape)[ag], act_ly.xA[ag], slack=sl_state[ag])}"
+            if xt1 is not None:
+                e = rel_err(xt1.reshape(shape)[ag], act_ly.xT[ag], slack=sl_state[ag])
+                assert e <= (0.0 if exact else tol), f"{what}: x^T off by {e:.2e}; {worst(xt1.reshape(shape)[ag], act_ly.xT[ag], slack=sl_state[ag])}"
+        if folded:
+            # the folded output layer writes O = f(new x^A) where the oracle's adds the rounded delta onto O
+            acc = orc.Accumulate(S)
+            acc.O = o0.reshape(want.data.shape).copy()
+            o_ref = acc.step(want)
+            e = rel_err(o1.reshape(o_ref.shape)[agree], o_ref[agree], slack=(sl + ulp(want.data, S))[agree])
+            assert e <= tol, f"{what}: dense output off by {e:.2e}"
+    return ties
+
+
+def _run_net(spec, seed, n_streams, flags=3, frames=None, check_dense=True, replay=True, diag=None):
     S = spec["dtype"]
     wts = wl.make_weights(spec, seed)
     vid = wl.make_batch(spec["video"], seed, n_streams)
@@ -34,88 +220,155 @@ def _run_net(spec, seed, n_streams, flags=3, frames=None, check_dense=True):
     # dense reference uses the weights as stored (rounded to S), like both implementations
     wts_s = {i: (w.astype(NP_DTYPE[S]).astype(np.float64), b.astype(NP_DTYPE[S]).astype(np.float64))
              for i, (w, b) in wts.items()}
+    nodes = spec["nodes"]
     shapes = wl.node_shapes(spec)
+    depth = _depths(nodes)
     max_px = n_streams * max(h * w for h, w, _ in shapes)
     ctx = pkg.Context(max_px)
     net = pkg.Net(ctx, spec, wts, n_streams, flags)
     oh, ow, oc = shapes[-1]
     out = torch.empty((n_streams, oh, ow, oc), dtype=torch.float16 if S == "f16" else torch.float32, device="cuda")
-    eps_of = {i: nd["eps"] for i, nd in enumerate(spec["nodes"]) if nd["kind"] in ("act", "deltagen")}
-    # Free-running, every stored intermediate is rounded independently by the two implementations
-    # (fp32 vs float64 convolution sums), and these differences random-walk through the layers: the
-    # single-operation tolerance is widened with the square root of the depth (1x up to 4 convolutions).
-    n_conv = sum(1 for nd in spec["nodes"] if nd["kind"] == "conv")
-    tol = TOL[S] * max(1.0, (n_conv ** 0.5) / 2.0)
-    diverged = False
-    ties = 0
+    tol = TOL[S]
+    layer_of = {net.layer_node(li): li for li in range(net.num_layers)}
+    # cone[i]: pixels of node i's output that a threshold tie has reached so far (persistent: state differs there)
+    cone = [np.zeros((n_streams, h, w), bool) for h, w, _ in shapes]
+    scale = {}                                                       # running largest magnitude per compared tensor
+
+    sum_unit = [0.0]                                                 # fp32 storage: largest fp32-summation allowance of any convolution so far
+
+    def allowance(key, ref_t, d):
+        # rounding unit of a stage: one unit in the last place of the tensor's scale, plus -- it only matters next to
+        # fp32's own unit -- what an fp32 sum may differ by from the exact one (sum_slack)
+        scale[key] = max(scale.get(key, 0.0), float(np.abs(ref_t).max(initial=0)))
+        return QUANTA * max(1.0, d) ** 0.5 * (float(ulp(scale[key], S)) + sum_unit[0])
+
+    ties_per_frame, replay_ties = [], []
     report = []
     for t in range(vid.shape[0]):
         fr = vid[t].astype(NP_DTYPE[S])
         frame = torch.from_numpy(fr).cuda()
+        do_replay = t > 0 and (replay is True or (replay and t in replay))
+        pre = _snapshot(net) if do_replay else None
         (net.init if t == 0 else net.step)(frame, out)
         ctx.sync()
         ref = oracle.frame(fr)
         got = to_np(out)
         assert not np.isnan(got.astype(np.float64)).any(), f"frame {t}: NaN in the dense output"
+        if S == "f32":
+            for j, ndj in enumerate(nodes):
+                if ndj["kind"] == "conv":
+                    xin = oracle.outs[ndj["in"][0]]
+                    xin = xin.zero_filled() if isinstance(xin, ODelta) else xin
+                    sum_unit[0] = max(sum_unit[0], float(sum_slack(oracle.layers[j], xin, bias=(t == 0)).max(initial=0)))
+        ties = 0
+        if do_replay:
+            replay_ties.append(_replay_layers(net, spec, oracle, layer_of, pre, S, t))
         if t > 0:
-            for li in range(net.num_layers):
-                nid, view, _ = net.layer_output(li)
-                o = oracle.outs[nid]
-                if not isinstance(o, ODelta) or view.mask is None:
-                    continue
-                gm = to_np(view.mask)
-                diff = gm != o.mask
-                if diff.any() and not diverged:
-                    # the first difference of the run must sit on a threshold tie of this very layer
-                    ly = oracle.layers[nid]
-                    assert getattr(ly, "last_u", None) is not None, f"frame {t} node {nid}: mask differs"
-                    eps = eps_of[nid]
-                    near = np.abs(np.nan_to_num(ly.last_u, nan=np.inf) - eps) <= tol * abs(eps)
-                    assert np.all(near[diff]), f"frame {t} node {nid}: mask differs away from a threshold tie"
-                    ties += int(diff.sum())
-                    diverged = True
-                if not diverged:
-                    if view.count is not None and (flags & 2):
+            for i, nd in enumerate(nodes):
+                if nd["in"]:
+                    cone[i] |= _spread(nd, cone)
+                li = layer_of.get(i)
+                if li is None:
+                    continue                                        # fused into a later layer
+                _, view, _ = net.layer_output(li)
+                o = oracle.outs[i]
+                ly = oracle.layers[i]
+                clean = ~cone[i]
+                if isinstance(o, ODelta) and view.mask is not None:
+                    gm = to_np(view.mask)
+                    diff = gm != o.mask
+                    new = diff & clean
+                    if new.any():
+                        assert getattr(ly, "last_u", None) is not None, \
+                            f"frame {t} node {i} ({nd['kind']}): {int(new.sum())} mask differences outside any tie's cone"
+                        # free-running, what decides is the delta path (x^T + dx): its rounding quanta, this frame's
+                        # and -- through x^T -- earlier frames'
+                        # free-running, the two sides' accumulated inputs s and x^A of this layer agree to within the
+                        # tensor's allowance (checked below), so their max-norms of f(s) - f(x^A) to within twice that;
+                        # the replay above decides the same pixel at single-operation tolerance
+                        al = allowance(i, ly.xA.astype(np.float64) + ly.xT.astype(np.float64), depth[i])
+                        room = tol * abs(ly.eps) + 2.0 * al
+                        gap = np.abs(np.nan_to_num(ly.last_u, nan=np.inf) - ly.eps)
+                        if diag is not None:
+                            diag.setdefault("tie_need", []).append(float((gap[new].max() - tol * abs(ly.eps)) / al))
+                        else:
+                            assert np.all(gap[new] <= room), \
+                                f"frame {t} node {i}: mask differs away from a threshold tie (gap {gap[new].max():.3e}, room {room:.3e})"
+                        ties += int(new.sum())
+                        cone[i] |= new
+                        clean = ~cone[i]
+                    if view.count is not None and view.idx is not None and (flags & 2):
                         cnt = int(to_np(view.count)[0])
-                        assert cnt == o.count, f"frame {t} node {nid}: count {cnt} vs {o.count}"
-                        assert np.array_equal(to_np(view.idx)[:cnt], o.idx), f"frame {t} node {nid}: index list"
-                    # free-running, the delta streams themselves are small differences of rounded
-                    # accumulated values; what must agree is the accumulated input of every
-                    # non-linear layer, x^A + x^T (deltas are compared teacher-forced in test_gpu_layers)
-                    ly = oracle.layers[nid]
-                    xa, xt = net.layer_state(li, 0), net.layer_state(li, 1)
-                    if xa is not None and getattr(ly, "xT", None) is not None:
-                        # (a layer without a buffer of truncated values has x^T = 0 on both sides)
-                        got_acc = to_np(xa).astype(np.float64) + (to_np(xt).astype(np.float64) if xt is not None else 0.0)
-                        ref_acc = ly.xA.astype(np.float64).reshape(-1) + ly.xT.astype(np.float64).reshape(-1)
-                        e = rel_err(got_acc, ref_acc, floor=0.1)
-                        assert e <= tol, f"frame {t} node {nid}: accumulated input off by {e:.2e}"
+                        assert cnt == int(gm.sum()), f"frame {t} node {i}: count {cnt} vs mask {int(gm.sum())}"
+                        assert np.array_equal(to_np(view.idx)[:cnt], np.flatnonzero(gm.reshape(-1))), f"frame {t} node {i}: index list"
+                        if not diff.any():
+                            assert np.array_equal(to_np(view.idx)[:cnt], o.idx), f"frame {t} node {i}: index list vs oracle"
+        # buffers and dense output, outside the cone of every tie so far (frame 0: everywhere)
+        for i, nd in enumerate(nodes):
+            li = layer_of.get(i)
+            if li is None:
+                continue
+            ly = oracle.layers[i]
+            xa, xt = net.layer_state(li, 0), net.layer_state(li, 1)
+            if nd["kind"] == "deltagen":
+                assert np.array_equal(to_np(xa).reshape(ly.P.shape), ly.P), f"frame {t}: stored input frame"
+            elif nd["kind"] == "maxpool":
+                cl = ~cone[nd["in"][0]]
+                e = rel_err(to_np(xa).reshape(ly.xA.shape)[cl], ly.xA[cl], slack=allowance(i, ly.xA, depth[i]))
+                if diag is None:
+                    assert e <= tol, f"frame {t} node {i}: pooling buffer off by {e:.2e} outside the ties' cone"
+            elif xa is not None and getattr(ly, "xT", None) is not None:
+                # x^A + x^T = everything received so far (Eqs. 5, 6); (a layer without x^T keeps zeros)
+                clean = ~cone[i]
+                ref_acc = ly.xA.astype(np.float64) + ly.xT.astype(np.float64)
+                got_acc = (to_np(xa).astype(np.float64) + (to_np(xt).astype(np.float64) if xt is not None else 0.0)).reshape(ref_acc.shape)
+                al = allowance(i, ref_acc, depth[i])
+                if diag is not None:
+                    err = np.abs(got_acc - ref_acc)[clean]
+                    den = np.maximum(np.abs(ref_acc), 1e-3 * np.abs(ref_acc).max())[clean]
+                    diag.setdefault("acc_need", []).append((t, i, float((err - tol * den).max(initial=0) / (al / QUANTA)), float(clean.mean())))
                 else:
-                    assert diff.mean() < 0.02, f"frame {t} node {nid}: masks drifted apart ({diff.mean():.3f})"
-        if not diverged:
-            e = rel_err(got, ref)
-            assert e <= tol, f"frame {t}: dense output off by {e:.2e}"
+                    e = rel_err(got_acc[clean], ref_acc[clean], slack=al)
+                    assert e <= tol, f"frame {t} node {i}: accumulated input off by {e:.2e} outside the ties' cone"
+        clean = ~cone[-1]
+        al = allowance("out", ref, depth[-1])
+        if diag is not None:
+            err = np.abs(got.astype(np.float64) - ref)[clean]
+            den = np.maximum(np.abs(ref), 1e-3 * np.abs(ref).max())[clean]
+            diag.setdefault("out_need", []).append((t, float((err - tol * den).max(initial=0) / (al / QUANTA)), float(clean.mean())))
+        else:
+            e = rel_err(got[clean], ref[clean], slack=al)
+            assert e <= tol, f"frame {t}: dense output off by {e:.2e} outside the ties' cone"
+        ties_per_frame.append(ties)
         if check_dense:
             dense = orc.dense_reference(spec, wts_s, fr.astype(np.float64))
-            scale = np.abs(dense).max()
-            err_o = np.abs(ref.astype(np.float64) - dense).max() / scale
-            err_g = np.abs(got.astype(np.float64) - dense).max() / scale
+            sc = np.abs(dense).max()
+            err_o = np.abs(ref.astype(np.float64) - dense).max() / sc
+            err_g = np.abs(got.astype(np.float64) - dense).max() / sc
             report.append((err_o, err_g))
             assert err_g <= 2.0 * err_o + 4 * tol, f"frame {t}: library drifts from dense inference ({err_g:.2e} vs oracle {err_o:.2e})"
-    return {"ties": ties, "diverged": diverged, "errs": report, "net": net, "ctx": ctx, "oracle": oracle}
+    first = next((t for t, n in enumerate(ties_per_frame) if n), None)
+    summary = {"ties": sum(ties_per_frame), "ties_per_frame": ties_per_frame, "first_tie_frame": first,
+               "replay_ties": replay_ties, "diverged": first is not None,
+               "compared_output_fraction": float((~cone[-1]).mean()),
+               "errs": report, "net": net, "ctx": ctx, "oracle": oracle}
+    print(f"[{spec['name']} {S} x{n_streams}] frames {vid.shape[0]}: free-running ties per frame {ties_per_frame} "
+          f"(first at frame {first}), output pixels still outside every cone {summary['compared_output_fraction']:.3f}; "
+          f"replayed frames {len(replay_ties)}, ties in replay {replay_ties}")
+    return summary
 
 
 def test_config1_single_conv_fp32_full_size():
     """BASELINE config 1: 3x3 conv + ReLU, 32 channels, 64x64, fp32, 4 frames, eps 0.05."""
     r = _run_net(wl.single_conv_relu(), wl.CONFIG_SEEDS[1], 1)
-    assert r["ties"] == 0
+    assert r["ties"] == 0 and sum(r["replay_ties"]) == 0
 
 
 @pytest.mark.parametrize("flags", [1, 3, 2])
 def test_config2_bottleneck_fp16_full_size(flags):
-    """BASELINE config 2 at its real size (128x128, 64->64->256, fp16), 6 of its 16 frames."""
-    r = _run_net(wl.bottleneck_block(eps=0.1), wl.CONFIG_SEEDS[2], 1, flags=flags, frames=6)
-    assert r["ties"] <= 20
+    """BASELINE config 2 at its real size (128x128, 64->64->256, fp16), all 16 frames of its clip."""
+    r = _run_net(wl.bottleneck_block(eps=0.1), wl.CONFIG_SEEDS[2], 1, flags=flags)
+    assert r["ties"] <= 20 and sum(r["replay_ties"]) <= 20, f"ties per frame {r['ties_per_frame']}, in replay {r['replay_ties']}"
 
 
 def test_config2_batched_streams():
@@ -249,7 +502,8 @@ def test_config2_bench_configuration_sampled_streams():
         assert not np.isnan(got.astype(np.float64)).any()
         for b in sampled:
             ref = oracles[b].frame(vid[t, b:b + 1])
-            assert rel_err(got[b:b + 1], ref) <= tol, f"frame {t} stream {b}: dense output vs oracle"
+            e = rel_err(got[b:b + 1], ref, slack=free_running_slack(spec, ref, S))
+            assert e <= tol, f"frame {t} stream {b}: dense output vs oracle ({e:.2e})"
         for b, sn in solo.items():
             (sn.init if t == 0 else sn.step)(frame[b:b + 1].contiguous(), solo_out)
             solo_ctx.sync()
@@ -284,10 +538,11 @@ def test_tensors_beyond_2gib_take_the_plain_kernels():
             sn = solo[b]
             (sn.init if t == 0 else sn.step)(frame[b:b + 1].contiguous(), solo_out)
             solo_ctx.sync()
-            # same numbers up to the rounding of the output layer: the stand-alone one (large batch) adds rounded
-            # deltas to O, the folded one (single stream) writes f(x^A); one fp16 ulp per update at most
-            e = rel_err(to_np(view.data[b]), to_np(solo_out[0]))
-            assert e <= 3e-3, f"frame {t} stream {b}: differs from the stream alone ({e:.2e})"
+            # two kernel families (plain / wave-specialised, stand-alone / folded output layer): the same numbers up to
+            # where each rounds its intermediates, i.e. two free-running implementations of the same network
+            want = to_np(solo_out[0])
+            e = rel_err(to_np(view.data[b]), want, slack=free_running_slack(spec, want, S))
+            assert e <= TOL[S], f"frame {t} stream {b}: differs from the stream alone ({e:.2e})"
 
 
 def test_density_budget_tuner_matches_the_oracle():
@@ -364,7 +619,7 @@ def test_free_running_without_touching_the_state(eps):
         (net.init if t == 0 else net.step)(torch.from_numpy(fr).cuda(), out)
         ctx.sync()
         ref = oracle.frame(fr)
-        assert rel_err(to_np(out), ref) <= 2 * tol, f"frame {t}"
+        assert rel_err(to_np(out), ref, slack=free_running_slack(spec, ref, "f16")) <= tol, f"frame {t}"
     checked = 0
     for li in range(net.num_layers):
         nid = net.layer_node(li)
@@ -374,14 +629,16 @@ def test_free_running_without_touching_the_state(eps):
             continue
         got = to_np(xa).astype(np.float64) + to_np(xt).astype(np.float64)
         want = ly.xA.astype(np.float64).reshape(-1) + ly.xT.astype(np.float64).reshape(-1)
-        assert rel_err(got, want, floor=0.1) <= 2 * tol, f"layer {li}"
+        depth = _depths(spec["nodes"])[nid]
+        assert rel_err(got, want, slack=QUANTA * depth ** 0.5 * float(ulp(float(np.abs(want).max()), "f16"))) <= tol, f"layer {li}"
         checked += 1
     assert checked >= 3
     # one more frame after the state was handed out (flags rebuilt from x^T)
     fr = vid[-2].astype(np.float16)
     net.step(torch.from_numpy(fr).cuda(), out)
     ctx.sync()
-    assert rel_err(to_np(out), oracle.frame(fr)) <= 2 * tol
+    ref = oracle.frame(fr)
+    assert rel_err(to_np(out), ref, slack=free_running_slack(spec, ref, "f16")) <= tol
 
 
 def test_frames_of_the_wrong_shape_are_refused_before_any_launch():

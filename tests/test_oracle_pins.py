@@ -240,6 +240,60 @@ def test_input_mask_dilation_is_a_square():
     assert out.sum() == 15 * 15 and out[0, 3, 3] == 1 and out[0, 2, 3] == 0
 
 
+def test_input_layer_with_dilation_updates_the_whole_square():
+    """Section 4 (high input threshold + dilated input mask): a single pixel that crosses the threshold flags
+    the (2r+1)^2 square around it, and the delta AND the stored input are updated on that whole square --
+    also at pixels whose own change is below the threshold -- and nowhere else.  By hand on a 9x9 map."""
+    r, eps = 2, 0.3
+    rng = np.random.default_rng(4)
+    f0 = rng.normal(0, 1, (1, 9, 9, 2))
+    small = rng.uniform(0.01, 0.05, (1, 9, 9, 2))            # every pixel changes a little (below the threshold)
+    f1 = f0 + small
+    f1[0, 4, 5, 1] += 1.0                                    # ... and one pixel a lot
+    layer = orc.DeltaGen(eps, r, "f64")
+    layer.init(f0)
+    out = layer.step(f1)
+    square = np.zeros((1, 9, 9), bool)
+    square[0, 2:7, 3:8] = True
+    assert np.array_equal(out.mask.astype(bool), square) and out.count == 25
+    assert np.array_equal(out.data[square], (f1 - f0)[square])           # delta on the whole square, own change only
+    assert np.all(np.abs(out.data[square]).max(axis=-1)[:12] < eps)      # most of it below the threshold by itself
+    assert np.array_equal(layer.P[square], f1[square])                   # stored input follows on the whole square
+    assert np.array_equal(layer.P[~square], f0[~square])                 # and is untouched elsewhere
+    # the change that was not propagated is not lost: it is still pending against the stored input
+    out2 = layer.step(f1)
+    assert out2.count == 0
+    f2 = f1.copy()
+    f2[0, 0, 0, 0] += 0.3 - small[0, 0, 0, 0] + 1e-9                     # frame-to-frame change below eps, total above
+    out3 = layer.step(f2)
+    assert out3.mask[0, 0, 0] == 1 and out3.data[0, 0, 0, 0] == f2[0, 0, 0, 0] - f0[0, 0, 0, 0]
+    # r = 0 flags the one pixel only
+    plain = orc.DeltaGen(eps, 0, "f64")
+    plain.init(f0)
+    assert plain.step(f1).count == 1
+
+
+def test_dilated_input_mask_with_dense_layers_behind_equals_dense_inference_of_the_stored_input():
+    """With every later threshold negative the network output is dense inference of the input layer's stored
+    frame P, whatever the input threshold and dilation (Eq. 1 + Eq. 3): an input layer that emitted deltas at
+    other pixels than it updated P at -- thresholded pixels only, say, instead of the dilated set -- breaks it."""
+    net = wl.tiny_mixed_net(eps=-1.0, eps0=0.4, frames=5)
+    net["nodes"][0]["dilate_r"] = 2
+    wts = wl.make_weights(net, 6)
+    vid = _video(net, 6)
+    onet = orc.OracleNet(net, wts, "f64")
+    saw_partial = False
+    for t in range(vid.shape[0]):
+        out = onet.frame(vid[t])
+        P = onet.layers[0].P
+        dense = orc.dense_reference(net, wts, P)
+        assert np.abs(out - dense).max() <= 1e-10 * max(1.0, np.abs(dense).max()), f"frame {t}"
+        if t:
+            m = onet.outs[0].mask
+            saw_partial |= 0 < m.sum() < m.size and not np.array_equal(P, vid[t])
+    assert saw_partial, "the input threshold must hold some pixels back for this pin to bite"
+
+
 # ---- P7: the paper's scalar example -----------------------------------------------------------
 def test_relu_scalar_example(golden):
     prev, dlt = float(golden["relu_prev"]), float(golden["relu_delta"])
