@@ -167,6 +167,20 @@ dcnn_status dcnn_mask_compact(dcnn_ctx* ctx, const uint8_t* mask_in_dev, int32_t
                               int32_t k, int32_t stride, int32_t pad, const uint8_t* mask_b_dev,
                               uint8_t* mask_out_dev, int32_t* idx_out_dev, int32_t* count_out_dev);
 
+/* The same operation for callers that cannot allocate device memory or provide a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The chunk counts (and, when
+ * mask_out_dev is NULL, the output mask) live in a static device array inside the library instead of the
+ * context's workspace: 8 KiB + 4 MiB per GPU, held until the process ends; its device address is resolved
+ * once per device by dcnn_ctx_create.  The context may have been created without a workspace.  Limit: at
+ * most 4 Mi (4 * 2^20) OUTPUT pixels n*oh*ow per call, beyond which DCNN_ENOMEM is returned and nothing is
+ * launched.  The call allocates and frees nothing and does not synchronise; every entry of the scratch that
+ * is read has been written by the same call, so nothing is cleared between calls.  All calls on one GPU
+ * share that GPU's array: calls that overlap on one GPU (different streams, different contexts) race.
+ * Arguments, results and error behaviour are otherwise those of dcnn_mask_compact. */
+dcnn_status dcnn_mask_compact_static(dcnn_ctx* ctx, const uint8_t* mask_in_dev, int32_t n, int32_t h, int32_t w,
+                                     int32_t k, int32_t stride, int32_t pad, const uint8_t* mask_b_dev,
+                                     uint8_t* mask_out_dev, int32_t* idx_out_dev, int32_t* count_out_dev);
+
 /* ---- layers -------------------------------------------------------------------------------- */
 dcnn_status dcnn_layer_query(const dcnn_layer_desc* desc, dcnn_layer_sizes* out);
 /* weights_dev: CONV [kh][kw][cin][cout], DWCONV [kh][kw][c]; bias_dev [cout] or NULL; with a fused

@@ -27,7 +27,7 @@ STATUS_NAMES = ["OK", "EINVAL", "ESHAPE", "EDTYPE", "ESTATE", "ENOMEM", "EHIP", 
 
 EXPORTS = [
     "dcnn_workspace_bytes", "dcnn_ctx_create", "dcnn_ctx_destroy", "dcnn_ctx_sync", "dcnn_status_str",
-    "dcnn_last_error", "dcnn_mask_compact", "dcnn_layer_query", "dcnn_layer_create", "dcnn_layer_destroy",
+    "dcnn_last_error", "dcnn_mask_compact", "dcnn_mask_compact_static", "dcnn_layer_query", "dcnn_layer_create", "dcnn_layer_destroy",
     "dcnn_layer_init", "dcnn_layer_step", "dcnn_layer_output", "dcnn_layer_reset", "dcnn_layer_state",
     "dcnn_layer_stats", "dcnn_layer_set_eps", "dcnn_layer_set_timing", "dcnn_layer_timing", "dcnn_net_create", "dcnn_net_destroy", "dcnn_net_add", "dcnn_net_finalize",
     "dcnn_net_bind", "dcnn_net_init", "dcnn_net_step", "dcnn_net_reset", "dcnn_net_output",
@@ -97,6 +97,7 @@ def load_library() -> C.CDLL:
     lib.dcnn_last_error.restype = C.c_char_p
     lib.dcnn_last_error.argtypes = [vp]
     lib.dcnn_mask_compact.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+    lib.dcnn_mask_compact_static.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.dcnn_layer_query.argtypes = [P(LayerDesc), P(LayerSizes)]
     lib.dcnn_layer_create.argtypes = [vp, P(LayerDesc), vp, vp, vp, sz, P(vp)]
     lib.dcnn_layer_destroy.argtypes = [vp]
@@ -150,15 +151,16 @@ class Context:
     """dcnn_ctx on torch's current stream, with a torch-allocated workspace."""
 
     def __init__(self, max_pixels: int, device="cuda"):
+        """max_pixels = 0 creates the context without a workspace (enough for mask_compact_static)."""
         self.lib = load_library()
         if not torch.cuda.is_available():
             raise RuntimeError("libdeltacnn needs an MI355X (gfx950); no GPU is visible and there is no CPU path")
         self.device = torch.device(device)
-        nbytes = self.lib.dcnn_workspace_bytes(int(max_pixels))
-        self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=self.device)
+        nbytes = self.lib.dcnn_workspace_bytes(int(max_pixels)) if max_pixels > 0 else 0
+        self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=self.device) if nbytes else None
         self.stream = torch.cuda.current_stream(self.device)
         h = C.c_void_p()
-        st = self.lib.dcnn_ctx_create(C.c_void_p(self.stream.cuda_stream), C.c_void_p(self.workspace.data_ptr()),
+        st = self.lib.dcnn_ctx_create(C.c_void_p(self.stream.cuda_stream), C.c_void_p(_ptr(self.workspace)),
                                       nbytes, C.byref(h))
         if st != 0:
             raise DcnnError(st, self.lib.dcnn_status_str(st).decode())
@@ -204,6 +206,13 @@ class Context:
         self.check(self.lib.dcnn_mask_compact(self.handle, _ptr(mask_in), n, h, w, k, stride, pad, _ptr(mask_b),
                                               _ptr(mask_out), _ptr(idx), _ptr(count)))
         return mask_out, idx, count
+
+    def mask_compact_static(self, mask_in, mask_out, idx, count, k=1, stride=1, pad=0, mask_b=None):
+        """dcnn_mask_compact_static: the caller passes every output buffer (mask_out may be None); the call
+        itself allocates nothing."""
+        n, h, w = mask_in.shape
+        self.check(self.lib.dcnn_mask_compact_static(self.handle, _ptr(mask_in), n, h, w, k, stride, pad, _ptr(mask_b),
+                                                     _ptr(mask_out), _ptr(idx), _ptr(count)))
 
     def __del__(self):
         try:

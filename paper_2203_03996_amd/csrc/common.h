@@ -39,6 +39,7 @@ inline FastDiv make_fastdiv(uint32_t d) {
 
 struct dcnn_ctx {
     hipStream_t stream;
+    int device;              // HIP device that was current when the context was created
     char* ws;
     size_t ws_bytes;
     int num_cu;
@@ -80,6 +81,9 @@ struct MaskPassArgs {
     int kw, pad_w;               // kw > 0: the window is k rows x kw columns with padding pad / pad_w (stride 1)
 };
 dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& a);
+// Resolves the device address of the library's static scratch array for HIP device `dev`, which must be the
+// current device (set-up step of dcnn_mask_compact_static; called by dcnn_ctx_create).
+hipError_t static_scratch_setup(int dev);
 
 // Ordered compaction of the entries of a work list that survived (bit set in surv).
 dcnn_status launch_emit_sublist(dcnn_ctx* ctx, const int32_t* list, const int32_t* count, int64_t max_count,

@@ -60,9 +60,12 @@ dcnn_status dcnn_ctx_create(void* hip_stream, void* workspace_dev, size_t worksp
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return DCNN_EHIP;
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return DCNN_EUNSUPPORTED;   // kernels are built for CDNA4 only
     if (prop.sharedMemPerBlock < 160 * 1024) return DCNN_EUNSUPPORTED;           // the conv plans assume 160 KB of LDS
+    // set-up of the entry point that allocates nothing: the address of this device's copy of the static scratch array
+    if (static_scratch_setup(dev) != hipSuccess) return DCNN_EHIP;
     dcnn_ctx* c = new (std::nothrow) dcnn_ctx();
     if (!c) return DCNN_ENOMEM;
     c->stream = static_cast<hipStream_t>(hip_stream);
+    c->device = dev;
     c->ws = static_cast<char*>(workspace_dev);
     c->ws_bytes = workspace_bytes;
     c->num_cu = prop.multiProcessorCount;
@@ -94,23 +97,5 @@ const char* dcnn_status_str(dcnn_status s) {
 }
 
 const char* dcnn_last_error(const dcnn_ctx* ctx) { return ctx ? ctx->err : "no context"; }
-
-dcnn_status dcnn_mask_compact(dcnn_ctx* ctx, const uint8_t* mask_in_dev, int32_t n, int32_t h, int32_t w, int32_t k,
-                              int32_t stride, int32_t pad, const uint8_t* mask_b_dev, uint8_t* mask_out_dev,
-                              int32_t* idx_out_dev, int32_t* count_out_dev) {
-    if (!ctx) return DCNN_EINVAL;
-    if (!mask_in_dev || !idx_out_dev || !count_out_dev) return fail(ctx, DCNN_EINVAL, "mask_compact: null pointer");
-    if (n < 1 || h < 1 || w < 1 || k < 1 || k > 15 || stride < 1 || pad < 0 || pad >= k)
-        return fail(ctx, DCNN_EINVAL, "mask_compact: bad geometry n=%d h=%d w=%d k=%d stride=%d pad=%d", n, h, w, k, stride, pad);
-    if (h + 2 * pad < k || w + 2 * pad < k) return fail(ctx, DCNN_ESHAPE, "mask_compact: window larger than the map");
-    MaskPassArgs m{};
-    m.mask_in = mask_in_dev; m.mask_b = mask_b_dev; m.mask_out = mask_out_dev;
-    m.idx_out = idx_out_dev; m.count_out = count_out_dev;
-    m.n = n; m.h = h; m.w = w;
-    m.oh = (h + 2 * pad - k) / stride + 1;
-    m.ow = (w + 2 * pad - k) / stride + 1;
-    m.k = k; m.stride = stride; m.pad = pad; m.up = 1; m.emit_only = 0;
-    return launch_mask_compact(ctx, m);
-}
 
 }  // extern "C"

@@ -464,12 +464,12 @@ __global__ __launch_bounds__(kMaskThreads) void mask_emit_kernel(MaskKernelArgs 
     if (total != 0) emit_entries(e, p0, word, prefix + loc, er);
 }
 
-dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
+// The pass on explicit scratch memory: ws.chunk_counts (one int per chunk; every entry the list emission reads
+// has been written by the mask pass of the same call, nothing has to start at zero) and ws.scratch_mask (the
+// output mask when the caller does not want one).
+static dcnn_status mask_compact_on(dcnn_ctx* ctx, const MaskPassArgs& m, const Workspace& ws) {
     const int64_t out_pixels = (int64_t)m.n * m.oh * m.ow;
-    if (out_pixels <= 0 || out_pixels > INT32_MAX) return fail(ctx, DCNN_ESHAPE, "mask pass: bad pixel count");
-    Workspace ws;
-    dcnn_status st = workspace_view(ctx, out_pixels, &ws);
-    if (st != DCNN_OK) return st;
+    dcnn_status st = DCNN_OK;
     const int nchunks = (int)cdiv(out_pixels, kChunk);
     const uint8_t* emit_mask = m.mask_in;
     // one launch for small maps; large maps keep the two passes
@@ -505,6 +505,40 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
     }
     hipLaunchKernelGGL(emit_kernel, dim3(nchunks), dim3(kMaskThreads), 0, ctx->stream, e);
     return check_hip(ctx, hipGetLastError(), "emit_kernel launch");
+}
+
+dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
+    const int64_t out_pixels = (int64_t)m.n * m.oh * m.ow;
+    if (out_pixels <= 0 || out_pixels > INT32_MAX) return fail(ctx, DCNN_ESHAPE, "mask pass: bad pixel count");
+    Workspace ws;
+    dcnn_status st = workspace_view(ctx, out_pixels, &ws);
+    if (st != DCNN_OK) return st;
+    return mask_compact_on(ctx, m, ws);
+}
+
+// ---- library-owned scratch for the entry point that allocates nothing ------------------------------
+// One array per GPU the library runs on, held until the process ends: the chunk counts of the largest
+// accepted map, followed by a mask for callers that only want the list.
+constexpr int64_t kStaticMaxPixels = 4ll << 20;                               // 4 Mi output pixels per call
+constexpr size_t kStaticCountBytes = (size_t)(kStaticMaxPixels / kChunk) * sizeof(int32_t);   // 8 KiB
+constexpr size_t kStaticScratchBytes = kStaticCountBytes + (size_t)kStaticMaxPixels;          // + 4 MiB of mask
+static_assert(kStaticCountBytes % kAlign == 0, "the mask part starts aligned");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of each GPU's copy of `scratch` (the array's name is only a host-side handle for
+// hipGetSymbolAddress; kernels and copies get the resolved pointer).
+constexpr int kMaxDevices = 64;
+static unsigned char* g_scratch_ptr[kMaxDevices];
+
+hipError_t static_scratch_setup(int dev) {
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (g_scratch_ptr[dev]) return hipSuccess;
+    void* p = nullptr;
+    const hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));       // resolves for the CURRENT device
+    if (err != hipSuccess) return err;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    return hipSuccess;
 }
 
 // ---- list-space compaction ---------------------------------------------------------------------
@@ -547,3 +581,62 @@ dcnn_status launch_emit_sublist(dcnn_ctx* ctx, const int32_t* list, const int32_
 }
 
 }  // namespace dcnn
+
+using namespace dcnn;
+
+static dcnn_status mask_compact_args(dcnn_ctx* ctx, const char* who, const uint8_t* mask_in_dev, int32_t n, int32_t h, int32_t w,
+                                     int32_t k, int32_t stride, int32_t pad, const uint8_t* mask_b_dev, uint8_t* mask_out_dev,
+                                     int32_t* idx_out_dev, int32_t* count_out_dev, MaskPassArgs* out) {
+    if (!mask_in_dev || !idx_out_dev || !count_out_dev) return fail(ctx, DCNN_EINVAL, "%s: null pointer", who);
+    if (n < 1 || h < 1 || w < 1 || k < 1 || k > 15 || stride < 1 || pad < 0 || pad >= k)
+        return fail(ctx, DCNN_EINVAL, "%s: bad geometry n=%d h=%d w=%d k=%d stride=%d pad=%d", who, n, h, w, k, stride, pad);
+    if (h + 2 * pad < k || w + 2 * pad < k) return fail(ctx, DCNN_ESHAPE, "%s: window larger than the map", who);
+    MaskPassArgs m{};
+    m.mask_in = mask_in_dev; m.mask_b = mask_b_dev; m.mask_out = mask_out_dev;
+    m.idx_out = idx_out_dev; m.count_out = count_out_dev;
+    m.n = n; m.h = h; m.w = w;
+    m.oh = (h + 2 * pad - k) / stride + 1;
+    m.ow = (w + 2 * pad - k) / stride + 1;
+    m.k = k; m.stride = stride; m.pad = pad; m.up = 1; m.emit_only = 0;
+    *out = m;
+    return DCNN_OK;
+}
+
+extern "C" {
+
+dcnn_status dcnn_mask_compact(dcnn_ctx* ctx, const uint8_t* mask_in_dev, int32_t n, int32_t h, int32_t w, int32_t k,
+                              int32_t stride, int32_t pad, const uint8_t* mask_b_dev, uint8_t* mask_out_dev,
+                              int32_t* idx_out_dev, int32_t* count_out_dev) {
+    if (!ctx) return DCNN_EINVAL;
+    MaskPassArgs m;
+    dcnn_status st = mask_compact_args(ctx, "mask_compact", mask_in_dev, n, h, w, k, stride, pad, mask_b_dev, mask_out_dev,
+                                       idx_out_dev, count_out_dev, &m);
+    if (st != DCNN_OK) return st;
+    return launch_mask_compact(ctx, m);
+}
+
+dcnn_status dcnn_mask_compact_static(dcnn_ctx* ctx, const uint8_t* mask_in_dev, int32_t n, int32_t h, int32_t w, int32_t k,
+                                     int32_t stride, int32_t pad, const uint8_t* mask_b_dev, uint8_t* mask_out_dev,
+                                     int32_t* idx_out_dev, int32_t* count_out_dev) {
+    if (!ctx) return DCNN_EINVAL;
+    MaskPassArgs m;
+    dcnn_status st = mask_compact_args(ctx, "mask_compact_static", mask_in_dev, n, h, w, k, stride, pad, mask_b_dev,
+                                       mask_out_dev, idx_out_dev, count_out_dev, &m);
+    if (st != DCNN_OK) return st;
+    const int64_t out_pixels = (int64_t)m.n * m.oh * m.ow;
+    if (out_pixels > kStaticMaxPixels)
+        return fail(ctx, DCNN_ENOMEM, "mask_compact_static: %lld output pixels exceed the static scratch of %lld pixels; "
+                    "use dcnn_mask_compact with a workspace", (long long)out_pixels, (long long)kStaticMaxPixels);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device)
+        return fail(ctx, DCNN_ESTATE, "mask_compact_static: the context's device %d is not the current device", ctx->device);
+    unsigned char* base = g_scratch_ptr[dev];          // resolved by dcnn_ctx_create on this device
+    if (!base) return fail(ctx, DCNN_ESTATE, "mask_compact_static: the static scratch was not set up on device %d", dev);
+    Workspace ws{};
+    ws.chunk_counts = reinterpret_cast<int32_t*>(base);
+    ws.scratch_mask = base + kStaticCountBytes;
+    ws.max_pixels = kStaticMaxPixels;
+    return mask_compact_on(ctx, m, ws);
+}
+
+}  // extern "C"
