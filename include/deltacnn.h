@@ -115,6 +115,13 @@ typedef struct {
      * left out to save memory): a truncated update is dropped, an update is x^A <- x^A + dx.  Small changes
      * below the threshold are then lost instead of accumulated (Eq. 6 does not hold). */
     int32_t no_xT;
+    /* 1: on an update the layer keeps in x^T what the stored x^A lost to rounding, x^T <- s - round(s), instead
+     * of 0 (s = x^A + x^T + dx in fp32; Eq. 6 then holds to the precision of the arithmetic rather than of the
+     * storage type, which removes the slow error growth of long runs in fp16 -- supplementary Section 1.4).
+     * The emitted delta and the threshold test are unchanged.  Layers with an activation and an x^T buffer
+     * only; with fp32 storage the residue is zero and the option changes nothing.  x^T rows are then read and
+     * written at every visited pixel. */
+    int32_t xT_residue;
 } dcnn_layer_desc;
 
 typedef struct {

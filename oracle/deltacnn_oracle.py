@@ -215,10 +215,19 @@ class ActTrunc:
     """Activation fused with truncation (Section 3.1, Eqs. 4-6; Fig. 3).
 
     use_xT=False gives the variant without the truncated-values buffer
-    (Section 6, memory remark): truncated input is simply dropped."""
+    (Section 6, memory remark): truncated input is simply dropped.
 
-    def __init__(self, f: str, eps: float, S: str = "f32", use_xT: bool = True):
-        self.f, self.eps, self.S, self.use_xT = f, eps, S, use_xT
+    carry=True is an option beyond the paper for reduced-precision storage (supplementary
+    Section 1.4 accepts that floating-point error accumulates in the buffers and resets them
+    periodically): on an update x^A <- round_S(s) loses s - round_S(s); instead of x^T <- 0 the
+    layer keeps that rounding residue, x^T <- round_S(s - x^A), so that x^A + x^T still equals
+    everything received (Eq. 6) to the precision of the arithmetic, not of the storage type.
+    The emitted delta and the threshold test are unchanged.  With S = f64 the residue is 0."""
+
+    def __init__(self, f: str, eps: float, S: str = "f32", use_xT: bool = True, carry: bool = False):
+        self.f, self.eps, self.S, self.use_xT, self.carry = f, eps, S, use_xT, bool(carry)
+        if self.carry and not self.use_xT:
+            raise ValueError("the rounding residue lives in x^T")
         self.xA = self.xT = self.last_u = None
 
     def init(self, x: np.ndarray) -> np.ndarray:
@@ -244,7 +253,8 @@ class ActTrunc:
             upd = u >= mt(self.eps)
             new_xa = np.where(upd[:, None], s.astype(st), self.xA[sel])
             if self.use_xT:
-                new_xt = np.where(upd[:, None], st(0), (xt + dx).astype(st))
+                kept = (s - s.astype(st).astype(mt)).astype(st) if self.carry else st(0)
+                new_xt = np.where(upd[:, None], kept, (xt + dx).astype(st))
             else:
                 new_xt = np.zeros_like(new_xa)
             self.xA[sel] = new_xa
@@ -434,7 +444,7 @@ def build_layers(net: dict, weights: dict, S: str, use_xT: bool = True):
             wgt, bias = weights[i]
             layers.append(Conv(wgt, bias, nd["stride"], nd["pad"], nd["depthwise"], S))
         elif k == "act":
-            layers.append(ActTrunc(nd["f"], nd["eps"], S, use_xT and not nd.get("no_xT", False)))
+            layers.append(ActTrunc(nd["f"], nd["eps"], S, use_xT and not nd.get("no_xT", False), nd.get("xT_residue", False)))
         elif k == "add":
             layers.append(Add(S))
         elif k == "concat":

@@ -46,7 +46,7 @@ class LayerDesc(C.Structure):
                 ("cout", C.c_int32), ("act", C.c_int32), ("eps", C.c_float), ("n_in", C.c_int32),
                 ("dilate_r", C.c_int32), ("factor", C.c_int32), ("want_idx", C.c_int32),
                 ("proj_c", C.c_int32), ("proj_h", C.c_int32), ("proj_w", C.c_int32), ("proj_stride", C.c_int32),
-                ("fuse_accum", C.c_int32), ("no_xT", C.c_int32)]
+                ("fuse_accum", C.c_int32), ("no_xT", C.c_int32), ("xT_residue", C.c_int32)]
 
 
 class LayerSizes(C.Structure):
@@ -224,11 +224,11 @@ class Context:
 
 
 def make_desc(kind, dtype, n, h, w, c, k=1, stride=1, pad=0, cout=0, act=ACT_NONE, eps=0.0, n_in=1, dilate_r=0,
-              factor=1, want_idx=1, proj=None, fuse_accum=0, no_xT=0) -> LayerDesc:
+              factor=1, want_idx=1, proj=None, fuse_accum=0, no_xT=0, xT_residue=0) -> LayerDesc:
     """proj = (channels, height, width, stride) of the input of a fused 1x1 projection shortcut, or None."""
     pc, ph, pw, ps = proj if proj is not None else (0, 0, 0, 0)
     return LayerDesc(kind, dtype, n, h, w, c, k, k, stride, pad, cout, act, float(eps), n_in, dilate_r, factor,
-                     want_idx, pc, ph, pw, ps, fuse_accum, int(no_xT))
+                     want_idx, pc, ph, pw, ps, fuse_accum, int(no_xT), int(xT_residue))
 
 
 class Layer:
@@ -349,7 +349,7 @@ class Net:
                 desc = make_desc(DELTAGEN, self.dtype, 0, 0, 0, 0, eps=nd["eps"], dilate_r=nd.get("dilate_r", 0))
             elif kind == "act":
                 desc = make_desc(ACT, self.dtype, 0, 0, 0, 0, act=ACT_CODES[nd["f"]], eps=nd["eps"], n_in=1,
-                                 no_xT=1 if nd.get("no_xT") else 0)
+                                 no_xT=1 if nd.get("no_xT") else 0, xT_residue=1 if nd.get("xT_residue") else 0)
             elif kind == "add":
                 desc = make_desc(ACT, self.dtype, 0, 0, 0, 0, act=ACT_NONE, n_in=2)
             elif kind == "concat":

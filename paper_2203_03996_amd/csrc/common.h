@@ -111,6 +111,7 @@ struct EpilogueArgs {
                                  // not read; 1 = it may hold values.  Kept up to date by the wave-specialised kernel only.
     void* accum_O;               // fused final accumulation: dense output O (output shape); the emitted delta is
                                  // added to it and not stored (sparse steps of layers with an activation only)
+    int carry;                   // 1: an update leaves the rounding residue of x^A in x^T (s - round(s)) instead of 0
 };
 
 struct ListArgs {

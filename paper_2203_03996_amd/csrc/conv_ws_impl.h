@@ -406,6 +406,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         const bool has_tflag = e.xt_flags != nullptr;
         const bool has_omask = e.out_mask != nullptr;
         const float hi = act_hi(e.act);
+        const bool carry = e.carry != 0;
         // this lane's 16 bytes in row 0 of the producer slice that holds its channels (lanes without
         // channels read slot 0 and discard it; their stores go nowhere)
         const unsigned char* my_stage = stage0 + (size_t)(slot * cs + spart) * stage_tile + (size_t)(ch_on ? vi : 0) * V * ES;
@@ -477,7 +478,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     // is f of the new x^A, so O is written without being read, and without the rounding an accumulation
                     // in the storage type would add frame after frame.  f(s) rounded to the storage type IS f of the
                     // rounded s: rounding is monotone and keeps 0 and the upper bound, which are representable.
-                    Raw o_a, o_t, o_y;
+                    Raw o_a, o_t, o_y, o_r = raw_zero<T, V>();
                     float u = 0.0f;
 #pragma unroll
                     for (int i = 0; i < V; ++i) {
@@ -490,16 +491,18 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                         raw_set<T, V>(o_a, i, sum);
                         raw_set<T, V>(o_t, i, tt + dd);             // x^T if the pixel is truncated
                         raw_set<T, V>(o_y, i, ACC ? fs : dy);
+                        if (carry) raw_set<T, V>(o_r, i, round_residue<T>(sum));   // x^T if it is updated and keeps the residue
                     }
                     u = group_max(u, LP);
                     upd = u >= e.eps;
                     const uint32_t o_upd = upd ? o : kOob;
                     state_store(rs_xA, o_upd, o_a);
-                    // an update resets x^T to zero: where this lane's x^T already is all zero bits nothing needs to be
-                    // written (most pixels that update every frame never accumulate anything)
+                    // an update resets x^T to zero (or to the rounding residue of the new x^A): where this lane's x^T
+                    // already is all zero bits and stays so nothing needs to be written (most pixels that update every
+                    // frame never accumulate anything)
                     {
-                        const uint32_t o_t_off = (upd && all_bits_zero(st.rt[h])) ? kOob : o;
-                        if (__builtin_amdgcn_ballot_w64(o_t_off != kOob)) state_store(rs_xT, o_t_off, upd ? raw_zero<T, V>() : o_t);
+                        const uint32_t o_t_off = (upd && all_bits_zero(st.rt[h]) && all_bits_zero(o_r)) ? kOob : o;
+                        if (__builtin_amdgcn_ballot_w64(o_t_off != kOob)) state_store(rs_xT, o_t_off, upd ? o_r : o_t);
                     }
                     if constexpr (ACC) state_store(rs_res, o_upd, o_y);
                     else ws_store16<Raw>(rs_out, o_upd, o_y);
@@ -514,8 +517,8 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 if (has_omask && __builtin_amdgcn_ballot_w64(clear))
                     __builtin_amdgcn_raw_buffer_store_b8((uint8_t)0, rs_omask, clear ? t.pix[it] : (int)kOob, 0, 0);
                 if constexpr (decltype(sf)::value) {
-                    // after an update the row is zero again; after a truncation it holds values
-                    const uint8_t keep = upd ? 0 : 1;
+                    // after an update the row is zero again (unless it keeps residues); after a truncation it holds values
+                    const uint8_t keep = (upd && !carry) ? 0 : 1;
                     const bool change = lead && keep != t.tflag[it];
                     if (has_tflag && __builtin_amdgcn_ballot_w64(change))
                         __builtin_amdgcn_raw_buffer_store_b8(keep, rs_tflag, change ? t.pix[it] : (int)kOob, 0, 0);

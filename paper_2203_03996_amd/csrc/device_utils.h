@@ -50,6 +50,8 @@ template <typename T, int V> __device__ __forceinline__ void store_vec(T* p, con
 
 // Value as it will read back after a store in the storage type.
 template <typename T> __device__ __forceinline__ float round_store(float x) { return (float)(T)x; }
+// What the stored value loses: exact in fp32 (the difference of an fp32 number and its rounding to fewer bits).
+template <typename T> __device__ __forceinline__ float round_residue(float x) { return x - (float)(T)x; }
 
 // ReLU and ReLU6 as one clamp to [0, hi] (hi = +inf / 6): a single median-of-three instruction,
 // exact for every finite x.  Callers compute hi once from the layer's activation.
@@ -302,7 +304,20 @@ __device__ __forceinline__ uint32_t act_trunc_tile(const EpilogueArgs& e, bool i
                     raw_store<T, V>(out + off, o_y[ub][v]);
                 } else if (upd) {
                     raw_store<T, V>(xA + off, o_a[ub][v]);
-                    if (xT) raw_store<T, V>(xT + off, raw_zero<T, V>());
+                    if (xT) {
+                        Raw keep = raw_zero<T, V>();
+                        if (e.carry && !init) {
+                            // the rounding residue of the new x^A, from the same operands in the same order
+#pragma unroll
+                            for (int i = 0; i < V; ++i) {
+                                float d = raw_get<T, V>(rd[ub][v], i);
+                                if (res) d = round_store<T>(d + raw_get<T, V>(rr[ub][v], i));
+                                const float s = (raw_get<T, V>(ra[ub][v], i) + raw_get<T, V>(rt[ub][v], i)) + d;
+                                raw_set<T, V>(keep, i, round_residue<T>(s));
+                            }
+                        }
+                        raw_store<T, V>(xT + off, keep);
+                    }
                     raw_store<T, V>(out + off, o_y[ub][v]);
                 } else if (xT) {
                     raw_store<T, V>(xT + off, o_t[ub][v]);
@@ -376,15 +391,17 @@ __device__ __forceinline__ uint32_t tail_finish(const EpilogueArgs& e, bool init
     T* out = static_cast<T*>(e.out_data);
     const bool stateful = e.act != DCNN_ACT_NONE;
     const float hi = act_hi(e.act);
-    Raw o_a[NIT], o_t[NIT], o_y[NIT];
+    Raw o_a[NIT], o_t[NIT], o_y[NIT], o_r[NIT];
     float umax[NIT];
     uint32_t bits = 0;
+    const bool carry = e.carry && !init;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         const int ent = it * PPI + grp;
         const bool on = r.pix[it] >= 0 && sub < nvec;
         Raw rd = raw_zero<T, V>();
         if (on) rd = dx(ent, (int64_t)r.pix[it], ch0 + sub * V);
+        o_r[it] = raw_zero<T, V>();
         float u = 0.0f;
 #pragma unroll
         for (int i = 0; i < V; ++i) {
@@ -404,6 +421,7 @@ __device__ __forceinline__ uint32_t tail_finish(const EpilogueArgs& e, bool init
                     raw_set<T, V>(o_a[it], i, s);
                     raw_set<T, V>(o_t[it], i, t + d);
                     raw_set<T, V>(o_y[it], i, dy);
+                    if (carry) raw_set<T, V>(o_r[it], i, round_residue<T>(s));   // x^T of an updated pixel
                 } else {
                     raw_set<T, V>(o_a[it], i, 0.0f);
                     raw_set<T, V>(o_t[it], i, 0.0f);
@@ -440,7 +458,7 @@ __device__ __forceinline__ uint32_t tail_finish(const EpilogueArgs& e, bool init
                 raw_store<T, V>(out + off, o_y[it]);
             } else if (upd) {
                 raw_store<T, V>(xA + off, o_a[it]);
-                if (xT) raw_store<T, V>(xT + off, raw_zero<T, V>());
+                if (xT) raw_store<T, V>(xT + off, o_r[it]);
                 raw_store<T, V>(out + off, o_y[it]);
             } else if (xT) {
                 raw_store<T, V>(xT + off, o_t[it]);

@@ -91,6 +91,8 @@ static dcnn_status validate_desc(const dcnn_layer_desc& d) {
     if (d.fuse_accum != 0 && d.fuse_accum != 1) return DCNN_EINVAL;
     if (d.no_xT != 0 && d.no_xT != 1) return DCNN_EINVAL;
     if (d.no_xT && (d.act == DCNN_ACT_NONE || d.kind == DCNN_DELTAGEN)) return DCNN_EINVAL;
+    if (d.xT_residue != 0 && d.xT_residue != 1) return DCNN_EINVAL;
+    if (d.xT_residue && (d.act == DCNN_ACT_NONE || d.kind == DCNN_DELTAGEN || d.no_xT)) return DCNN_EINVAL;
     if (d.fuse_accum && (d.kind != DCNN_CONV || d.act == DCNN_ACT_NONE || (d.n_in == 2 && !has_proj(d)))) return DCNN_EINVAL;
     return DCNN_OK;
 }
@@ -596,6 +598,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             }
             e.xA = L->buf0; e.xT = L->buf1; e.out_data = L->out_data;
             e.accum_O = d.fuse_accum ? L->buf2 : nullptr;
+            e.carry = d.xT_residue;
             if (L->xt_flags) {
                 if (L->xt_flags_stale) {                          // the caller may have written x^T: look at it once
                     st = launch_row_flags(ctx, d.dtype, L->buf1, L->xt_flags, L->out_pixels, L->oc);
@@ -616,6 +619,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             e.c = L->oc; e.act = d.act; e.eps = d.eps;
             e.res_data = n_in == 2 ? in[1]->data : nullptr; e.res_mask = n_in == 2 ? in[1]->mask : nullptr;
             e.xA = L->buf0; e.xT = L->buf1; e.out_data = L->out_data;
+            e.carry = d.xT_residue;
             e.out_mask = act ? L->out_mask : nullptr;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;
             e.out_count = (act && !d.want_idx) ? L->out_count : nullptr;

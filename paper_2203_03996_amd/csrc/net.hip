@@ -164,6 +164,7 @@ dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t fuse, size_t* arena_bytes) 
                 d.act = net->nodes[k].d.act;
                 d.eps = net->nodes[k].d.eps;
                 d.no_xT = net->nodes[k].d.no_xT;
+                d.xT_residue = net->nodes[k].d.xT_residue;
                 taken.push_back(k);
                 cur = k;
             }
@@ -189,6 +190,7 @@ dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t fuse, size_t* arena_bytes) 
                 p.d.act = net->nodes[k].d.act;
                 p.d.eps = net->nodes[k].d.eps;
                 p.d.no_xT = net->nodes[k].d.no_xT;
+                p.d.xT_residue = net->nodes[k].d.xT_residue;
                 p.out_node = k;
                 absorbed[k] = 1;
             }

@@ -74,11 +74,12 @@ __device__ __forceinline__ uint32_t sparse_tile_tail(const EpilogueArgs& e, cons
         // ---- phase 2: arithmetic, per-pixel maximum, decision, stores -----------------------------
 #pragma unroll
         for (int ub = 0; ub < UB; ++ub) {
-            Raw o_a[VPL], o_t[VPL], o_y[VPL];
+            Raw o_a[VPL], o_t[VPL], o_y[VPL], o_r[VPL];
             float u = 0.0f;
 #pragma unroll
             for (int v = 0; v < VPL; ++v) {
                 const Raw d0 = src.finish(ub, v, (sub + v * LP) * V);
+                o_r[v] = raw_zero<T, V>();
 #pragma unroll
                 for (int i = 0; i < V; ++i) {
                     float d = raw_get<T, V>(d0, i);
@@ -91,6 +92,7 @@ __device__ __forceinline__ uint32_t sparse_tile_tail(const EpilogueArgs& e, cons
                         raw_set<T, V>(o_a[v], i, sum);
                         raw_set<T, V>(o_t[v], i, t + d);                       // x^T if the pixel is truncated
                         raw_set<T, V>(o_y[v], i, dy);
+                        if (e.carry) raw_set<T, V>(o_r[v], i, round_residue<T>(sum));   // x^T if it is updated and keeps the residue
                     } else {
                         raw_set<T, V>(o_y[v], i, d);
                     }
@@ -107,8 +109,8 @@ __device__ __forceinline__ uint32_t sparse_tile_tail(const EpilogueArgs& e, cons
                 if (stateful) {
                     const uint32_t o_upd = upd ? o : kOob;
                     ws_store16_nt<Raw>(rs.xA, o_upd, o_a[v]);
-                    // (an x^T that already is all zero bits is not rewritten on an update)
-                    ws_store16_nt<Raw>(rs.xT, (upd && all_bits_zero(rt[ub][v])) ? kOob : o, upd ? raw_zero<T, V>() : o_t[v]);
+                    // (an x^T that already is all zero bits is not rewritten by an update that leaves zeros)
+                    ws_store16_nt<Raw>(rs.xT, (upd && all_bits_zero(rt[ub][v]) && all_bits_zero(o_r[v])) ? kOob : o, upd ? o_r[v] : o_t[v]);
                     ws_store16<Raw>(rs.out, o_upd, o_y[v]);
                 } else {
                     ws_store16<Raw>(rs.out, o, o_y[v]);

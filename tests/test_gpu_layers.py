@@ -88,16 +88,17 @@ def test_deltagen(S, shape, r):
 
 # ---- activation + truncation (bit-exact) ---------------------------------------------------------
 @pytest.mark.parametrize("S", ["f32", "f16"])
-@pytest.mark.parametrize("f", ["relu", "relu6"])
+@pytest.mark.parametrize("f,carry", [("relu", False), ("relu6", False), ("relu", True)])
 @pytest.mark.parametrize("shape", [(1, 64, 64, 32), (2, 33, 29, 64), (1, 24, 24, 256), (1, 12, 12, 960),
                                    (1, 10, 10, 2048), (1, 9, 11, 3), (1, 9, 11, 17), (1, 8, 8, 100)])
-def test_act_trunc(S, f, shape):
+def test_act_trunc(S, f, carry, shape):
+    """carry: the variant that leaves the rounding residue of x^A in x^T on an update (bit-exact like the rest)."""
     rng = np.random.default_rng(sum(shape) + len(f))
     n, h, w, c = shape
     eps = 0.35
-    ref = orc.ActTrunc(f, eps, S)
+    ref = orc.ActTrunc(f, eps, S, carry=carry)
     ctx = pkg.Context(n * h * w)
-    layer = pkg.Layer(ctx, pkg.make_desc(pkg.ACT, DT[S], n, h, w, c, act=pkg.ACT_CODES[f], eps=eps))
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.ACT, DT[S], n, h, w, c, act=pkg.ACT_CODES[f], eps=eps, xT_residue=int(carry)))
     x0 = rng.normal(0, 2, shape).astype(NP_DTYPE[S])
     r0 = ref.init(x0)
     g0 = layer.init([torch.from_numpy(x0).cuda()])
@@ -118,6 +119,8 @@ def test_act_trunc(S, f, shape):
         if want.count < d.count:
             saw.add("trunc")
     assert "upd" in saw and ("trunc" in saw or c > 64)     # wide pixels always exceed the threshold
+    if carry and S == "f16":
+        assert np.any(ref.xT[want.mask == 1] != 0) if want.count else True
 
 
 @pytest.mark.parametrize("S", ["f32", "f16"])

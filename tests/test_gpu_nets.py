@@ -137,7 +137,7 @@ def _replay_layers(net, spec, oracle, layer_of, pre, S, t):
                 # the sum of two stored streams is one exact fp32 addition and one rounding on both sides
                 slk[j] = (sa + sb + ulp(vals[j].data, S)) if (np.any(sa) or np.any(sb)) else 0.0
             elif k == "act":
-                act_ly = orc.ActTrunc(ly.f, ly.eps, S, ly.use_xT)
+                act_ly = orc.ActTrunc(ly.f, ly.eps, S, ly.use_xT, ly.carry)
                 act_ly.xA = xa0.reshape(ins[0].data.shape).copy()
                 act_ly.xT = np.zeros_like(act_ly.xA) if xt0 is None else xt0.reshape(ins[0].data.shape).copy()
                 vals[j] = act_ly.step(ins[0]).poisoned()
@@ -197,7 +197,14 @@ def _replay_layers(net, spec, oracle, layer_of, pre, S, t):
             ag = agree if isinstance(act_ly, orc.ActTrunc) else np.ones(shape[:3], bool)
             e = rel_err(xa1.reshape(shape)[ag], act_ly.xA[ag], slack=sl_state[ag])
             assert e <= (0.0 if exact else tol), f"{what}: x^A off by {e:.2e}; {worst(xa1.reshape(shape)[ag], act_ly.xA[ag], slack=sl_state[ag])}"
-            if xt1 is not None:
+            if xt1 is not None and getattr(act_ly, "carry", False) and not exact:
+                # a kept residue s - round(s) flips with the last bit of s; what both sides must agree on is
+                # x^A + x^T, i.e. s itself (and x^A, above) -- to within what s may differ by, not a relative term
+                got_s = xa1.reshape(shape).astype(np.float64) + xt1.reshape(shape).astype(np.float64)
+                ref_s = act_ly.xA.astype(np.float64) + act_ly.xT.astype(np.float64)
+                over = np.abs(got_s - ref_s)[ag] - (sl_state + 2 * ulp(act_ly.xT, S) + 2 * ulp(ref_s, "f32"))[ag]
+                assert over.max(initial=0) <= 0, f"{what}: x^A + x^T off by {over.max():.2e} beyond the intermediates' rounding"
+            elif xt1 is not None:
                 e = rel_err(xt1.reshape(shape)[ag], act_ly.xT[ag], slack=sl_state[ag])
                 assert e <= (0.0 if exact else tol), f"{what}: x^T off by {e:.2e}; {worst(xt1.reshape(shape)[ag], act_ly.xT[ag], slack=sl_state[ag])}"
         if folded:
@@ -596,6 +603,68 @@ def test_networks_without_truncated_value_buffers(spec_fn):
     with_xt = pkg.Net(r["ctx"], dict(spec, nodes=[{k: v for k, v in nd.items() if k != "no_xT"} for nd in spec["nodes"]]),
                       wl.make_weights(spec, 23), 2, 3)
     assert net.arena.numel() < with_xt.arena.numel()
+
+
+@pytest.mark.parametrize("spec_fn", [lambda: wl.bottleneck_block(eps=0.08, h=48, w=40, frames=8, xT_residue=True),
+                                     lambda: wl.single_conv_relu(eps=0.05, h=40, w=36, dtype="f16", xT_residue=True),
+                                     lambda: wl.tiny_mixed_net(eps=0.05, dtype="f16", xT_residue=True),
+                                     lambda: wl.tiny_mixed_net(eps=0.05, dtype="f32", xT_residue=True)])
+@pytest.mark.parametrize("flags", [1, 2])
+def test_networks_that_keep_the_rounding_residue_in_xT(spec_fn, flags):
+    """xT_residue = 1: an update leaves s - round(s) in x^T instead of 0.  Same frame-by-frame comparison and layer
+    replay as every other network, against the oracle run in the same mode (fused and unfused plans: the
+    wave-specialised convolution, the plain one, the stand-alone activation and the depthwise kernel)."""
+    spec = spec_fn()
+    r = _run_net(spec, 37, 2, flags=flags)
+    net, onet = r["net"], r["oracle"]
+    seen = 0
+    for li in range(net.num_layers):
+        ly = onet.layers[net.layer_node(li)]
+        if isinstance(ly, orc.ActTrunc):
+            assert ly.carry
+            xt = net.layer_state(li, 1)
+            if spec["dtype"] == "f16":
+                assert bool((xt != 0).any()), f"layer {li}: no residue was kept"
+            seen += 1
+    assert seen >= 1
+
+
+def test_long_run_error_with_and_without_truncated_values_and_residue():
+    """Supplementary Section 1.4 / Section 3.1 (Eqs. 5, 6) over a few hundred frames: a looped clip with a slow global
+    brightness drift (per frame far below the thresholds).  Against float64 dense inference of the same frame:
+    with x^T the error stays bounded (truncated changes accumulate and eventually propagate); without x^T the
+    drift is lost and the error grows with the number of frames; with the rounding residue kept in x^T the
+    error is no larger than with plain x^T (the growth that remains there is the rounding of x^A)."""
+    T, frames, B = 8, 320, 2
+    mk = lambda **kw: wl.bottleneck_block(eps=0.05, h=32, w=32, frames=T, n_objects=2, **kw)
+    specs = {"xT": mk(), "no_xT": mk(no_xT=True), "residue": mk(xT_residue=True)}
+    seed = 41
+    wts = wl.make_weights(specs["xT"], seed)
+    wts_s = {i: (w.astype(np.float16).astype(np.float64), b.astype(np.float16).astype(np.float64)) for i, (w, b) in wts.items()}
+    clip = wl.make_batch(specs["xT"]["video"], seed, B).astype(np.float64)              # [T, B, H, W, C]
+    order = list(range(1, T)) + list(range(T - 2, -1, -1))
+    drift = 0.0008
+
+    def frame(t):
+        return (clip[order[t % len(order)] if t else 0] + drift * t).astype(np.float16)
+
+    ctx = pkg.Context(B * 32 * 32)
+    nets = {k: pkg.Net(ctx, sp, wts, B, 1) for k, sp in specs.items()}
+    out = torch.empty((B, 32, 32, 256), dtype=torch.float16, device="cuda")
+    checks = (40, 80, 160, 240, 320)
+    err = {k: {} for k in nets}
+    for t in range(frames + 1):
+        fr = frame(t)
+        dense = orc.dense_reference(specs["xT"], wts_s, fr.astype(np.float64)) if t in checks else None
+        for k, net in nets.items():
+            (net.init if t == 0 else net.step)(torch.from_numpy(fr).cuda(), out)
+            if dense is not None:
+                ctx.sync()
+                err[k][t] = float(np.abs(to_np(out).astype(np.float64) - dense).max() / np.abs(dense).max())
+    print("long run, max |out - dense| / max |dense| at frames", checks, {k: [round(v, 4) for v in e.values()] for k, e in err.items()})
+    assert max(err["xT"].values()) < 0.05, err["xT"]                       # bounded by the thresholds, not by the run length
+    assert err["no_xT"][320] > 3 * err["xT"][320] and err["no_xT"][320] > 1.5 * err["no_xT"][80], err["no_xT"]
+    assert err["residue"][320] <= 1.1 * err["xT"][320] + 1e-3, (err["residue"], err["xT"])
 
 
 @pytest.mark.parametrize("eps", [0.05, 0.3])

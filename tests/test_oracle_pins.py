@@ -294,6 +294,82 @@ def test_dilated_input_mask_with_dense_layers_behind_equals_dense_inference_of_t
     assert saw_partial, "the input threshold must hold some pixels back for this pin to bite"
 
 
+# ---- x^T that carries the rounding residue of x^A (option for reduced-precision storage) ---------
+def test_residue_in_xT_keeps_the_accumulated_input_to_arithmetic_precision():
+    """Eq. 6 says x^A + x^T is everything the layer has received.  In fp16 storage an update rounds x^A to 11
+    bits and, with x^T <- 0, loses the rest; with the residue kept in x^T the pair still holds the fp32 sum
+    (to one rounding of the residue itself).  Checked against the float64 sum of the very inputs."""
+    rng = np.random.default_rng(21)
+    shape = (1, 6, 7, 16)
+    x0 = rng.normal(0, 2, shape).astype(np.float16)
+    plain, carry = orc.ActTrunc("relu", -1.0, "f16"), orc.ActTrunc("relu", -1.0, "f16", carry=True)
+    plain.init(x0), carry.init(x0)
+    total = x0.astype(np.float64)
+    m = np.ones(shape[:3], np.uint8)
+    worst_plain = worst_carry = 0.0
+    for t in range(400):
+        d = rng.normal(0, 0.01, shape).astype(np.float16)           # far below one unit in the last place of x^A
+        total = total + d.astype(np.float64)
+        op, oc = plain.step(Delta(d, m)), carry.step(Delta(d, m))
+        assert op.count == oc.count == m.size                       # eps < 0: every pixel updates, every frame
+        acc_p = plain.xA.astype(np.float64) + plain.xT.astype(np.float64)
+        acc_c = carry.xA.astype(np.float64) + carry.xT.astype(np.float64)
+        worst_plain = max(worst_plain, np.abs(acc_p - total).max())
+        worst_carry = max(worst_carry, np.abs(acc_c - total).max())
+        # one step: x^A + x^T is the fp32 sum s up to the rounding of the residue (<= 2^-11 of half a unit of x^A)
+        assert np.all(np.abs(carry.xT.astype(np.float64)) <= 0.5 * np.spacing(np.abs(carry.xA)).astype(np.float64) + 1e-12)
+    scale = np.abs(total).max()
+    assert worst_carry <= 2.0 ** -16 * scale, worst_carry           # 400 fp32 + residue roundings (measured 4e-6 at scale 6)
+    assert worst_plain >= 20 * worst_carry and worst_plain >= 2.0 ** -11 * scale / 4, (worst_plain, worst_carry)
+    # what is emitted is the same rule, f(s) - f(x^A): with identical state the deltas are identical
+    a, b = orc.ActTrunc("relu", 0.3, "f16"), orc.ActTrunc("relu", 0.3, "f16", carry=True)
+    a.init(x0), b.init(x0)
+    d = rng.normal(0, 0.5, shape).astype(np.float16)
+    oa, ob = a.step(Delta(d, m)), b.step(Delta(d, m))
+    assert np.array_equal(oa.mask, ob.mask) and np.array_equal(oa.data[oa.mask == 1], ob.data[ob.mask == 1])
+    assert np.array_equal(a.xA, b.xA) and np.array_equal(a.xT[oa.mask == 0], b.xT[oa.mask == 0])
+    assert np.any(b.xT[ob.mask == 1] != 0) and not np.any(a.xT[oa.mask == 1] != 0)
+    with pytest.raises(ValueError):
+        orc.ActTrunc("relu", 0.3, "f16", use_xT=False, carry=True)
+
+
+@pytest.mark.parametrize("S", ["f64", "f32"])
+def test_residue_option_changes_nothing_where_storage_is_the_arithmetic_type(S):
+    """f64 / f32 storage: s is stored as computed, the residue is exactly zero, both variants are bit-identical."""
+    net_a = wl.tiny_mixed_net(eps=0.05, frames=5)
+    net_b = wl.tiny_mixed_net(eps=0.05, frames=5, xT_residue=True)
+    wts = wl.make_weights(net_a, 8)
+    vid = _video(net_a, 8)
+    a, b = orc.OracleNet(net_a, wts, S), orc.OracleNet(net_b, wts, S)
+    for t in range(vid.shape[0]):
+        assert np.array_equal(a.frame(vid[t]), b.frame(vid[t]))
+    for la, lb in zip(a.layers, b.layers):
+        if isinstance(la, orc.ActTrunc):
+            assert lb.carry and np.array_equal(la.xA, lb.xA) and np.array_equal(la.xT, lb.xT)
+
+
+def test_residue_option_tracks_dense_inference_closer_over_a_long_run():
+    """fp16 bottleneck-shaped block, 150 frames of slow brightness drift over a static scene, every threshold
+    negative so that nothing is truncated: what is left is the rounding of the buffers (supplementary Section
+    1.4).  With the residue carried the output stays closer to float64 dense inference of the same frame."""
+    net_p = wl.bottleneck_block(eps=-1.0, h=12, w=12, cin=8, mid=8, cout=16, frames=2, n_objects=1)
+    net_c = wl.bottleneck_block(eps=-1.0, h=12, w=12, cin=8, mid=8, cout=16, frames=2, n_objects=1, xT_residue=True)
+    wts = wl.make_weights(net_p, 31)
+    base = _video(net_p, 31)[0].astype(np.float16)
+    wts_s = {i: (w.astype(np.float16).astype(np.float64), b.astype(np.float16).astype(np.float64)) for i, (w, b) in wts.items()}
+    p, c = orc.OracleNet(net_p, wts, "f16"), orc.OracleNet(net_c, wts, "f16")
+    err_p = err_c = 0.0
+    for t in range(150):
+        fr = (base.astype(np.float64) + 0.0007 * t).astype(np.float16)
+        op, oc = p.frame(fr), c.frame(fr)
+        if t >= 100:
+            dense = orc.dense_reference(net_p, wts_s, fr.astype(np.float64))
+            sc = np.abs(dense).max()
+            err_p = max(err_p, np.abs(op - dense).max() / sc)
+            err_c = max(err_c, np.abs(oc - dense).max() / sc)
+    assert err_c < 0.5 * err_p and err_c < 4e-3, (err_p, err_c)
+
+
 # ---- P7: the paper's scalar example -----------------------------------------------------------
 def test_relu_scalar_example(golden):
     prev, dlt = float(golden["relu_prev"]), float(golden["relu_delta"])

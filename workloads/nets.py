@@ -7,7 +7,7 @@ attributes of that kind:
 
     deltagen  eps, dilate_r                      (first node, consumes the camera frame)
     conv      k, stride, pad, cin, cout, depthwise   (weights W[k,k,cin,cout] or W[k,k,c], bias[cout])
-    act       f ("relu"|"relu6"), eps            (activation + truncation, Section 3.1)
+    act       f ("relu"|"relu6"), eps            (activation + truncation, Section 3.1); optional no_xT, xT_residue
     add       two inputs
     maxpool   k, stride, pad
     upsample  factor (nearest)
@@ -28,9 +28,10 @@ CONFIG_SEEDS = {i: 0xDE17A + i for i in range(1, 6)}
 class _B:
     """Tiny helper that appends nodes and returns their index."""
 
-    def __init__(self, no_xT=False):
+    def __init__(self, no_xT=False, xT_residue=False):
         self.nodes = []
         self.no_xT = bool(no_xT)
+        self.xT_residue = bool(xT_residue)
 
     def _add(self, **kw) -> int:
         self.nodes.append(kw)
@@ -48,6 +49,8 @@ class _B:
         nd = dict(kind="act", **{"in": [src]}, f=f, eps=float(eps))
         if self.no_xT:
             nd["no_xT"] = True                                     # activations keep no buffer of truncated values
+        if self.xT_residue:
+            nd["xT_residue"] = True                                # an update leaves x^A's rounding residue in x^T
         return self._add(**nd)
 
     def add(self, a, b):
@@ -76,10 +79,10 @@ def _net(name, dtype, h, w, c, video, b: _B):
     return {"name": name, "dtype": dtype, "h": h, "w": w, "c": c, "video": video, "nodes": b.nodes}
 
 
-def single_conv_relu(eps=0.05, eps0=None, h=64, w=64, c=32, frames=4, dtype="f32", no_xT=False):
+def single_conv_relu(eps=0.05, eps0=None, h=64, w=64, c=32, frames=4, dtype="f32", no_xT=False, xT_residue=False):
     """3x3 s1 conv + ReLU on a C-channel map (the smallest configuration)."""
     eps0 = eps if eps0 is None else eps0
-    b = _B(no_xT)
+    b = _B(no_xT, xT_residue)
     x = b.deltagen(eps0)
     x = b.conv(x, 3, 1, c, c)
     x = b.act(x, "relu", eps)
@@ -89,11 +92,11 @@ def single_conv_relu(eps=0.05, eps0=None, h=64, w=64, c=32, frames=4, dtype="f32
 
 
 def bottleneck_block(eps=0.05, eps0=None, h=128, w=128, cin=64, mid=64, cout=256, frames=16, dtype="f16",
-                     n_objects=4, dilate_r=0, no_xT=False):
+                     n_objects=4, dilate_r=0, no_xT=False, xT_residue=False):
     """ResNet bottleneck with a projection shortcut: 1x1 cin->mid, 3x3 mid->mid,
     1x1 mid->cout, shortcut 1x1 cin->cout, add, ReLU."""
     eps0 = eps if eps0 is None else eps0
-    b = _B(no_xT)
+    b = _B(no_xT, xT_residue)
     x0 = b.deltagen(eps0, dilate_r)
     x = b.act(b.conv(x0, 1, 1, cin, mid), "relu", eps)
     x = b.act(b.conv(x, 3, 1, mid, mid), "relu", eps)
@@ -299,12 +302,12 @@ def tiny_pool_net(eps=0.05, eps0=None, h=18, w=22, c=8, frames=6, dtype="f32"):
     return _net("tiny_pool", dtype, h, w, c, video, b)
 
 
-def tiny_mixed_net(eps=0.05, eps0=None, h=24, w=20, c=8, frames=6, dtype="f32", no_xT=False):
+def tiny_mixed_net(eps=0.05, eps0=None, h=24, w=20, c=8, frames=6, dtype="f32", no_xT=False, xT_residue=False):
     """A small network that touches every node kind once (tests only): strided and
     depthwise convs, ReLU and ReLU6, max-pool, a coarser branch that is upsampled
     back, two adds."""
     eps0 = eps if eps0 is None else eps0
-    b = _B(no_xT)
+    b = _B(no_xT, xT_residue)
     x0 = b.deltagen(eps0)
     x = b.act(b.conv(x0, 3, 1, c, 16), "relu", eps)
     p = b.maxpool(x, 3, 2, 1)                                   # h/2
