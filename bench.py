@@ -69,6 +69,22 @@ def layer_bytes(s: dict, b: int) -> float:
     return total
 
 
+def layer_bytes_moved(s: dict, b: int) -> float:
+    """Bytes the layer's kernels must move for the step after their own elisions: the formula above with the x^T
+    terms (read at every visited pixel, written at every visited pixel) replaced by the rows the step really
+    touched -- convolutions on the wave-specialised kernel neither read nor rewrite x^T rows that are all zero
+    (an update leaves zeros, and most pixels of the later layers update every time); counted by the library in
+    statistics mode.  Layers that do not count move the formula's bytes."""
+    from paper_2203_03996_amd import ACT_NONE
+    total = layer_bytes(s, b)
+    if s["act"] == ACT_NONE or s.get("xT_bytes_read", -1) < 0:
+        return total
+    work, cout = s["pixels_work"], s["c_out"]
+    total -= 2.0 * work * cout * b                                        # formula: x^T read + x^T written at every visited pixel
+    total += s["xT_bytes_read"] + s["xT_bytes_written"]
+    return total
+
+
 def layer_flops(s: dict) -> tuple[float, float]:
     """(needed, issued) FLOPs of one step of a convolution layer (1 multiply-add = 2 FLOP)."""
     from paper_2203_03996_amd import CONV, DWCONV
@@ -102,6 +118,16 @@ class Workload:
 
     def spec(self, eps: float):
         return self.wl.bottleneck_block(eps=eps, frames=self.frames)
+
+    def widened(self, streams: int):
+        """The same clip with its streams repeated to `streams` (throughput measurements beyond the generated
+        batch: the repeated streams do the same work as the originals)."""
+        import copy
+        w = copy.copy(self)
+        reps = -(-streams // self.streams)
+        w.streams = streams
+        w.video = [torch.cat([f] * reps, dim=0)[:streams].contiguous() for f in self.video]
+        return w
 
 
 def make_net(work: Workload, eps: float, streams: int):
@@ -159,6 +185,7 @@ def run_timed(work: Workload, eps: float, steps: int, warmup: int, streams: int,
     order = work.order
     per_step_stats = None
     if collect_stats:
+        net.set_counting(True)                            # statistics mode: two small extra launches per counted layer
         net.init(frames[0])
         per_step_stats = []
         for k in range(warmup + steps):
@@ -166,6 +193,7 @@ def run_timed(work: Workload, eps: float, steps: int, warmup: int, streams: int,
             if k >= warmup:
                 per_step_stats.append(net.stats())
         net.reset()
+        net.set_counting(False)
     net.init(frames[0])
     for k in range(warmup):
         net.step(frames[order[k % len(order)]])
@@ -199,9 +227,14 @@ def profile_layers(work: Workload, eps: float, steps: int, warmup: int, streams:
     for i in range(net.num_layers):
         ms, n = net.timing(i)
         out.append(ms / max(n, 1))
+    for i in range(net.num_layers):
+        net.set_timing(i, 0)
+    net.set_counting(True)
+    net.step(frames[work.order[(warmup + steps) % len(work.order)]])
     st = net.stats()
-    nbytes = [layer_bytes(st[i], 2) for i in range(net.num_layers)]          # the last step's algorithmic bytes (fp16)
-    return out, nbytes
+    nbytes = [layer_bytes(st[i], 2) for i in range(net.num_layers)]          # one step's algorithmic bytes (fp16), by the formula
+    moved = [layer_bytes_moved(st[i], 2) for i in range(net.num_layers)]     # and what the kernels must move
+    return out, nbytes, moved
 
 
 def dense_baseline(work: Workload, steps: int, warmup: int, streams: int):
@@ -246,28 +279,59 @@ def dense_baseline(work: Workload, steps: int, warmup: int, streams: int):
     return e0.elapsed_time(e1) / steps
 
 
-def cpu_baseline(work: Workload, eps: float, budget_s: float = 12.0):
-    """The CPU oracle as it stands, timed on this machine's host cores on one stream of the same video."""
+def cpu_baseline(work: Workload, eps: float, budget_s: float = 10.0):
+    """The CPU oracle as it stands, timed on this machine's host cores on one stream of the same video: once with
+    the numerical library's threads limited to one, once with all it takes by itself."""
     from oracle import deltacnn_oracle as orc
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = 1
+    from threadpoolctl import threadpool_info, threadpool_limits
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     spec = work.spec(eps)
     vid = work.video_np[:, :1]
-    net = orc.OracleNet(spec, work.weights, "f16")
-    net.frame(vid[0])
-    done, t0 = 0, time.time()
-    k = 0
-    while time.time() - t0 < budget_s or done < 4:
-        net.frame(vid[work.order[k % len(work.order)]])
-        k += 1
-        done += 1
-    dt = time.time() - t0
+
+    def timed(budget):
+        net = orc.OracleNet(spec, work.weights, "f16")
+        net.frame(vid[0])
+        done, k, t0 = 0, 0, time.time()
+        while time.time() - t0 < budget or done < 4:
+            net.frame(vid[work.order[k % len(work.order)]])
+            k += 1
+            done += 1
+        return done, time.time() - t0
+
+    with threadpool_limits(limits=1):
+        done1, dt1 = timed(budget_s)
+    done, dt = timed(budget_s)
     return {"value": done / dt, "unit": "frames/s", "cores": int(threads), "kind": "oracle",
             "sample": f"1 stream, {done} sparse frames (frames >= 2) of the same clip at the headline threshold, "
-                      f"numpy fp16-storage oracle, {dt:.1f} s", "host_cpus": os.cpu_count()}
+                      f"numpy fp16-storage oracle, {dt:.1f} s",
+            "single_thread": {"value": done1 / dt1, "unit": "frames/s", "cores": 1,
+                              "sample": f"the same, {done1} frames, {dt1:.1f} s, numerical library limited to one thread"},
+            "host_cpus": os.cpu_count()}
+
+
+def measured_peaks():
+    """What this GPU delivers on two plain library operations, next to the nominal peaks the roofline uses:
+    a 1 GiB device-to-device copy (bytes read + written per second) and a dense fp16 GEMM 8192^3."""
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    a = torch.randn(8192, 8192, dtype=torch.float16, device="cuda")
+    bm = torch.randn(8192, 8192, dtype=torch.float16, device="cuda")
+    out = {}
+    for name, fn, work_units, reps in (("copy", lambda: dst.copy_(src), 2.0 * src.numel() * 4, 20),
+                                       ("gemm", lambda: torch.matmul(a, bm), 2.0 * 8192 ** 3, 10)):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = work_units * reps / (e0.elapsed_time(e1) * 1e-3)
+    return {"hbm_copy_gbs": out["copy"] / 1e9, "hbm_nominal_gbs": HBM_PEAK_GBS,
+            "fp16_gemm_tflops": out["gemm"] / 1e12, "fp16_mfma_nominal_tflops": MFMA_F16_PEAK_TFLOPS,
+            "how": "torch copy_ of 1 GiB fp32 (read + write counted), torch.matmul 8192x8192x8192 fp16 (hipBLASLt)"}
 
 
 def tile_ablation(streams: int, steps: int, warmup: int):
@@ -555,7 +619,7 @@ def main():
 
     # headline: per-layer kernel profile picks the dominant kernel, then the timed region
     eps_h = eps_of[HEADLINE_DENSITY][0]
-    prof, prof_bytes = profile_layers(work, eps_h, min(K, 30), W, B)
+    prof, prof_bytes, prof_moved = profile_layers(work, eps_h, min(K, 30), W, B)
     # the dominant kernel: the longest one; layers within 3 % of it (two of this block's kernels take the same time
     # to within the noise of the measurement) count as tied, and of those the one that moves the most bytes is taken
     longest = max(prof)
@@ -564,9 +628,12 @@ def main():
     fps = B * 1e3 / ms
     kern_ms = kern[0] / max(kern[1], 1)
     dom_bytes = float(np.mean([layer_bytes(st[dominant], b) for st in stats]))
+    dom_moved = float(np.mean([layer_bytes_moved(st[dominant], b) for st in stats]))
     dom_need, dom_issued = [float(np.mean(x)) for x in zip(*[layer_flops(st[dominant]) for st in stats])]
-    achieved_gbs = dom_bytes / (kern_ms * 1e-3) / 1e9
+    achieved_gbs = dom_moved / (kern_ms * 1e-3) / 1e9
+    formula_gbs = dom_bytes / (kern_ms * 1e-3) / 1e9
     step_bytes = float(np.mean([sum(layer_bytes(s, b) for s in st) for st in stats]))
+    step_moved = float(np.mean([sum(layer_bytes_moved(s, b) for s in st) for st in stats]))
     dens_h = float(np.mean([conv_density(st) for st in stats]))
     layer_names = []
     for i in range(net.num_layers):
@@ -592,20 +659,32 @@ def main():
                    "streams": B, "update_density": dens_h, "eps": eps_h, "frames_per_step": B,
                    "density_definition": "mean over frames>=2 and conv layers of flagged input pixels / pixels"},
         "dense_equiv_gflops": fps * work.dense_flops / 1e9,
+        # achieved: the bytes the dominant kernel must move after its own elisions (x^T rows that are all zero are
+        # neither read nor rewritten -- counted by the kernel -- and a folded output layer writes O without reading
+        # it) / its launch time; formula_*: the method's per-pixel figure (x^T read and written at every visited
+        # pixel), which credits bytes the kernel no longer moves; traffic: rocprofv3 FETCH_SIZE + WRITE_SIZE
         "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": layer_names[dominant], "kernel_ms": kern_ms, "algorithmic_bytes_per_launch": dom_bytes,
+                     "kernel": layer_names[dominant], "kernel_ms": kern_ms, "moved_bytes_per_launch": dom_moved,
+                     "formula_bytes_per_launch": dom_bytes, "formula_gbs": formula_gbs, "formula_frac": formula_gbs / HBM_PEAK_GBS,
+                     "algorithmic_bytes_per_launch": dom_moved,
                      "needed_gflop_per_launch": dom_need / 1e9, "issued_gflop_per_launch": dom_issued / 1e9,
                      "mfma_frac_of_fp16_peak": dom_issued / (kern_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
                      # measured HBM bytes over the same time (below the algorithmic figure: an x^T that is already
                      # zero is not rewritten when its pixel updates)
                      "traffic_gbs": (traffic / (kern_ms * 1e-3) / 1e9) if traffic else None,
                      "traffic_frac_of_peak": (traffic / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS) if traffic else None},
-        "whole_step": {"algorithmic_bytes": step_bytes, "achieved_gbs": step_bytes / (ms * 1e-3) / 1e9,
-                       "frac_of_hbm_peak": step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "whole_step": {"moved_bytes": step_moved, "achieved_gbs": step_moved / (ms * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": step_moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "formula_bytes": step_bytes, "formula_gbs": step_bytes / (ms * 1e-3) / 1e9,
+                       "formula_frac_of_hbm_peak": step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "layer_kernel_ms": dict(zip(layer_names, [round(x, 5) for x in prof])),
-                       "layer_algorithmic_gbs": dict(zip(layer_names, [round(nb / (x * 1e-3) / 1e9, 1) if x > 0 else None
-                                                                        for nb, x in zip(prof_bytes, prof)]))},
+                       "layer_moved_gbs": dict(zip(layer_names, [round(nb / (x * 1e-3) / 1e9, 1) if x > 0 else None
+                                                                 for nb, x in zip(prof_moved, prof)])),
+                       "layer_frac_of_hbm_peak": dict(zip(layer_names, [round(nb / (x * 1e-3) / 1e9 / HBM_PEAK_GBS, 3) if x > 0 else None
+                                                                        for nb, x in zip(prof_moved, prof)])),
+                       "layer_formula_gbs": dict(zip(layer_names, [round(nb / (x * 1e-3) / 1e9, 1) if x > 0 else None
+                                                                   for nb, x in zip(prof_bytes, prof)]))},
     }
     if not args.quick:
         sweep = []
@@ -613,18 +692,34 @@ def main():
             eps = eps_of[d][0]
             ms_d, _, st_d, _ = run_timed(work, eps, K, W, B, collect_stats=True)
             by = float(np.mean([sum(layer_bytes(s, b) for s in st) for st in st_d]))
+            mv = float(np.mean([sum(layer_bytes_moved(s, b) for s in st) for st in st_d]))
             sweep.append({"density_target": d, "density": float(np.mean([conv_density(st) for st in st_d])), "eps": eps,
                           "ms_per_step": ms_d, "frames_per_s": B * 1e3 / ms_d,
                           "dense_equiv_gflops": B * 1e3 / ms_d * work.dense_flops / 1e9,
-                          "algorithmic_gbs": by / (ms_d * 1e-3) / 1e9})
+                          "moved_gbs": mv / (ms_d * 1e-3) / 1e9, "formula_gbs": by / (ms_d * 1e-3) / 1e9})
             log(f"[bench] density {d}: {ms_d:.3f} ms/step, {B * 1e3 / ms_d:.0f} frames/s")
         for name, eps in (("ours_dense_eps<0", -1.0), ("eps=inf", float("inf"))):
             ms_d, _, _, _ = run_timed(work, eps, K, W, B)
             sweep.append({"density_target": name, "eps": eps if np.isfinite(eps) else "inf", "ms_per_step": ms_d,
                           "frames_per_s": B * 1e3 / ms_d, "dense_equiv_gflops": B * 1e3 / ms_d * work.dense_flops / 1e9})
             log(f"[bench] {name}: {ms_d:.3f} ms/step")
-        ms1, _, _, _ = run_timed(work, eps_h, max(K, 200), max(W, 20), 1)    # launch-bound: needs more steps to settle
-        result["single_stream"] = {"streams": 1, "ms_per_step": ms1, "frames_per_s": 1e3 / ms1}
+        # streams batched on the GPU (the paper's batch axis): N = 1 is the configuration's own number
+        rows = []
+        for n_streams in (1, 8, 32, 128):
+            wk = work if n_streams <= B else work.widened(n_streams)
+            ms_n, _, st_n, _ = run_timed(wk, eps_h, max(K, 200) if n_streams == 1 else K, max(W, 20) if n_streams == 1 else W,
+                                         n_streams, collect_stats=True)   # (one stream is launch-bound: more steps to settle)
+            mv = float(np.mean([sum(layer_bytes_moved(s, b) for s in st) for st in st_n]))
+            by = float(np.mean([sum(layer_bytes(s, b) for s in st) for st in st_n]))
+            rows.append({"streams": n_streams, "ms_per_step": ms_n, "frames_per_s": n_streams * 1e3 / ms_n,
+                         "density": float(np.mean([conv_density(st) for st in st_n])),
+                         "moved_gbs": mv / (ms_n * 1e-3) / 1e9, "frac_of_hbm_peak": mv / (ms_n * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "formula_gbs": by / (ms_n * 1e-3) / 1e9})
+            log(f"[bench] {n_streams} streams: {ms_n:.3f} ms/step, {n_streams * 1e3 / ms_n:.0f} frames/s, {mv / (ms_n * 1e-3) / 1e9:.0f} GB/s moved")
+            del wk
+        result["stream_sweep"] = rows
+        result["single_stream"] = {"streams": 1, "ms_per_step": rows[0]["ms_per_step"], "frames_per_s": rows[0]["frames_per_s"]}
+        result["measured_peaks"] = measured_peaks()
         md = dense_baseline(work, K, W, B)
         md1 = dense_baseline(work, K, W, 1)
         result["dense_baseline"] = {"kind": "PyTorch-ROCm conv2d/relu/add fp16 channels-last, same GPU",

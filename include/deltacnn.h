@@ -76,7 +76,8 @@ typedef struct {
 } dcnn_delta;
 
 /* One layer.  n,h,w,c is the shape of the (first) input.
- *  CONV / DWCONV : kh=kw in {1,3,5,7}, stride in {1,2}, pad < k; cout (DWCONV: cout == c).
+ *  CONV / DWCONV : kh = kw in 1..7 (odd windows for CONV in the networks here; DWCONV also serves 2x2 average
+ *                  pooling), stride in {1,2}, pad < k; cout (DWCONV: cout == c).
  *                  act != NONE fuses activation + truncation (threshold eps) behind the
  *                  convolution; n_in == 2 adds a second delta stream of the OUTPUT shape
  *                  (residual) before the activation.
@@ -146,6 +147,11 @@ typedef struct {
     int32_t proj_c;         /* channels of the fused projection's input (input 1), 0 if none */
     int32_t fuse_accum;     /* 1: the layer also accumulates the dense output             */
     int32_t reserved;
+    /* Bytes of the truncated-values buffer x^T the last step read / wrote, in whole pixel rows.  Only counted
+     * while dcnn_layer_set_counting is on, and only by convolutions whose sparse steps skip x^T rows that are
+     * all zero (an update leaves zeros); otherwise both are -1: x^T is read and written at every visited pixel. */
+    int64_t xT_bytes_read;
+    int64_t xT_bytes_written;
 } dcnn_stats;
 
 typedef struct dcnn_ctx dcnn_ctx;
@@ -215,7 +221,12 @@ dcnn_status dcnn_layer_reset(dcnn_layer* layer);
 dcnn_status dcnn_layer_set_eps(dcnn_layer* layer, float eps);
 /* which: 0 = x^A (ACT/CONV+act/MAXPOOL), stored frame (DELTAGEN), dense output (ACCUM); 1 = x^T;
  * 2 = dense output of a layer with fuse_accum.
- * Returns the device pointer and byte size of that buffer inside the state memory. */
+ * Returns the device pointer and byte size of that buffer inside the state memory.
+ * Writing through the pointer (restoring a checkpoint, teacher forcing) is allowed between steps, with one
+ * rule for x^T: the library keeps, per pixel, whether the x^T row is all zero and skips such rows; it rebuilds
+ * that knowledge from x^T before the next step ONLY IF dcnn_layer_state(which = 1) has been called since the
+ * last step.  So call dcnn_layer_state(layer, 1, ...) again before EVERY external write of x^T -- a pointer
+ * kept from an earlier call must not be written through after a step has run in between. */
 dcnn_status dcnn_layer_state(const dcnn_layer* layer, int32_t which, void** ptr_dev, size_t* bytes);
 /* Counters of the last step; synchronises the stream. */
 dcnn_status dcnn_layer_stats(dcnn_layer* layer, dcnn_stats* stats_host);
@@ -225,6 +236,9 @@ dcnn_status dcnn_layer_stats(dcnn_layer* layer, dcnn_stats* stats_host);
  * steps; 0 switches it off.  dcnn_layer_timing synchronises, reports the summed kernel time and the
  * number of timed launches since the last call, and starts over. */
 dcnn_status dcnn_layer_set_timing(dcnn_layer* layer, int32_t max_steps);
+/* Statistics for measurements: with on = 1 every step of the layer also counts the x^T rows its kernel reads and
+ * writes (two small extra launches around the main kernel -- keep it off in timed runs); see dcnn_stats. */
+dcnn_status dcnn_layer_set_counting(dcnn_layer* layer, int32_t on);
 dcnn_status dcnn_layer_timing(dcnn_layer* layer, float* total_ms_host, int32_t* launches_host);
 
 /* ---- networks ------------------------------------------------------------------------------ */

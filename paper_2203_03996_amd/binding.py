@@ -29,7 +29,7 @@ EXPORTS = [
     "dcnn_workspace_bytes", "dcnn_ctx_create", "dcnn_ctx_destroy", "dcnn_ctx_sync", "dcnn_status_str",
     "dcnn_last_error", "dcnn_mask_compact", "dcnn_mask_compact_static", "dcnn_layer_query", "dcnn_layer_create", "dcnn_layer_destroy",
     "dcnn_layer_init", "dcnn_layer_step", "dcnn_layer_output", "dcnn_layer_reset", "dcnn_layer_state",
-    "dcnn_layer_stats", "dcnn_layer_set_eps", "dcnn_layer_set_timing", "dcnn_layer_timing", "dcnn_net_create", "dcnn_net_destroy", "dcnn_net_add", "dcnn_net_finalize",
+    "dcnn_layer_stats", "dcnn_layer_set_eps", "dcnn_layer_set_timing", "dcnn_layer_set_counting", "dcnn_layer_timing", "dcnn_net_create", "dcnn_net_destroy", "dcnn_net_add", "dcnn_net_finalize",
     "dcnn_net_bind", "dcnn_net_init", "dcnn_net_step", "dcnn_net_reset", "dcnn_net_output",
     "dcnn_net_num_layers", "dcnn_net_layer", "dcnn_net_stats",
 ]
@@ -60,7 +60,7 @@ class Stats(C.Structure):
                 ("pixels_in2_total", C.c_int64),
                 ("kind", C.c_int32), ("act", C.c_int32), ("n_in", C.c_int32), ("c_in", C.c_int32),
                 ("c_out", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32), ("proj_c", C.c_int32), ("fuse_accum", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("reserved", C.c_int32), ("xT_bytes_read", C.c_int64), ("xT_bytes_written", C.c_int64)]
 
     def as_dict(self) -> dict:
         return {name: getattr(self, name) for name, _ in self._fields_ if name != "reserved"}
@@ -110,6 +110,7 @@ def load_library() -> C.CDLL:
     lib.dcnn_layer_stats.argtypes = [vp, P(Stats)]
     lib.dcnn_layer_set_eps.argtypes = [vp, C.c_float]
     lib.dcnn_layer_set_timing.argtypes = [vp, i32]
+    lib.dcnn_layer_set_counting.argtypes = [vp, i32]
     lib.dcnn_layer_timing.argtypes = [vp, P(C.c_float), P(i32)]
     lib.dcnn_net_create.argtypes = [vp, i32, i32, i32, i32, i32, P(vp)]
     lib.dcnn_net_destroy.argtypes = [vp]
@@ -444,6 +445,13 @@ class Net:
         lh, nid = C.c_void_p(), C.c_int32()
         self.ctx.check(self.ctx.lib.dcnn_net_layer(self.handle, i, C.byref(lh), C.byref(nid)))
         self.ctx.check(self.ctx.lib.dcnn_layer_set_timing(lh, max_steps))
+
+    def set_counting(self, on: bool):
+        """Statistics mode for every layer: steps also count the x^T rows read / written (see dcnn_stats)."""
+        for i in range(self.num_layers):
+            lh, nid = C.c_void_p(), C.c_int32()
+            self.ctx.check(self.ctx.lib.dcnn_net_layer(self.handle, i, C.byref(lh), C.byref(nid)))
+            self.ctx.check(self.ctx.lib.dcnn_layer_set_counting(lh, 1 if on else 0))
 
     def timing(self, i: int):
         """(summed kernel milliseconds, launches) of layer i since the last call."""

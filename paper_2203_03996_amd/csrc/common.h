@@ -123,6 +123,12 @@ struct ListArgs {
                                  // bounds and flagged in the input mask (written with the list by the mask pass)
 };
 
+// Statistics (never on a timed path): x^T rows a convolution that keeps row flags reads and writes in one step.
+// phase 0, before the step's kernel: before[j] = flag of list entry j's pixel, io[0] = their number (rows read);
+// phase 1, after it: io[1] = entries whose row held values before or holds values now (rows written).
+dcnn_status launch_xt_row_count(dcnn_ctx* ctx, int phase, const ListArgs& l, const uint8_t* flags, uint8_t* before,
+                                unsigned long long* io);
+
 struct ConvArgs {
     const void* in_data;
     const uint8_t* in_mask;      // nullptr: every in-bounds pixel is flagged (first frame)

@@ -406,7 +406,6 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         const bool has_tflag = e.xt_flags != nullptr;
         const bool has_omask = e.out_mask != nullptr;
         const float hi = act_hi(e.act);
-        const bool carry = e.carry != 0;
         // this lane's 16 bytes in row 0 of the producer slice that holds its channels (lanes without
         // channels read slot 0 and discard it; their stores go nowhere)
         const unsigned char* my_stage = stage0 + (size_t)(slot * cs + spart) * stage_tile + (size_t)(ch_on ? vi : 0) * V * ES;
@@ -454,7 +453,8 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
             }
         };
         // arithmetic, decision and stores of set s; returns the survivor bits of its pixels
-        auto finish_set = [&](auto sf, const Tile& t, int s, const Set& st, const unsigned char* tile_stage) -> uint32_t {
+        auto finish_set = [&](auto sf, auto cf, const Tile& t, int s, const Set& st, const unsigned char* tile_stage) -> uint32_t {
+            constexpr bool carry = decltype(cf)::value;            // an update leaves x^A's rounding residue in x^T
             uint32_t bits = 0;
             Raw rd[H];
 #pragma unroll
@@ -491,7 +491,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                         raw_set<T, V>(o_a, i, sum);
                         raw_set<T, V>(o_t, i, tt + dd);             // x^T if the pixel is truncated
                         raw_set<T, V>(o_y, i, ACC ? fs : dy);
-                        if (carry) raw_set<T, V>(o_r, i, round_residue<T>(sum));   // x^T if it is updated and keeps the residue
+                        if constexpr (carry) raw_set<T, V>(o_r, i, round_residue<T>(sum));   // x^T if it is updated and keeps it
                     }
                     u = group_max(u, LP);
                     upd = u >= e.eps;
@@ -501,7 +501,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     // already is all zero bits and stays so nothing needs to be written (most pixels that update every
                     // frame never accumulate anything)
                     {
-                        const uint32_t o_t_off = (upd && all_bits_zero(st.rt[h]) && all_bits_zero(o_r)) ? kOob : o;
+                        const uint32_t o_t_off = (upd && all_bits_zero(st.rt[h]) && (!carry || all_bits_zero(o_r))) ? kOob : o;
                         if (__builtin_amdgcn_ballot_w64(o_t_off != kOob)) state_store(rs_xT, o_t_off, upd ? o_r : o_t);
                     }
                     if constexpr (ACC) state_store(rs_res, o_upd, o_y);
@@ -528,7 +528,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
             return bits;
         };
 
-        auto run = [&](auto sf) {
+        auto run = [&](auto sf, auto cf) {
             // Software pipeline.  List entries are requested two tiles ahead, residual flags one tile ahead,
             // and over the sets of consecutive tiles: while set s is finished, the loads of set s+1 (issued
             // one step earlier) and of set s+2 (issued right after) are in flight.
@@ -553,9 +553,9 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 uint32_t bits = 0;
     #pragma unroll
                 for (int s = 0; s < NS; s += 2) {
-                    bits |= finish_set(sf, cur, s, set0, tile_stage);
+                    bits |= finish_set(sf, cf, cur, s, set0, tile_stage);
                     if (s + 2 < NS) load_set(sf, cur, s + 2, set0); else load_set(sf, nxt, s + 2 - NS, set0);
-                    bits |= finish_set(sf, cur, s + 1, set1, tile_stage);
+                    bits |= finish_set(sf, cf, cur, s + 1, set1, tile_stage);
                     if (s + 3 < NS) load_set(sf, cur, s + 3, set1); else load_set(sf, nxt, s + 3 - NS, set1);
                 }
     #pragma unroll
@@ -584,7 +584,9 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
             }
         };
         // layers with an activation keep state (x^A, x^T) and truncate; linear ones pass the delta on
-        if (stateful) run(std::true_type{}); else run(std::false_type{});
+        if (!stateful) run(std::false_type{}, std::false_type{});
+        else if (e.carry) run(std::true_type{}, std::true_type{});
+        else run(std::true_type{}, std::false_type{});
         // one atomic per wave: a counter bumped once per tile by every wave serialises in L2
         if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
     }

@@ -29,6 +29,7 @@ struct dcnn_layer {
     uint32_t* taps;                     // per work-list entry: flagged window taps (dense convolutions, 1x1 / 3x3)
     uint8_t* xt_flags;                  // per output pixel: 0 = its x^T row is all zero and need not be read (layers whose
                                         // sparse steps run on the wave-specialised kernel); nullptr: none
+    bool counting = false, counted = false;   // statistics mode (dcnn_layer_set_counting); the last step was counted
     mutable bool xt_flags_stale = false;  // the state memory was handed out: the flags are rebuilt from x^T before the next step
     void* wpacked;
     void* bias;

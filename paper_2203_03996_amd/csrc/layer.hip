@@ -189,11 +189,14 @@ static void carve(dcnn_layer* L, void* state) {
     L->state_bytes = cv.off;
 }
 
+// the block that holds a layer's output count also holds, 64 bytes in, two 64-bit counters of x^T vectors read / written
+constexpr int kXtIoOffset = 16;                                  // in int32 units
+
 static dcnn_status clear_sparse_output(dcnn_layer* L) {
     if (L->alias_mask) return DCNN_OK;
     dcnn_status st = launch_fill_u8(L->ctx, L->out_mask, 0, (int64_t)align_up((size_t)L->out_pixels, 4));
     if (st != DCNN_OK) return st;
-    st = launch_fill_i32(L->ctx, L->out_count, 0, 1);
+    st = launch_fill_i32(L->ctx, L->out_count, 0, kXtIoOffset + 4);     // the count and the x^T row counters behind it
     if (st != DCNN_OK) return st;
     if (L->list_count && L->list_count != L->out_count) st = launch_fill_i32(L->ctx, L->list_count, 0, 1);
     return st;
@@ -365,6 +368,14 @@ dcnn_status dcnn_layer_set_timing(dcnn_layer* L, int32_t max_steps) {
         if (st != DCNN_OK) { (void)hipEventDestroy(a); return st; }
         L->events.emplace_back(a, b);
     }
+    return DCNN_OK;
+}
+
+dcnn_status dcnn_layer_set_counting(dcnn_layer* L, int32_t on) {
+    if (!L) return DCNN_EINVAL;
+    if (on != 0 && on != 1) return fail(L->ctx, DCNN_EINVAL, "set_counting: on must be 0 or 1");
+    L->counting = on != 0;
+    if (!on) L->counted = false;
     return DCNN_OK;
 }
 
@@ -610,7 +621,17 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             e.out_mask = act ? L->out_mask : nullptr;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;
             e.out_count = (act && !d.want_idx) ? L->out_count : nullptr;
+            // statistics mode: which x^T rows the kernel will read, and afterwards which it wrote
+            const bool counting = L->counting && L->xt_flags && L->out_count && !timed;
+            unsigned long long* io = counting ? reinterpret_cast<unsigned long long*>(L->out_count + kXtIoOffset) : nullptr;
+            if (counting) {
+                st = launch_fill_i32(ctx, L->out_count + kXtIoOffset, 0, 4);
+                if (st == DCNN_OK) st = launch_xt_row_count(ctx, 0, l, L->xt_flags, ws.scratch_mask2, io);
+                if (st != DCNN_OK) break;
+            }
             st = launch_conv(ctx, d.dtype, false, l, c, e);
+            if (st == DCNN_OK && counting) st = launch_xt_row_count(ctx, 1, l, L->xt_flags, ws.scratch_mask2, io);
+            L->counted = counting;
             break;
         }
         case DCNN_ACT: {
@@ -720,6 +741,14 @@ dcnn_status dcnn_layer_stats(dcnn_layer* L, dcnn_stats* s) {
     s->c_in = L->d.c; s->c_out = L->oc;
     const bool window = L->d.kind == DCNN_CONV || L->d.kind == DCNN_DWCONV || L->d.kind == DCNN_MAXPOOL;
     s->k = window ? L->d.kh : 1; s->stride = window ? L->d.stride : 1; s->proj_c = L->d.proj_c; s->fuse_accum = L->d.fuse_accum; s->reserved = 0;
+    s->xT_bytes_read = s->xT_bytes_written = -1;
+    if (st == DCNN_OK && L->counted) {
+        unsigned long long io[2] = {0, 0};
+        st = check_hip(ctx, hipMemcpy(io, L->out_count + kXtIoOffset, sizeof(io), hipMemcpyDeviceToHost), "hipMemcpy(x^T counters)");
+        const int64_t row = (int64_t)L->oc * (int64_t)dtype_size(L->d.dtype);
+        s->xT_bytes_read = (int64_t)io[0] * row;
+        s->xT_bytes_written = (int64_t)io[1] * row;
+    }
     return st;
 }
 

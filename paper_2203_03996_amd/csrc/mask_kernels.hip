@@ -516,6 +516,29 @@ dcnn_status launch_mask_compact(dcnn_ctx* ctx, const MaskPassArgs& m) {
     return mask_compact_on(ctx, m, ws);
 }
 
+// ---- statistics: x^T rows read / written by a step (see launch_xt_row_count) --------------------------
+__global__ __launch_bounds__(kMaskThreads) void xt_row_count_kernel(int phase, ListArgs l, const uint8_t* flags, uint8_t* before,
+                                                                    unsigned long long* io) {
+    __shared__ int s_red[kMaskThreads / kWave];
+    const int64_t count = list_count(l);
+    int local = 0;
+    for (int64_t j = (int64_t)blockIdx.x * kMaskThreads + threadIdx.x; j < count; j += (int64_t)gridDim.x * kMaskThreads) {
+        const int now = flags[list_pixel(l.list, j, count)] != 0;
+        if (phase == 0) { before[j] = (uint8_t)now; local += now; }
+        else local += (now | before[j]) ? 1 : 0;
+    }
+    const int total = block_sum(local, s_red);
+    if (threadIdx.x == 0 && total) atomicAdd(io + phase, (unsigned long long)total);
+}
+
+dcnn_status launch_xt_row_count(dcnn_ctx* ctx, int phase, const ListArgs& l, const uint8_t* flags, uint8_t* before,
+                                unsigned long long* io) {
+    const int64_t want = cdiv(l.max_count > 0 ? l.max_count : 1, kMaskThreads);
+    const int grid = (int)(want < 1024 ? want : 1024);
+    hipLaunchKernelGGL(xt_row_count_kernel, dim3(grid), dim3(kMaskThreads), 0, ctx->stream, phase, l, flags, before, io);
+    return check_hip(ctx, hipGetLastError(), "xt_row_count_kernel launch");
+}
+
 // ---- library-owned scratch for the entry point that allocates nothing ------------------------------
 // One array per GPU the library runs on, held until the process ends: the chunk counts of the largest
 // accepted map, followed by a mask for callers that only want the list.

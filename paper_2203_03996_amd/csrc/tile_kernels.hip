@@ -257,7 +257,9 @@ static dcnn_status launch_act_t(dcnn_ctx* ctx, bool init, const ListArgs& l, con
         if (vpl <= 1) DCNN_ACT_LAUNCH(VEC, 1);
         else if (vpl <= 2) DCNN_ACT_LAUNCH(VEC, 2);
         else if (vpl <= 4) DCNN_ACT_LAUNCH(VEC, 4);
-        else if (vpl <= 8 && sizeof(T) == 4) DCNN_ACT_LAUNCH(VEC, 8);
+        else if (vpl <= 8 && sizeof(T) == 4) {
+            if constexpr (sizeof(T) == 4) DCNN_ACT_LAUNCH(VEC, 8);     // (fp32 only: 2048 channels = 8 KB per pixel)
+        }
         else return fail(ctx, DCNN_EUNSUPPORTED, "activation: %d channels exceed the supported 8 KB per pixel", e.c);
     } else {
         if (vpl <= 1) DCNN_ACT_LAUNCH(1, 1);

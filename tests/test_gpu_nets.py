@@ -710,6 +710,47 @@ def test_free_running_without_touching_the_state(eps):
     assert rel_err(to_np(out), ref, slack=free_running_slack(spec, ref, "f16")) <= tol
 
 
+def test_statistics_mode_counts_the_truncated_value_rows_a_step_touches():
+    """dcnn_layer_set_counting: convolutions whose sparse steps skip all-zero x^T rows report the rows they read and
+    wrote.  With negative thresholds every visited pixel updates, x^T stays zero: nothing is read or written.  With
+    thresholds that truncate, rows read are rows that held values, rows written at least those; both are bounded
+    by the visited pixels, and the counts equal what the x^T buffers themselves show before and after the step."""
+    def run(eps, steps):
+        spec = wl.bottleneck_block(eps=eps, eps0=0.05, h=40, w=48, frames=6)
+        wts = wl.make_weights(spec, 43)
+        vid = wl.make_batch(spec["video"], 43, 2).astype(np.float16)
+        ctx = pkg.Context(2 * 40 * 48)
+        net = pkg.Net(ctx, spec, wts, 2, 1)
+        net.init(torch.from_numpy(vid[0]).cuda())
+        rows = []
+        for t in range(1, steps + 1):
+            if t == steps:
+                net.set_counting(True)
+                before = {li: to_np(net.layer_state(li, 1)).copy() for li in range(net.num_layers) if net.layer_state(li, 1) is not None}
+            net.step(torch.from_numpy(vid[t]).cuda())
+        st = net.stats()
+        for li, s in enumerate(st):
+            if s["xT_bytes_read"] >= 0:
+                c = s["c_out"]
+                b4 = (before[li].reshape(-1, c) != 0).any(axis=1)
+                now = (to_np(net.layer_state(li, 1)).reshape(-1, c) != 0).any(axis=1)
+                rows.append((s, int(b4.sum()), int((b4 | now).sum())))
+        return rows
+    dense = run(-1.0, 3)
+    assert len(dense) >= 2
+    for s, _, _ in dense:
+        assert s["xT_bytes_read"] == 0 and s["xT_bytes_written"] == 0, s
+    mixed = run(0.3, 4)
+    saw = 0
+    for s, held_before, held_any in mixed:
+        row = s["c_out"] * 2
+        assert 0 <= s["xT_bytes_read"] <= s["xT_bytes_written"] <= s["pixels_work"] * row, s
+        # rows that held values and were visited were read; no more than all rows that held values
+        assert s["xT_bytes_read"] <= held_before * row and s["xT_bytes_written"] <= held_any * row, (s, held_before, held_any)
+        saw += s["xT_bytes_written"] > 0
+    assert saw >= 1
+
+
 def test_frames_of_the_wrong_shape_are_refused_before_any_launch():
     """The ABI takes bare pointers; the binding refuses a frame whose shape or type does not match the network."""
     spec = wl.single_conv_relu(h=16, w=16, c=8, frames=2)
