@@ -493,9 +493,10 @@ def networks(streams: int, steps: int, warmup: int, target: float = 0.10):
         frames = [torch.from_numpy(vid[t]).cuda() for t in range(T)]
         maxpix = max(streams * h * w for h, w, _ in wl.node_shapes(spec))
 
-        def timed(eps, tune):
+        def timed(eps, tune, flags=5):
+            # flags: 1 = fused plan on one stream, 5 = independent branches on streams of their own as well
             ctx = pkg.Context(maxpix)
-            net = pkg.Net(ctx, fn(eps=eps, frames=T), weights, streams, 1)
+            net = pkg.Net(ctx, fn(eps=eps, frames=T), weights, streams, flags)
             net.init(frames[0])
             net.step(frames[1])
             if tune:
@@ -515,6 +516,7 @@ def networks(streams: int, steps: int, warmup: int, target: float = 0.10):
             return e0.elapsed_time(e1) / steps, dens, net.num_layers
 
         ms_sparse, dens, nlayers = timed(0.05, True)
+        ms_one_stream, _, _ = timed(0.05, True, flags=1)
         ms_all, _, _ = timed(-1.0, False)
         nodes = spec["nodes"]
         tw = {}
@@ -562,8 +564,10 @@ def networks(streams: int, steps: int, warmup: int, target: float = 0.10):
             torch.cuda.synchronize()
         ms_dense = e0.elapsed_time(e1) / steps
         rows.append({"network": name, "layers": nlayers, "conv_input_density": dens, "ms_sparse": ms_sparse,
+                     "ms_sparse_single_hip_stream": ms_one_stream,
                      "ms_all_propagated": ms_all, "ms_dense_library": ms_dense, "speedup_vs_dense_library": ms_dense / ms_sparse})
-        log(f"[bench] {name}: sparse {ms_sparse:.3f} ms (density {dens:.3f}), eps<0 {ms_all:.3f} ms, dense library {ms_dense:.3f} ms")
+        log(f"[bench] {name}: sparse {ms_sparse:.3f} ms (one HIP stream {ms_one_stream:.3f}; density {dens:.3f}), eps<0 {ms_all:.3f} ms, "
+            f"dense library {ms_dense:.3f} ms")
     return {"metric": "ms per frame of all streams, full-size networks at a tuned density budget", "unit": "ms", "n_gpus": 1,
             "steps": steps, "warmup": warmup, "higher_is_better": False, "dtype": "f16", "data": "synthetic",
             "config": {"workload": "BASELINE configs[2..4] at full size, random weights, per-layer thresholds tuned to "

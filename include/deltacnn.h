@@ -254,7 +254,11 @@ dcnn_status dcnn_net_add(dcnn_net* net, const dcnn_layer_desc* desc, const int32
                          const void* weights_dev, const void* bias_dev, int32_t* node_id);
 /* flags: bit 0 fuses conv -> (add) -> activation chains into one layer (otherwise every node is a
  * layer of its own); bit 1 makes every layer produce its output index list even when no consumer
- * reads it.  Reports the arena size. */
+ * reads it; bit 2 runs independent branches of the graph on up to three HIP streams (the context's own
+ * plus streams the network creates at dcnn_net_bind, all at the default priority; each gets a workspace
+ * of its own inside the arena; every dcnn_net_init / dcnn_net_step starts behind the work already on the
+ * context's stream and the context's stream continues behind all of them, so callers see one stream).
+ * Results do not depend on the flags.  Reports the arena size. */
 dcnn_status dcnn_net_finalize(dcnn_net* net, int32_t flags, size_t* arena_bytes);
 dcnn_status dcnn_net_bind(dcnn_net* net, void* arena_dev, size_t arena_bytes);
 /* First frame / later frames.  frame_dev: dense [n,h,w,c].  out_dev: dense output of the last

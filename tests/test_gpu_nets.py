@@ -710,6 +710,53 @@ def test_free_running_without_touching_the_state(eps):
     assert rel_err(to_np(out), ref, slack=free_running_slack(spec, ref, "f16")) <= tol
 
 
+def _small_hrnet():
+    spec = wl.hrnet_like(eps=0.05, h=96, w=64, frames=4)
+    spec["video"] = wl.VideoSpec(h=96, w=64, c=3, frames=4, n_objects=1, obj_kind="stick", obj_size=40, noise_sigma=0.01)
+    return spec
+
+
+def _small_resnet():
+    spec = wl.resnet50_backbone(eps=0.05, h=64, w=64, frames=4, stages=(2, 1, 1, 1))
+    spec["video"] = wl.VideoSpec(h=64, w=64, c=3, frames=4, n_objects=2, obj_kind="blob", obj_size=12, noise_sigma=0.02, drift=0.002)
+    return spec
+
+
+@pytest.mark.parametrize("spec_fn", [_small_hrnet, _small_resnet, lambda: wl.tiny_mixed_net(eps=0.05, dtype="f16"),
+                                     lambda: wl.tiny_concat_net(eps=0.05), lambda: wl.bottleneck_block(eps=0.08, h=40, w=48, frames=5)])
+@pytest.mark.parametrize("flags", [5, 6])
+def test_independent_branches_on_streams_of_their_own(spec_fn, flags):
+    """Finalize flag bit 2: independent branches run on up to three HIP streams with event dependencies.  The
+    same checks against the oracle as every other network (fused and unfused plans), and bit-identical dense
+    outputs and buffers to the single-stream run of the same plan -- a missing dependency shows as a difference."""
+    spec = spec_fn()
+    seed, B = 47, 2
+    r = _run_net(spec, seed, B, flags=flags)
+    lanes, wts = r["net"], wl.make_weights(spec, seed)
+    vid = wl.make_batch(spec["video"], seed, B).astype(NP_DTYPE[spec["dtype"]])
+    shapes = wl.node_shapes(spec)
+    ctx = pkg.Context(B * max(h * w for h, w, _ in shapes))
+    tdt = torch.float16 if spec["dtype"] == "f16" else torch.float32
+    outs = []
+    for fl in (flags, flags & 3):
+        for rep_ in range(2 if fl == flags else 1):               # the lanes twice: run-to-run identical as well
+            net = pkg.Net(ctx, spec, wts, B, fl)
+            out = torch.empty((B,) + shapes[-1], dtype=tdt, device="cuda")
+            per_frame = []
+            for t in range(vid.shape[0]):
+                (net.init if t == 0 else net.step)(torch.from_numpy(vid[t]).cuda(), out)
+                ctx.sync()
+                per_frame.append(out.clone())
+            states = [net.layer_state(li, w) for li in range(net.num_layers) for w in (0, 1)]
+            outs.append((per_frame, [None if s_ is None else s_.clone() for s_ in states]))
+    for other in outs[1:]:
+        for a, b in zip(outs[0][0], other[0]):
+            assert torch.equal(a, b), "dense outputs differ between stream layouts / runs"
+        for a, b in zip(outs[0][1], other[1]):
+            assert (a is None) == (b is None) and (a is None or torch.equal(a, b)), "buffers differ between stream layouts / runs"
+    del lanes
+
+
 def test_statistics_mode_counts_the_truncated_value_rows_a_step_touches():
     """dcnn_layer_set_counting: convolutions whose sparse steps skip all-zero x^T rows report the rows they read and
     wrote.  With negative thresholds every visited pixel updates, x^T stays zero: nothing is read or written.  With
