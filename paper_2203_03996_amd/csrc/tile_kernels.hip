@@ -199,6 +199,148 @@ __global__ __launch_bounds__(kTileThreads) void act_sparse_kernel(ListArgs l, Ac
     if (e.out_count && !e.surv && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
 }
 
+// ---- activation + truncation (+ add) of wide pixels on short lists -------------------------------------------
+// A pixel of 1024 .. 2048 channels fills a whole wave, so act_sparse_kernel walks the 8 entries of a run one or
+// two at a time: four dependent round trips to memory per run, on a handful of waves when the list holds a few
+// hundred pixels (the deep stages of a residual backbone: 38 us for 264 pixels of 2048 channels).  Here the four
+// waves of a workgroup split the CHANNELS of a run's pixels instead (one vector per lane and pixel), request all
+// 8 pixels at once -- one round trip -- and agree on the per-pixel maximum through LDS.  Arithmetic, rounding and
+// decisions are those of sparse_tile_tail (Section 3.1, Eqs. 4-6).  Channels a multiple of 4 vectors.
+constexpr int kWideRun = 8;                                     // list entries per workgroup unit (a quarter tile)
+
+template <typename T, int V, int VPW>
+__global__ __launch_bounds__(kTileThreads) void act_wide_kernel(ListArgs l, ActArgs a, EpilogueArgs e, uint32_t map_bytes, uint32_t pixels) {
+    typedef typename RawOf<T, V>::type Raw;
+    constexpr uint32_t ES = sizeof(T);
+    __shared__ float s_max[2][kWideRun][kTileWaves];
+    const int64_t count = list_count(l);
+    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const __amdgpu_buffer_rsrc_t rs_in = ws_rsrc(a.in_data, map_bytes), rs_res = ws_rsrc(e.res_data, map_bytes);
+    const __amdgpu_buffer_rsrc_t rs_xA = ws_rsrc(e.xA, map_bytes), rs_xT = ws_rsrc(e.xT, map_bytes);
+    const __amdgpu_buffer_rsrc_t rs_out = ws_rsrc(e.out_data, map_bytes), rs_omask = ws_rsrc(e.out_mask, pixels);
+    const __amdgpu_buffer_rsrc_t rs_rmask = ws_rsrc(e.res_mask, pixels), rs_imask = ws_rsrc(a.in_mask, pixels);
+    const int quarter = e.c / kTileWaves;                      // channels per wave
+    const int nvec_q = quarter / V;
+    const uint32_t row_bytes = (uint32_t)e.c * ES;
+    const bool stateful = e.act != DCNN_ACT_NONE;
+    const bool has_res = e.res_data != nullptr;
+    const float hi = act_hi(e.act);
+    const int64_t ntiles = (count + kTile - 1) / kTile;
+    const int64_t units = ntiles * (kTile / kWideRun);
+    int survivors = 0;
+    int parity = 0;
+    for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x, parity ^= 1) {
+        const int64_t tile = unit / (kTile / kWideRun);
+        const int part = (int)(unit - tile * (kTile / kWideRun));
+        const int64_t base = tile * kTile + part * kWideRun;
+        // entry lane % 8 of the run: pixel and the update flags of both streams (one round trip for the run)
+        const int p_mine = list_pixel(l.list, base + lane % kWideRun, count);
+        const int p_off = p_mine >= 0 ? p_mine : (int)kOob;
+        const int rflag_mine = e.res_mask ? __builtin_amdgcn_raw_buffer_load_b8(rs_rmask, p_off, 0, 0) : 1;
+        const int iflag_mine = a.in_mask ? __builtin_amdgcn_raw_buffer_load_b8(rs_imask, p_off, 0, 0) : 1;
+        int pix[kWideRun];
+        uint32_t off[kWideRun][VPW];
+        Raw rd[kWideRun][VPW], rr[kWideRun][VPW], ra[kWideRun][VPW], rt[kWideRun][VPW];
+#pragma unroll
+        for (int ub = 0; ub < kWideRun; ++ub) {
+            const int p = __shfl(p_mine, ub, kWave);
+            const int rf = __shfl(rflag_mine, ub, kWave), fi = __shfl(iflag_mine, ub, kWave);
+            pix[ub] = p;
+#pragma unroll
+            for (int v = 0; v < VPW; ++v) {
+                const int vi = lane + v * kWave;
+                const bool on = p >= 0 && vi < nvec_q;
+                const uint32_t o = on ? (uint32_t)p * row_bytes + (uint32_t)(wave * quarter + vi * V) * ES : kOob;
+                off[ub][v] = o;
+                rd[ub][v] = ws_load16<Raw>(rs_in, fi ? o : kOob);
+                rr[ub][v] = ws_load16<Raw>(rs_res, rf ? o : kOob);           // empty descriptor without a second stream
+                ra[ub][v] = ws_load16_nt<Raw>(rs_xA, o);                      // empty descriptors without an activation
+                rt[ub][v] = ws_load16_nt<Raw>(rs_xT, o);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        Raw o_a[kWideRun][VPW], o_t[kWideRun][VPW], o_y[kWideRun][VPW];
+        float umax[kWideRun];
+#pragma unroll
+        for (int ub = 0; ub < kWideRun; ++ub) {
+            float u = 0.0f;
+#pragma unroll
+            for (int v = 0; v < VPW; ++v) {
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    float d = raw_get<T, V>(rd[ub][v], i);
+                    if (has_res) d = round_store<T>(d + raw_get<T, V>(rr[ub][v], i));
+                    if (stateful) {
+                        const float xa = raw_get<T, V>(ra[ub][v], i), t = raw_get<T, V>(rt[ub][v], i);
+                        const float sum = (xa + t) + d;
+                        const float dy = act_clamp(sum, hi) - act_clamp(xa, hi);
+                        u = fmaxf(u, fabsf(dy));
+                        raw_set<T, V>(o_a[ub][v], i, sum);
+                        // x^T afterwards: the truncated sum, or -- if the pixel updates and keeps it -- x^A's rounding residue
+                        raw_set<T, V>(o_t[ub][v], i, t + d);
+                        raw_set<T, V>(o_y[ub][v], i, dy);
+                    } else {
+                        raw_set<T, V>(o_y[ub][v], i, d);
+                    }
+                }
+            }
+            if (stateful) u = group_max(u, kWave);
+            umax[ub] = u;
+        }
+        if (stateful) {
+            if (lane == 0) {
+#pragma unroll
+                for (int ub = 0; ub < kWideRun; ++ub) s_max[parity][ub][wave] = umax[ub];
+            }
+            lds_block_sync();           // (one barrier per unit: the buffers alternate, so a wave that runs ahead writes the other one)
+#pragma unroll
+            for (int ub = 0; ub < kWideRun; ++ub) {
+                float u = 0.0f;
+#pragma unroll
+                for (int q = 0; q < kTileWaves; ++q) u = fmaxf(u, s_max[parity][ub][q]);
+                umax[ub] = u;
+            }
+        }
+        uint32_t bits = 0;
+#pragma unroll
+        for (int ub = 0; ub < kWideRun; ++ub) {
+            const bool upd = stateful ? (umax[ub] >= e.eps) : true;
+#pragma unroll
+            for (int v = 0; v < VPW; ++v) {
+                const uint32_t o = off[ub][v];
+                if (stateful) {
+                    const uint32_t o_upd = upd ? o : kOob;
+                    Raw keep = raw_zero<T, V>();
+                    if (e.carry) {
+#pragma unroll
+                        for (int i = 0; i < V; ++i) {
+                            float d = raw_get<T, V>(rd[ub][v], i);
+                            if (has_res) d = round_store<T>(d + raw_get<T, V>(rr[ub][v], i));
+                            const float sum = (raw_get<T, V>(ra[ub][v], i) + raw_get<T, V>(rt[ub][v], i)) + d;
+                            raw_set<T, V>(keep, i, round_residue<T>(sum));
+                        }
+                    }
+                    ws_store16_nt<Raw>(rs_xA, o_upd, o_a[ub][v]);
+                    ws_store16_nt<Raw>(rs_xT, (upd && all_bits_zero(rt[ub][v]) && all_bits_zero(keep)) ? kOob : o, upd ? keep : o_t[ub][v]);
+                    ws_store16<Raw>(rs_out, o_upd, o_y[ub][v]);
+                } else {
+                    ws_store16<Raw>(rs_out, o, o_y[ub][v]);
+                }
+            }
+            const bool lead = pix[ub] >= 0 && lane == 0 && wave == 0;
+            if (stateful) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)(upd ? 1 : 0), rs_omask, lead ? pix[ub] : (int)kOob, 0, 0);
+            if (pix[ub] >= 0 && upd) bits |= 1u << (part * kWideRun + ub);
+        }
+        if (wave == 0 && tile * kTile < count) {               // (a run past the end of the list still clears its byte)
+            if (e.surv) { if (lane == 0) store_survivors(e.surv, tile, part, kTile / kWideRun, bits); }
+            else survivors += __popc(bits);
+        }
+    }
+    // one atomic per workgroup
+    if (e.out_count && !e.surv && wave == 0 && lane == 0 && survivors) atomicAdd(e.out_count, survivors);
+}
+
 // ---- activation + truncation (+ add) ----------------------------------------------------------
 template <typename T, int V, int VPL>
 __global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a, EpilogueArgs e, int init) {
@@ -236,6 +378,16 @@ static dcnn_status launch_act_t(dcnn_ctx* ctx, bool init, const ListArgs& l, con
     const int vpl = (int)cdiv(nvec, kWave);
     // sparse steps over vector channels, tensors below 2 GiB: the buffer-addressed kernel
     const uint64_t map_bytes = (uint64_t)(l.max_count > 0 ? l.max_count : 0) * e.c * sizeof(T);
+    // wide pixels on maps of at most 64 K pixels: the channels of a pixel are split over the waves of a workgroup
+    if (!init && vec && nvec >= 2 * kWave && nvec % kTileWaves == 0 && nvec <= kWave * kTileWaves && map_bytes > 0 &&
+        map_bytes <= kWsMaxBytes && l.max_count <= 65536) {
+        const int64_t units = cdiv(l.max_count, kWideRun);
+        const int64_t cap = (int64_t)ctx->num_cu * 8;
+        const int wgrid = (int)(units < cap ? units : cap);
+        const uint32_t mb = (uint32_t)map_bytes, px = (uint32_t)l.max_count;
+        hipLaunchKernelGGL((act_wide_kernel<T, VEC, 1>), dim3(wgrid), dim3(kTileThreads), 0, ctx->stream, l, a, e, mb, px);
+        return check_hip(ctx, hipGetLastError(), "act_wide_kernel launch");
+    }
     if (!init && vec && vpl <= 4 && map_bytes > 0 && map_bytes <= kWsMaxBytes) {
         const int vpl_used = vpl <= 1 ? 1 : (vpl <= 2 ? 2 : 4);
         const int ub = vpl_used == 4 ? 2 : 4;

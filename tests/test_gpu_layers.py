@@ -90,7 +90,9 @@ def test_deltagen(S, shape, r):
 @pytest.mark.parametrize("S", ["f32", "f16"])
 @pytest.mark.parametrize("f,carry", [("relu", False), ("relu6", False), ("relu", True)])
 @pytest.mark.parametrize("shape", [(1, 64, 64, 32), (2, 33, 29, 64), (1, 24, 24, 256), (1, 12, 12, 960),
-                                   (1, 10, 10, 2048), (1, 9, 11, 3), (1, 9, 11, 17), (1, 8, 8, 100)])
+                                   (1, 10, 10, 2048), (1, 9, 11, 3), (1, 9, 11, 17), (1, 8, 8, 100),
+                                   # wide pixels on short lists: the channels of a pixel are split over a workgroup's waves
+                                   (2, 9, 7, 1024), (1, 5, 5, 1536), (3, 6, 7, 512)])
 def test_act_trunc(S, f, carry, shape):
     """carry: the variant that leaves the rounding residue of x^A in x^T on an update (bit-exact like the rest)."""
     rng = np.random.default_rng(sum(shape) + len(f))
@@ -125,9 +127,9 @@ def test_act_trunc(S, f, carry, shape):
 
 @pytest.mark.parametrize("S", ["f32", "f16"])
 @pytest.mark.parametrize("act", ["relu", "none"])
-def test_add_act(S, act):
+@pytest.mark.parametrize("shape", [(2, 31, 30, 64), (2, 11, 9, 2048), (1, 13, 5, 1024)])
+def test_add_act(S, act, shape):
     rng = np.random.default_rng(17)
-    shape = (2, 31, 30, 64)
     n, h, w, c = shape
     eps = 0.4
     radd, ract = orc.Add(S), orc.ActTrunc(act, eps, S)
