@@ -411,24 +411,41 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         const unsigned char* my_stage = stage0 + (size_t)(slot * cs + spart) * stage_tile + (size_t)(ch_on ? vi : 0) * V * ES;
         int survivors = 0;
 
+        // Per-entry values (list entry, flags) are fetched ONCE per tile, entry lane % 32 per lane, and handed to the
+        // lanes that work on an entry by lane shuffles: a vector memory instruction costs its issue slots whatever it
+        // moves (a byte per lane as much as a quarter of a 16-byte access), and one per iteration added up to a
+        // sixth of this role's memory instructions.
         struct Tile {
-            int pix[NIT];          // pixel of iteration it (-1 beyond the list)
+            int pix_mine;          // pixel of entry lane % 32 (-1 beyond the list)
+            int rflag_mine;        // update flag of the residual stream at that pixel
+            int tflag_mine;        // 0: that pixel's x^T row is known to be all zero and is not read
+            int pix[NIT];          // pixel of iteration it
             uint32_t off[NIT];     // byte offset of this lane's channels (out of range: nothing to do)
-            uint8_t rflag[NIT];    // update flag of the residual stream
-            uint8_t tflag[NIT];    // 0: the pixel's x^T row is known to be all zero and is not read
+            uint8_t rflag[NIT];
+            uint8_t tflag[NIT];
         };
-        // derived values of a tile whose list entries have arrived; requests its residual flags
+        // derived values of a tile whose list entries have arrived; requests its flags
         auto prepare = [&](Tile& t) {
+            const int pm = t.pix_mine;
+            t.rflag_mine = 1;
+            if constexpr (RES) {
+                if (has_rmask) t.rflag_mine = __builtin_amdgcn_raw_buffer_load_b8(rs_rmask, pm >= 0 ? pm : (int)kOob, 0, 0);
+            }
+            t.tflag_mine = 1;
+            if (has_tflag) t.tflag_mine = __builtin_amdgcn_raw_buffer_load_b8(rs_tflag, pm >= 0 ? pm : (int)kOob, 0, 0);
 #pragma unroll
             for (int it = 0; it < NIT; ++it) {
-                const int p = t.pix[it];
+                const int p = __shfl(pm, ent0 + it * PPI, kWave);
+                t.pix[it] = p;
                 t.off[it] = (p >= 0 && ch_on) ? (uint32_t)p * row_bytes + ch_bytes : kOob;
-                t.rflag[it] = 1;
-                if constexpr (RES) {
-                    if (has_rmask) t.rflag[it] = __builtin_amdgcn_raw_buffer_load_b8(rs_rmask, p >= 0 ? p : (int)kOob, 0, 0);
-                }
-                t.tflag[it] = 1;
-                if (has_tflag) t.tflag[it] = __builtin_amdgcn_raw_buffer_load_b8(rs_tflag, p >= 0 ? p : (int)kOob, 0, 0);
+            }
+        };
+        // the flags have arrived: hand them to the lanes of each iteration
+        auto resolve = [&](Tile& t) {
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                t.rflag[it] = (uint8_t)__shfl(t.rflag_mine, ent0 + it * PPI, kWave);
+                t.tflag[it] = (uint8_t)__shfl(t.tflag_mine, ent0 + it * PPI, kWave);
             }
         };
         // x^A, x^T and the dense output O are touched once per frame: they stream past the caches (non-temporal), which
@@ -510,19 +527,6 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     ws_store16<Raw>(rs_out, o, d);
                 }
                 const bool lead = t.pix[it] >= 0 && sub == 0;
-                // The output mask arrives holding 1 at every listed pixel (the dilated flags, or a copy of the input's
-                // mask), so only truncated pixels are written; and a store instruction that no lane needs is not
-                // issued at all -- the vector memory pipeline is what this kernel queues on.
-                const bool clear = lead && !upd;
-                if (has_omask && __builtin_amdgcn_ballot_w64(clear))
-                    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)0, rs_omask, clear ? t.pix[it] : (int)kOob, 0, 0);
-                if constexpr (decltype(sf)::value) {
-                    // after an update the row is zero again (unless it keeps residues); after a truncation it holds values
-                    const uint8_t keep = (upd && !carry) ? 0 : 1;
-                    const bool change = lead && keep != t.tflag[it];
-                    if (has_tflag && __builtin_amdgcn_ballot_w64(change))
-                        __builtin_amdgcn_raw_buffer_store_b8(keep, rs_tflag, change ? t.pix[it] : (int)kOob, 0, 0);
-                }
                 if (lead && upd) bits |= 1u << (ent0 + it * PPI);
             }
             return bits;
@@ -532,17 +536,17 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
             // Software pipeline.  List entries are requested two tiles ahead, residual flags one tile ahead,
             // and over the sets of consecutive tiles: while set s is finished, the loads of set s+1 (issued
             // one step earlier) and of set s+2 (issued right after) are in flight.
+            constexpr bool carry = decltype(cf)::value;
+            const int my_first = part * (kTile / cs), my_end = my_first + kTile / cs;    // tile entries this wave owns
             Tile cur, nxt;
-            int pix_nn[NIT];
-    #pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                cur.pix[it] = list_entry(0, ent0 + it * PPI);
-                nxt.pix[it] = list_entry(1, ent0 + it * PPI);
-                pix_nn[it] = list_entry(2, ent0 + it * PPI);
-            }
+            int pix_nn;
+            cur.pix_mine = list_entry(0, lane % kTile);
+            nxt.pix_mine = list_entry(1, lane % kTile);
+            pix_nn = list_entry(2, lane % kTile);
             load_weights();
             prepare(cur);
             prepare(nxt);
+            resolve(cur);
             Set set0, set1;
             load_set(sf, cur, 0, set0);
             load_set(sf, cur, 1, set1);
@@ -554,12 +558,28 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
     #pragma unroll
                 for (int s = 0; s < NS; s += 2) {
                     bits |= finish_set(sf, cf, cur, s, set0, tile_stage);
+                    if (s + 2 == NS) resolve(nxt);                 // (its flags were requested a round ago)
                     if (s + 2 < NS) load_set(sf, cur, s + 2, set0); else load_set(sf, nxt, s + 2 - NS, set0);
                     bits |= finish_set(sf, cf, cur, s + 1, set1, tile_stage);
                     if (s + 3 < NS) load_set(sf, cur, s + 3, set1); else load_set(sf, nxt, s + 3 - NS, set1);
                 }
     #pragma unroll
                 for (int m = kWave >> 1; m >= 1; m >>= 1) bits |= __shfl_xor(bits, m, kWave);
+                if constexpr (decltype(sf)::value) {
+                    // Flags of the tile's entries, one store instruction each and only if some lane needs it (entry
+                    // `lane` by lane `lane`).  The output mask arrives holding 1 at every listed pixel (the dilated
+                    // flags, or a copy of the input's mask), so only truncated pixels are written.  x^T row flag: after
+                    // an update the row is zero again (unless it keeps residues), after a truncation it holds values.
+                    const bool mine = lane >= my_first && lane < my_end && cur.pix_mine >= 0;
+                    const bool upd_e = (bits >> (lane & 31)) & 1u;
+                    const bool clear = mine && !upd_e;
+                    if (has_omask && __builtin_amdgcn_ballot_w64(clear))
+                        __builtin_amdgcn_raw_buffer_store_b8((uint8_t)0, rs_omask, clear ? cur.pix_mine : (int)kOob, 0, 0);
+                    const int keep = (upd_e && !carry) ? 0 : 1;
+                    const bool change = mine && keep != cur.tflag_mine;
+                    if (has_tflag && __builtin_amdgcn_ballot_w64(change))
+                        __builtin_amdgcn_raw_buffer_store_b8((uint8_t)keep, rs_tflag, change ? cur.pix_mine : (int)kOob, 0, 0);
+                }
                 const int64_t tile = tile_of(rd - 1);
                 if (tile * kTile < count) {
                     if (e.surv) {
@@ -574,11 +594,8 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     }
                 }
                 cur = nxt;
-    #pragma unroll
-                for (int it = 0; it < NIT; ++it) {
-                    nxt.pix[it] = pix_nn[it];
-                    pix_nn[it] = list_entry(rd + 2, ent0 + it * PPI);
-                }
+                nxt.pix_mine = pix_nn;
+                pix_nn = list_entry(rd + 2, lane % kTile);
                 prepare(nxt);
                 lds_block_sync();
             }
