@@ -97,13 +97,27 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
 
     // The weights travel global -> LDS once per workgroup.  Every wave calls this exactly once, right after it
     // has requested the list entries of its first tiles, so that round trip hides behind the copy.
-    auto load_weights = [&]() {
-        const Vec* wglob = static_cast<const Vec*>(c.wpacked);
-        for (int i = threadIdx.x; i < w1_vecs; i += kWsWaves * kWave) w_lds[i] = wglob[i];
-        if constexpr (DUAL) {
-            const Vec* wglob2 = static_cast<const Vec*>(c.wpacked2);
-            for (int i = threadIdx.x; i < w2_vecs; i += kWsWaves * kWave) w_lds[w1_vecs + i] = wglob2[i];
+    // Four loads are in flight per lane before the first is stored: the copy costs a couple of memory round trips
+    // instead of one per 16 KiB, which counts in a kernel that runs for ten rounds.
+    auto copy_weights = [&](const Vec* src, Vec* dst, int n) {
+        constexpr int B = 4, TH = kWsWaves * kWave;
+        for (int i0 = threadIdx.x; i0 < n; i0 += B * TH) {
+            Vec v[B];
+#pragma unroll
+            for (int u = 0; u < B; ++u) {
+                const int i = i0 + u * TH;
+                v[u] = src[i < n ? i : n - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < B; ++u) {
+                const int i = i0 + u * TH;
+                if (i < n) dst[i] = v[u];
+            }
         }
+    };
+    auto load_weights = [&]() {
+        copy_weights(static_cast<const Vec*>(c.wpacked), w_lds, w1_vecs);
+        if constexpr (DUAL) copy_weights(static_cast<const Vec*>(c.wpacked2), w_lds + w1_vecs, w2_vecs);
         lds_block_sync();
     };
 
