@@ -439,9 +439,12 @@ def drift_study(streams: int, frames: int):
     rows = []
     checkpoints = [c for c in (100, 500, 1000, 2000, 5000) if c <= frames]
     for eps in (0.02, 0.05):
-        for no_xT in (False, True):
+        # x^T as in Eqs. 5-6; no x^T at all (Section 6); x^T that also keeps the storage rounding residue of x^A
+        for no_xT, residue in ((False, False), (True, False), (False, True)):
             for period in (0, 500, 100):
-                spec = wl.bottleneck_block(eps=eps, frames=T, no_xT=no_xT)
+                if residue and period:
+                    continue
+                spec = wl.bottleneck_block(eps=eps, frames=T, no_xT=no_xT, xT_residue=residue)
                 ctx = pkg.Context(streams * 128 * 128)
                 net = pkg.Net(ctx, spec, weights, streams, 1)
                 out = torch.empty((streams, 128, 128, 256), dtype=torch.float16, device="cuda")
@@ -461,9 +464,9 @@ def drift_study(streams: int, frames: int):
                         if t in checkpoints:
                             errs[t] = worst
                             worst = 0.0
-                rows.append({"eps": eps, "x_T": not no_xT, "reset_every": period,
+                rows.append({"eps": eps, "x_T": not no_xT, "xT_residue": residue, "reset_every": period,
                              "max_rel_err_up_to_frame": {str(k): v for k, v in errs.items()}})
-                log(f"[bench] drift eps {eps} x_T {not no_xT} reset {period}: " + " ".join(f"{k}:{v:.3g}" for k, v in errs.items()))
+                log(f"[bench] drift eps {eps} x_T {not no_xT} residue {residue} reset {period}: " + " ".join(f"{k}:{v:.3g}" for k, v in errs.items()))
     return {"metric": "max relative error of the dense output vs dense inference over a long run", "unit": "max|out-dense|/max|dense|",
             "n_gpus": 1, "higher_is_better": False, "dtype": "f16", "data": "synthetic",
             "config": {"workload": "drift study: bottleneck block 128x128 fp16, looped 16-frame clip + 0.0005/frame brightness drift",

@@ -132,6 +132,7 @@ dcnn_status launch_xt_row_count(dcnn_ctx* ctx, int phase, const ListArgs& l, con
 struct ConvArgs {
     const void* in_data;
     const uint8_t* in_mask;      // nullptr: every in-bounds pixel is flagged (first frame)
+    const int32_t* in_count;     // optional, device: number of flagged input pixels (how dense the window taps are)
     const void* wpacked;
     const void* zero_page;       // >= 16 bytes of zeros: what lanes read instead of an unflagged / padded input
     int n, h, w, cin, oh, ow, cout, cout_pad, k, stride, pad, kch;

@@ -597,6 +597,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         case DCNN_DWCONV: {
             ConvArgs c{};
             c.in_data = in[0]->data; c.in_mask = in[0]->mask; c.wpacked = L->wpacked; c.zero_page = L->counters;
+            c.in_count = in[0]->count;
             c.n = d.n; c.h = d.h; c.w = d.w; c.cin = d.c; c.oh = L->oh; c.ow = L->ow; c.cout = L->oc;
             c.k = d.kh; c.stride = d.stride; c.pad = d.pad; c.depthwise = d.kind == DCNN_DWCONV;
             EpilogueArgs e{};

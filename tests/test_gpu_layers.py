@@ -264,6 +264,32 @@ def test_conv3x3_row_gathers_on_structured_masks(pattern, nhw):
     check_delta(out, want, S, f"row gathers, {pattern}", slack=sum_slack(ref, d.zero_filled()))
 
 
+@pytest.mark.parametrize("pattern", ["all", "holes", "sevenths"])
+@pytest.mark.parametrize("S,cin,cout", [("f16", 128, 128), ("f32", 64, 128)])
+def test_conv3x3_row_gathers_on_the_register_blocked_kernel(S, cin, cout, pattern):
+    """The same window-row gathers on a layer whose weights do not fit LDS, with a list long enough for several
+    pixel tiles per wave (more than 65,536 entries) and at least three quarters of all window taps flagged: three
+    tiles per wave, left / right taps from neighbouring lanes, the tiles' edge columns fetched separately."""
+    nhw = (5, 128, 136)
+    rng = np.random.default_rng(len(pattern) * 11 + cin)
+    n, h, w = nhw
+    ctx, layer, ref = _conv_layers(S, 3, 1, 1, cin, cout, nhw, rng)
+    x0 = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
+    ref.init(x0)
+    layer.init([torch.from_numpy(x0).cuda()])
+    yy, xx = np.meshgrid(np.arange(h), np.arange(w), indexing="ij")
+    mask2d = {"all": xx >= 0, "holes": (xx * 7 + yy * 13) % 11 != 0, "sevenths": (xx * 5 + yy * 3) % 7 != 0}[pattern]
+    mask = np.broadcast_to(mask2d, (n, h, w)).astype(np.uint8).copy()
+    mask[-1, h - 9:, : w // 3] = 0                       # a corner of the last image without any flag
+    data = rng.normal(0, 1, (n, h, w, cin)).astype(NP_DTYPE[S])
+    d = ODelta(data, mask).poisoned()
+    want = ref.step(d).poisoned()
+    out = layer.step([_upload(d)])
+    ctx.sync()
+    assert want.count > 65536 and d.count * 4 >= want.count * 3, "long list, at least three quarters of the taps flagged"
+    check_delta(out, want, S, f"row gathers, register-blocked, {pattern}", slack=sum_slack(ref, d.zero_filled()))
+
+
 @pytest.mark.parametrize("S,k,stride,cin,cout,nhw,res", [
     # streamed weights, long lists, fused tail: two waves per tile with a residual, four waves per tile, three
     # column blocks per wave in fp32
