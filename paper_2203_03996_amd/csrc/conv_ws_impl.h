@@ -10,7 +10,8 @@
 //   consumers (waves 8-15)  pick the tile of the PREVIOUS round up from LDS, apply residual /
 //                           activation / truncation (Section 3.1, Eqs. 4-6), and write state, output
 //                           delta, update mask and survivor word with coalesced 16-byte accesses.
-// The result tiles are double-buffered, so one workgroup barrier per round is the only coupling.
+// The result tiles are double-buffered and handed over per tile slot through two LDS counters (tiles staged /
+// tiles consumed), so a slot's producers and consumers wait for each other only, never for the whole workgroup.
 // Each role needs at most 128 registers: four waves per SIMD, and while the consumers wait for
 // HBM the producers keep the matrix cores and the L2 busy.
 //
@@ -37,6 +38,8 @@ namespace dcnn {
 
 constexpr int kWsProducers = 8;
 constexpr int kWsWaves = 16;
+constexpr int kWsSyncBytes = 64;                               // hand-over counters: tiles staged / tiles consumed, per tile slot
+constexpr int kWsSpinLimit = 1 << 22;                          // polls after which a wait gives up (never reached: see hand_over)
 constexpr int kTapProj = 30;                                   // bit of a tap word: the projection's input pixel is flagged
 
 constexpr int ws_pow2_ceil(int v) { int p = 1; while (p < v) p <<= 1; return p; }
@@ -48,7 +51,7 @@ inline size_t conv_ws_lds_bytes(const ConvPlan& p, int dtype, int k, int cout, i
     const int lpb = ws_pow2_ceil(p.nb * 32 / vec);
     if (p.cs * lpb > kWave) return 0;
     const size_t w2_bytes = (size_t)cdiv(cin2, dtype == DCNN_F16 ? 16 : 8) * 2 * p.cout_pad * 16;   // projection weights
-    const size_t bytes = p.w_bytes + w2_bytes + 2 * conv_stage_bytes(kWsProducers, p.nb, dtype);
+    const size_t bytes = p.w_bytes + w2_bytes + 2 * conv_stage_bytes(kWsProducers, p.nb, dtype) + kWsSyncBytes;
     return bytes <= kLdsBytes ? bytes : 0;
 }
 
@@ -91,6 +94,26 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
     constexpr int stage_stride = COLS * ES + kStagePad;
     constexpr int stage_tile = kTile * stage_stride;
     unsigned char* stage0 = smem + (size_t)w_vecs * 16;        // [2][NP][32 pixels][stage_stride]
+    // Hand-over of result tiles.  A tile slot is the business of its cs producers and cs consumers only, so instead of
+    // a workgroup barrier per round (every wave waiting for the slowest of sixteen, round after round) each slot keeps
+    // two counters in LDS: `staged` (bumped by a producer once its slice of a tile is in the staging buffer) and
+    // `consumed` (bumped by a consumer once it has read its pixels of a tile).  A consumer starts tile r when staged
+    // >= cs*(r+1); a producer overwrites the buffer of tile r-2 when consumed >= cs*(r-1).  Tiles 0 and 1 need no
+    // wait, every wave bumps its counter once per tile, so by induction over r every wait ends; the poll limit only
+    // bounds the damage of a programming error (a kernel that gives wrong results instead of one that never ends).
+    uint32_t* staged_ctr = reinterpret_cast<uint32_t*>(stage0 + (size_t)2 * NP * stage_tile) + slot;
+    uint32_t* consumed_ctr = staged_ctr + kWsProducers;
+    auto bump = [&](uint32_t* ctr) {
+        // release at workgroup scope: this wave's LDS accesses so far are complete before the counter moves
+        if (lane == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto await = [&](uint32_t* ctr, int target) {
+        if (target <= 0) return;
+        for (int spin = 0; spin < kWsSpinLimit; ++spin) {
+            if ((int)__hip_atomic_load(ctr, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) return;
+            __builtin_amdgcn_s_sleep(2);
+        }
+    };
     // pixel of entry `j` of the work list of round `rd` (this wave's tile), -1 beyond the list
     auto tile_of = [&](int rd) { return (r.begin + (int64_t)rd * r.step) * tiles_per_iter + slot; };
     auto list_entry = [&](int rd, int j) { return rd < rounds ? list_pixel(l.list, tile_of(rd) * kTile + j, count) : -1; };
@@ -118,10 +141,11 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
     auto load_weights = [&]() {
         copy_weights(static_cast<const Vec*>(c.wpacked), w_lds, w1_vecs);
         if constexpr (DUAL) copy_weights(static_cast<const Vec*>(c.wpacked2), w_lds + w1_vecs, w2_vecs);
+        if (threadIdx.x < 2 * kWsProducers) reinterpret_cast<uint32_t*>(stage0 + (size_t)2 * NP * stage_tile)[threadIdx.x] = 0u;
         lds_block_sync();
     };
 
-    // Both roles pass the same number of workgroup barriers: the weight copy, then one per round 0..rounds.
+    // The only workgroup barrier is the one behind the weight copy; after it the roles meet through the counters.
     if (producer) {
         // =====================================================================================
         // producer: tile -> gathered taps x weights -> rounded result tile in LDS
@@ -176,8 +200,13 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
         const Vec* wbase = w_lds + ((size_t)part * ksteps * 2 + g) * COLS + col;
         const Vec* wbase2 = w_lds + w1_vecs + ((size_t)part * (DUAL ? c.kch2 : 0) * 2 + g) * COLS + col;
 
-        for (int rd = 0; rd <= rounds; ++rd) {
-            if (rd < rounds) {
+        for (int rd = 0; rd < rounds; ++rd) {
+            {
+                bool buffer_free = false;                          // this tile's staging buffer has been waited for
+                auto claim_buffer = [&]() {
+                    if (!buffer_free) await(consumed_ctr, cs * (rd - 1));
+                    buffer_free = true;
+                };
                 // byte offset of this lane's 16 bytes in tap (0,0), K-step 0
                 const int p32_cur = p32_next;
                 const uint32_t base00 = (uint32_t)origin(p32_cur) * (uint32_t)cin_bytes + (uint32_t)g * 16u;
@@ -246,6 +275,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                             // The main result waits, rounded to the storage type, in the staging tile while
                             // the accumulators are reused: both results are rounded before they are added,
                             // as if each had been stored.
+                            claim_buffer();
                             stage_accumulators<T, NB, false>(acc, tile_row, g);
 #pragma unroll
                             for (int b = 0; b < NB; ++b)
@@ -382,10 +412,11 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     }
                 }
                 }
+                claim_buffer();
                 if (main_staged) stage_accumulators<T, NB, true>(acc, tile_row, g);
                 else stage_accumulators<T, NB, false>(acc, tile_row, g);
+                bump(staged_ctr);
             }
-            lds_block_sync();
         }
     } else {
         // =====================================================================================
@@ -564,10 +595,10 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
             Set set0, set1;
             load_set(sf, cur, 0, set0);
             load_set(sf, cur, 1, set1);
-            lds_block_sync();                                      // round 0: the producers fill the first tiles
             for (int rd = 1; rd <= rounds; ++rd) {
                 // `cur` is the tile produced in round rd-1, `nxt` the one being produced now
                 const unsigned char* tile_stage = my_stage + (size_t)(((rd - 1) & 1) * NP) * stage_tile;
+                await(staged_ctr, cs * rd);
                 uint32_t bits = 0;
     #pragma unroll
                 for (int s = 0; s < NS; s += 2) {
@@ -577,6 +608,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                     bits |= finish_set(sf, cf, cur, s + 1, set1, tile_stage);
                     if (s + 3 < NS) load_set(sf, cur, s + 3, set1); else load_set(sf, nxt, s + 3 - NS, set1);
                 }
+                bump(consumed_ctr);                                // (every row of the tile has been read from LDS)
     #pragma unroll
                 for (int m = kWave >> 1; m >= 1; m >>= 1) bits |= __shfl_xor(bits, m, kWave);
                 if constexpr (decltype(sf)::value) {
@@ -611,7 +643,6 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
                 nxt.pix_mine = pix_nn;
                 pix_nn = list_entry(rd + 2, lane % kTile);
                 prepare(nxt);
-                lds_block_sync();
             }
         };
         // layers with an activation keep state (x^A, x^T) and truncate; linear ones pass the delta on
