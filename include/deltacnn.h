@@ -70,7 +70,7 @@ typedef struct {
     void*    data;          /* [n,h,w,c] NHWC                                      */
     uint8_t* mask;          /* [n,h,w], 0/1                                         */
     int32_t* idx;           /* ascending flagged pixel indices, first *count valid  */
-    int32_t* count;         /* number of flagged pixels                             */
+    int32_t* count;         /* number of flagged pixels; NULL where it is not produced (see want_idx) */
     int32_t  n, h, w, c;
     int32_t  dtype;         /* dcnn_dtype                                           */
 } dcnn_delta;
@@ -101,7 +101,8 @@ typedef struct {
     int32_t n_in;
     int32_t dilate_r;
     int32_t factor;
-    int32_t want_idx;       /* 0: the output's idx/count need not be produced (no consumer reads them) */
+    int32_t want_idx;       /* 0: the output's idx/count need not be produced (no consumer reads them): a layer with
+                             * an activation then hands out count = NULL, and dcnn_layer_stats counts its mask */
     /* Optional fused projection shortcut (CONV with activation and n_in == 2 only; 0 = none): input 1 is
      * then not a residual of the output shape but the [n, proj_h, proj_w, proj_c] input of a 1x1
      * convolution (stride proj_stride, no padding, proj_c -> cout) whose result is added before the

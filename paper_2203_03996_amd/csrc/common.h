@@ -89,6 +89,8 @@ hipError_t static_scratch_setup(int dev);
 dcnn_status launch_emit_sublist(dcnn_ctx* ctx, const int32_t* list, const int32_t* count, int64_t max_count,
                                 const uint32_t* surv, int32_t* idx_out, int32_t* count_out);
 dcnn_status launch_fill_i32(dcnn_ctx* ctx, int32_t* p, int32_t v, int64_t n);
+// Statistics (never on a timed path): *out = number of non-zero bytes among mask[0 .. pixels).
+dcnn_status launch_mask_sum(dcnn_ctx* ctx, const uint8_t* mask, int64_t pixels, int32_t* out);
 // flags[p] = 1 iff row p of `data` ([pixels, c] elements) has a non-zero bit.
 dcnn_status launch_row_flags(dcnn_ctx* ctx, int dtype, const void* data, uint8_t* flags, int64_t pixels, int c);
 dcnn_status launch_fill_u8(dcnn_ctx* ctx, uint8_t* p, uint8_t v, int64_t n);

@@ -290,8 +290,10 @@ __global__ __launch_bounds__(kDirectWaves* kWave, 2) void conv_direct_kernel(Lis
             // of (up to) nine listed outputs, so flagged inputs / listed outputs IS the mean fraction of flagged taps
             // per window.  Measured on 3x3 128->128, 256x256 maps, uniform-random masks: all taps flagged 0.40 ->
             // 0.30 ms, half of them 0.231 -> 0.243 ms, a tenth 0.127 -> 0.156 ms; hence three quarters.
-            const int64_t in_count = c.in_count ? (int64_t)*c.in_count : 0;
-            if (c.stride == 1 && c.pad == 1 && in_count * 4 >= count * 3) {
+            // (an input that comes without a count: the rule of the resident-weight kernel, most of the map listed)
+            const bool dense_taps = c.in_count ? (int64_t)*c.in_count * 4 >= count * 3
+                                               : count * 4 >= (int64_t)c.n * c.oh * c.ow * 3;
+            if (c.stride == 1 && c.pad == 1 && dense_taps) {
                 conv_direct_body<T, NB, KS, (TI > 3 ? 3 : TI), 2, true>(l, c, e, npass, cs, count, smem);   // 3 tiles: two operand sets of 12 vectors fit beside 96 accumulators
                 return;
             }

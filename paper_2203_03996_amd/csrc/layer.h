@@ -42,6 +42,8 @@ struct dcnn_layer {
     const int32_t* last_in_count;
     const int32_t* last_work_count;
     const int32_t* last_in2_count;
+    const uint8_t* last_in_mask;        // for statistics of inputs that come without a count
+    const uint8_t* last_in2_mask;
     // optional kernel timing
     std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
     size_t events_used = 0;

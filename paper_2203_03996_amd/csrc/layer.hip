@@ -191,12 +191,13 @@ static void carve(dcnn_layer* L, void* state) {
 
 // the block that holds a layer's output count also holds, 64 bytes in, two 64-bit counters of x^T vectors read / written
 constexpr int kXtIoOffset = 16;                                  // in int32 units
+constexpr int kStatsScratchOffset = 8;                           // where dcnn_layer_stats counts a mask that came without a count
 
 static dcnn_status clear_sparse_output(dcnn_layer* L) {
     if (L->alias_mask) return DCNN_OK;
     dcnn_status st = launch_fill_u8(L->ctx, L->out_mask, 0, (int64_t)align_up((size_t)L->out_pixels, 4));
     if (st != DCNN_OK) return st;
-    st = launch_fill_i32(L->ctx, L->out_count, 0, kXtIoOffset + 4);     // the count and the x^T row counters behind it
+    st = launch_fill_i32(L->ctx, L->out_count, 0, kXtIoOffset + 4);     // the count, the statistics scratch and the x^T row counters behind it
     if (st != DCNN_OK) return st;
     if (L->list_count && L->list_count != L->out_count) st = launch_fill_i32(L->ctx, L->list_count, 0, 1);
     return st;
@@ -496,6 +497,8 @@ dcnn_status dcnn_layer_init(dcnn_layer* L, const void* const* dense_in, int32_t 
     L->inited = true;
     L->last_in_count = nullptr;
     L->last_in2_count = nullptr;
+    L->last_in_mask = nullptr;
+    L->last_in2_mask = nullptr;
     L->last_work_count = nullptr;
     L->view = dcnn_delta{};
     return DCNN_OK;
@@ -527,9 +530,14 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
     v.data = d.fuse_accum ? L->buf2 : L->out_data;
     v.mask = L->alias_mask ? in[0]->mask : L->out_mask;
     v.idx = L->alias_mask ? in[0]->idx : L->out_idx;
-    v.count = L->alias_mask ? in[0]->count : L->out_count;
+    // A layer with an activation whose output list nobody walks (want_idx == 0) does not count its flagged outputs:
+    // atomics on one counter are served one after the other (~2.4 ns each; a few thousand waves adding their share at
+    // the end of a kernel cost 10-20 us), and nothing on a step's path needs the number.  Statistics count the mask.
+    v.count = L->alias_mask ? in[0]->count : ((act && !d.want_idx) ? nullptr : L->out_count);
     L->last_in_count = in[0]->count;
     L->last_in2_count = n_in == 2 ? in[1]->count : nullptr;
+    L->last_in_mask = in[0]->mask;
+    L->last_in2_mask = n_in == 2 ? in[1]->mask : nullptr;
 
     if (d.kind == DCNN_DELTAGEN) {
         DeltaGenArgs a{};
@@ -561,7 +569,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         m.mask_out = L->out_mask; m.idx_out = L->list; m.count_out = L->list_count;
         m.n = d.n; m.h = d.h; m.w = d.w; m.oh = L->oh; m.ow = L->ow;
         m.k = 1; m.stride = 1; m.pad = 0; m.up = 1; m.emit_only = 0;
-        m.zero_count = (act && !d.want_idx) ? L->out_count : nullptr;
+        m.zero_count = nullptr;
         if (d.kind == DCNN_CONV || d.kind == DCNN_DWCONV || d.kind == DCNN_MAXPOOL) { m.k = d.kh; m.stride = d.stride; m.pad = d.pad; }
         if (d.kind == DCNN_UPSAMPLE || d.kind == DCNN_UPSAMPLE_BILINEAR) { m.up = d.factor; m.bilinear = d.kind == DCNN_UPSAMPLE_BILINEAR; }
         if (d.kind == DCNN_GAVGPOOL) { m.k = d.h; m.kw = d.w; m.pad_w = 0; }   // one window over the whole map
@@ -579,7 +587,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             MaskPassArgs m{};
             m.mask_in = in[0]->mask; m.mask_out = L->out_mask; m.idx_out = nullptr;
             m.n = d.n; m.h = d.h; m.w = d.w; m.oh = L->oh; m.ow = L->ow; m.k = 1; m.stride = 1; m.pad = 0; m.up = 1;
-            m.zero_count = !d.want_idx ? L->out_count : nullptr;
+            m.zero_count = nullptr;
             st = launch_mask_compact(ctx, m);
             if (st != DCNN_OK) return st;
         }
@@ -621,7 +629,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             }
             e.out_mask = act ? L->out_mask : nullptr;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;
-            e.out_count = (act && !d.want_idx) ? L->out_count : nullptr;
+            e.out_count = nullptr;                                 // (see the output view above)
             // statistics mode: which x^T rows the kernel will read, and afterwards which it wrote
             const bool counting = L->counting && L->xt_flags && L->out_count && !timed;
             unsigned long long* io = counting ? reinterpret_cast<unsigned long long*>(L->out_count + kXtIoOffset) : nullptr;
@@ -644,7 +652,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             e.carry = d.xT_residue;
             e.out_mask = act ? L->out_mask : nullptr;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;
-            e.out_count = (act && !d.want_idx) ? L->out_count : nullptr;
+            e.out_count = nullptr;                                 // (see the output view above)
             st = launch_act(ctx, d.dtype, false, l, a, e);
             break;
         }
@@ -702,7 +710,8 @@ dcnn_status dcnn_layer_output(const dcnn_layer* L, dcnn_delta* out_view) {
         dcnn_delta v{};
         v.n = L->d.n; v.h = L->oh; v.w = L->ow; v.c = L->oc; v.dtype = L->d.dtype;
         v.data = L->d.kind == DCNN_ACCUM ? L->buf0 : (L->d.fuse_accum ? L->buf2 : L->out_data);
-        v.mask = L->out_mask; v.idx = L->out_idx; v.count = L->out_count;
+        v.mask = L->out_mask; v.idx = L->out_idx;
+        v.count = (has_act(L->d) && !L->d.want_idx) ? nullptr : L->out_count;
         *out_view = v;
         return DCNN_OK;
     }
@@ -731,13 +740,21 @@ dcnn_status dcnn_layer_stats(dcnn_layer* L, dcnn_stats* s) {
         *dst = v;
         return r;
     };
-    st = read(L->last_in_count, &s->pixels_in);
-    if (st == DCNN_OK) st = read(L->last_in2_count, &s->pixels_in2);
-    if (st == DCNN_OK) st = read(L->last_work_count, &s->pixels_work);
-    if (st == DCNN_OK) st = read(L->view.count, &s->pixels_out);
     s->pixels_total = L->out_pixels;
     s->pixels_in_total = L->in_pixels;
     s->pixels_in2_total = L->d.n_in == 2 ? (L->d.proj_c > 0 ? (int64_t)L->d.n * L->d.proj_h * L->d.proj_w : L->out_pixels) : 0;
+    // an update that comes without a count (see dcnn_layer_step): its mask is counted here, off every step's path
+    int32_t* scratch = L->out_count ? L->out_count + kStatsScratchOffset : nullptr;
+    auto read_or_count = [&](const int32_t* p, const uint8_t* mask, int64_t pixels, int64_t* dst) -> dcnn_status {
+        if (p || !mask || !scratch) return read(p, dst);
+        dcnn_status r = launch_mask_sum(ctx, mask, pixels, scratch);
+        if (r == DCNN_OK) r = check_hip(ctx, hipStreamSynchronize(ctx->stream), "hipStreamSynchronize");
+        return r == DCNN_OK ? read(scratch, dst) : r;
+    };
+    st = read_or_count(L->last_in_count, L->last_in_mask, s->pixels_in_total, &s->pixels_in);
+    if (st == DCNN_OK) st = read_or_count(L->last_in2_count, L->last_in2_mask, s->pixels_in2_total, &s->pixels_in2);
+    if (st == DCNN_OK) st = read(L->last_work_count, &s->pixels_work);
+    if (st == DCNN_OK) st = read_or_count(L->view.count, L->view.mask, L->out_pixels, &s->pixels_out);
     s->kind = L->d.kind; s->act = L->d.act; s->n_in = L->d.n_in;
     s->c_in = L->d.c; s->c_out = L->oc;
     const bool window = L->d.kind == DCNN_CONV || L->d.kind == DCNN_DWCONV || L->d.kind == DCNN_MAXPOOL;

@@ -531,6 +531,24 @@ __global__ __launch_bounds__(kMaskThreads) void xt_row_count_kernel(int phase, L
     if (threadIdx.x == 0 && total) atomicAdd(io + phase, (unsigned long long)total);
 }
 
+// ---- statistics: flagged pixels of a mask whose producer keeps no count -------------------------------------
+__global__ __launch_bounds__(256) void mask_sum_kernel(const uint8_t* mask, int64_t pixels, int32_t* out) {
+    int mine = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < pixels; i += (int64_t)gridDim.x * blockDim.x)
+        mine += mask[i] != 0;
+    for (int m = kWave >> 1; m >= 1; m >>= 1) mine += __shfl_xor(mine, m, kWave);
+    if (threadIdx.x % kWave == 0 && mine) atomicAdd(out, mine);
+}
+
+dcnn_status launch_mask_sum(dcnn_ctx* ctx, const uint8_t* mask, int64_t pixels, int32_t* out) {
+    dcnn_status st = launch_fill_i32(ctx, out, 0, 1);
+    if (st != DCNN_OK || pixels <= 0) return st;
+    const int64_t want = (pixels + 255) / 256;
+    const int grid = (int)(want < 1024 ? want : 1024);
+    hipLaunchKernelGGL(mask_sum_kernel, dim3(grid), dim3(256), 0, ctx->stream, mask, pixels, out);
+    return check_hip(ctx, hipGetLastError(), "mask_sum_kernel launch");
+}
+
 dcnn_status launch_xt_row_count(dcnn_ctx* ctx, int phase, const ListArgs& l, const uint8_t* flags, uint8_t* before,
                                 unsigned long long* io) {
     const int64_t want = cdiv(l.max_count > 0 ? l.max_count : 1, kMaskThreads);
