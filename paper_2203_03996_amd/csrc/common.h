@@ -114,6 +114,8 @@ struct EpilogueArgs {
     void* accum_O;               // fused final accumulation: dense output O (output shape); the emitted delta is
                                  // added to it and not stored (sparse steps of layers with an activation only)
     int carry;                   // 1: an update leaves the rounding residue of x^A in x^T (s - round(s)) instead of 0
+    uint8_t* clear_mask;         // optional: a byte array every workgroup of the grid zeroes a share of before anything else
+    int64_t clear_bytes;         // (the output mask of the layer's NEXT step, see dcnn_layer_step)
 };
 
 struct ListArgs {

@@ -283,6 +283,7 @@ template <typename T, int NB, int KS, int TI>
 __global__ __launch_bounds__(kDirectWaves* kWave, 2) void conv_direct_kernel(ListArgs l, ConvArgs c, EpilogueArgs e, int npass, int cs,
                                                                              int blocked_min_tiles) {
     extern __shared__ __align__(16) unsigned char smem[];
+    clear_ahead(e);
     const int64_t count = list_count(l);
     if (count >= (int64_t)blocked_min_tiles * kTile) {
         if constexpr (KS == 3 && NB <= 2) {

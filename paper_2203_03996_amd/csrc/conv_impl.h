@@ -43,6 +43,7 @@ __global__ __launch_bounds__(WMODE == 2 ? 256 : DCNN_CONV_BOUNDS) void conv_mfma
     constexpr int GK = 4;                                      // K-steps whose gathers are in flight together
     constexpr bool STREAM = WMODE == 1;
     extern __shared__ __align__(16) unsigned char smem[];
+    clear_ahead(e);
 
     const int nwaves = blockDim.x / kWave, nthreads = blockDim.x;
     const int tiles_per_iter = nwaves / cs;

@@ -74,6 +74,7 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
     constexpr int ES = (int)sizeof(T);
     static_assert(sizeof(Vec) == 16 && sizeof(Raw) == 16, "16-byte channel vectors");
     extern __shared__ __align__(16) unsigned char smem[];
+    clear_ahead(e);
 
     const int tiles_per_iter = NP / cs;
     const int64_t count = list_count(l);
@@ -612,15 +613,14 @@ __global__ __launch_bounds__(kWsWaves* kWave) void conv_ws_kernel(ListArgs l, Co
     #pragma unroll
                 for (int m = kWave >> 1; m >= 1; m >>= 1) bits |= __shfl_xor(bits, m, kWave);
                 if constexpr (decltype(sf)::value) {
-                    // Flags of the tile's entries, one store instruction each and only if some lane needs it (entry
-                    // `lane` by lane `lane`).  The output mask arrives holding 1 at every listed pixel (the dilated
-                    // flags, or a copy of the input's mask), so only truncated pixels are written.  x^T row flag: after
-                    // an update the row is zero again (unless it keeps residues), after a truncation it holds values.
+                    // Flags of the tile's entries, one store instruction each (entry `lane` by lane `lane`).  The
+                    // output mask gets the decision of every listed pixel: whatever it held before (1 from the dilated
+                    // flags, or 0 from the clearing a step ahead) does not matter.  x^T row flag: after an update the
+                    // row is zero again (unless it keeps residues), after a truncation it holds values.
                     const bool mine = lane >= my_first && lane < my_end && cur.pix_mine >= 0;
                     const bool upd_e = (bits >> (lane & 31)) & 1u;
-                    const bool clear = mine && !upd_e;
-                    if (has_omask && __builtin_amdgcn_ballot_w64(clear))
-                        __builtin_amdgcn_raw_buffer_store_b8((uint8_t)0, rs_omask, clear ? cur.pix_mine : (int)kOob, 0, 0);
+                    if (has_omask && __builtin_amdgcn_ballot_w64(mine))
+                        __builtin_amdgcn_raw_buffer_store_b8((uint8_t)(upd_e ? 1 : 0), rs_omask, mine ? cur.pix_mine : (int)kOob, 0, 0);
                     const int keep = (upd_e && !carry) ? 0 : 1;
                     const bool change = mine && keep != cur.tflag_mine;
                     if (has_tflag && __builtin_amdgcn_ballot_w64(change))

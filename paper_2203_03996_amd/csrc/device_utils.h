@@ -142,6 +142,19 @@ __device__ __forceinline__ float group_max(float u, int LP) {
 
 // LDS-only synchronisation: orders shared-memory traffic without waiting for outstanding global
 // loads and stores (a generic fence would drain them and stall the memory pipeline).
+// Zeroes e.clear_mask cooperatively: every workgroup of the grid takes a share, before any of them may leave.  A layer
+// that walks its input's own list alternates between two output masks; the one its next step will write is cleared
+// here, a step ahead, so that step finds zeros wherever it does not write and needs no mask pass of its own.
+__device__ __forceinline__ void clear_ahead(const EpilogueArgs& e) {
+    if (e.clear_mask == nullptr) return;
+    const int64_t n16 = e.clear_bytes / 16;                    // (state pieces are 256-byte aligned)
+    const int64_t nthreads = (int64_t)gridDim.x * gridDim.y * blockDim.x;
+    const int64_t me = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+    uint4* p16 = reinterpret_cast<uint4*>(e.clear_mask);
+    for (int64_t i = me; i < n16; i += nthreads) p16[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (me < e.clear_bytes - n16 * 16) e.clear_mask[n16 * 16 + me] = 0;
+}
+
 __device__ __forceinline__ void lds_wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
     __builtin_amdgcn_wave_barrier();

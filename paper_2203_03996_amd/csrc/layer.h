@@ -24,6 +24,8 @@ struct dcnn_layer {
     uint8_t* out_mask;
     int32_t* out_idx;
     int32_t* out_count;
+    uint8_t* out_mask_alt;              // second output mask of a layer that alternates between two (see dcnn_layer_step)
+    int mask_phase;                     // which of the two the NEXT step writes
     int32_t* list;                      // work list when the layer builds its own
     int32_t* list_count;
     uint32_t* taps;                     // per work-list entry: flagged window taps (dense convolutions, 1x1 / 3x3)

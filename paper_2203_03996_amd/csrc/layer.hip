@@ -127,6 +127,7 @@ static void carve(dcnn_layer* L, void* state) {
     const bool act = has_act(d), own = own_list(d);
     L->buf0 = L->buf1 = L->buf2 = nullptr; L->buf0_bytes = L->buf1_bytes = L->buf2_bytes = 0;
     L->out_data = nullptr; L->out_mask = nullptr; L->out_idx = nullptr; L->out_count = nullptr;
+    L->out_mask_alt = nullptr; L->mask_phase = 0;
     L->list = nullptr; L->list_count = nullptr; L->taps = nullptr; L->wpacked = nullptr; L->bias = nullptr;
     L->wpacked2 = nullptr; L->wpacked2_dense = nullptr; L->bias2 = nullptr; L->xt_flags = nullptr;
     L->counters = static_cast<int32_t*>(cv.take(kAlign));      // stays all zero: doubles as the zero page of the gathers
@@ -162,6 +163,11 @@ static void carve(dcnn_layer* L, void* state) {
             L->out_mask = static_cast<uint8_t*>(cv.take((size_t)L->out_pixels));
             L->out_idx = static_cast<int32_t*>(cv.take((size_t)L->out_pixels * sizeof(int32_t)));
             L->out_count = static_cast<int32_t*>(cv.take(kAlign));
+            // A convolution or activation that walks its input's own list and truncates needs an output mask that is 0
+            // wherever it does not write.  Instead of a mask pass per step it alternates between two masks, and
+            // its kernel clears the one of the next step while it runs (clear_ahead).
+            if (act && !own && (d.kind == DCNN_CONV || d.kind == DCNN_ACT))
+                L->out_mask_alt = static_cast<uint8_t*>(cv.take((size_t)L->out_pixels));
         }
         if (own) {
             if (act) {                                            // work list distinct from the output list
@@ -196,6 +202,8 @@ constexpr int kStatsScratchOffset = 8;                           // where dcnn_l
 static dcnn_status clear_sparse_output(dcnn_layer* L) {
     if (L->alias_mask) return DCNN_OK;
     dcnn_status st = launch_fill_u8(L->ctx, L->out_mask, 0, (int64_t)align_up((size_t)L->out_pixels, 4));
+    if (st == DCNN_OK && L->out_mask_alt) st = launch_fill_u8(L->ctx, L->out_mask_alt, 0, (int64_t)align_up((size_t)L->out_pixels, 4));
+    L->mask_phase = 0;
     if (st != DCNN_OK) return st;
     st = launch_fill_i32(L->ctx, L->out_count, 0, kXtIoOffset + 4);     // the count, the statistics scratch and the x^T row counters behind it
     if (st != DCNN_OK) return st;
@@ -528,7 +536,10 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
     dcnn_delta& v = L->view;
     v.n = d.n; v.h = L->oh; v.w = L->ow; v.c = L->oc; v.dtype = d.dtype;
     v.data = d.fuse_accum ? L->buf2 : L->out_data;
-    v.mask = L->alias_mask ? in[0]->mask : L->out_mask;
+    // (a layer with two output masks: this step writes one, which is all zero, and clears the other for the next step)
+    uint8_t* const mask_cur = (L->out_mask_alt && L->mask_phase) ? L->out_mask_alt : L->out_mask;
+    uint8_t* const mask_next = L->out_mask_alt ? (L->mask_phase ? L->out_mask : L->out_mask_alt) : nullptr;
+    v.mask = L->alias_mask ? in[0]->mask : mask_cur;
     v.idx = L->alias_mask ? in[0]->idx : L->out_idx;
     // A layer with an activation whose output list nobody walks (want_idx == 0) does not count its flagged outputs:
     // atomics on one counter are served one after the other (~2.4 ns each; a few thousand waves adding their share at
@@ -582,7 +593,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         l.list = L->list; l.count = L->list_count; l.taps = L->taps;
     } else {
         l.list = in[0]->idx; l.count = in[0]->count;
-        if (act) {
+        if (act && !mask_next) {
             // the truncation below rewrites the mask at the visited pixels only: start from a copy
             MaskPassArgs m{};
             m.mask_in = in[0]->mask; m.mask_out = L->out_mask; m.idx_out = nullptr;
@@ -627,7 +638,8 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
                 }
                 e.xt_flags = L->xt_flags;
             }
-            e.out_mask = act ? L->out_mask : nullptr;
+            e.out_mask = act ? mask_cur : nullptr;
+            e.clear_mask = mask_next; e.clear_bytes = mask_next ? L->out_pixels : 0;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;
             e.out_count = nullptr;                                 // (see the output view above)
             // statistics mode: which x^T rows the kernel will read, and afterwards which it wrote
@@ -650,7 +662,8 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
             e.res_data = n_in == 2 ? in[1]->data : nullptr; e.res_mask = n_in == 2 ? in[1]->mask : nullptr;
             e.xA = L->buf0; e.xT = L->buf1; e.out_data = L->out_data;
             e.carry = d.xT_residue;
-            e.out_mask = act ? L->out_mask : nullptr;
+            e.out_mask = act ? mask_cur : nullptr;
+            e.clear_mask = mask_next; e.clear_bytes = mask_next ? L->out_pixels : 0;
             e.surv = (act && d.want_idx) ? ws.surv : nullptr;
             e.out_count = nullptr;                                 // (see the output view above)
             st = launch_act(ctx, d.dtype, false, l, a, e);
@@ -692,6 +705,7 @@ dcnn_status dcnn_layer_step(dcnn_layer* L, const dcnn_delta* const* in, int32_t 
         default: return fail(ctx, DCNN_EINVAL, "step: bad layer kind");
     }
     if (st != DCNN_OK) return st;
+    if (mask_next) L->mask_phase ^= 1;
     if (timed) {
         st = check_hip(ctx, hipEventRecord(L->events[L->events_used].second, ctx->stream), "hipEventRecord");
         if (st != DCNN_OK) return st;

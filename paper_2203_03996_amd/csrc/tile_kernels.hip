@@ -165,6 +165,7 @@ template <typename T, int V, int VPL, int UB> struct ActSrc {
 template <typename T, int V, int VPL, int UB>
 __global__ __launch_bounds__(kTileThreads) void act_sparse_kernel(ListArgs l, ActArgs a, EpilogueArgs e, TailShape shape,
                                                                    uint32_t map_bytes, uint32_t pixels) {
+    clear_ahead(e);
     const int64_t count = list_count(l);
     const int lane = threadIdx.x % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -213,6 +214,7 @@ __global__ __launch_bounds__(kTileThreads) void act_wide_kernel(ListArgs l, ActA
     typedef typename RawOf<T, V>::type Raw;
     constexpr uint32_t ES = sizeof(T);
     __shared__ float s_max[2][kWideRun][kTileWaves];
+    clear_ahead(e);
     const int64_t count = list_count(l);
     const int lane = threadIdx.x % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -346,6 +348,7 @@ template <typename T, int V, int VPL>
 __global__ __launch_bounds__(kTileThreads) void act_kernel(ListArgs l, ActArgs a, EpilogueArgs e, int init) {
     typedef typename RawOf<T, V>::type Raw;
     constexpr int UB = (V * VPL >= 16) ? 2 : 4;
+    clear_ahead(e);
     const int64_t count = list_count(l);
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int C = e.c;
