@@ -211,7 +211,8 @@ void        dcnn_layer_destroy(dcnn_layer* layer);
 dcnn_status dcnn_layer_init(dcnn_layer* layer, const void* const* dense_in_dev, int32_t n_in, void* dense_out_dev);
 /* Frames >= 2: consume sparse inputs, update the buffers, produce the sparse output, which
  * lives in the layer's state memory and is described by dcnn_layer_output.  For DCNN_ACCUM the
- * output's data is the dense accumulated map (all pixels valid). */
+ * output's data is the dense accumulated map (all pixels valid).  The view is that of the LAST step: ask
+ * again after every step (a layer may alternate between two mask arrays), and read it before the next. */
 dcnn_status dcnn_layer_step(dcnn_layer* layer, const dcnn_delta* const* in, int32_t n_in);
 dcnn_status dcnn_layer_output(const dcnn_layer* layer, dcnn_delta* out_view);
 /* Forget the buffers: the next call must be dcnn_layer_init (supplementary Section 1.4). */
