@@ -125,6 +125,35 @@ def test_act_trunc(S, f, carry, shape):
         assert np.any(ref.xT[want.mask == 1] != 0) if want.count else True
 
 
+@pytest.mark.parametrize("shape", [(2, 40, 37, 64), (1, 9, 7, 1024)])
+def test_layer_whose_list_nobody_walks_keeps_no_count_and_alternates_its_masks(shape):
+    """want_idx = 0: the view hands out no count (nothing on a step's path keeps one) and dcnn_layer_stats counts
+    the mask instead; the layer walks its input's list, so it alternates between two output masks, each cleared a
+    step ahead -- frames whose lists are disjoint, full and empty in turn must leave no stale flag behind."""
+    S, f, eps = "f16", "relu", 0.35
+    rng = np.random.default_rng(shape[3])
+    n, h, w, c = shape
+    ref = orc.ActTrunc(f, eps, S)
+    ctx = pkg.Context(n * h * w)
+    layer = pkg.Layer(ctx, pkg.make_desc(pkg.ACT, DT[S], n, h, w, c, act=pkg.ACT_CODES[f], eps=eps, want_idx=0))
+    x0 = rng.normal(0, 2, shape).astype(NP_DTYPE[S])
+    ref.init(x0)
+    layer.init([torch.from_numpy(x0).cuda()])
+    masks = set()
+    for t, dens in enumerate([0.4, 0.4, 1.0, 0.0, 0.1, 0.0, 0.6]):
+        d = _rand_delta(rng, shape, dens, S, scale=0.3)
+        want = ref.step(d).poisoned()
+        out = layer.step([_upload(d)])
+        ctx.sync()
+        assert out.count is None
+        masks.add(out.mask.data_ptr())
+        assert np.array_equal(to_np(out.mask), want.mask), f"frame {t}"
+        assert layer.stats()["pixels_out"] == want.count and layer.stats()["pixels_in"] == d.count
+        sel = want.mask.astype(bool)
+        assert np.array_equal(to_np(out.data)[sel], want.data[sel])
+    assert len(masks) == 2
+
+
 @pytest.mark.parametrize("S", ["f32", "f16"])
 @pytest.mark.parametrize("act", ["relu", "none"])
 @pytest.mark.parametrize("shape", [(2, 31, 30, 64), (2, 11, 9, 2048), (1, 13, 5, 1024)])
