@@ -108,7 +108,9 @@ struct EpilogueArgs {
     void* out_data;
     uint8_t* out_mask;           // written at every visited pixel (0 or 1); nullptr: not written
     uint32_t* surv;              // survivor word per tile; nullptr: not written
-    int32_t* out_count;          // when surv is null: survivors are added here (zeroed by the mask pass)
+    int32_t* out_count;          // when surv is null: survivors are added here, one atomic per wave.  The layer code
+                                 // passes nullptr: atomics on one address are served one after the other, and a
+                                 // few thousand of them at the end of a kernel cost 10-20 us (see dcnn_layer_step)
     uint8_t* xt_flags;           // optional, per output pixel: 0 = the pixel's x^T row is all zero bits in memory and is
                                  // not read; 1 = it may hold values.  Kept up to date by the wave-specialised kernel only.
     void* accum_O;               // fused final accumulation: dense output O (output shape); the emitted delta is
